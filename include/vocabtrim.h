@@ -1,0 +1,160 @@
+/*
+ * vocabtrim.h -- C ABI of libvocabtrim.so: the trimmed-LM-head hot path of
+ * VocabTrim (training-free vocabulary trimming of a speculative-decoding
+ * drafter's LM head) for AMD MI355X (gfx950).
+ *
+ * Three operations, named after the paper's problem statement:
+ *
+ *   vt_count_tokens        Algorithm 1 (Count Token Frequencies)
+ *   vt_build_trimmed_head  Eq. 1 (V_trim = V[Top-K(c,k)], W_trim = W[Top-K(c,k), :])
+ *                          and the token index mapper T_{d->t} of Algorithm 2
+ *   vt_draft_head_step     Algorithm 2, the two drafting lines: the trimmed
+ *                          drafter's output z_hat over the trimmed vocabulary
+ *                          and y_hat = T_{d->t}(z_hat), with the EAGLE-2 style
+ *                          draft-token selection named in the experimental
+ *                          settings (top-m tokens per node with log-probs;
+ *                          greedy top-1 for chain drafting)
+ *
+ * General conventions
+ * -------------------
+ * - Every data pointer is DEVICE memory owned by the caller (for example a
+ *   torch tensor's data_ptr()).  The library never allocates, frees, or keeps
+ *   a pointer after the call returns.  No call synchronises the device or
+ *   reads device memory on the host.
+ * - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   All work is enqueued on it; outputs are valid once the stream has reached
+ *   that point.
+ * - `ws` is caller-provided device scratch of at least the size returned by
+ *   the matching *_ws_bytes() function (a pure host function), 256-byte
+ *   aligned.  A workspace may be reused by successive calls on one stream;
+ *   two calls that may overlap in time need separate workspaces.
+ * - Host-detectable errors return a non-zero vt_status and enqueue nothing.
+ *   Data-dependent conditions (token ids outside [0,V)) cannot be reported
+ *   synchronously; see vt_count_tokens.
+ * - Layouts are row-major and contiguous.  Vocabulary ids and the map are
+ *   int32 (V < 2^31); counters are int64; log-probs are fp32.
+ * - Supported element types of (h, W): both VT_BF16 or both VT_F32.  bf16
+ *   products are accumulated in fp32.
+ */
+#ifndef VOCABTRIM_H_
+#define VOCABTRIM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VT_OK = 0,
+    VT_ERR_NULL = 1,      /* a required pointer is NULL */
+    VT_ERR_SHAPE = 2,     /* a size is out of range (V, d, n <= 0; k not in [1,V]; m not in [1,min(k,VT_MAX_TOP_M)]) */
+    VT_ERR_DTYPE = 3,     /* unknown or unsupported element / index type, or h and W differ */
+    VT_ERR_ALIGN = 4,     /* a pointer is not 16-byte aligned, or d is not a multiple of 16 bytes of elements */
+    VT_ERR_WORKSPACE = 5, /* ws is NULL, misaligned or smaller than *_ws_bytes() */
+    VT_ERR_DEVICE = 6     /* a HIP call failed (launch error, no device) */
+} vt_status;
+
+typedef enum { VT_F32 = 0, VT_BF16 = 1 } vt_dtype;
+typedef enum { VT_I32 = 0, VT_I64 = 1 } vt_itype;
+
+/* Largest m (tokens kept per hidden row) vt_draft_head_step accepts. */
+#define VT_MAX_TOP_M 64
+
+/* Human-readable name of a status code (static storage). */
+const char *vt_status_string(int status);
+
+/* Text of the HIP error behind the calling thread's most recent VT_ERR_DEVICE
+ * (static storage; "no error" if there was none). */
+const char *vt_last_device_error(void);
+
+/* ------------------------------------------------------------------------
+ * Algorithm 1 -- Count Token Frequencies.
+ *
+ * For every token id t in ids[0..n_ids): counts[t] += 1.  `counts` is
+ * accumulated into, so a calibration corpus can be fed in chunks and the
+ * vector saved / resumed by the caller; zero it before the first chunk (the
+ * algorithm's "initialize with zeros").  Tokenisation is the caller's: the
+ * function consumes ids.
+ *
+ *   ids        [n_ids] int32 or int64 (id_type), device; may be NULL iff n_ids == 0
+ *   n_ids      number of ids, >= 0 (0 is a valid no-op)
+ *   V          vocabulary size, > 0
+ *   counts     [V] int64, device, in/out
+ *   n_invalid  device uint64, in/out, nullable: ids < 0 or >= V are skipped
+ *              and added here, so sum(counts) + *n_invalid grows by n_ids
+ *   ws         >= vt_count_tokens_ws_bytes(V, n_ids) bytes; contents need no
+ *              initialisation
+ * ---------------------------------------------------------------------- */
+int vt_count_tokens(const void *ids, int id_type, int64_t n_ids, int32_t V, int64_t *counts,
+                    uint64_t *n_invalid, void *ws, size_t ws_bytes, void *stream);
+size_t vt_count_tokens_ws_bytes(int32_t V, int64_t n_ids);
+
+/* ------------------------------------------------------------------------
+ * Eq. 1 -- vocabulary trimming.
+ *
+ * Top-K(c,k): the k ids with the largest counts; among equal counts the
+ * lower id is taken first (ids never seen have count 0 and fill the tail by
+ * ascending id).  The selected ids are written in ASCENDING id order:
+ *
+ *   map[j]        the j-th smallest selected id  (token index mapper T_{d->t})
+ *   W_trim[j, :]  = W[map[j], :]                 (bit copy of the stored type)
+ *
+ * so k == V gives map = identity and W_trim == W.
+ *
+ *   counts  [V] int64, device (values >= 0)
+ *   W       [V, d] row-major, w_type, device
+ *   d       hidden size; d * sizeof(element) must be a multiple of 16
+ *   k       trimmed vocabulary size, 1 <= k <= V
+ *   map     [k] int32, device, out
+ *   W_trim  [k, d] row-major, w_type, device, out; must not overlap W
+ *   ws      >= vt_build_trimmed_head_ws_bytes(V, d, k) bytes; no initialisation
+ * W may be NULL together with W_trim to compute the map only.
+ * ---------------------------------------------------------------------- */
+int vt_build_trimmed_head(const int64_t *counts, int32_t V, const void *W, int w_type, int32_t d,
+                          int32_t k, int32_t *map, void *W_trim, void *ws, size_t ws_bytes,
+                          void *stream);
+size_t vt_build_trimmed_head_ws_bytes(int32_t V, int32_t d, int32_t k);
+
+/* ------------------------------------------------------------------------
+ * Algorithm 2, drafting lines -- one draft step of the trimmed LM head.
+ *
+ *   z[i, j]   = sum_t h[i, t] * W_trim[j, t]            (never stored unless asked)
+ *   lse[i]    = log sum_j exp z[i, j]   over the k trimmed logits only
+ *   per row i: the m largest z[i, .], descending; equal logits -> lower target
+ *              id first
+ *   out_ids[i, r]  = map[j_r]                            (y_hat = T_{d->t}(z_hat))
+ *   out_logp[i, r] = z[i, j_r] - lse[i]
+ *
+ *   h              [n, d] row-major, h_type, device
+ *   n              hidden rows this step (chain drafting: 1; tree drafting: nodes), 1 <= n
+ *   W_trim         [k, d] row-major, w_type (== h_type), device
+ *   map            [k] int32 target ids, device
+ *   m              tokens kept per row, 1 <= m <= min(k, VT_MAX_TOP_M)
+ *   out_ids        [n, m] int32, device, out
+ *   out_logp       [n, m] fp32, device, out
+ *   out_lse        [n] fp32, device, out, nullable
+ *   out_logp_full  [n, k] fp32, device, out, nullable: log-softmax of every
+ *                  trimmed logit (costs an extra pass; meant for checks)
+ *   ws             >= vt_draft_head_step_ws_bytes(n, k, d, m) bytes, prepared
+ *                  once by vt_draft_head_step_ws_init() after allocation.  The
+ *                  step leaves the workspace ready for the next call, so no
+ *                  further initialisation is needed between steps, whatever
+ *                  their shapes (as long as the size suffices).
+ * ---------------------------------------------------------------------- */
+int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim, int w_type,
+                       int32_t k, int32_t d, const int32_t *map, int32_t m, int32_t *out_ids,
+                       float *out_logp, float *out_lse, float *out_logp_full, void *ws,
+                       size_t ws_bytes, void *stream);
+size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m);
+
+/* Clears the arrival counters at the head of a draft-step workspace (a small
+ * fill kernel on `stream`; safe under stream capture).  Call once after
+ * allocating the workspace, and again only if a step was aborted mid-flight. */
+int vt_draft_head_step_ws_init(void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VOCABTRIM_H_ */

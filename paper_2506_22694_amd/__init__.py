@@ -1,0 +1,11 @@
+"""MI355X-native trimmed-LM-head path of VocabTrim: count -> select/gather -> draft step.
+
+The arithmetic lives in libvocabtrim.so (hand-written HIP for gfx950, C ABI in
+include/vocabtrim.h); this package is the thin binding plus the seeded input
+generators used by tests and the benchmark.
+"""
+from .binding import (StepWorkspace, VocabTrimError, build_trimmed_head, count_tokens, draft_head_step,
+                      load_library)
+
+__all__ = ["StepWorkspace", "VocabTrimError", "build_trimmed_head", "count_tokens", "draft_head_step",
+           "load_library"]

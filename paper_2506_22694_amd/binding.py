@@ -1,0 +1,200 @@
+"""Thin Python binding over the C ABI of libvocabtrim.so (include/vocabtrim.h).
+
+Argument marshalling only: torch tensors supply device memory and the current
+HIP stream; every step of the path runs in the library's kernels.  There is no
+fallback: if the library is missing, or a call returns an error status, a
+RuntimeError is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libvocabtrim.so")
+
+VT_F32, VT_BF16 = 0, 1
+VT_I32, VT_I64 = 0, 1
+VT_MAX_TOP_M = 64
+
+EXPORTS = (
+    "vt_status_string", "vt_last_device_error",
+    "vt_count_tokens", "vt_count_tokens_ws_bytes",
+    "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes",
+    "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
+)
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen libvocabtrim.so and declare its prototypes.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(hipcc, gfx950). There is no CPU fallback.")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz, ci = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int
+    L.vt_status_string.argtypes = [ci]
+    L.vt_status_string.restype = ctypes.c_char_p
+    L.vt_last_device_error.argtypes = []
+    L.vt_last_device_error.restype = ctypes.c_char_p
+    L.vt_count_tokens.argtypes = [vp, ci, i64, i32, vp, vp, vp, sz, vp]
+    L.vt_count_tokens.restype = ci
+    L.vt_count_tokens_ws_bytes.argtypes = [i32, i64]
+    L.vt_count_tokens_ws_bytes.restype = sz
+    L.vt_build_trimmed_head.argtypes = [vp, i32, vp, ci, i32, i32, vp, vp, vp, sz, vp]
+    L.vt_build_trimmed_head.restype = ci
+    L.vt_build_trimmed_head_ws_bytes.argtypes = [i32, i32, i32]
+    L.vt_build_trimmed_head_ws_bytes.restype = sz
+    L.vt_draft_head_step.argtypes = [vp, ci, i32, vp, ci, i32, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.vt_draft_head_step.restype = ci
+    L.vt_draft_head_step_ws_bytes.argtypes = [i32, i32, i32, i32]
+    L.vt_draft_head_step_ws_bytes.restype = sz
+    L.vt_draft_head_step_ws_init.argtypes = [vp, sz, vp]
+    L.vt_draft_head_step_ws_init.restype = ci
+    _lib = L
+    return L
+
+
+class VocabTrimError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        L = load_library()
+        msg = L.vt_status_string(status).decode()
+        if status == 6:
+            msg += " (" + L.vt_last_device_error().decode() + ")"
+        super().__init__(msg)
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise VocabTrimError(status)
+
+
+def _stream(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return VT_BF16
+    if t.dtype == torch.float32:
+        return VT_F32
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _require_cuda(*ts):
+    for t in ts:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def _scratch(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# --------------------------------------------------------------------------- Alg. 1
+def count_tokens(ids: torch.Tensor, V: int, counts: torch.Tensor | None = None,
+                 n_invalid: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """counts[t] += 1 for every id in `ids` (int32/int64 device tensor).  Returns counts (int64 [V])."""
+    L = load_library()
+    _require_cuda(ids, counts, n_invalid, ws)
+    if ids.dtype == torch.int32:
+        it = VT_I32
+    elif ids.dtype == torch.int64:
+        it = VT_I64
+    else:
+        raise TypeError("ids must be int32 or int64")
+    dev = ids.device
+    if counts is None:
+        counts = torch.zeros(V, dtype=torch.int64, device=dev)
+    n = ids.numel()
+    need = L.vt_count_tokens_ws_bytes(V, n)
+    if ws is None:
+        ws = _scratch(need, dev)
+    _check(L.vt_count_tokens(_ptr(ids) if n else None, it, n, V, _ptr(counts), _ptr(n_invalid), _ptr(ws),
+                             ws.numel(), _stream(dev)))
+    return counts
+
+
+# --------------------------------------------------------------------------- Eq. 1
+def build_trimmed_head(counts: torch.Tensor, W: torch.Tensor | None, k: int, ws: torch.Tensor | None = None):
+    """Top-k ids by count (ties -> lower id), ascending, and the gathered head rows.
+
+    Returns (map int32 [k], W_trim [k,d] or None).
+    """
+    L = load_library()
+    _require_cuda(counts, W, ws)
+    if counts.dtype != torch.int64:
+        raise TypeError("counts must be int64")
+    dev = counts.device
+    V = counts.numel()
+    map_ = torch.empty(k, dtype=torch.int32, device=dev)
+    if W is not None:
+        d = W.shape[1]
+        W_trim = torch.empty((k, d), dtype=W.dtype, device=dev)
+        wt = _dtype_code(W)
+    else:
+        d, W_trim, wt = 8, None, VT_BF16
+    if ws is None:
+        ws = _scratch(L.vt_build_trimmed_head_ws_bytes(V, d, k), dev)
+    _check(L.vt_build_trimmed_head(_ptr(counts), V, _ptr(W), wt, d, k, _ptr(map_), _ptr(W_trim), _ptr(ws),
+                                   ws.numel(), _stream(dev)))
+    return map_, W_trim
+
+
+# --------------------------------------------------------------------------- Alg. 2, drafting lines
+class StepWorkspace:
+    """Device scratch of the draft step: allocated and initialised once, reused by every step."""
+
+    def __init__(self, n: int, k: int, d: int, m: int, device):
+        L = load_library()
+        nbytes = L.vt_draft_head_step_ws_bytes(n, k, d, m)
+        if nbytes == 0:
+            raise VocabTrimError(2)
+        self.buf = _scratch(nbytes, device)
+        _check(L.vt_draft_head_step_ws_init(_ptr(self.buf), self.buf.numel(), _stream(device)))
+
+    @property
+    def nbytes(self) -> int:
+        return self.buf.numel()
+
+
+def draft_head_step(h: torch.Tensor, W_trim: torch.Tensor, map_: torch.Tensor, m: int,
+                    ws: StepWorkspace | None = None, return_lse: bool = False, return_full: bool = False,
+                    out_ids: torch.Tensor | None = None, out_logp: torch.Tensor | None = None):
+    """One draft step: (ids int32 [n,m] in target vocabulary, logp fp32 [n,m]) [+ lse [n]] [+ logp_full [n,k]]."""
+    L = load_library()
+    _require_cuda(h, W_trim, map_)
+    n, d = h.shape
+    k = W_trim.shape[0]
+    if W_trim.shape[1] != d or map_.numel() != k or map_.dtype != torch.int32:
+        raise ValueError("shape / dtype mismatch between h, W_trim and map")
+    dev = h.device
+    if ws is None:
+        ws = StepWorkspace(n, k, d, m, dev)
+    if out_ids is None:
+        out_ids = torch.empty((n, m), dtype=torch.int32, device=dev)
+    if out_logp is None:
+        out_logp = torch.empty((n, m), dtype=torch.float32, device=dev)
+    lse = torch.empty(n, dtype=torch.float32, device=dev) if return_lse else None
+    full = torch.empty((n, k), dtype=torch.float32, device=dev) if return_full else None
+    _check(L.vt_draft_head_step(_ptr(h), _dtype_code(h), n, _ptr(W_trim), _dtype_code(W_trim), k, d, _ptr(map_), m,
+                                _ptr(out_ids), _ptr(out_logp), _ptr(lse), _ptr(full), _ptr(ws.buf), ws.nbytes,
+                                _stream(dev)))
+    res = [out_ids, out_logp]
+    if return_lse:
+        res.append(lse)
+    if return_full:
+        res.append(full)
+    return tuple(res)

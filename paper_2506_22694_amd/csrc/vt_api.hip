@@ -1,0 +1,241 @@
+// C ABI of libvocabtrim.so: argument validation, workspace layout, kernel dispatch.
+// Every entry point only enqueues work on the caller's stream.
+#include "vocabtrim.h"
+
+#include <hip/hip_runtime.h>
+
+#include "vt_build.h"
+#include "vt_step.h"
+
+namespace {
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int elem_size(int dtype) { return dtype == VT_BF16 ? 2 : 4; }
+
+// last HIP error seen by this thread's calls into the library (for vt_last_device_error)
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+inline int device_status(hipError_t e) {
+    if (e == hipSuccess) return VT_OK;
+    g_last_hip_error = e;
+    return VT_ERR_DEVICE;
+}
+inline int launch_status() { return device_status(hipGetLastError()); }
+
+// ---------------------------------------------------------------- draft-step plan
+struct StepPlan {
+    bool ok = false;
+    bool gemv = false;     // small-n VALU path
+    int NP = 0, CS = 0, S = 0;
+    int rpb = 0, nblocks = 0, tpitch = 0, L = 0, fin_conc = 0;
+    size_t lds = 0;
+    // workspace layout (byte offsets)
+    size_t off_lse = 0, off_pmax = 0, off_psum = 0, off_pkeys = 0, bytes = 0;
+};
+
+constexpr size_t kTicketBytes = 256;   // 64 arrival counters
+
+StepPlan plan_step(int n, int k, int d, int m, int dtype) {
+    StepPlan p;
+    if (n <= 0 || k <= 0 || d <= 0 || m <= 0 || k > vt::kStepMaxK) return p;
+    int rpb = (k + vt::kStepMaxBlocks - 1) / vt::kStepMaxBlocks;
+    rpb = (rpb + 7) / 8 * 8;
+    p.rpb = rpb;
+    p.nblocks = (k + rpb - 1) / rpb;
+    p.tpitch = rpb + 1;
+    p.L = m < rpb ? m : rpb;
+    const size_t stage = (size_t)p.nblocks * p.L * sizeof(unsigned long long);
+    int conc = (int)(vt::kFinalizeLdsBytes / stage);
+    if (conc < 1) return p;
+    p.fin_conc = conc < vt::kStepWaves ? conc : vt::kStepWaves;
+
+    if (n <= vt::kGemvMaxN) {
+        const int NP = n <= 1 ? 1 : (n <= 2 ? 2 : (n <= 4 ? 4 : 8));
+        const int epc = dtype == VT_BF16 ? 8 : 4;
+        const int CT = (d + 64 * epc - 1) / (64 * epc);
+        static const int cs_bf16[] = {1, 2, 3, 4, 6};
+        static const int cs_f32[] = {1, 2, 4};
+        const int *cs_set = dtype == VT_BF16 ? cs_bf16 : cs_f32;
+        const int ncs = dtype == VT_BF16 ? 5 : 3;
+        for (int S = 1; S <= vt::kStepWaves && !p.gemv; S *= 2) {
+            const int need = (CT + S - 1) / S;
+            for (int q = 0; q < ncs; ++q) {
+                const int CS = cs_set[q];
+                if (CS >= need && CS * NP <= 24) {
+                    const size_t tile = (size_t)S * NP * p.tpitch * sizeof(float);
+                    if (tile <= 96 * 1024) {
+                        p.gemv = true;
+                        p.NP = NP;
+                        p.CS = CS;
+                        p.S = S;
+                        p.lds = tile;
+                    }
+                    break;
+                }
+            }
+        }
+    }
+    if (!p.gemv) return p;   // larger n / d: handled by the matrix-core path
+    const size_t fin = (size_t)p.fin_conc * stage;
+    if (fin > p.lds) p.lds = fin;
+
+    size_t off = kTicketBytes;
+    p.off_lse = off;
+    off = round_up(off + (size_t)n * sizeof(float), 256);
+    p.off_pmax = off;
+    off = round_up(off + (size_t)p.nblocks * n * sizeof(float), 256);
+    p.off_psum = off;
+    off = round_up(off + (size_t)p.nblocks * n * sizeof(float), 256);
+    p.off_pkeys = off;
+    off = round_up(off + (size_t)n * p.nblocks * p.L * sizeof(unsigned long long), 256);
+    p.bytes = off;
+    p.ok = true;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *vt_status_string(int status) {
+    switch (status) {
+        case VT_OK: return "VT_OK";
+        case VT_ERR_NULL: return "VT_ERR_NULL: a required pointer is NULL";
+        case VT_ERR_SHAPE: return "VT_ERR_SHAPE: a size is out of range";
+        case VT_ERR_DTYPE: return "VT_ERR_DTYPE: unknown or unsupported element or index type";
+        case VT_ERR_ALIGN: return "VT_ERR_ALIGN: pointer or row size not 16-byte aligned";
+        case VT_ERR_WORKSPACE: return "VT_ERR_WORKSPACE: workspace missing, misaligned or too small";
+        case VT_ERR_DEVICE: return "VT_ERR_DEVICE: a HIP call failed";
+        default: return "unknown vt_status";
+    }
+}
+
+const char *vt_last_device_error(void) { return hipGetErrorString(g_last_hip_error); }
+
+// ------------------------------------------------------------------ Algorithm 1
+size_t vt_count_tokens_ws_bytes(int32_t V, int64_t n_ids) {
+    if (V <= 0 || n_ids < 0) return 0;
+    return round_up((size_t)vt::hist_num_chunks(n_ids) * (size_t)V * sizeof(unsigned), 256);
+}
+
+int vt_count_tokens(const void *ids, int id_type, int64_t n_ids, int32_t V, int64_t *counts,
+                    uint64_t *n_invalid, void *ws, size_t ws_bytes, void *stream) {
+    if (id_type != VT_I32 && id_type != VT_I64) return VT_ERR_DTYPE;
+    if (V <= 0 || n_ids < 0 || n_ids > ((int64_t)1 << 37)) return VT_ERR_SHAPE;
+    if (counts == nullptr || (ids == nullptr && n_ids > 0)) return VT_ERR_NULL;
+    if (n_ids == 0) return VT_OK;
+    const size_t idb = id_type == VT_I64 ? 8 : 4;
+    if (!aligned(ids, idb) || !aligned(counts, 8) || (n_invalid && !aligned(n_invalid, 8))) return VT_ERR_ALIGN;
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < vt_count_tokens_ws_bytes(V, n_ids)) return VT_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    return device_status(vt::launch_count_tokens(ids, id_type == VT_I64, n_ids, V,
+                                                 reinterpret_cast<long long *>(counts),
+                                                 reinterpret_cast<unsigned long long *>(n_invalid),
+                                                 static_cast<unsigned *>(ws), static_cast<hipStream_t>(stream)));
+}
+
+// ------------------------------------------------------------------ Eq. 1
+size_t vt_build_trimmed_head_ws_bytes(int32_t V, int32_t d, int32_t k) {
+    (void)V;
+    (void)d;
+    (void)k;
+    return 256;   // the select kernel keeps its state in LDS; a token amount keeps the contract uniform
+}
+
+int vt_build_trimmed_head(const int64_t *counts, int32_t V, const void *W, int w_type, int32_t d, int32_t k,
+                          int32_t *map, void *W_trim, void *ws, size_t ws_bytes, void *stream) {
+    if (w_type != VT_F32 && w_type != VT_BF16) return VT_ERR_DTYPE;
+    if (V <= 0 || d <= 0 || k < 1 || k > V) return VT_ERR_SHAPE;
+    if (counts == nullptr || map == nullptr) return VT_ERR_NULL;
+    if ((W == nullptr) != (W_trim == nullptr)) return VT_ERR_NULL;
+    const size_t row_bytes = (size_t)d * elem_size(w_type);
+    if (!aligned(counts, 8) || !aligned(map, 4)) return VT_ERR_ALIGN;
+    if (W != nullptr && ((row_bytes & 15) != 0 || !aligned(W, 16) || !aligned(W_trim, 16))) return VT_ERR_ALIGN;
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < vt_build_trimmed_head_ws_bytes(V, d, k))
+        return VT_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    vt::launch_select_topk(reinterpret_cast<const long long *>(counts), V, k, map, st);
+    if (W != nullptr) vt::launch_gather_rows(W, row_bytes, map, k, W_trim, st);
+    return launch_status();
+}
+
+// ------------------------------------------------------------------ Algorithm 2, drafting lines
+size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m) {
+    // sized for either element type (the layout does not depend on it)
+    const StepPlan p = plan_step(n, k, d, m, VT_BF16);
+    const StepPlan q = plan_step(n, k, d, m, VT_F32);
+    size_t b = p.ok ? p.bytes : 0;
+    if (q.ok && q.bytes > b) b = q.bytes;
+    return b;
+}
+
+int vt_draft_head_step_ws_init(void *ws, size_t ws_bytes, void *stream) {
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < kTicketBytes) return VT_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    vt::launch_ws_clear(static_cast<unsigned *>(ws), (int)(kTicketBytes / sizeof(unsigned)),
+                        static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim, int w_type, int32_t k, int32_t d,
+                       const int32_t *map, int32_t m, int32_t *out_ids, float *out_logp, float *out_lse,
+                       float *out_logp_full, void *ws, size_t ws_bytes, void *stream) {
+    if ((h_type != VT_F32 && h_type != VT_BF16) || (w_type != VT_F32 && w_type != VT_BF16)) return VT_ERR_DTYPE;
+    if (h_type != w_type) return VT_ERR_DTYPE;
+    if (n <= 0 || k <= 0 || d <= 0 || k > vt::kStepMaxK) return VT_ERR_SHAPE;
+    if (m < 1 || m > k || m > VT_MAX_TOP_M) return VT_ERR_SHAPE;
+    if (h == nullptr || W_trim == nullptr || map == nullptr || out_ids == nullptr || out_logp == nullptr)
+        return VT_ERR_NULL;
+    const size_t row_bytes = (size_t)d * elem_size(w_type);
+    if ((row_bytes & 15) != 0 || !aligned(h, 16) || !aligned(W_trim, 16) || !aligned(map, 4) ||
+        !aligned(out_ids, 4) || !aligned(out_logp, 4) || (out_lse && !aligned(out_lse, 4)) ||
+        (out_logp_full && !aligned(out_logp_full, 4)))
+        return VT_ERR_ALIGN;
+    const StepPlan p = plan_step(n, k, d, m, w_type);
+    if (!p.ok) return VT_ERR_SHAPE;
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < p.bytes) return VT_ERR_WORKSPACE;
+
+    char *wsb = static_cast<char *>(ws);
+    vt::StepArgs a;
+    a.h = h;
+    a.W = W_trim;
+    a.map = map;
+    a.n = n;
+    a.k = k;
+    a.d = d;
+    a.m = m;
+    a.S = p.S;
+    a.rpb = p.rpb;
+    a.tpitch = p.tpitch;
+    a.L = p.L;
+    a.nblocks = p.nblocks;
+    a.pmax = reinterpret_cast<float *>(wsb + p.off_pmax);
+    a.psum = reinterpret_cast<float *>(wsb + p.off_psum);
+    a.pkeys = reinterpret_cast<unsigned long long *>(wsb + p.off_pkeys);
+    a.ticket = reinterpret_cast<unsigned *>(wsb);
+    a.out_ids = out_ids;
+    a.out_logp = out_logp;
+    a.out_lse = out_lse;
+    a.out_logp_full = out_logp_full;
+    a.fin_conc = p.fin_conc;
+
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool bf16 = w_type == VT_BF16;
+    hipError_t e = hipErrorInvalidValue;
+    switch (p.NP) {
+        case 1: e = vt::launch_head_gemv_np1(bf16, p.CS, a, p.lds, st); break;
+        case 2: e = vt::launch_head_gemv_np2(bf16, p.CS, a, p.lds, st); break;
+        case 4: e = vt::launch_head_gemv_np4(bf16, p.CS, a, p.lds, st); break;
+        case 8: e = vt::launch_head_gemv_np8(bf16, p.CS, a, p.lds, st); break;
+        default: break;
+    }
+    if (e != hipSuccess) return device_status(e);
+    if (out_logp_full != nullptr)
+        vt::launch_sub_lse(out_logp_full, reinterpret_cast<const float *>(wsb + p.off_lse), n, k, st);
+    return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,26 @@
+// Internal interface of the calibration-side kernels (count, select, gather).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace vt {
+
+// ---- Algorithm 1 ----
+constexpr int kHistBinsPerBlock = 32768;   // uint32 bins privatised in LDS per workgroup (128 KiB)
+constexpr int kHistMaxChunks = 64;         // id-stream chunks (partial histograms) per launch
+constexpr int kHistThreads = 1024;
+
+int hist_num_ranges(int V);
+int hist_num_chunks(int64_t n_ids);
+// partial: [chunks, V] uint32 scratch
+hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V, long long *counts,
+                         unsigned long long *n_invalid, unsigned *partial, hipStream_t st);
+
+// ---- Eq. 1 ----
+constexpr int kSelectThreads = 1024;
+// scratch: a few words (threshold, tie budget)
+void launch_select_topk(const long long *counts, int V, int k, int *map, hipStream_t st);
+void launch_gather_rows(const void *W, size_t row_bytes, const int *map, int k, void *W_trim, hipStream_t st);
+
+}  // namespace vt

@@ -1,0 +1,417 @@
+// Draft step for a few hidden rows (n <= 8): bandwidth-bound GEMV-class kernel.
+//
+// Algorithm 2's drafting lines with a trimmed head: z = h W_trim^T over the k
+// trimmed rows, then log-softmax over those k logits, the m best per hidden row
+// and the map back to target ids.
+//
+// Data flow of one workgroup (8 waves):
+//   * it owns `rpb` consecutive rows of W_trim;
+//   * a wave streams whole rows (or one of S column segments of them): each
+//     load instruction fetches 64 lanes x 16 B = 1 KiB contiguous, non-temporal,
+//     with several rows in flight per wave;
+//   * h lives in registers (packed bf16, or fp32), a lane owning the same
+//     columns of every row, so the stream is consumed by dot2 / fma only;
+//   * after a batch of 4 or 8 rows a "transposed" wave reduction (permlane swaps + DPP) leaves
+//     one finished logit per lane, which goes to an LDS tile;
+//   * the workgroup epilogue turns the tile into (max, sum-exp) and the
+//     workgroup's best m candidates per hidden row;
+//   * the last workgroup to arrive (ticket) merges all partials: lse, top-m,
+//     remap.  No second launch, no host round trip.
+#pragma once
+#include "vt_device.h"
+#include "vt_step.h"
+#include <type_traits>
+
+namespace vt {
+
+// ------------------------------------------------------------------ dot
+// acc + a.lo * b.lo + a.hi * b.hi on packed bf16 pairs (products exact in fp32).
+// The operands are passed as plain scalars: bit-casting a vector element
+// expression directly reads element 0 whatever the swizzle.
+__device__ __forceinline__ float dot2_bf16(unsigned a, unsigned b, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc,
+                                           false);
+}
+
+template <bool BF16>
+__device__ __forceinline__ float dot_chunk(const u32x4 &w, const u32x4 &x, float acc) {
+    if constexpr (BF16) {
+        acc = dot2_bf16(w.x, x.x, acc);
+        acc = dot2_bf16(w.y, x.y, acc);
+        acc = dot2_bf16(w.z, x.z, acc);
+        acc = dot2_bf16(w.w, x.w, acc);
+    } else {
+        acc = fmaf(__uint_as_float(w.x), __uint_as_float(x.x), acc);
+        acc = fmaf(__uint_as_float(w.y), __uint_as_float(x.y), acc);
+        acc = fmaf(__uint_as_float(w.z), __uint_as_float(x.z), acc);
+        acc = fmaf(__uint_as_float(w.w), __uint_as_float(x.w), acc);
+    }
+    return acc;
+}
+
+// ------------------------------------------------------------------ transposed wave reduction
+// Each lane holds V partial sums v[0..V).  On return v[0] of lane l is the
+// 64-lane total of value number (l >> (6 - log2 V)); every total is formed by
+// the same balanced tree over lanes whatever its number, so two rows of W with
+// identical bits give identical logits.
+template <int D>
+__device__ __forceinline__ float lane_xor(float x) {
+    if constexpr (D == 8) {
+        return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x128 /*row_ror:8*/,
+                                                           0xF, 0xF, false));
+    } else if constexpr (D == 2) {
+        return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x4E /*quad_perm 2,3,0,1*/,
+                                                           0xF, 0xF, false));
+    } else if constexpr (D == 1) {
+        return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0xB1 /*quad_perm 1,0,3,2*/,
+                                                           0xF, 0xF, false));
+    } else {
+        return __shfl_xor(x, D);
+    }
+}
+
+// one stage: values a (kept by lanes with bit D clear) and b (kept by lanes with bit D set)
+template <int D>
+__device__ __forceinline__ float xstage(float a, float b, int lane) {
+    if constexpr (D == 32) {
+        auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else if constexpr (D == 16) {
+        auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else {
+        const bool hi = (lane & D) != 0;
+        const float send = hi ? a : b;
+        const float keep = hi ? b : a;
+        return keep + lane_xor<D>(send);
+    }
+}
+
+template <int V>
+__device__ __forceinline__ float xreduce(float (&v)[V], int lane) {
+    static_assert(V == 8 || V == 16 || V == 32 || V == 64, "V must be 8..64");
+    // stage D=32
+    constexpr int c0 = V;
+#pragma unroll
+    for (int j = 0; j < c0 / 2; ++j) v[j] = xstage<32>(v[j], v[j + c0 / 2], lane);
+    constexpr int c1 = c0 / 2;
+#pragma unroll
+    for (int j = 0; j < c1 / 2; ++j) v[j] = xstage<16>(v[j], v[j + c1 / 2], lane);
+    constexpr int c2 = c1 / 2;
+#pragma unroll
+    for (int j = 0; j < c2 / 2; ++j) v[j] = xstage<8>(v[j], v[j + c2 / 2], lane);
+    constexpr int c3 = c2 / 2;   // V=8 -> 1
+    if constexpr (c3 >= 2) {
+#pragma unroll
+        for (int j = 0; j < c3 / 2; ++j) v[j] = xstage<4>(v[j], v[j + c3 / 2], lane);
+    } else {
+        v[0] += lane_xor<4>(v[0]);
+    }
+    constexpr int c4 = c3 >= 2 ? c3 / 2 : 1;
+    if constexpr (c4 >= 2) {
+#pragma unroll
+        for (int j = 0; j < c4 / 2; ++j) v[j] = xstage<2>(v[j], v[j + c4 / 2], lane);
+    } else {
+        v[0] += lane_xor<2>(v[0]);
+    }
+    constexpr int c5 = c4 >= 2 ? c4 / 2 : 1;
+    if constexpr (c5 >= 2) {
+        v[0] = xstage<1>(v[0], v[1], lane);
+    } else {
+        v[0] += lane_xor<1>(v[0]);
+    }
+    return v[0];
+}
+
+// ------------------------------------------------------------------ finalize (last workgroup)
+// Merges the per-workgroup partials of every hidden row: lse, then m rounds of
+// "best remaining head" over the sorted candidate lists staged in LDS.
+__device__ __noinline__ void finalize_rows(const float *__restrict__ pmax, const float *__restrict__ psum,
+                                           const unsigned long long *__restrict__ pkeys, int B, int L, int n,
+                                           int m, int fin_conc, int *__restrict__ out_ids,
+                                           float *__restrict__ out_logp, float *__restrict__ out_lse,
+                                           float *__restrict__ lse_buf, unsigned char *smem, int w, int lane) {
+    if (w >= fin_conc) return;
+    unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * B * L;
+    constexpr int BQ = kStepMaxBlocks / kWave;
+    for (int i = w; i < n; i += fin_conc) {
+        // log-sum-exp over all workgroups
+        float lm = -INFINITY;
+        for (int b = lane; b < B; b += kWave) lm = fmaxf(lm, pmax[(size_t)b * n + i]);
+        const float M = wave_max(lm);
+        float ls = 0.f;
+        for (int b = lane; b < B; b += kWave)
+            ls += psum[(size_t)b * n + i] * __expf(pmax[(size_t)b * n + i] - M);
+        const float lse = M + __logf(wave_sum(ls));
+        // stage this row's candidate lists: [B][L] keys, contiguous
+        const unsigned long long *src = pkeys + (size_t)i * B * L;
+        for (int e = lane; e < B * L; e += kWave) stage[e] = src[e];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        unsigned long long hk[BQ];
+        int pos[BQ];
+#pragma unroll
+        for (int q = 0; q < BQ; ++q) {
+            const int b = lane + kWave * q;
+            pos[q] = 0;
+            hk[q] = b < B ? stage[(size_t)b * L] : kNoKey;
+        }
+        for (int r = 0; r < m; ++r) {
+            unsigned long long lb = hk[0];
+#pragma unroll
+            for (int q = 1; q < BQ; ++q) lb = hk[q] > lb ? hk[q] : lb;
+            const unsigned long long best = wave_max_u64(lb);
+            if (lane == 0) {
+                out_ids[(size_t)i * m + r] = key_id(best);
+                out_logp[(size_t)i * m + r] = key_logit(best) - lse;
+            }
+#pragma unroll
+            for (int q = 0; q < BQ; ++q) {
+                if (hk[q] == best && best != kNoKey) {
+                    const int b = lane + kWave * q;
+                    pos[q] += 1;
+                    hk[q] = pos[q] < L ? stage[(size_t)b * L + pos[q]] : kNoKey;
+                }
+            }
+        }
+        if (lane == 0) {
+            lse_buf[i] = lse;
+            if (out_lse) out_lse[i] = lse;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ------------------------------------------------------------------ workgroup epilogue
+// Turns the LDS logit tile of one hidden row into (max, sum-exp, best L keys).
+template <int NP, int QMAX>
+__device__ __noinline__ void block_epilogue_row(const float *zt, int S, int tpitch, int i, int n, int k,
+                                                int row0, int rows_b, int L, int nblocks,
+                                                const int *__restrict__ map, float *__restrict__ logp_full,
+                                                float *__restrict__ pmax, float *__restrict__ psum,
+                                                unsigned long long *__restrict__ pkeys, int lane) {
+    unsigned long long kq[QMAX];
+    float lmax = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < QMAX; ++q) {
+        kq[q] = kNoKey;
+        if (q * kWave < rows_b) {
+            const int t = lane + q * kWave;
+            if (t < rows_b) {
+                float z = 0.f;
+                for (int s = 0; s < S; ++s) z += zt[(size_t)(s * NP + i) * tpitch + t];
+                if (logp_full) logp_full[(size_t)i * k + row0 + t] = z;
+                lmax = fmaxf(lmax, z);
+                kq[q] = make_key(z, map[row0 + t]);
+            }
+        }
+    }
+    const float M = wave_max(lmax);
+    float ls = 0.f;
+#pragma unroll
+    for (int q = 0; q < QMAX; ++q) {
+        if (q * kWave < rows_b) {
+            if (kq[q] != kNoKey) ls += __expf(key_logit(kq[q]) - M);
+        }
+    }
+    const float Ssum = wave_sum(ls);
+    if (lane == 0) {
+        pmax[(size_t)blockIdx.x * n + i] = M;
+        psum[(size_t)blockIdx.x * n + i] = Ssum;
+    }
+    unsigned long long *dst = pkeys + ((size_t)i * nblocks + blockIdx.x) * L;
+    for (int r = 0; r < L; ++r) {
+        unsigned long long lb = kq[0];
+#pragma unroll
+        for (int q = 1; q < QMAX; ++q) {
+            if (q * kWave < rows_b) lb = kq[q] > lb ? kq[q] : lb;
+        }
+        const unsigned long long best = wave_max_u64(lb);
+        if (lane == 0) dst[r] = best;
+#pragma unroll
+        for (int q = 0; q < QMAX; ++q) {
+            if (q * kWave < rows_b) {
+                if (kq[q] == best) kq[q] = kNoKey;
+            }
+        }
+    }
+}
+
+// Publishes this workgroup's partials and elects the last one to arrive.
+__device__ __forceinline__ bool arrive_and_elect(unsigned *ticket, int nblocks) {
+    __shared__ int s_last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned t = atomicAdd(ticket, 1u);
+        s_last = (t == (unsigned)(nblocks - 1));
+    }
+    __syncthreads();
+    const bool last = s_last != 0;
+    if (last) __threadfence();
+    return last;
+}
+
+// ------------------------------------------------------------------ the kernel
+// Rows per batch (R) and row buffers in flight per wave (NSLOT), chosen so that
+// h registers + accumulators + buffers stay below 256 VGPRs (two waves per SIMD).
+template <int NP>
+struct BatchRows {
+    static constexpr int value = NP >= 8 ? 4 : 8;
+};
+template <int NP, int CS>
+struct SlotsFor {
+    static constexpr int want = CS >= 4 ? 2 : (CS >= 2 ? 4 : 8);
+    static constexpr int value = want < BatchRows<NP>::value ? want : BatchRows<NP>::value;
+};
+
+template <bool BF16, int NP, int CS>
+__global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const StepArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *zt = reinterpret_cast<float *>(smem);
+    constexpr int NW = kStepWaves;
+    constexpr int EPC = BF16 ? 8 : 4;   // elements per 16-byte chunk
+    constexpr int ES = BF16 ? 2 : 4;    // element size
+    constexpr int R = BatchRows<NP>::value;   // rows per batch
+    constexpr int RSH = R == 8 ? 3 : 2;
+    constexpr int NSLOT = SlotsFor<NP, CS>::value;
+    constexpr int V = R * NP;
+
+    const int lane = lane_id();
+    const int w = (int)(threadIdx.x >> 6);
+    const int S = a.S, G = NW / S;
+    const int s = w % S, g = w / S;
+    const int row0 = blockIdx.x * a.rpb;
+    const int rows_b = min(a.rpb, a.k - row0);
+    const size_t rs = (size_t)a.d * ES;   // row stride in bytes
+
+    // Columns this lane owns in every row.  A lane whose columns lie beyond d
+    // streams column 0 instead (always in bounds) against zeroed h registers,
+    // so the loads need no predicate.
+    int coff[CS];
+    bool cval[CS];
+    u32x4 hreg[CS][NP];
+#pragma unroll
+    for (int c = 0; c < CS; ++c) {
+        const int col = ((s * CS + c) * kWave + lane) * EPC;
+        cval[c] = col < a.d;
+        coff[c] = cval[c] ? col * ES : 0;
+    }
+#pragma unroll
+    for (int c = 0; c < CS; ++c) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int ii = min(i, a.n - 1);
+            hreg[c][i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.h) + (size_t)ii * rs + coff[c]);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CS; ++c) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const unsigned keep = (cval[c] && i < a.n) ? 0xFFFFFFFFu : 0u;
+            hreg[c][i].x &= keep;
+            hreg[c][i].y &= keep;
+            hreg[c][i].z &= keep;
+            hreg[c][i].w &= keep;
+        }
+    }
+
+    const char *Wb = static_cast<const char *>(a.W) + (size_t)row0 * rs;
+    const int nbt = (rows_b + R - 1) >> RSH;              // R-row batches in this workgroup
+    const int nbw = nbt > g ? (nbt - g + G - 1) / G : 0;  // batches of this wave
+
+    u32x4 wb[NSLOT][CS];
+    auto load_row = [&](int j, int r, u32x4(&dst)[CS]) {
+        int lr = ((g + G * j) << RSH) + r;
+        lr = min(lr, rows_b - 1);
+        const char *p = Wb + (size_t)lr * rs;
+#pragma unroll
+        for (int c = 0; c < CS; ++c)
+            dst[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + coff[c]));
+    };
+    if (nbw > 0) {
+#pragma unroll
+        for (int x = 0; x < NSLOT; ++x) load_row(0, x, wb[x]);
+    }
+
+    // One R-row batch.  Refills that stay inside the batch are unconditional;
+    // those that reach into the next batch exist only in the non-final variant,
+    // so the loop body has no branch and the load counter stays exact.
+    auto batch = [&](int j, auto last_tag) {
+        constexpr bool LAST = decltype(last_tag)::value;
+        float acc[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) acc[q] = 0.f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int slot = r % NSLOT;
+#pragma unroll
+            for (int c = 0; c < CS; ++c) {
+#pragma unroll
+                for (int i = 0; i < NP; ++i)
+                    acc[r * NP + i] = dot_chunk<BF16>(wb[slot][c], hreg[c][i], acc[r * NP + i]);
+            }
+            const int xr = r + NSLOT;
+            if (xr < R) {
+                load_row(j, xr, wb[slot]);
+            } else if constexpr (!LAST) {
+                load_row(j + 1, xr - R, wb[slot]);
+            }
+            // keep the software pipeline as written: consume a row, refill its slot
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        const float tot = xreduce<V>(acc, lane);
+        // lane l holds value number (l >> (6 - log2 V)) = r * NP + i
+        constexpr int SH = V == 64 ? 0 : (V == 32 ? 1 : (V == 16 ? 2 : 3));
+        static_assert(V >= 8, "at least 8 values per batch");
+        if ((lane & ((1 << SH) - 1)) == 0) {
+            const int idx = lane >> SH;
+            const int r = idx / NP, i = idx % NP;
+            const int t = ((g + G * j) << RSH) + r;
+            zt[(size_t)(s * NP + i) * a.tpitch + t] = tot;
+        }
+    };
+    for (int j = 0; j + 1 < nbw; ++j) batch(j, std::false_type{});
+    if (nbw > 0) batch(nbw - 1, std::true_type{});
+    __syncthreads();
+
+    if (rows_b <= 2 * kWave) {
+        for (int i = w; i < a.n; i += NW)
+            block_epilogue_row<NP, 2>(zt, S, a.tpitch, i, a.n, a.k, row0, rows_b, a.L, a.nblocks, a.map,
+                                      a.out_logp_full, a.pmax, a.psum, a.pkeys, lane);
+    } else {
+        constexpr int QMAX = kStepMaxRowsPerBlock / kWave;
+        for (int i = w; i < a.n; i += NW)
+            block_epilogue_row<NP, QMAX>(zt, S, a.tpitch, i, a.n, a.k, row0, rows_b, a.L, a.nblocks, a.map,
+                                         a.out_logp_full, a.pmax, a.psum, a.pkeys, lane);
+    }
+
+    float *lse_buf = reinterpret_cast<float *>(a.ticket + 64);
+    if (!arrive_and_elect(a.ticket, a.nblocks)) return;
+    finalize_rows(a.pmax, a.psum, a.pkeys, a.nblocks, a.L, a.n, a.m, a.fin_conc, a.out_ids, a.out_logp,
+                  a.out_lse, lse_buf, smem, w, lane);
+    if (threadIdx.x == 0) *a.ticket = 0u;
+}
+
+template <bool BF16, int NP, int CS>
+inline hipError_t launch_gemv_inst(const StepArgs &a, size_t lds, hipStream_t st) {
+    auto kern = head_gemv_kernel<BF16, NP, CS>;
+    // allow large dynamic LDS (finalize staging budget + headroom), once per device
+    static bool attr_set[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kMaxDynamicLds);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.nblocks), dim3(kStepWaves * kWave), lds, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace vt

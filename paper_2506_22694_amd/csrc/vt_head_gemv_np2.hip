@@ -1,0 +1,25 @@
+// Instantiations of the small-n draft-step kernel for NP = 2 padded hidden rows.
+#include "vt_head_gemv.cuh"
+
+namespace vt {
+
+hipError_t launch_head_gemv_np2(bool bf16, int CS, const StepArgs &a, size_t lds, hipStream_t st) {
+    if (bf16) {
+        switch (CS) {
+            case 1: return launch_gemv_inst<true, 2, 1>(a, lds, st);
+            case 2: return launch_gemv_inst<true, 2, 2>(a, lds, st);
+            case 3: return launch_gemv_inst<true, 2, 3>(a, lds, st);
+            case 4: return launch_gemv_inst<true, 2, 4>(a, lds, st);
+            case 6: return launch_gemv_inst<true, 2, 6>(a, lds, st);
+            default: return hipErrorInvalidValue;
+        }
+    }
+    switch (CS) {
+        case 1: return launch_gemv_inst<false, 2, 1>(a, lds, st);
+        case 2: return launch_gemv_inst<false, 2, 2>(a, lds, st);
+        case 4: return launch_gemv_inst<false, 2, 4>(a, lds, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace vt

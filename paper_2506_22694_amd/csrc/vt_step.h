@@ -1,0 +1,51 @@
+// Internal interface between the draft-step host code and its kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace vt {
+
+// Limits shared by host sizing code and kernels.
+constexpr int kStepWaves = 8;          // waves per workgroup of the draft-step kernels
+constexpr int kStepMaxBlocks = 256;    // one workgroup per CU on MI355X
+constexpr int kStepMaxRowsPerBlock = 1024;
+constexpr int kStepMaxK = kStepMaxBlocks * kStepMaxRowsPerBlock;
+constexpr int kFinalizeLdsBytes = 128 * 1024;  // staging budget of the finalize stage
+constexpr int kMaxDynamicLds = 144 * 1024;     // dynamic LDS the step kernels may request
+constexpr int kGemvMaxN = 8;           // the VALU GEMV path covers n <= 8
+
+struct StepArgs {
+    const void *h;            // [n, d]
+    const void *W;            // [k, d]
+    const int *map;           // [k]
+    int n, k, d, m;
+    int S;                    // number of column segments d is split into across waves
+    int rpb;                  // vocabulary rows per workgroup (multiple of 8)
+    int tpitch;               // pitch (floats) of one row of the LDS logit tile
+    int L;                    // candidates kept per (workgroup, hidden row) = min(m, rpb)
+    int nblocks;
+    float *pmax;              // [nblocks, n]
+    float *psum;              // [nblocks, n]
+    unsigned long long *pkeys;  // [n, nblocks, L]
+    unsigned *ticket;         // arrival counter, zero between calls
+    int *out_ids;             // [n, m]
+    float *out_logp;          // [n, m]
+    float *out_lse;           // [n] or null
+    float *out_logp_full;     // [n, k] or null (raw logits are written first, lse subtracted later)
+    int fin_conc;             // waves that run the finalize stage concurrently (LDS budget)
+};
+
+// Launchers, one translation unit per padded row count NP (1, 2, 4, 8).
+// hipErrorInvalidValue if (bf16, CS) is not instantiated.
+hipError_t launch_head_gemv_np1(bool bf16, int CS, const StepArgs &a, size_t lds, hipStream_t st);
+hipError_t launch_head_gemv_np2(bool bf16, int CS, const StepArgs &a, size_t lds, hipStream_t st);
+hipError_t launch_head_gemv_np4(bool bf16, int CS, const StepArgs &a, size_t lds, hipStream_t st);
+hipError_t launch_head_gemv_np8(bool bf16, int CS, const StepArgs &a, size_t lds, hipStream_t st);
+
+// logp_full[i, j] -= lse[i]
+void launch_sub_lse(float *logp_full, const float *lse, int n, int k, hipStream_t st);
+// zero the arrival counters
+void launch_ws_clear(unsigned *p, int nwords, hipStream_t st);
+
+}  // namespace vt

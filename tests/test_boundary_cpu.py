@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the public header declares, sizes workspaces deterministically and rejects
+bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_22694_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2506_22694_amd import build
+        build.build_library()
+    return binding.load_library()
+
+
+def declared_functions():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            src = open(os.path.join(ROOT, "include", fn)).read()
+            src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+            names |= set(re.findall(r"\b(vt_[a-z0-9_]+)\s*\(", src))
+    return names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    decl = declared_functions()
+    assert decl == set(binding.EXPORTS)
+    for name in decl:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    assert lib.vt_status_string(0) == b"VT_OK"
+    for s in range(1, 7):
+        assert lib.vt_status_string(s).startswith(b"VT_ERR_")
+    assert b"unknown" in lib.vt_status_string(99)
+
+
+def test_workspace_sizes_are_pure_host_functions(lib):
+    a = lib.vt_draft_head_step_ws_bytes(8, 32768, 3072, 8)
+    assert a > 0 and a % 256 == 0 and a == lib.vt_draft_head_step_ws_bytes(8, 32768, 3072, 8)
+    assert lib.vt_draft_head_step_ws_bytes(1, 32768, 3072, 1) <= a
+    assert lib.vt_draft_head_step_ws_bytes(0, 32768, 3072, 1) == 0
+    assert lib.vt_draft_head_step_ws_bytes(1, 1 << 20, 3072, 1) == 0      # beyond the supported k
+    c = lib.vt_count_tokens_ws_bytes(128256, 10_000_000)
+    assert c >= 128256 * 4 and c % 256 == 0
+    assert lib.vt_count_tokens_ws_bytes(128256, 100_000_000) == lib.vt_count_tokens_ws_bytes(128256, 10**9)
+    assert lib.vt_build_trimmed_head_ws_bytes(128256, 3072, 32768) >= 1
+
+
+A = ctypes.c_void_p(0x10000)      # a well-aligned fake device address; never dereferenced on these paths
+ODD = ctypes.c_void_p(0x10004)
+
+
+def test_count_tokens_argument_errors(lib):
+    f = lib.vt_count_tokens
+    assert f(A, 7, 10, 100, A, None, A, 1 << 30, None) == 3            # bad id type
+    assert f(A, 0, 10, 0, A, None, A, 1 << 30, None) == 2              # V <= 0
+    assert f(A, 0, -1, 100, A, None, A, 1 << 30, None) == 2            # negative length
+    assert f(None, 0, 10, 100, A, None, A, 1 << 30, None) == 1         # ids NULL
+    assert f(A, 0, 10, 100, None, None, A, 1 << 30, None) == 1         # counts NULL
+    assert f(A, 0, 0, 100, A, None, None, 0, None) == 0                # empty stream: no-op
+    assert f(None, 0, 0, 100, A, None, None, 0, None) == 0
+    assert f(ctypes.c_void_p(0x10002), 0, 10, 100, A, None, A, 1 << 30, None) == 4   # ids not 4-byte aligned
+    assert f(A, 0, 10, 100, ODD, None, A, 1 << 30, None) == 4          # counts not 8-byte aligned
+    assert f(A, 0, 10, 100, A, None, None, 1 << 30, None) == 5         # ws NULL
+    assert f(A, 0, 10, 100, A, None, A, 16, None) == 5                 # ws too small
+    assert f(A, 0, 10, 100, A, None, ODD, 1 << 30, None) == 5          # ws misaligned
+
+
+def test_build_trimmed_head_argument_errors(lib):
+    f = lib.vt_build_trimmed_head
+    ok_ws = (A, 1 << 20, None)
+    assert f(A, 100, A, 5, 64, 10, A, A, *ok_ws) == 3                  # bad dtype
+    assert f(A, 0, A, 1, 64, 10, A, A, *ok_ws) == 2                    # V <= 0
+    assert f(A, 100, A, 1, 0, 10, A, A, *ok_ws) == 2                   # d <= 0
+    assert f(A, 100, A, 1, 64, 0, A, A, *ok_ws) == 2                   # k < 1
+    assert f(A, 100, A, 1, 64, 101, A, A, *ok_ws) == 2                 # k > V
+    assert f(None, 100, A, 1, 64, 10, A, A, *ok_ws) == 1               # counts NULL
+    assert f(A, 100, A, 1, 64, 10, None, A, *ok_ws) == 1               # map NULL
+    assert f(A, 100, A, 1, 64, 10, A, None, *ok_ws) == 1               # W without W_trim
+    assert f(A, 100, A, 1, 12, 10, A, A, *ok_ws) == 4                  # row of 24 bytes
+    assert f(A, 100, ODD, 1, 64, 10, A, A, *ok_ws) == 4                # W misaligned
+    assert f(A, 100, A, 1, 64, 10, A, A, None, 1 << 20, None) == 5     # ws NULL
+    assert f(A, 100, A, 1, 64, 10, A, A, A, 0, None) == 5              # ws too small
+
+
+def test_draft_head_step_argument_errors(lib):
+    f = lib.vt_draft_head_step
+    need = lib.vt_draft_head_step_ws_bytes(2, 1000, 512, 4)
+
+    def call(h=A, ht=1, n=2, W=A, wt=1, k=1000, d=512, mp=A, m=4, oi=A, ol=A, lse=None, full=None, ws=A,
+             wsb=need):
+        return f(h, ht, n, W, wt, k, d, mp, m, oi, ol, lse, full, ws, wsb, None)
+
+    assert call(ht=2) == 3 and call(wt=9) == 3
+    assert call(ht=0, wt=1) == 3                                        # h and W must agree
+    assert call(n=0) == 2 and call(k=0) == 2 and call(d=0) == 2
+    assert call(m=0) == 2 and call(m=1001) == 2 and call(m=65) == 2
+    assert call(k=1 << 20) == 2
+    assert call(h=None) == 1 and call(W=None) == 1 and call(mp=None) == 1
+    assert call(oi=None) == 1 and call(ol=None) == 1
+    assert call(d=516) == 4                                             # row of 1032 bytes: not 16-byte rows
+    assert call(h=ODD) == 4 and call(W=ODD) == 4
+    assert call(ws=None) == 5 and call(wsb=need - 1) == 5 and call(ws=ODD) == 5
+    assert lib.vt_draft_head_step_ws_init(None, 1024, None) == 5
+    assert lib.vt_draft_head_step_ws_init(A, 8, None) == 5
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        binding.count_tokens(torch.zeros(4, dtype=torch.int32), 10)

@@ -1,0 +1,334 @@
+"""Parity of the HIP path (through the C ABI binding) against the CPU oracle, on a real MI355X.
+
+Integer results (histogram, map, gathered bits, token ids) must match bit for
+bit; log-probs within 2e-3 absolute of the fp64 oracle.  Where fp32 and fp64
+summation can legitimately order two logits differently (gap below EPS), the
+near-tie rule below applies; exact ties (bit-identical logits) must still go to
+the lower target id.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_22694_amd as vt
+from paper_2506_22694_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LOGP_TOL = 2e-3     # absolute, bf16/fp32 inputs with fp32 accumulation vs fp64
+EPS = 1e-4          # logit gap below which fp32 vs fp64 ordering may differ (about 10x the
+                    # worst fp32 accumulation error observed at d <= 8192 with |z| ~ 1)
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def to_dev(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint16:      # bf16 bit patterns
+        return torch.from_numpy(a.view(np.int16)).to(dev()).view(torch.bfloat16)
+    return torch.from_numpy(a).to(dev())
+
+
+def from_bf16(t: torch.Tensor) -> np.ndarray:
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+# ----------------------------------------------------------------------------- helpers
+def check_step(out_ids, out_logp, ref, map_np, m, lse=None):
+    """ids exact except inside near-ties; log-probs within tolerance.  Returns #near-tie rows."""
+    ids = out_ids.cpu().numpy()
+    lp = out_logp.cpu().numpy().astype(np.float64)
+    z = ref["z"]
+    n, k = z.shape
+    inv = {int(t): j for j, t in enumerate(map_np)}
+    near = 0
+    for i in range(n):
+        if np.array_equal(ids[i], ref["ids"][i]):
+            assert np.max(np.abs(lp[i] - ref["logp"][i])) <= LOGP_TOL
+            continue
+        near += 1
+        assert len(set(ids[i].tolist())) == m, "duplicate ids in a row"
+        for r in range(m):
+            assert int(ids[i, r]) in inv, "emitted id not in the map"
+            j_gpu = inv[int(ids[i, r])]
+            j_ref = int(ref["trim_idx"][i, r])
+            # the GPU's choice at this rank is within EPS of the oracle's logit at this rank
+            assert abs(z[i, j_gpu] - z[i, j_ref]) <= EPS, (i, r, z[i, j_gpu], z[i, j_ref])
+            assert abs(lp[i, r] - (z[i, j_gpu] - ref["lse"][i])) <= LOGP_TOL
+    if lse is not None:
+        assert np.max(np.abs(lse.cpu().numpy().astype(np.float64) - ref["lse"])) <= LOGP_TOL
+    return near
+
+
+def run_step(h_np, W_np, map_np, m, **kw):
+    h, W, mp = to_dev(h_np), to_dev(W_np), to_dev(map_np)
+    out = vt.draft_head_step(h, W, mp, m, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+# ----------------------------------------------------------------------------- Alg. 1
+def test_count_tiny_exact():
+    wl = synth.WORKLOADS["tiny"]
+    ids = synth.zipf_ids(wl.n_ids, wl.V, wl.zipf_s, wl.seed, wl.permute)
+    c = vt.count_tokens(to_dev(ids), wl.V)
+    ref, _ = oracle.count(ids, wl.V)
+    assert np.array_equal(c.cpu().numpy(), ref)
+    assert int(c.sum()) == wl.n_ids
+
+
+@pytest.fixture(scope="module")
+def llama_ids():
+    wl = synth.WORKLOADS["llama3b"]
+    return synth.zipf_ids(wl.n_ids, wl.V, wl.zipf_s, wl.seed, wl.permute)
+
+
+@pytest.fixture(scope="module")
+def llama_counts(llama_ids):
+    return oracle.count(llama_ids, 128256)[0]
+
+
+def test_count_llama_10m_exact(llama_ids, llama_counts):
+    c = vt.count_tokens(to_dev(llama_ids), 128256)
+    assert np.array_equal(c.cpu().numpy(), llama_counts)
+
+
+def test_count_chunked_unaligned_int64_and_invalid():
+    V = 5000
+    ids = synth.zipf_ids(300_007, V, 1.1, seed=77, permute=True, dtype=np.int64)
+    ids[::1000] = -3
+    ids[5::1000] = V
+    ids[7::1000] = 2**40
+    ref, inv_ref = oracle.count(ids, V)
+    d_ids = to_dev(ids)
+    counts = torch.zeros(V, dtype=torch.int64, device=dev())
+    n_inv = torch.zeros(1, dtype=torch.int64, device=dev())
+    # three chunks, the later two start at addresses that are not 16-byte aligned
+    for lo, hi in ((0, 100_001), (100_001, 100_004), (100_004, 300_007)):
+        vt.count_tokens(d_ids[lo:hi], V, counts=counts, n_invalid=n_inv)
+    assert np.array_equal(counts.cpu().numpy(), ref)
+    assert int(n_inv.item()) == inv_ref
+    assert int(counts.sum().item()) + inv_ref == ids.size
+    # int32 ids, unaligned start, tiny streams
+    ids32 = synth.zipf_ids(1003, V, 1.1, seed=78, permute=True)
+    for lo in (0, 1, 2, 3):
+        for hi in (lo, lo + 1, lo + 5, 1003):
+            c = vt.count_tokens(to_dev(ids32)[lo:hi], V)
+            assert np.array_equal(c.cpu().numpy(), oracle.count(ids32[lo:hi], V)[0]), (lo, hi)
+
+
+def test_count_all_tokens_identical_and_small_vocab():
+    ids = np.full(1_000_000, 17, dtype=np.int32)
+    c = vt.count_tokens(to_dev(ids), 40_000)
+    assert int(c[17].item()) == 1_000_000 and int(c.sum().item()) == 1_000_000
+    ids = synth.zipf_ids(100_000, 3, 1.1, seed=5, permute=False)
+    assert np.array_equal(vt.count_tokens(to_dev(ids), 3).cpu().numpy(), oracle.count(ids, 3)[0])
+
+
+# ----------------------------------------------------------------------------- Eq. 1
+def test_build_tiny_exact():
+    wl = synth.WORKLOADS["tiny"]
+    ids = synth.zipf_ids(wl.n_ids, wl.V, wl.zipf_s, wl.seed, wl.permute)
+    W = synth.head_weights(wl.V, wl.d, wl.seed, wl.dtype)
+    counts = vt.count_tokens(to_dev(ids), wl.V)
+    map_, Wt = vt.build_trimmed_head(counts, to_dev(W), 1024)
+    c_ref, _ = oracle.count(ids, wl.V)
+    m_ref = oracle.select(c_ref, 1024)
+    assert np.array_equal(map_.cpu().numpy(), m_ref)
+    assert np.array_equal(Wt.cpu().numpy(), oracle.gather(W, m_ref))
+
+
+def test_select_llama_k_sweep_exact(llama_counts):
+    c = torch.from_numpy(llama_counts).to(dev())
+    for k in (1, 8192, 16384, 32768, 65536, 128255, 128256):
+        map_, _ = vt.build_trimmed_head(c, None, k)
+        assert np.array_equal(map_.cpu().numpy(), oracle.select(llama_counts, k)), k
+    ident, _ = vt.build_trimmed_head(c, None, 128256)
+    assert np.array_equal(ident.cpu().numpy(), np.arange(128256))
+
+
+def test_select_adversarial_counts():
+    rng = np.random.default_rng(3)
+    cases = [np.zeros(1000, dtype=np.int64), np.full(777, 9, dtype=np.int64),
+             rng.integers(0, 3, size=4099).astype(np.int64),
+             rng.integers(0, 2**62, size=5000).astype(np.int64),
+             (np.arange(3000, dtype=np.int64) * 2**33)[::-1].copy(),
+             np.array([5], dtype=np.int64)]
+    for c in cases:
+        V = c.size
+        for k in sorted(kk for kk in {1, 2, V // 3 + 1, V - 1, V} if 1 <= kk <= V):
+            map_, _ = vt.build_trimmed_head(to_dev(c), None, k)
+            assert np.array_equal(map_.cpu().numpy(), oracle.select(c, k)), (V, k)
+
+
+def test_gather_llama3b_full_size(llama_counts):
+    V, d, k = 128256, 3072, 32768
+    W = synth.head_weights(V, d, seed=3000, dtype="bf16")
+    dW = to_dev(W)
+    map_, Wt = vt.build_trimmed_head(torch.from_numpy(llama_counts).to(dev()), dW, k)
+    m_ref = oracle.select(llama_counts, k)
+    assert np.array_equal(map_.cpu().numpy(), m_ref)
+    assert np.array_equal(from_bf16(Wt), oracle.gather(W, m_ref))
+    # k = V reproduces the head bit for bit
+    _, Wall = vt.build_trimmed_head(torch.from_numpy(llama_counts).to(dev()), dW, V)
+    assert torch.equal(Wall.view(torch.int16), dW.view(torch.int16))
+
+
+# ----------------------------------------------------------------------------- draft step
+def test_step_tiny_exhaustive():
+    wl = synth.WORKLOADS["tiny"]
+    ids = synth.zipf_ids(wl.n_ids, wl.V, wl.zipf_s, wl.seed, wl.permute)
+    W = synth.head_weights(wl.V, wl.d, wl.seed, wl.dtype)
+    h = synth.hidden_rows(4, wl.d, wl.seed, wl.dtype)
+    m_ref = oracle.select(oracle.count(ids, wl.V)[0], 1024)
+    Wt = oracle.gather(W, m_ref)
+    for m in (1, 4):
+        ref = oracle.draft_head_step(h, Wt, m_ref, m)
+        oi, ol, lse, full = run_step(h, Wt, m_ref, m, return_lse=True, return_full=True)
+        assert check_step(oi, ol, ref, m_ref, m, lse) == 0
+        _, logp_ref = oracle.log_softmax(ref["z"])
+        full = full.cpu().numpy().astype(np.float64)
+        assert np.max(np.abs(full - logp_ref)) <= LOGP_TOL
+        assert np.max(np.abs(np.exp(full).sum(axis=1) - 1.0)) <= 1e-4
+    # k = V: the untrimmed head
+    mV = np.arange(wl.V, dtype=np.int32)
+    ref = oracle.draft_head_step(h, W, mV, 4)
+    oi, ol = run_step(h, W, mV, 4)
+    assert check_step(oi, ol, ref, mV, 4) == 0
+
+
+@pytest.mark.parametrize("d", [2048, 3072, 4096])
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 8])
+def test_step_bf16_mid_size(n, d):
+    k, m = 4099, 8           # ragged: k is not a multiple of the row batch or the tile
+    W, map_ = synth.trimmed_head_direct(k, d, seed=100 + n, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=100 + n, dtype="bf16")
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+    check_step(oi, ol, ref, map_, m, lse)
+
+
+@pytest.mark.parametrize("k", [8192, 16384, 32768, 65536, 128256])
+def test_step_llama3b_k_sweep_full_size(k):
+    d = 3072
+    W, map_ = synth.trimmed_head_direct(k, d, seed=3000, dtype="bf16")
+    dW, dmap = to_dev(W), to_dev(map_)
+    total_near = 0
+    for n in (1, 2, 4, 8):
+        h = synth.hidden_rows(n, d, seed=3000 + n, dtype="bf16")
+        ref8 = oracle.draft_head_step(h, W, map_, 8)
+        for m in (1, 8):
+            ws = vt.StepWorkspace(n, k, d, m, dev())
+            oi, ol, lse = vt.draft_head_step(to_dev(h), dW, dmap, m, ws=ws, return_lse=True)
+            torch.cuda.synchronize()
+            ref = {key: (v[:, :m] if key in ("ids", "logp", "trim_idx") else v) for key, v in ref8.items()}
+            total_near += check_step(oi, ol, ref, map_, m, lse)
+    assert total_near <= 2
+
+
+def test_step_llama1b_chain_and_full_vocab_control():
+    d = 2048
+    for k in (32768, 128256):
+        W, map_ = synth.trimmed_head_direct(k, d, seed=2000, dtype="bf16")
+        h = synth.hidden_rows(1, d, seed=2000, dtype="bf16")
+        ref = oracle.draft_head_step(h, W, map_, 1)
+        oi, ol = run_step(h, W, map_, 1)
+        check_step(oi, ol, ref, map_, 1)
+
+
+def test_step_odd_shapes():
+    # d not a multiple of the 512-column wave chunk; k tiny; m = k; fp32 with a ragged d
+    for (k, d, n, m, dt) in ((1, 64, 1, 1, "bf16"), (7, 264, 3, 7, "bf16"), (64, 520, 8, 64, "bf16"),
+                             (130, 1032, 2, 5, "bf16"), (1000, 260, 4, 3, "f32"), (9, 4, 8, 9, "f32"),
+                             (2049, 776, 7, 16, "bf16")):
+        W, map_ = synth.trimmed_head_direct(k, d, seed=k + d, dtype=dt)
+        h = synth.hidden_rows(n, d, seed=k + d, dtype=dt)
+        ref = oracle.draft_head_step(h, W, map_, m)
+        oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+        check_step(oi, ol, ref, map_, m, lse)
+
+
+def test_step_h_zero_uniform_and_lowest_ids():
+    k, d = 32768, 3072
+    W, map_ = synth.trimmed_head_direct(k, d, seed=9, dtype="bf16")
+    h = np.zeros((2, d), dtype=np.uint16)
+    oi, ol = run_step(h, W, map_, 8)
+    assert np.array_equal(oi.cpu().numpy(), np.tile(map_[:8], (2, 1)))
+    assert np.max(np.abs(ol.cpu().numpy() - (-math.log(k)))) <= 1e-5   # closed form -ln k
+
+
+def test_step_exact_ties_from_duplicate_rows():
+    k, d, n, m = 8192, 3072, 4, 8
+    W, map_ = synth.trimmed_head_direct(k, d, seed=10, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=10, dtype="bf16")
+    z = oracle.logits(h, W)
+    # copy the best row of hidden row 0 to far-away positions (other workgroups, other wave slots)
+    j = int(np.argmax(z[0]))
+    for off in (1, 37, 1000, 4097, 8000):
+        W[(j + off) % k] = W[j]
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol = run_step(h, W, map_, m)
+    ids = oi.cpu().numpy()
+    # the six tied rows fill ranks 0..5 of hidden row 0 in ascending id order, exactly
+    assert np.array_equal(ids[0, :6], ref["ids"][0, :6])
+    assert np.all(np.diff(ids[0, :6]) > 0)
+    lp = ol.cpu().numpy()
+    assert np.all(lp[0, :6] == lp[0, 0])
+    check_step(oi, ol, ref, map_, m)
+
+
+def test_step_non_ascending_map_ties_follow_target_id():
+    k, d = 512, 512
+    W, map_ = synth.trimmed_head_direct(k, d, seed=11, dtype="bf16")
+    map_ = map_[::-1].copy()          # descending ids: lower target id = higher trimmed index
+    h = np.zeros((1, d), dtype=np.uint16)
+    ref = oracle.draft_head_step(h, W, map_, 4)
+    oi, _ = run_step(h, W, map_, 4)
+    assert np.array_equal(oi.cpu().numpy(), ref["ids"])
+    assert oi.cpu().numpy()[0].tolist() == sorted(map_.tolist())[:4]
+
+
+def test_step_workspace_reuse_poison_and_determinism():
+    k, d, n, m = 32768, 3072, 8, 8
+    W, map_ = synth.trimmed_head_direct(k, d, seed=12, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=12, dtype="bf16")
+    dW, dmap, dh = to_dev(W), to_dev(map_), to_dev(h)
+    ws = vt.StepWorkspace(n, k, d, m, dev())
+    first = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
+    torch.cuda.synchronize()
+    a_ids, a_lp = first[0].clone(), first[1].clone()
+    # poison everything behind the arrival counters; the next call must not read stale partials
+    ws.buf[256:] = 0xFF
+    for _ in range(3):
+        oi, ol = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(oi, a_ids) and torch.equal(ol, a_lp)
+    # a different, smaller shape on the same workspace, then the first shape again
+    W2, map2 = synth.trimmed_head_direct(1000, 512, seed=13, dtype="bf16")
+    h2 = synth.hidden_rows(2, 512, seed=13, dtype="bf16")
+    ref2 = oracle.draft_head_step(h2, W2, map2, 3)
+    oi2, ol2 = vt.draft_head_step(to_dev(h2), to_dev(W2), to_dev(map2), 3, ws=ws)
+    torch.cuda.synchronize()
+    check_step(oi2, ol2, ref2, map2, 3)
+    oi, ol = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(oi, a_ids) and torch.equal(ol, a_lp)
+    ref = oracle.draft_head_step(h, W, map_, m)
+    check_step(oi, ol, ref, map_, m)
+
+
+def test_error_statuses_on_device():
+    L = vt.load_library()
+    k, d = 64, 64
+    W, map_ = synth.trimmed_head_direct(k, d, seed=14, dtype="bf16")
+    h = synth.hidden_rows(1, d, seed=14, dtype="bf16")
+    with pytest.raises(vt.VocabTrimError) as e:
+        vt.draft_head_step(to_dev(h), to_dev(W), to_dev(map_), 65)
+    assert e.value.status == 2
+    with pytest.raises(vt.VocabTrimError) as e:
+        vt.build_trimmed_head(torch.zeros(10, dtype=torch.int64, device=dev()), None, 11)
+    assert e.value.status == 2

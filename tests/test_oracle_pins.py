@@ -216,6 +216,11 @@ def test_log_softmax_invariants_and_library():
     lse2, lp2 = oracle.log_softmax(z + 12.5)
     assert np.max(np.abs(lp2 - lp)) <= 1e-11
     assert np.array_equal(oracle.lse_only(z), lse)
+    # the shift must be the row maximum: any other shift overflows or underflows here
+    wide = np.linspace(-1000.0, 1000.0, 401)[None, :]
+    lse_w, lp_w = oracle.log_softmax(wide)
+    assert np.isfinite(lse_w[0]) and abs(lse_w[0] - scipy.special.logsumexp(wide[0])) <= 1e-9
+    assert lp_w[0, -1] > -0.01 and np.isfinite(lp_w).all()
 
 
 # ---------------------------------------------------------------- top-m + remap
