@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the trimmed-LM-head draft step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Headline workload ("llama3b"): Llama-3.2-3B-shaped head, V = 128256, d = 3072,
+bf16; 10M Zipf(1.1) calibration ids; k = 32768; a draft step with n = 8 hidden
+rows and top-8 per row.  One timed "step" is one draft step (projection,
+log-softmax over k, top-m, remap) -- the per-token hot loop the metric names;
+the offline calibration rows (count, select, gather) run once before it on the
+same inputs and are timed and reported in the same JSON line under
+"calibration".
+
+Cold-cache rule: W_trim (192 MiB) would fit the memory-side cache, so the timed
+steps rotate over several distinct device copies of W_trim.
+
+Prints ONE JSON line on stdout.  Everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+# HBM bytes per launch of the step kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE),
+# scaled by the same counters on a plain copy of known size; see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=300)
+    p.add_argument("--warmup", type=int, default=30)
+    p.add_argument("--n", type=int, default=8, help="hidden rows per draft step")
+    p.add_argument("--m", type=int, default=8, help="tokens kept per row")
+    p.add_argument("--k", type=int, default=32768)
+    p.add_argument("--workload", default="llama3b", choices=["llama1b", "llama3b"])
+    p.add_argument("--copies", type=int, default=6, help="distinct W_trim copies visited round-robin")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-calibration", action="store_true",
+                   help="draw W_trim directly instead of running count/select/gather on a full head")
+    p.add_argument("--sweep", action="store_true", help="also time the k / n sweep (table on stderr)")
+    p.add_argument("--pmc-copy", action="store_true",
+                   help="only run plain device copies of the W_trim size (counter calibration under rocprofv3)")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        log(f"bench.py: this build measures one GPU only (got --gpus {args.gpus}); "
+            "the path is a single-device kernel and no multi-GPU figure exists.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2506_22694_amd as vt
+    from paper_2506_22694_amd import synth
+
+    vt.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = synth.WORKLOADS[args.workload]
+    V, d, k, n, m = wl.V, wl.d, args.k, args.n, args.m
+    step_bytes = k * d * 2
+
+    def to_dev_bf16(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    if args.pmc_copy:
+        src = torch.empty(step_bytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_copy_bytes": step_bytes, "launches": 10}))
+        return
+
+    stream = torch.cuda.current_stream(dev)
+
+    def time_region(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for r in range(reps):
+            fn(r)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps      # us per rep
+
+    # ------------------------------------------------------------------ inputs + calibration rows
+    calib = None
+    t0 = time.time()
+    if args.no_calibration:
+        W_np, map_np = synth.trimmed_head_direct(k, d, wl.seed, "bf16")
+        W_trim, map_ = to_dev_bf16(W_np), torch.from_numpy(map_np).to(dev)
+    else:
+        ids_np = synth.zipf_ids(wl.n_ids, V, wl.zipf_s, wl.seed, wl.permute)
+        W_full = to_dev_bf16(synth.head_weights(V, d, wl.seed, "bf16"))
+        ids = torch.from_numpy(ids_np).to(dev)
+        log(f"inputs ready in {time.time() - t0:.1f}s")
+        counts = torch.zeros(V, dtype=torch.int64, device=dev)
+        ws_c = torch.empty(vt.load_library().vt_count_tokens_ws_bytes(V, ids.numel()), dtype=torch.uint8, device=dev)
+
+        def do_count(_):
+            counts.zero_()
+            vt.count_tokens(ids, V, counts=counts, ws=ws_c)
+        do_count(0)
+        us_count = time_region(do_count, 10)
+        us_zero = time_region(lambda _: counts.zero_(), 10)
+        us_count -= us_zero
+        us_select = time_region(lambda _: vt.build_trimmed_head(counts, None, k), 10)
+        map_, W_trim = vt.build_trimmed_head(counts, W_full, k)
+        us_build = time_region(lambda _: vt.build_trimmed_head(counts, W_full, k), 5)
+        us_gather = us_build - us_select
+        calib = {
+            "count_us": round(us_count, 2), "count_ids": wl.n_ids,
+            "count_gids_per_s": round(wl.n_ids / us_count / 1e3, 2),
+            "count_id_stream_gbps": round(wl.n_ids * 4 / us_count / 1e3, 1),
+            "select_us": round(us_select, 2),
+            "gather_us": round(us_gather, 2),
+            "gather_gbps": round(2 * step_bytes / us_gather / 1e3, 1),
+            "gather_frac_of_hbm_peak": round(2 * step_bytes / us_gather / 1e3 / HBM_PEAK_GBPS, 4),
+        }
+        log("calibration:", calib)
+        del W_full, ids
+    h = to_dev_bf16(synth.hidden_rows(n, d, wl.seed, "bf16"))
+    copies = [W_trim] + [W_trim.clone() for _ in range(max(1, args.copies) - 1)]
+    ws = vt.StepWorkspace(n, k, d, m, dev)
+    out_ids = torch.empty((n, m), dtype=torch.int32, device=dev)
+    out_logp = torch.empty((n, m), dtype=torch.float32, device=dev)
+
+    def step(r, W=None):
+        vt.draft_head_step(h, copies[r % len(copies)] if W is None else W, map_, m, ws=ws,
+                           out_ids=out_ids, out_logp=out_logp)
+
+    # ------------------------------------------------------------------ timed region
+    for r in range(args.warmup):
+        step(r)
+    us_cold = time_region(step, args.steps)
+    # per-launch kernel duration: an event pair around every launch of the same K steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for r, (a, b) in enumerate(evs):
+        a.record(stream)
+        step(r)
+        b.record(stream)
+    torch.cuda.synchronize()
+    per = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+    us_kernel = sum(per) / len(per)
+    us_warm = time_region(lambda r: step(r, copies[0]), args.steps)
+    log(f"step n={n} m={m} k={k} d={d}: cold {us_cold:.2f} us/step (back-to-back), "
+        f"per-launch avg {us_kernel:.2f} us (p10 {per[len(per)//10]:.2f}, p50 {per[len(per)//2]:.2f}, "
+        f"p90 {per[len(per)*9//10]:.2f}), warm single buffer {us_warm:.2f} us")
+
+    sweep = None
+    if args.sweep:
+        sweep = []
+        for kk in (8192, 16384, 32768, 65536, 128256):
+            Wk_np, mapk_np = synth.trimmed_head_direct(kk, d, wl.seed, "bf16")
+            Wk = to_dev_bf16(Wk_np)
+            mapk = torch.from_numpy(mapk_np).to(dev)
+            ncop = max(2, min(24, int(1.3e9 // (kk * d * 2))))
+            cps = [Wk] + [Wk.clone() for _ in range(ncop - 1)]
+            for nn in (1, 2, 4, 8):
+                for mm in (1, 8):
+                    hh = to_dev_bf16(synth.hidden_rows(nn, d, wl.seed + nn, "bf16"))
+                    wsk = vt.StepWorkspace(nn, kk, d, mm, dev)
+                    f = lambda r: vt.draft_head_step(hh, cps[r % ncop], mapk, mm, ws=wsk)
+                    for r in range(10):
+                        f(r)
+                    us = time_region(f, 100)
+                    row = {"k": kk, "n": nn, "m": mm, "us": round(us, 2), "gbps": round(kk * d * 2 / us / 1e3, 1),
+                           "frac": round(kk * d * 2 / us / 1e3 / HBM_PEAK_GBPS, 4)}
+                    sweep.append(row)
+                    log("sweep", row)
+            del cps, Wk
+
+    # ------------------------------------------------------------------ CPU baseline (the oracle, untuned)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        W_host = copies[0].view(torch.int16).cpu().numpy().view(np.uint16)
+        h_host = h.view(torch.int16).cpu().numpy().view(np.uint16)
+        map_host = map_.cpu().numpy()
+        oracle.draft_head_step(h_host, W_host, map_host, m)       # untimed first call (page-in)
+        t0 = time.time()
+        reps = 0
+        while reps < 3 or (time.time() - t0 < 12.0 and reps < 50):
+            oracle.draft_head_step(h_host, W_host, map_host, m)
+            reps += 1
+        us_cpu = (time.time() - t0) / reps * 1e6
+        cpu = {"value": round(us_cpu, 1), "unit": "us", "cores": oracle.get_threads(), "kind": "oracle",
+               "sample": f"{reps} full draft steps of the same workload (n={n}, k={k}, d={d}, m={m}), fp64"}
+        log("cpu_baseline:", cpu)
+
+    gbps_cold = step_bytes / us_cold / 1e3
+    gbps_kernel = step_bytes / us_kernel / 1e3
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, k, n, m))
+    out = {
+        "metric": "trimmed LM-head draft-step latency (us) + achieved HBM GB/s, d=3072 k=32768",
+        "value": round(us_cold, 3),
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(us_cold / 1e3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: V={V} d={d} bf16, k={k}, n={n}, top-{m}, "
+                               f"{len(copies)} W_trim copies round-robin (cold cache)",
+                   "V": V, "d": d, "k": k, "n": n, "m": m, "copies": len(copies)},
+        "hbm_gbps": round(gbps_cold, 1),
+        "frac_of_hbm_peak": round(gbps_cold / HBM_PEAK_GBPS, 4),
+        "warm_single_buffer_us": round(us_warm, 3),
+        "roofline": {"bound": "hbm", "achieved": round(gbps_kernel, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps_kernel / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "kernel": "head_gemv_kernel", "algorithmic_bytes": step_bytes,
+                     "avg_launch_us": round(us_kernel, 3)},
+        "cpu_baseline": cpu,
+        "calibration": calib,
+    }
+    if sweep is not None:
+        out["sweep"] = sweep
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -31,10 +31,10 @@ struct StepPlan {
     int rpb = 0, nblocks = 0, tpitch = 0, L = 0, fin_conc = 0;
     size_t lds = 0;
     // workspace layout (byte offsets)
-    size_t off_lse = 0, off_pmax = 0, off_psum = 0, off_pkeys = 0, bytes = 0;
+    size_t off_lse = 0, off_pms = 0, off_pkeys = 0, bytes = 0;
 };
 
-constexpr size_t kTicketBytes = 256;   // 64 arrival counters
+using vt::kTicketBytes;
 
 StepPlan plan_step(int n, int k, int d, int m, int dtype) {
     StepPlan p;
@@ -83,10 +83,8 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
     size_t off = kTicketBytes;
     p.off_lse = off;
     off = round_up(off + (size_t)n * sizeof(float), 256);
-    p.off_pmax = off;
-    off = round_up(off + (size_t)p.nblocks * n * sizeof(float), 256);
-    p.off_psum = off;
-    off = round_up(off + (size_t)p.nblocks * n * sizeof(float), 256);
+    p.off_pms = off;
+    off = round_up(off + (size_t)p.nblocks * n * sizeof(unsigned long long), 256);
     p.off_pkeys = off;
     off = round_up(off + (size_t)n * p.nblocks * p.L * sizeof(unsigned long long), 256);
     p.bytes = off;
@@ -211,10 +209,9 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
     a.tpitch = p.tpitch;
     a.L = p.L;
     a.nblocks = p.nblocks;
-    a.pmax = reinterpret_cast<float *>(wsb + p.off_pmax);
-    a.psum = reinterpret_cast<float *>(wsb + p.off_psum);
+    a.pms = reinterpret_cast<unsigned long long *>(wsb + p.off_pms);
     a.pkeys = reinterpret_cast<unsigned long long *>(wsb + p.off_pkeys);
-    a.ticket = reinterpret_cast<unsigned *>(wsb);
+    a.tickets = reinterpret_cast<unsigned *>(wsb);
     a.out_ids = out_ids;
     a.out_logp = out_logp;
     a.out_lse = out_lse;

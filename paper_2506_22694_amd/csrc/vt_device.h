@@ -36,17 +36,53 @@ __device__ __forceinline__ int key_id(unsigned long long key) { return (int)(~(u
 // the logit is a negative NaN; NaN inputs are outside the contract).
 constexpr unsigned long long kNoKey = 0ull;
 
-// ---- wave-wide reductions (all 64 lanes receive the result) ----
+// ---- wave-wide all-reductions on DPP / permlane swaps (no LDS traffic) ----
+// Four DPP steps reduce within a row of 16 lanes; permlane16_swap and
+// permlane32_swap (gfx950) then combine the four rows.  Every lane receives the
+// result and the combination order is fixed, so float sums are reproducible.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_mov(unsigned v) {
+    return __builtin_amdgcn_update_dpp(0u, v, CTRL, 0xF, 0xF, false);
+}
+template <typename Op>
+__device__ __forceinline__ unsigned wave_allreduce_u32(unsigned v, Op op) {
+    v = op(v, dpp_mov<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = op(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = op(v, dpp_mov<0x141>(v));   // row_half_mirror
+    v = op(v, dpp_mov<0x140>(v));   // row_mirror
+    auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = op(r[0], r[1]);
+    r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return op(r[0], r[1]);
+}
+struct OpMaxU32 {
+    __device__ __forceinline__ unsigned operator()(unsigned a, unsigned b) const { return a > b ? a : b; }
+};
+struct OpMinU32 {
+    __device__ __forceinline__ unsigned operator()(unsigned a, unsigned b) const { return a < b ? a : b; }
+};
+struct OpAddU32 {
+    __device__ __forceinline__ unsigned operator()(unsigned a, unsigned b) const { return a + b; }
+};
+struct OpMaxF32 {
+    __device__ __forceinline__ unsigned operator()(unsigned a, unsigned b) const {
+        return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b)));
+    }
+};
+struct OpAddF32 {
+    __device__ __forceinline__ unsigned operator()(unsigned a, unsigned b) const {
+        return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
+    }
+};
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v) { return wave_allreduce_u32(v, OpMaxU32{}); }
+__device__ __forceinline__ unsigned wave_min_u32(unsigned v) { return wave_allreduce_u32(v, OpMinU32{}); }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    return __uint_as_float(wave_allreduce_u32(__float_as_uint(v), OpMaxF32{}));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    return __uint_as_float(wave_allreduce_u32(__float_as_uint(v), OpAddF32{}));
 }
+__device__ __forceinline__ int wave_sum_i32(int v) { return (int)wave_allreduce_u32((unsigned)v, OpAddU32{}); }
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
@@ -55,20 +91,19 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
     }
     return v;
 }
-__device__ __forceinline__ int wave_sum_i32(int v) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
 
-// Per (block, hidden row) partial result of the draft step, merged by the
-// finalize stage:  running maximum M, sum of exp(z - M), and the block's best
-// candidates as keys sorted descending.
-struct StepPartials {
-    float *pmax;                 // [B, n]
-    float *psum;                 // [B, n]
-    unsigned long long *pkeys;   // [B, n, L]
-    int L;                       // candidates kept per (block, row) = min(m, rows per block)
-};
+// ---- cross-workgroup publication without cache-wide fences ----
+// Partials are written with relaxed agent-scope atomic stores (write-through past
+// the XCD-local L2) and read back with relaxed agent-scope atomic loads (which
+// do not hit in the reader's L2).  A device-scope release fence would instead
+// write back the whole L2 -- tens of microseconds on this part.
+__device__ __forceinline__ void publish_u64(unsigned long long *p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long acquire_u64(const unsigned long long *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Wait until every store this wave has issued is acknowledged (vmcnt(0)).
+__device__ __forceinline__ void wait_stores_done() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 }  // namespace vt

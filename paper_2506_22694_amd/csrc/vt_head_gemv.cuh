@@ -15,11 +15,12 @@
 //     one finished logit per lane, which goes to an LDS tile;
 //   * the workgroup epilogue turns the tile into (max, sum-exp) and the
 //     workgroup's best m candidates per hidden row;
-//   * the last workgroup to arrive (ticket) merges all partials: lse, top-m,
-//     remap.  No second launch, no host round trip.
+//   * the last workgroup to arrive (two-level ticket) merges all partials: lse,
+//     top-m, remap.  No second launch, no host round trip, no cache-wide fence.
 #pragma once
 #include "vt_device.h"
 #include "vt_step.h"
+#include "vt_step_tail.cuh"
 #include <type_traits>
 
 namespace vt {
@@ -123,136 +124,6 @@ __device__ __forceinline__ float xreduce(float (&v)[V], int lane) {
     return v[0];
 }
 
-// ------------------------------------------------------------------ finalize (last workgroup)
-// Merges the per-workgroup partials of every hidden row: lse, then m rounds of
-// "best remaining head" over the sorted candidate lists staged in LDS.
-__device__ __noinline__ void finalize_rows(const float *__restrict__ pmax, const float *__restrict__ psum,
-                                           const unsigned long long *__restrict__ pkeys, int B, int L, int n,
-                                           int m, int fin_conc, int *__restrict__ out_ids,
-                                           float *__restrict__ out_logp, float *__restrict__ out_lse,
-                                           float *__restrict__ lse_buf, unsigned char *smem, int w, int lane) {
-    if (w >= fin_conc) return;
-    unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * B * L;
-    constexpr int BQ = kStepMaxBlocks / kWave;
-    for (int i = w; i < n; i += fin_conc) {
-        // log-sum-exp over all workgroups
-        float lm = -INFINITY;
-        for (int b = lane; b < B; b += kWave) lm = fmaxf(lm, pmax[(size_t)b * n + i]);
-        const float M = wave_max(lm);
-        float ls = 0.f;
-        for (int b = lane; b < B; b += kWave)
-            ls += psum[(size_t)b * n + i] * __expf(pmax[(size_t)b * n + i] - M);
-        const float lse = M + __logf(wave_sum(ls));
-        // stage this row's candidate lists: [B][L] keys, contiguous
-        const unsigned long long *src = pkeys + (size_t)i * B * L;
-        for (int e = lane; e < B * L; e += kWave) stage[e] = src[e];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        unsigned long long hk[BQ];
-        int pos[BQ];
-#pragma unroll
-        for (int q = 0; q < BQ; ++q) {
-            const int b = lane + kWave * q;
-            pos[q] = 0;
-            hk[q] = b < B ? stage[(size_t)b * L] : kNoKey;
-        }
-        for (int r = 0; r < m; ++r) {
-            unsigned long long lb = hk[0];
-#pragma unroll
-            for (int q = 1; q < BQ; ++q) lb = hk[q] > lb ? hk[q] : lb;
-            const unsigned long long best = wave_max_u64(lb);
-            if (lane == 0) {
-                out_ids[(size_t)i * m + r] = key_id(best);
-                out_logp[(size_t)i * m + r] = key_logit(best) - lse;
-            }
-#pragma unroll
-            for (int q = 0; q < BQ; ++q) {
-                if (hk[q] == best && best != kNoKey) {
-                    const int b = lane + kWave * q;
-                    pos[q] += 1;
-                    hk[q] = pos[q] < L ? stage[(size_t)b * L + pos[q]] : kNoKey;
-                }
-            }
-        }
-        if (lane == 0) {
-            lse_buf[i] = lse;
-            if (out_lse) out_lse[i] = lse;
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
-}
-
-// ------------------------------------------------------------------ workgroup epilogue
-// Turns the LDS logit tile of one hidden row into (max, sum-exp, best L keys).
-template <int NP, int QMAX>
-__device__ __noinline__ void block_epilogue_row(const float *zt, int S, int tpitch, int i, int n, int k,
-                                                int row0, int rows_b, int L, int nblocks,
-                                                const int *__restrict__ map, float *__restrict__ logp_full,
-                                                float *__restrict__ pmax, float *__restrict__ psum,
-                                                unsigned long long *__restrict__ pkeys, int lane) {
-    unsigned long long kq[QMAX];
-    float lmax = -INFINITY;
-#pragma unroll
-    for (int q = 0; q < QMAX; ++q) {
-        kq[q] = kNoKey;
-        if (q * kWave < rows_b) {
-            const int t = lane + q * kWave;
-            if (t < rows_b) {
-                float z = 0.f;
-                for (int s = 0; s < S; ++s) z += zt[(size_t)(s * NP + i) * tpitch + t];
-                if (logp_full) logp_full[(size_t)i * k + row0 + t] = z;
-                lmax = fmaxf(lmax, z);
-                kq[q] = make_key(z, map[row0 + t]);
-            }
-        }
-    }
-    const float M = wave_max(lmax);
-    float ls = 0.f;
-#pragma unroll
-    for (int q = 0; q < QMAX; ++q) {
-        if (q * kWave < rows_b) {
-            if (kq[q] != kNoKey) ls += __expf(key_logit(kq[q]) - M);
-        }
-    }
-    const float Ssum = wave_sum(ls);
-    if (lane == 0) {
-        pmax[(size_t)blockIdx.x * n + i] = M;
-        psum[(size_t)blockIdx.x * n + i] = Ssum;
-    }
-    unsigned long long *dst = pkeys + ((size_t)i * nblocks + blockIdx.x) * L;
-    for (int r = 0; r < L; ++r) {
-        unsigned long long lb = kq[0];
-#pragma unroll
-        for (int q = 1; q < QMAX; ++q) {
-            if (q * kWave < rows_b) lb = kq[q] > lb ? kq[q] : lb;
-        }
-        const unsigned long long best = wave_max_u64(lb);
-        if (lane == 0) dst[r] = best;
-#pragma unroll
-        for (int q = 0; q < QMAX; ++q) {
-            if (q * kWave < rows_b) {
-                if (kq[q] == best) kq[q] = kNoKey;
-            }
-        }
-    }
-}
-
-// Publishes this workgroup's partials and elects the last one to arrive.
-__device__ __forceinline__ bool arrive_and_elect(unsigned *ticket, int nblocks) {
-    __shared__ int s_last;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned t = atomicAdd(ticket, 1u);
-        s_last = (t == (unsigned)(nblocks - 1));
-    }
-    __syncthreads();
-    const bool last = s_last != 0;
-    if (last) __threadfence();
-    return last;
-}
-
 // ------------------------------------------------------------------ the kernel
 // Rows per batch (R) and row buffers in flight per wave (NSLOT), chosen so that
 // h registers + accumulators + buffers stay below 256 VGPRs (two waves per SIMD).
@@ -318,6 +189,10 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
         }
     }
 
+    // target ids of the tile rows this lane will rank in the epilogue (small tiles)
+    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
+    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
+
     const char *Wb = static_cast<const char *>(a.W) + (size_t)row0 * rs;
     const int nbt = (rows_b + R - 1) >> RSH;              // R-row batches in this workgroup
     const int nbw = nbt > g ? (nbt - g + G - 1) / G : 0;  // batches of this wave
@@ -377,22 +252,24 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
     if (nbw > 0) batch(nbw - 1, std::true_type{});
     __syncthreads();
 
-    if (rows_b <= 2 * kWave) {
-        for (int i = w; i < a.n; i += NW)
-            block_epilogue_row<NP, 2>(zt, S, a.tpitch, i, a.n, a.k, row0, rows_b, a.L, a.nblocks, a.map,
-                                      a.out_logp_full, a.pmax, a.psum, a.pkeys, lane);
-    } else {
-        constexpr int QMAX = kStepMaxRowsPerBlock / kWave;
-        for (int i = w; i < a.n; i += NW)
-            block_epilogue_row<NP, QMAX>(zt, S, a.tpitch, i, a.n, a.k, row0, rows_b, a.L, a.nblocks, a.map,
-                                         a.out_logp_full, a.pmax, a.psum, a.pkeys, lane);
+    {
+        const int sstride = NP * a.tpitch;
+        for (int i = w; i < a.n; i += NW) {
+            const float *zrow = zt + (size_t)i * a.tpitch;
+            float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
+            unsigned long long *pms_slot = a.pms + (size_t)i * a.nblocks + blockIdx.x;
+            unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nblocks + blockIdx.x) * a.L;
+            if (rows_b <= 2 * kWave)
+                block_epilogue_small(zrow, S, sstride, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane);
+            else
+                block_epilogue_large(zrow, S, sstride, rows_b, a.L, a.map + row0, full, pms_slot, pk_slot, lane);
+        }
     }
 
-    float *lse_buf = reinterpret_cast<float *>(a.ticket + 64);
-    if (!arrive_and_elect(a.ticket, a.nblocks)) return;
-    finalize_rows(a.pmax, a.psum, a.pkeys, a.nblocks, a.L, a.n, a.m, a.fin_conc, a.out_ids, a.out_logp,
-                  a.out_lse, lse_buf, smem, w, lane);
-    if (threadIdx.x == 0) *a.ticket = 0u;
+    float *lse_buf = reinterpret_cast<float *>(reinterpret_cast<char *>(a.tickets) + kTicketBytes);
+    if (!arrive_and_elect(a.tickets, a.nblocks)) return;
+    finalize_rows(a.pms, a.pkeys, a.nblocks, a.L, a.n, a.m, a.fin_conc, a.out_ids, a.out_logp, a.out_lse, lse_buf,
+                  smem, w, lane);
 }
 
 template <bool BF16, int NP, int CS>

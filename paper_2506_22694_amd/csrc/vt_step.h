@@ -13,6 +13,7 @@ constexpr int kStepMaxRowsPerBlock = 1024;
 constexpr int kStepMaxK = kStepMaxBlocks * kStepMaxRowsPerBlock;
 constexpr int kFinalizeLdsBytes = 128 * 1024;  // staging budget of the finalize stage
 constexpr int kMaxDynamicLds = 144 * 1024;     // dynamic LDS the step kernels may request
+constexpr int kTicketBytes = 2048;             // top counter + one 64-byte line per group of 16 workgroups
 constexpr int kGemvMaxN = 8;           // the VALU GEMV path covers n <= 8
 
 struct StepArgs {
@@ -25,10 +26,9 @@ struct StepArgs {
     int tpitch;               // pitch (floats) of one row of the LDS logit tile
     int L;                    // candidates kept per (workgroup, hidden row) = min(m, rpb)
     int nblocks;
-    float *pmax;              // [nblocks, n]
-    float *psum;              // [nblocks, n]
-    unsigned long long *pkeys;  // [n, nblocks, L]
-    unsigned *ticket;         // arrival counter, zero between calls
+    unsigned long long *pms;    // [n, nblocks]  max | sumexp << 32
+    unsigned long long *pkeys;  // [n, nblocks, L] candidate keys, sorted descending per list
+    unsigned *tickets;        // arrival counters (kTicketBytes), zero between calls
     int *out_ids;             // [n, m]
     float *out_logp;          // [n, m]
     float *out_lse;           // [n] or null

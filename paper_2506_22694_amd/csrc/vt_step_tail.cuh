@@ -1,0 +1,271 @@
+// Tail of the draft step, shared by its kernels: per-workgroup epilogue
+// (log-sum-exp partial + best candidates of a tile of logits), publication,
+// election of the last workgroup, and the final cross-workgroup merge
+// (lse, top-m, remap to target ids).
+#pragma once
+#include "vt_device.h"
+#include "vt_step.h"
+
+namespace vt {
+
+// ------------------------------------------------------------------ top-L of a wave's candidates
+// Every lane holds Q candidates: ord[q] = orderable logit (0 = none), id[q] =
+// target id.  L rounds; round r finds the best remaining candidate of the whole
+// wave under (logit desc, id asc) and parks it in lane r.  Returns lane r's key.
+template <int Q>
+__device__ __forceinline__ unsigned long long wave_select_top(unsigned (&ord)[Q], int (&id)[Q], int L, int lane) {
+    unsigned res_ord = 0u;
+    unsigned res_id = 0u;
+    for (int r = 0; r < L; ++r) {
+        unsigned bo = ord[0];
+#pragma unroll
+        for (int q = 1; q < Q; ++q) bo = ord[q] > bo ? ord[q] : bo;
+        const unsigned wmax = wave_max_u32(bo);
+        unsigned myid = 0xFFFFFFFFu;
+        int cnt = 0;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            if (ord[q] == wmax) {
+                myid = (unsigned)id[q] < myid ? (unsigned)id[q] : myid;
+                ++cnt;
+            }
+        }
+        // exact ties are rare: one holder -> read its id; otherwise reduce for the lowest id
+        const unsigned long long holders = __ballot(cnt > 0);
+        const unsigned long long multi = __ballot(cnt > 1);
+        unsigned wid;
+        if (__popcll(holders) == 1 && multi == 0ull) {
+            wid = __builtin_amdgcn_readlane(myid, __ffsll((long long)holders) - 1);
+        } else {
+            wid = wave_min_u32(myid);
+        }
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            if (ord[q] == wmax && (unsigned)id[q] == wid) ord[q] = 0u;
+        }
+        if (lane == r) {
+            res_ord = wmax;
+            res_id = wid;
+        }
+    }
+    return res_ord == 0u ? kNoKey : (((unsigned long long)res_ord << 32) | (unsigned)(~res_id));
+}
+
+// ------------------------------------------------------------------ workgroup epilogue of one hidden row
+// zrow: the row's logit tile in LDS (S partial sums per logit, `sstride` floats
+// apart).  Publishes (max, sum-exp) and the L best keys of this workgroup.
+// QMAX*64 >= rows_b.  idq: target ids of tile rows lane + 64*q.
+template <int QMAX>
+__device__ __forceinline__ void block_epilogue_core(const float *zrow, int S, int sstride, int rows_b, int L,
+                                                    const int (&idq)[QMAX], float *__restrict__ logp_full_row,
+                                                    unsigned long long *__restrict__ pms_slot,
+                                                    unsigned long long *__restrict__ pkeys_slot, int lane) {
+    unsigned ord[QMAX];
+    int id[QMAX];
+    float zq[QMAX];
+    float lmax = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < QMAX; ++q) {
+        const int t = lane + q * kWave;
+        ord[q] = 0u;
+        id[q] = idq[q];
+        zq[q] = -INFINITY;
+        if (t < rows_b) {
+            float z = 0.f;
+            for (int s = 0; s < S; ++s) z += zrow[(size_t)s * sstride + t];
+            if (logp_full_row) logp_full_row[t] = z;
+            zq[q] = z;
+            ord[q] = orderable_f32(z);
+            lmax = fmaxf(lmax, z);
+        }
+    }
+    const float M = wave_max(lmax);
+    float ls = 0.f;
+#pragma unroll
+    for (int q = 0; q < QMAX; ++q) ls += __expf(zq[q] - M);   // exp(-inf) = 0 for absent rows
+    const float Ssum = wave_sum(ls);
+    const unsigned long long key = wave_select_top<QMAX>(ord, id, L, lane);
+    if (lane < L) publish_u64(pkeys_slot + lane, key);
+    if (lane == 0)
+        publish_u64(pms_slot, ((unsigned long long)__float_as_uint(Ssum) << 32) | __float_as_uint(M));
+}
+
+// small tiles (<= 128 rows): ids were prefetched by the caller
+__device__ __noinline__ void block_epilogue_small(const float *zrow, int S, int sstride, int rows_b, int L, int id0,
+                                                  int id1, float *__restrict__ logp_full_row,
+                                                  unsigned long long *__restrict__ pms_slot,
+                                                  unsigned long long *__restrict__ pkeys_slot, int lane) {
+    const int idq[2] = {id0, id1};
+    block_epilogue_core<2>(zrow, S, sstride, rows_b, L, idq, logp_full_row, pms_slot, pkeys_slot, lane);
+}
+
+// large tiles (<= 1024 rows): ids are read here
+__device__ __noinline__ void block_epilogue_large(const float *zrow, int S, int sstride, int rows_b, int L,
+                                                  const int *__restrict__ map_tile,
+                                                  float *__restrict__ logp_full_row,
+                                                  unsigned long long *__restrict__ pms_slot,
+                                                  unsigned long long *__restrict__ pkeys_slot, int lane) {
+    constexpr int QMAX = kStepMaxRowsPerBlock / kWave;
+    int idq[QMAX];
+#pragma unroll
+    for (int q = 0; q < QMAX; ++q) idq[q] = map_tile[min(lane + q * kWave, rows_b - 1)];
+    block_epilogue_core<QMAX>(zrow, S, sstride, rows_b, L, idq, logp_full_row, pms_slot, pkeys_slot, lane);
+}
+
+// ------------------------------------------------------------------ arrival
+// Two-level arrival counters (groups of 16 workgroups, then one counter for the
+// groups): same-address atomics are serialised at the memory side, so a single
+// counter would put ~256 of them on the critical path.  Counters return to
+// zero, so consecutive calls need no re-initialisation.
+// Returns true in exactly one workgroup: the last to arrive.
+__device__ __forceinline__ bool arrive_and_elect(unsigned *tickets, int nblocks) {
+    __shared__ int s_last;
+    wait_stores_done();     // this wave's publications are acknowledged
+    __syncthreads();        // ... and so are those of every other wave of the workgroup
+    if (threadIdx.x == 0) {
+        const int g = (int)blockIdx.x >> 4;
+        const int ngroups = (nblocks + 15) >> 4;
+        const int gsize = min(16, nblocks - (g << 4));
+        unsigned *gt = tickets + 16 * (1 + g);      // one 64-byte line per counter
+        int last = 0;
+        const unsigned v = __hip_atomic_fetch_add(gt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (v == (unsigned)(gsize - 1)) {
+            __hip_atomic_store(gt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned u = __hip_atomic_fetch_add(tickets, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (u == (unsigned)(ngroups - 1)) {
+                __hip_atomic_store(tickets, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                last = 1;
+            }
+        }
+        s_last = last;
+    }
+    __syncthreads();
+    return s_last != 0;
+}
+
+// ------------------------------------------------------------------ final merge of one hidden row (one wave)
+// pms_row: [B] (max | sumexp << 32); pkeys_row: [B][L] keys, each list sorted
+// descending.  stage: wave-private LDS for B * L keys.
+__device__ __forceinline__ void finalize_row(const unsigned long long *__restrict__ pms_row,
+                                             const unsigned long long *__restrict__ pkeys_row, int B, int L, int m,
+                                             unsigned long long *stage, int *__restrict__ out_ids_row,
+                                             float *__restrict__ out_logp_row, float *__restrict__ out_lse_i,
+                                             float *__restrict__ lse_buf_i, int lane) {
+    constexpr int BQ = kStepMaxBlocks / kWave;   // lists per lane
+    // everything this row needs is requested before the first wait
+    unsigned long long ms[BQ];
+#pragma unroll
+    for (int q = 0; q < BQ; ++q) {
+        const int b = lane + kWave * q;
+        ms[q] = acquire_u64(pms_row + min(b, B - 1));
+    }
+    const int total = B * L;
+    constexpr int U = 32;                        // 64-lane loads in flight per batch (16 KiB)
+    for (int base = 0; base < total; base += U * kWave) {
+        unsigned long long kreg[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = base + u * kWave + lane;
+            kreg[u] = acquire_u64(pkeys_row + min(e, total - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = base + u * kWave + lane;
+            if (e < total) stage[e] = kreg[u];
+        }
+    }
+    // log-sum-exp over the workgroups
+    float lm = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < BQ; ++q) {
+        if (lane + kWave * q < B) lm = fmaxf(lm, __uint_as_float((unsigned)ms[q]));
+    }
+    const float M = wave_max(lm);
+    float ls = 0.f;
+#pragma unroll
+    for (int q = 0; q < BQ; ++q) {
+        if (lane + kWave * q < B)
+            ls += __uint_as_float((unsigned)(ms[q] >> 32)) * __expf(__uint_as_float((unsigned)ms[q]) - M);
+    }
+    const float lse = M + __logf(wave_sum(ls));
+
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // m rounds over the heads of the sorted lists
+    unsigned ord[BQ];
+    int id[BQ];
+    int pos[BQ];
+#pragma unroll
+    for (int q = 0; q < BQ; ++q) {
+        const int b = lane + kWave * q;
+        const unsigned long long key = b < B ? stage[(size_t)b * L] : kNoKey;
+        ord[q] = (unsigned)(key >> 32);
+        id[q] = key_id(key);
+        pos[q] = 0;
+    }
+    unsigned res_ord = 0u;
+    unsigned res_id = 0u;
+    for (int r = 0; r < m; ++r) {
+        unsigned bo = ord[0];
+#pragma unroll
+        for (int q = 1; q < BQ; ++q) bo = ord[q] > bo ? ord[q] : bo;
+        const unsigned wmax = wave_max_u32(bo);
+        unsigned myid = 0xFFFFFFFFu;
+        int cnt = 0;
+#pragma unroll
+        for (int q = 0; q < BQ; ++q) {
+            if (ord[q] == wmax) {
+                myid = (unsigned)id[q] < myid ? (unsigned)id[q] : myid;
+                ++cnt;
+            }
+        }
+        const unsigned long long holders = __ballot(cnt > 0);
+        const unsigned long long multi = __ballot(cnt > 1);
+        unsigned wid;
+        if (__popcll(holders) == 1 && multi == 0ull) {
+            wid = __builtin_amdgcn_readlane(myid, __ffsll((long long)holders) - 1);
+        } else {
+            wid = wave_min_u32(myid);
+        }
+#pragma unroll
+        for (int q = 0; q < BQ; ++q) {
+            if (ord[q] == wmax && (unsigned)id[q] == wid && wmax != 0u) {
+                const int b = lane + kWave * q;
+                pos[q] += 1;
+                const unsigned long long key = pos[q] < L ? stage[(size_t)b * L + pos[q]] : kNoKey;
+                ord[q] = (unsigned)(key >> 32);
+                id[q] = key_id(key);
+            }
+        }
+        if (lane == r) {
+            res_ord = wmax;
+            res_id = wid;
+        }
+    }
+    if (lane < m) {
+        out_ids_row[lane] = (int)res_id;
+        out_logp_row[lane] = from_orderable_f32(res_ord) - lse;
+    }
+    if (lane == 0) {
+        *lse_buf_i = lse;
+        if (out_lse_i) *out_lse_i = lse;
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Last workgroup: waves split the hidden rows; `fin_conc` waves work at a time
+// (LDS staging budget).
+__device__ __noinline__ void finalize_rows(const unsigned long long *__restrict__ pms,
+                                           const unsigned long long *__restrict__ pkeys, int B, int L, int n, int m,
+                                           int fin_conc, int *__restrict__ out_ids, float *__restrict__ out_logp,
+                                           float *__restrict__ out_lse, float *__restrict__ lse_buf,
+                                           unsigned char *smem, int w, int lane) {
+    if (w >= fin_conc) return;
+    unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * B * L;
+    for (int i = w; i < n; i += fin_conc)
+        finalize_row(pms + (size_t)i * B, pkeys + (size_t)i * B * L, B, L, m, stage, out_ids + (size_t)i * m,
+                     out_logp + (size_t)i * m, out_lse ? out_lse + i : nullptr, lse_buf + i, lane);
+}
+
+}  // namespace vt

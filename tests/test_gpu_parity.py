@@ -301,8 +301,9 @@ def test_step_workspace_reuse_poison_and_determinism():
     first = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
     torch.cuda.synchronize()
     a_ids, a_lp = first[0].clone(), first[1].clone()
-    # poison everything behind the arrival counters; the next call must not read stale partials
-    ws.buf[256:] = 0xFF
+    # poison everything behind the arrival counters (the first 2048 bytes, kept at zero by the
+    # library); the next call must not read stale partials
+    ws.buf[2048:] = 0xFF
     for _ in range(3):
         oi, ol = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
         torch.cuda.synchronize()
