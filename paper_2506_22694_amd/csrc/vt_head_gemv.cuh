@@ -8,7 +8,7 @@
 //   * it owns `rpb` consecutive rows of W_trim;
 //   * a wave streams whole rows (or one of S column segments of them): each
 //     load instruction fetches 64 lanes x 16 B = 1 KiB contiguous, non-temporal,
-//     with several rows in flight per wave;
+//     with several rows in flight per wave (a hand-written load pipeline);
 //   * h lives in registers (packed bf16, or fp32), a lane owning the same
 //     columns of every row, so the stream is consumed by dot2 / fma only;
 //   * after a batch of 4 or 8 rows a "transposed" wave reduction (permlane swaps + DPP) leaves
@@ -48,6 +48,54 @@ __device__ __forceinline__ float dot_chunk(const u32x4 &w, const u32x4 &x, float
         acc = fmaf(__uint_as_float(w.w), __uint_as_float(x.w), acc);
     }
     return acc;
+}
+
+// ------------------------------------------------------------------ explicit load pipeline
+// The row stream is software-pipelined by hand: the loads and their waits are
+// inline assembly so that the compiler neither hoists a batch's loads into one
+// cluster (which needs twice the registers) nor splits them.  vmcnt counts this
+// wave's outstanding vector-memory operations, which return in issue order.
+//
+// 16 bytes per lane from (uniform base + per-lane byte offset), streaming hint.
+__device__ __forceinline__ void stream_load16(u32x4 &dst, unsigned voff, const void *sbase) {
+    asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(voff), "s"(sbase) : "memory");
+}
+// Wait until at most N vector-memory operations are outstanding.  The row buffer
+// is passed through so that its consumers cannot be scheduled above the wait.
+template <int N, int CS>
+__device__ __forceinline__ void wait_row(u32x4 (&b)[CS]) {
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    if constexpr (CS == 1) {
+        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(b[0]) : "n"(N));
+    } else if constexpr (CS == 2) {
+        asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b[0]), "+v"(b[1]) : "n"(N));
+    } else if constexpr (CS == 3) {
+        asm volatile("s_waitcnt vmcnt(%3)" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]) : "n"(N));
+    } else if constexpr (CS == 4) {
+        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]) : "n"(N));
+    } else {
+        static_assert(CS == 6, "unsupported chunk count");
+        asm volatile("s_waitcnt vmcnt(%6)"
+                     : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5])
+                     : "n"(N));
+    }
+}
+// Orders what follows after the last update of a row's accumulators (an empty
+// statement the scheduler cannot move accumulators or later loads across).
+template <int NP>
+__device__ __forceinline__ void pin_after(float (&acc)[NP]) {
+    if constexpr (NP == 1) {
+        asm volatile("" : "+v"(acc[0]));
+    } else if constexpr (NP == 2) {
+        asm volatile("" : "+v"(acc[0]), "+v"(acc[1]));
+    } else if constexpr (NP == 4) {
+        asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));
+    } else {
+        static_assert(NP == 8, "unsupported row count");
+        asm volatile(""
+                     : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]), "+v"(acc[5]),
+                       "+v"(acc[6]), "+v"(acc[7]));
+    }
 }
 
 // ------------------------------------------------------------------ transposed wave reduction
@@ -125,16 +173,19 @@ __device__ __forceinline__ float xreduce(float (&v)[V], int lane) {
 }
 
 // ------------------------------------------------------------------ the kernel
-// Rows per batch (R) and row buffers in flight per wave (NSLOT), chosen so that
-// h registers + accumulators + buffers stay below 256 VGPRs (two waves per SIMD).
+// Rows per reduction batch (R) and row buffers in flight per wave (NSLOT, a
+// power of two dividing R), chosen so that h registers + accumulators + row
+// buffers stay below 256 VGPRs (two waves per SIMD).
 template <int NP>
 struct BatchRows {
     static constexpr int value = NP >= 8 ? 4 : 8;
 };
 template <int NP, int CS>
 struct SlotsFor {
-    static constexpr int want = CS >= 4 ? 2 : (CS >= 2 ? 4 : 8);
-    static constexpr int value = want < BatchRows<NP>::value ? want : BatchRows<NP>::value;
+    static constexpr int R = BatchRows<NP>::value;
+    static constexpr int room = (216 - 4 * CS * NP - R * NP) / (4 * CS);
+    static constexpr int cap = room < R ? room : R;
+    static constexpr int value = cap >= 8 ? 8 : (cap >= 4 ? 4 : 2);
 };
 
 template <bool BF16, int NP, int CS>
@@ -150,9 +201,9 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
     constexpr int V = R * NP;
 
     const int lane = lane_id();
-    const int w = (int)(threadIdx.x >> 6);
-    const int S = a.S, G = NW / S;
-    const int s = w % S, g = w / S;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave index, uniform
+    const int S = a.S;
+    const int s = w % S;   // column segment of this wave; waves with equal s share its rows
     const int row0 = blockIdx.x * a.rpb;
     const int rows_b = min(a.rpb, a.k - row0);
     const size_t rs = (size_t)a.d * ES;   // row stride in bytes
@@ -162,13 +213,36 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
     // so the loads need no predicate.
     int coff[CS];
     bool cval[CS];
-    u32x4 hreg[CS][NP];
+    unsigned voff[CS];
 #pragma unroll
     for (int c = 0; c < CS; ++c) {
         const int col = ((s * CS + c) * kWave + lane) * EPC;
         cval[c] = col < a.d;
         coff[c] = cval[c] ? col * ES : 0;
+        voff[c] = (unsigned)coff[c];
     }
+
+    // A wave keeps NSLOT rows in flight.  Past the end of the tile it streams h
+    // instead (resident in L2, always in bounds): no branch around any load, so
+    // the load counter stays exact.
+    const char *Wb = static_cast<const char *>(a.W) + (size_t)row0 * rs;
+    auto load_row = [&](int row, u32x4(&dst)[CS]) {
+        const char *p = row < rows_b ? Wb + (size_t)row * rs : static_cast<const char *>(a.h);
+#pragma unroll
+        for (int c = 0; c < CS; ++c) stream_load16(dst[c], voff[c], p);
+    };
+    u32x4 wb[NSLOT][CS];
+    int rowq[R];   // rows of the batch being reduced (uniform values)
+#pragma unroll
+    for (int x = 0; x < NSLOT; ++x) {
+        rowq[x] = (w / S) * NSLOT + x;
+        load_row(rowq[x], wb[x]);      // the longest latency of the kernel starts first
+    }
+#pragma unroll
+    for (int x = NSLOT; x < R; ++x) rowq[x] = rows_b;   // filled as the batch proceeds
+
+    // hidden rows -> registers (zeros where the column or the row does not exist)
+    u32x4 hreg[CS][NP];
 #pragma unroll
     for (int c = 0; c < CS; ++c) {
 #pragma unroll
@@ -177,6 +251,9 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
             hreg[c][i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.h) + (size_t)ii * rs + coff[c]);
         }
     }
+    // target ids of the tile rows this lane will rank in the epilogue (small tiles)
+    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
+    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
 #pragma unroll
     for (int c = 0; c < CS; ++c) {
 #pragma unroll
@@ -189,67 +266,67 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
         }
     }
 
-    // target ids of the tile rows this lane will rank in the epilogue (small tiles)
-    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
-    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
-
-    const char *Wb = static_cast<const char *>(a.W) + (size_t)row0 * rs;
-    const int nbt = (rows_b + R - 1) >> RSH;              // R-row batches in this workgroup
-    const int nbw = nbt > g ? (nbt - g + G - 1) / G : 0;  // batches of this wave
-
-    u32x4 wb[NSLOT][CS];
-    auto load_row = [&](int j, int r, u32x4(&dst)[CS]) {
-        int lr = ((g + G * j) << RSH) + r;
-        lr = min(lr, rows_b - 1);
-        const char *p = Wb + (size_t)lr * rs;
-#pragma unroll
-        for (int c = 0; c < CS; ++c)
-            dst[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + coff[c]));
+    // Rows are dealt to the waves of a segment team round-robin.  (Handing them out
+    // dynamically from an LDS counter balances the two waves of a SIMD, the older
+    // of which runs ahead, but measured slower overall.)
+    const int G = NW / S;
+    int next_row = G * NSLOT + w / S;
+    auto take_row = [&]() -> int {
+        const int v = next_row;
+        next_row += G;
+        return v;
     };
-    if (nbw > 0) {
-#pragma unroll
-        for (int x = 0; x < NSLOT; ++x) load_row(0, x, wb[x]);
-    }
 
-    // One R-row batch.  Refills that stay inside the batch are unconditional;
-    // those that reach into the next batch exist only in the non-final variant,
-    // so the loop body has no branch and the load counter stays exact.
-    auto batch = [&](int j, auto last_tag) {
-        constexpr bool LAST = decltype(last_tag)::value;
-        float acc[V];
+    while (rowq[0] < rows_b) {
+        float acc[R][NP];
 #pragma unroll
-        for (int q = 0; q < V; ++q) acc[q] = 0.f;
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int i = 0; i < NP; ++i) acc[r][i] = 0.f;
+        }
+        int nextq[NSLOT];   // rows that will occupy the slots after this batch's refills
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int slot = r % NSLOT;
+            const int fresh = take_row();
+            // the slot's loads are the oldest outstanding: everything but the younger slots must be back
+            wait_row<CS *(NSLOT - 1), CS>(wb[slot]);
 #pragma unroll
             for (int c = 0; c < CS; ++c) {
 #pragma unroll
-                for (int i = 0; i < NP; ++i)
-                    acc[r * NP + i] = dot_chunk<BF16>(wb[slot][c], hreg[c][i], acc[r * NP + i]);
+                for (int i = 0; i < NP; ++i) acc[r][i] = dot_chunk<BF16>(wb[slot][c], hreg[c][i], acc[r][i]);
             }
-            const int xr = r + NSLOT;
-            if (xr < R) {
-                load_row(j, xr, wb[slot]);
-            } else if constexpr (!LAST) {
-                load_row(j + 1, xr - R, wb[slot]);
-            }
-            // keep the software pipeline as written: consume a row, refill its slot
-            __builtin_amdgcn_sched_barrier(0);
+            pin_after<NP>(acc[r]);
+            load_row(fresh, wb[slot]);
+            if (r + NSLOT < R) rowq[r + NSLOT] = fresh;   // later row of this batch
+            else nextq[(r + NSLOT) - R] = fresh;          // row of the next batch
         }
-        const float tot = xreduce<V>(acc, lane);
+        float flat[V];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int i = 0; i < NP; ++i) flat[r * NP + i] = acc[r][i];
+        }
+        const float tot = xreduce<V>(flat, lane);
         // lane l holds value number (l >> (6 - log2 V)) = r * NP + i
         constexpr int SH = V == 64 ? 0 : (V == 32 ? 1 : (V == 16 ? 2 : 3));
         static_assert(V >= 8, "at least 8 values per batch");
-        if ((lane & ((1 << SH) - 1)) == 0) {
+        {
             const int idx = lane >> SH;
             const int r = idx / NP, i = idx % NP;
-            const int t = ((g + G * j) << RSH) + r;
-            zt[(size_t)(s * NP + i) * a.tpitch + t] = tot;
+            int t = rowq[0];
+#pragma unroll
+            for (int q = 1; q < R; ++q) t = r == q ? rowq[q] : t;
+            if ((lane & ((1 << SH) - 1)) == 0 && t < rows_b) zt[(size_t)(s * NP + i) * a.tpitch + t] = tot;
         }
-    };
-    for (int j = 0; j + 1 < nbw; ++j) batch(j, std::false_type{});
-    if (nbw > 0) batch(nbw - 1, std::true_type{});
+#pragma unroll
+        for (int x = 0; x < NSLOT; ++x) rowq[x] = nextq[x];
+#pragma unroll
+        for (int x = NSLOT; x < R; ++x) rowq[x] = rows_b;
+    }
+    // loads past the end of the tile are still in flight: let them land before their registers are reused
+#pragma unroll
+    for (int x = 0; x < NSLOT; ++x) wait_row<0, CS>(wb[x]);
     __syncthreads();
 
     {
