@@ -54,6 +54,8 @@ def parse():
     p.add_argument("--no-calibration", action="store_true",
                    help="draw W_trim directly instead of running count/select/gather on a full head")
     p.add_argument("--sweep", action="store_true", help="also time the k / n sweep (table on stderr)")
+    p.add_argument("--configs", action="store_true",
+                   help="also time the other workloads' draft steps (1B chain + full-vocab control, 8B tree, stress)")
     p.add_argument("--pmc-copy", action="store_true",
                    help="only run plain device copies of the W_trim size (counter calibration under rocprofv3)")
     return p.parse_args()
@@ -192,6 +194,31 @@ def main():
                     log("sweep", row)
             del cps, Wk
 
+    others = None
+    if args.configs:
+        others = []
+        cases = [("llama1b chain", 2048, 32768, 1, 1), ("llama1b full-vocab control", 2048, 128256, 1, 1),
+                 ("llama3b full-vocab control", 3072, 128256, 8, 8),
+                 ("llama8b tree", 4096, 32768, 64, 8), ("stress", 8192, 32768, 256, 16)]
+        for name, dd, kk, nn, mm in cases:
+            Wk_np, mapk_np = synth.trimmed_head_direct(kk, dd, 77, "bf16")
+            Wk = to_dev_bf16(Wk_np)
+            mapk = torch.from_numpy(mapk_np).to(dev)
+            ncop = max(2, min(12, int(1.3e9 // (kk * dd * 2))))
+            cps = [Wk] + [Wk.clone() for _ in range(ncop - 1)]
+            hs = [to_dev_bf16(synth.hidden_rows(nn, dd, 77 + j, "bf16")) for j in range(4)]
+            wsk = vt.StepWorkspace(nn, kk, dd, mm, dev)
+            f = lambda r: vt.draft_head_step(hs[r % 4], cps[r % ncop], mapk, mm, ws=wsk)
+            for r in range(10):
+                f(r)
+            us = time_region(f, 100)
+            row = {"workload": name, "d": dd, "k": kk, "n": nn, "m": mm, "us": round(us, 2),
+                   "gbps": round(kk * dd * 2 / us / 1e3, 1), "frac_hbm": round(kk * dd * 2 / us / 1e3 / HBM_PEAK_GBPS, 4),
+                   "tflops": round(2.0 * nn * kk * dd / us / 1e6, 1)}
+            others.append(row)
+            log("config", row)
+            del cps, Wk
+
     # ------------------------------------------------------------------ CPU baseline (the oracle, untuned)
     cpu = None
     if not args.no_cpu_baseline:
@@ -241,6 +268,8 @@ def main():
     }
     if sweep is not None:
         out["sweep"] = sweep
+    if others is not None:
+        out["other_configs"] = others
     print(json.dumps(out), flush=True)
 
 

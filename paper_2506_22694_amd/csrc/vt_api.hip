@@ -27,7 +27,10 @@ inline int launch_status() { return device_status(hipGetLastError()); }
 struct StepPlan {
     bool ok = false;
     bool gemv = false;     // small-n VALU path
+    bool mfma = false;     // matrix-core path
     int NP = 0, CS = 0, S = 0;
+    int NT = 0, nlists = 0, KC = 0, hpitch = 0, fin_stage_keys = 0;
+    size_t fin_lds = 0;
     int rpb = 0, nblocks = 0, tpitch = 0, L = 0, fin_conc = 0;
     size_t lds = 0;
     // workspace layout (byte offsets)
@@ -46,9 +49,10 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
     p.tpitch = rpb + 1;
     p.L = m < rpb ? m : rpb;
     const size_t stage = (size_t)p.nblocks * p.L * sizeof(unsigned long long);
-    int conc = (int)(vt::kFinalizeLdsBytes / stage);
-    if (conc < 1) return p;
-    p.fin_conc = conc < vt::kStepWaves ? conc : vt::kStepWaves;
+    {
+        const int conc = (int)(vt::kFinalizeLdsBytes / stage);
+        p.fin_conc = conc < vt::kStepWaves ? conc : vt::kStepWaves;
+    }
 
     if (n <= vt::kGemvMaxN) {
         const int NP = n <= 1 ? 1 : (n <= 2 ? 2 : (n <= 4 ? 4 : 8));
@@ -64,7 +68,7 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
                 const int CS = cs_set[q];
                 if (CS >= need && CS * NP <= 24) {
                     const size_t tile = (size_t)S * NP * p.tpitch * sizeof(float);
-                    if (tile <= 96 * 1024) {
+                    if (tile <= 96 * 1024 && p.fin_conc >= 1) {
                         p.gemv = true;
                         p.NP = NP;
                         p.CS = CS;
@@ -76,9 +80,37 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
             }
         }
     }
-    if (!p.gemv) return p;   // larger n / d: handled by the matrix-core path
-    const size_t fin = (size_t)p.fin_conc * stage;
-    if (fin > p.lds) p.lds = fin;
+    if (!p.gemv) {
+        // larger n or d: the matrix-core path (bf16, d a multiple of 128, n <= 256)
+        if (dtype != VT_BF16 || (d % 128) != 0 || n > 256) return p;
+        int NT = 1;
+        while (16 * NT < n) NT *= 2;
+        const size_t stage = vt::mfma_stage_bytes();
+        const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage) / (16 * (size_t)NT);
+        if (hmax < 272) return p;
+        int KC = (int)(((hmax - 16) / 2) / 128) * 128;
+        if (KC > d) KC = d;
+        p.mfma = true;
+        p.NT = NT;
+        p.KC = KC;
+        p.hpitch = KC * 2 + 16;
+        p.nlists = (k + vt::kMfmaTileRows - 1) / vt::kMfmaTileRows;
+        p.L = m < vt::kMfmaTileRows ? m : vt::kMfmaTileRows;
+        p.nblocks = p.nlists;
+        p.lds = stage + (size_t)16 * NT * p.hpitch;
+        const size_t tile = (size_t)n * (vt::kMfmaTileRows + 1) * sizeof(float);
+        if (tile > p.lds) p.lds = tile;
+        if (p.lds > (size_t)vt::kMaxDynamicLds) return p;
+        const int group = p.nlists < vt::kStepMaxBlocks ? p.nlists : vt::kStepMaxBlocks;
+        p.fin_stage_keys = (group + 1) * p.L;
+        int fc = (int)(vt::kFinalizeLdsBytes / ((size_t)p.fin_stage_keys * sizeof(unsigned long long)));
+        if (fc < 1) return p;
+        p.fin_conc = fc < vt::kStepWaves ? fc : vt::kStepWaves;
+        p.fin_lds = (size_t)p.fin_conc * p.fin_stage_keys * sizeof(unsigned long long);
+    } else {
+        const size_t fin = (size_t)p.fin_conc * stage;
+        if (fin > p.lds) p.lds = fin;
+    }
 
     size_t off = kTicketBytes;
     p.off_lse = off;
@@ -196,42 +228,79 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
     if (ws == nullptr || !aligned(ws, 256) || ws_bytes < p.bytes) return VT_ERR_WORKSPACE;
 
     char *wsb = static_cast<char *>(ws);
-    vt::StepArgs a;
-    a.h = h;
-    a.W = W_trim;
-    a.map = map;
-    a.n = n;
-    a.k = k;
-    a.d = d;
-    a.m = m;
-    a.S = p.S;
-    a.rpb = p.rpb;
-    a.tpitch = p.tpitch;
-    a.L = p.L;
-    a.nblocks = p.nblocks;
-    a.pms = reinterpret_cast<unsigned long long *>(wsb + p.off_pms);
-    a.pkeys = reinterpret_cast<unsigned long long *>(wsb + p.off_pkeys);
-    a.tickets = reinterpret_cast<unsigned *>(wsb);
-    a.out_ids = out_ids;
-    a.out_logp = out_logp;
-    a.out_lse = out_lse;
-    a.out_logp_full = out_logp_full;
-    a.fin_conc = p.fin_conc;
-
     (void)hipGetLastError();
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool bf16 = w_type == VT_BF16;
-    hipError_t e = hipErrorInvalidValue;
-    switch (p.NP) {
-        case 1: e = vt::launch_head_gemv_np1(bf16, p.CS, a, p.lds, st); break;
-        case 2: e = vt::launch_head_gemv_np2(bf16, p.CS, a, p.lds, st); break;
-        case 4: e = vt::launch_head_gemv_np4(bf16, p.CS, a, p.lds, st); break;
-        case 8: e = vt::launch_head_gemv_np8(bf16, p.CS, a, p.lds, st); break;
-        default: break;
+    unsigned long long *pms = reinterpret_cast<unsigned long long *>(wsb + p.off_pms);
+    unsigned long long *pkeys = reinterpret_cast<unsigned long long *>(wsb + p.off_pkeys);
+    float *lse_buf = reinterpret_cast<float *>(wsb + p.off_lse);
+    if (p.gemv) {
+        vt::StepArgs a;
+        a.h = h;
+        a.W = W_trim;
+        a.map = map;
+        a.n = n;
+        a.k = k;
+        a.d = d;
+        a.m = m;
+        a.S = p.S;
+        a.rpb = p.rpb;
+        a.tpitch = p.tpitch;
+        a.L = p.L;
+        a.nblocks = p.nblocks;
+        a.pms = pms;
+        a.pkeys = pkeys;
+        a.tickets = reinterpret_cast<unsigned *>(wsb);
+        a.out_ids = out_ids;
+        a.out_logp = out_logp;
+        a.out_lse = out_lse;
+        a.out_logp_full = out_logp_full;
+        a.fin_conc = p.fin_conc;
+        const bool bf16 = w_type == VT_BF16;
+        hipError_t e = hipErrorInvalidValue;
+        switch (p.NP) {
+            case 1: e = vt::launch_head_gemv_np1(bf16, p.CS, a, p.lds, st); break;
+            case 2: e = vt::launch_head_gemv_np2(bf16, p.CS, a, p.lds, st); break;
+            case 4: e = vt::launch_head_gemv_np4(bf16, p.CS, a, p.lds, st); break;
+            case 8: e = vt::launch_head_gemv_np8(bf16, p.CS, a, p.lds, st); break;
+            default: break;
+        }
+        if (e != hipSuccess) return device_status(e);
+    } else {
+        vt::MfmaArgs a;
+        a.h = h;
+        a.W = W_trim;
+        a.map = map;
+        a.n = n;
+        a.k = k;
+        a.d = d;
+        a.m = m;
+        a.L = p.L;
+        a.nlists = p.nlists;
+        a.KC = p.KC;
+        a.hpitch = p.hpitch;
+        a.pms = pms;
+        a.pkeys = pkeys;
+        a.out_logp_full = out_logp_full;
+        hipError_t e = vt::launch_head_mfma(p.NT, a, p.lds, st);
+        if (e != hipSuccess) return device_status(e);
+        vt::FinalizeArgs f;
+        f.pms = pms;
+        f.pkeys = pkeys;
+        f.nlists = p.nlists;
+        f.L = p.L;
+        f.n = n;
+        f.m = m;
+        f.conc = p.fin_conc;
+        f.stage_keys = p.fin_stage_keys;
+        f.out_ids = out_ids;
+        f.out_logp = out_logp;
+        f.out_lse = out_lse;
+        f.lse_buf = lse_buf;
+        e = vt::launch_step_finalize(f, p.fin_lds, st);
+        if (e != hipSuccess) return device_status(e);
     }
-    if (e != hipSuccess) return device_status(e);
     if (out_logp_full != nullptr)
-        vt::launch_sub_lse(out_logp_full, reinterpret_cast<const float *>(wsb + p.off_lse), n, k, st);
+        vt::launch_sub_lse(out_logp_full, lse_buf, n, k, st);
     return launch_status();
 }
 

@@ -1,0 +1,232 @@
+// Draft step for many hidden rows (tree drafting, n > 8): the projection is a
+// real GEMM  z[n, k] = h[n, d] W_trim[k, d]^T  and runs on the matrix cores
+// (v_mfma_f32_16x16x32_bf16), still bound by the single pass over W_trim.
+//
+// One workgroup (8 waves) owns a tile of 128 rows of W_trim, 16 per wave:
+//   * W is read from HBM exactly once, with row-contiguous 256-byte segments per
+//     load instruction (4 rows x 256 B), several units in flight per wave; a unit
+//     (16 rows x 128 columns) passes through a small wave-private LDS buffer that
+//     re-lays it out as MFMA A-operands (row pitch 272 B: conflict-free reads);
+//   * h is the B-operand: a chunk of KC columns of all hidden rows sits in LDS,
+//     shared by the 8 waves, and is replaced chunk by chunk (h itself lives in L2);
+//   * accumulators (16 W-rows x n hidden rows per wave) stay in registers over
+//     the whole contraction; the logits are never written to memory;
+//   * the tile's logits go to an LDS tile (aliasing the staging buffers) and the
+//     same workgroup epilogue as the small-n kernel produces (max, sum-exp) and
+//     the tile's best candidates per hidden row;
+//   * a second small kernel merges the tiles: one wave per hidden row.
+#include "vt_device.h"
+#include "vt_step.h"
+#include "vt_step_tail.cuh"
+
+namespace vt {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kUnitCols = 128;                       // columns per staged unit (256 B per row)
+constexpr int kStagePitch = 272;                     // bytes per staged row: 256 + 16 (bank spread)
+constexpr int kStageUnitBytes = 16 * kStagePitch;    // one unit of one wave
+constexpr int kStageBytes = kStepWaves * 2 * kStageUnitBytes;   // double-buffered, all waves
+constexpr int kPrefetchUnits = 3;                    // units of W in flight per wave (12 KiB)
+
+__device__ __forceinline__ void stream_load16(u32x4 &dst, unsigned voff, const void *sbase) {
+    asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(voff), "s"(sbase) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_unit(u32x4 (&b)[4]) {
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]) : "n"(N));
+}
+
+template <int NT>
+__global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const MfmaArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *stage = smem;                       // [waves][2][16][272]
+    unsigned char *hbuf = smem + kStageBytes;          // [16 * NT][hpitch]
+    float *zt = reinterpret_cast<float *>(smem);       // logit tile, aliases both after the contraction
+
+    const int lane = lane_id();
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int row0 = blockIdx.x * kMfmaTileRows;
+    const int rows_b = min(kMfmaTileRows, a.k - row0);
+    const size_t rs = (size_t)a.d * 2;
+    const int lrow = lane & 15, lgrp = lane >> 4;
+
+    // target ids of the tile rows this lane ranks in the epilogue
+    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
+    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
+
+    // per-lane byte offsets of the 4 load instructions of a unit: instruction j covers rows 4j..4j+3
+    // of this wave's 16 rows, 16 lanes x 16 B per row; rows past the end of W repeat the last row
+    unsigned voff[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = min(16 * w + 4 * j + lgrp, rows_b - 1);
+        voff[j] = (unsigned)((size_t)r * rs + (size_t)lrow * 16);
+    }
+    const char *Wt = static_cast<const char *>(a.W) + (size_t)row0 * rs;
+    const int nunits = a.d / kUnitCols;
+    auto load_unit = [&](int u, u32x4(&dst)[4]) {
+        const char *p = Wt + (size_t)min(u, nunits - 1) * (kUnitCols * 2);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) stream_load16(dst[j], voff[j], p);
+    };
+    u32x4 areg[kPrefetchUnits][4];
+#pragma unroll
+    for (int x = 0; x < kPrefetchUnits; ++x) load_unit(x, areg[x]);
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    unsigned char *my_stage = stage + (size_t)w * 2 * kStageUnitBytes;
+    // staging writes: instruction j, lane (row 4j + lgrp, 16-byte chunk lrow)
+    // operand reads : lane (row lrow, k-group lgrp) of k-step ks -> bytes ks*64 + lgrp*16
+    const int wr_off = lgrp * kStagePitch + lrow * 16;
+    const int rd_off = lrow * kStagePitch + lgrp * 16;
+    const int hrow_off = lrow * a.hpitch + lgrp * 16;
+
+    // Units are consumed in order; unit u sits in register slot u % kPrefetchUnits.  Every
+    // units_per_chunk units the next KC columns of all hidden rows replace the h chunk in LDS.
+    const int units_per_chunk = a.KC / kUnitCols;
+    for (int u = 0; u < nunits;) {
+#pragma unroll
+        for (int x = 0; x < kPrefetchUnits; ++x) {
+            if (u < nunits) {   // uniform
+                const int uc = u % units_per_chunk;
+                if (uc == 0) {
+                    // ---- stage the next KC columns of every hidden row (zero rows up to 16 * NT)
+                    __syncthreads();
+                    const int c0 = u * kUnitCols;
+                    const int kc = min(a.KC, a.d - c0);
+                    const int pieces_per_row = kc >> 3;              // 16-byte pieces
+                    const int npieces = 16 * NT * pieces_per_row;
+                    for (int e = threadIdx.x; e < npieces; e += kStepWaves * kWave) {
+                        const int r = e / pieces_per_row, pc = e - r * pieces_per_row;
+                        u32x4 v = {0u, 0u, 0u, 0u};
+                        if (r < a.n)
+                            v = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.h) + (size_t)r * rs +
+                                                                 (size_t)(c0 + pc * 8) * 2);
+                        *reinterpret_cast<u32x4 *>(hbuf + (size_t)r * a.hpitch + pc * 16) = v;
+                    }
+                    __syncthreads();
+                }
+                // unit u's four loads are the oldest outstanding
+                wait_unit<4 * (kPrefetchUnits - 1)>(areg[x]);
+                unsigned char *sb = my_stage + (u & 1) * kStageUnitBytes;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<u32x4 *>(sb + 4 * j * kStagePitch + wr_off) = areg[x][j];
+                load_unit(u + kPrefetchUnits, areg[x]);
+                const unsigned char *hb = hbuf + hrow_off + (size_t)uc * (kUnitCols * 2);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const u32x4 av = *reinterpret_cast<const u32x4 *>(sb + rd_off + ks * 64);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const u32x4 bv = *reinterpret_cast<const u32x4 *>(hb + (size_t)t * 16 * a.hpitch + ks * 64);
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
+                                                                         __builtin_bit_cast(bf16x8, bv), acc[t], 0,
+                                                                         0, 0);
+                    }
+                }
+                ++u;
+            }
+        }
+    }
+    // prefetches past the last unit are still in flight: let them land before their registers die
+#pragma unroll
+    for (int x = 0; x < kPrefetchUnits; ++x) wait_unit<0>(areg[x]);
+
+    // ---- logits of this tile -> LDS tile zt[i][t] (aliases staging and h)
+    __syncthreads();
+    const int tp = kMfmaTileRows + 1;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int i = 16 * t + lrow;       // hidden row of this lane
+        if (i < a.n) {
+            float *dst = zt + (size_t)i * tp + 16 * w + 4 * lgrp;
+            dst[0] = acc[t].x;
+            dst[1] = acc[t].y;
+            dst[2] = acc[t].z;
+            dst[3] = acc[t].w;
+        }
+    }
+    __syncthreads();
+
+    for (int i = w; i < a.n; i += kStepWaves) {
+        const float *zrow = zt + (size_t)i * tp;
+        float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
+        unsigned long long *pms_slot = a.pms + (size_t)i * a.nlists + blockIdx.x;
+        unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nlists + blockIdx.x) * a.L;
+        block_epilogue_small(zrow, 1, 0, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane);
+    }
+}
+
+// Merges the per-tile partials: one wave per hidden row.
+__global__ void __launch_bounds__(kStepWaves *kWave) step_finalize_kernel(const FinalizeArgs f) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = lane_id();
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (w >= f.conc) return;
+    const int i = blockIdx.x * f.conc + w;
+    if (i >= f.n) return;
+    unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * f.stage_keys;
+    finalize_row<true>(f.pms + (size_t)i * f.nlists, f.pkeys + (size_t)i * f.nlists * f.L, f.nlists, f.L, f.m, stage,
+                 f.out_ids + (size_t)i * f.m, f.out_logp + (size_t)i * f.m, f.out_lse ? f.out_lse + i : nullptr,
+                 f.lse_buf + i, lane);
+}
+
+template <int NT>
+hipError_t launch_mfma_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
+    auto kern = head_mfma_kernel<NT>;
+    static bool attr_set[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kMaxDynamicLds);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.nlists), dim3(kStepWaves * kWave), lds, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t mfma_stage_bytes() { return kStageBytes; }
+
+hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t st) {
+    switch (NT) {
+        case 1: return launch_mfma_inst<1>(a, lds, st);
+        case 2: return launch_mfma_inst<2>(a, lds, st);
+        case 4: return launch_mfma_inst<4>(a, lds, st);
+        case 8: return launch_mfma_inst<8>(a, lds, st);
+        case 16: return launch_mfma_inst<16>(a, lds, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t st) {
+    static bool attr_set[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_finalize_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+    }
+    const int grid = (f.n + f.conc - 1) / f.conc;
+    hipLaunchKernelGGL(step_finalize_kernel, dim3(grid), dim3(kStepWaves * kWave), lds, st, f);
+    return hipGetLastError();
+}
+
+}  // namespace vt

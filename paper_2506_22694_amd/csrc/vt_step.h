@@ -36,6 +36,39 @@ struct StepArgs {
     int fin_conc;             // waves that run the finalize stage concurrently (LDS budget)
 };
 
+// ---- matrix-core path (n > 8) ----
+constexpr int kMfmaTileRows = 128;     // rows of W_trim per workgroup (16 per wave)
+
+struct MfmaArgs {
+    const void *h;            // [n, d] bf16
+    const void *W;            // [k, d] bf16
+    const int *map;           // [k]
+    int n, k, d, m;
+    int L;                    // candidates kept per (tile, hidden row) = min(m, 128)
+    int nlists;               // number of tiles = workgroups = candidate lists per hidden row
+    int KC;                   // columns of h resident in LDS at a time (multiple of 128)
+    int hpitch;               // bytes per hidden row in LDS = KC * 2 + 16
+    unsigned long long *pms;    // [n, nlists]
+    unsigned long long *pkeys;  // [n, nlists, L]
+    float *out_logp_full;     // [n, k] or null
+};
+
+struct FinalizeArgs {
+    const unsigned long long *pms;
+    const unsigned long long *pkeys;
+    int nlists, L, n, m;
+    int conc;                 // hidden rows (waves) per workgroup
+    int stage_keys;           // LDS keys reserved per wave
+    int *out_ids;
+    float *out_logp;
+    float *out_lse;           // or null
+    float *lse_buf;
+};
+
+size_t mfma_stage_bytes();
+hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t st);
+hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t st);
+
 // Launchers, one translation unit per padded row count NP (1, 2, 4, 8).
 // hipErrorInvalidValue if (bf16, CS) is not instantiated.
 hipError_t launch_head_gemv_np1(bool bf16, int CS, const StepArgs &a, size_t lds, hipStream_t st);

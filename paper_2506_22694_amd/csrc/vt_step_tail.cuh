@@ -145,103 +145,129 @@ __device__ __forceinline__ bool arrive_and_elect(unsigned *tickets, int nblocks)
 
 // ------------------------------------------------------------------ final merge of one hidden row (one wave)
 // pms_row: [B] (max | sumexp << 32); pkeys_row: [B][L] keys, each list sorted
-// descending.  stage: wave-private LDS for B * L keys.
+// descending.  stage: wave-private LDS for (min(B, 256) + 1) * L keys.
+// Lists are merged 256 at a time (4 per lane); with CARRY the best m of one
+// group are carried into the next as one more list, so B is unbounded.
+template <bool CARRY>
 __device__ __forceinline__ void finalize_row(const unsigned long long *__restrict__ pms_row,
                                              const unsigned long long *__restrict__ pkeys_row, int B, int L, int m,
                                              unsigned long long *stage, int *__restrict__ out_ids_row,
                                              float *__restrict__ out_logp_row, float *__restrict__ out_lse_i,
                                              float *__restrict__ lse_buf_i, int lane) {
-    constexpr int BQ = kStepMaxBlocks / kWave;   // lists per lane
-    // everything this row needs is requested before the first wait
-    unsigned long long ms[BQ];
-#pragma unroll
-    for (int q = 0; q < BQ; ++q) {
-        const int b = lane + kWave * q;
-        ms[q] = acquire_u64(pms_row + min(b, B - 1));
-    }
-    const int total = B * L;
+    constexpr int GROUP = kStepMaxBlocks;        // lists merged per pass
+    constexpr int BQ = GROUP / kWave + (CARRY ? 1 : 0);   // lists per lane
     constexpr int U = 32;                        // 64-lane loads in flight per batch (16 KiB)
-    for (int base = 0; base < total; base += U * kWave) {
-        unsigned long long kreg[U];
+    // log-sum-exp over all lists: requested first, reduced while the keys are in flight
+    float lm = -INFINITY, ls = 0.f;
+    {
+        unsigned long long ms[GROUP / kWave];
+        for (int b0 = 0; b0 < B; b0 += GROUP) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int e = base + u * kWave + lane;
-            kreg[u] = acquire_u64(pkeys_row + min(e, total - 1));
+            for (int q = 0; q < GROUP / kWave; ++q) ms[q] = acquire_u64(pms_row + min(b0 + lane + kWave * q, B - 1));
+#pragma unroll
+            for (int q = 0; q < GROUP / kWave; ++q) {
+                if (b0 + lane + kWave * q < B) {
+                    const float Mb = __uint_as_float((unsigned)ms[q]);
+                    const float Sb = __uint_as_float((unsigned)(ms[q] >> 32));
+                    const float Mn = fmaxf(lm, Mb);
+                    ls = ls * __expf(lm - Mn) + Sb * __expf(Mb - Mn);   // exp(-inf) = 0 on the first term
+                    lm = Mn;
+                }
+            }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int e = base + u * kWave + lane;
-            if (e < total) stage[e] = kreg[u];
-        }
-    }
-    // log-sum-exp over the workgroups
-    float lm = -INFINITY;
-#pragma unroll
-    for (int q = 0; q < BQ; ++q) {
-        if (lane + kWave * q < B) lm = fmaxf(lm, __uint_as_float((unsigned)ms[q]));
     }
     const float M = wave_max(lm);
-    float ls = 0.f;
-#pragma unroll
-    for (int q = 0; q < BQ; ++q) {
-        if (lane + kWave * q < B)
-            ls += __uint_as_float((unsigned)(ms[q] >> 32)) * __expf(__uint_as_float((unsigned)ms[q]) - M);
-    }
-    const float lse = M + __logf(wave_sum(ls));
+    const float lse = M + __logf(wave_sum(ls * __expf(lm - M)));
 
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // m rounds over the heads of the sorted lists
-    unsigned ord[BQ];
-    int id[BQ];
-    int pos[BQ];
-#pragma unroll
-    for (int q = 0; q < BQ; ++q) {
-        const int b = lane + kWave * q;
-        const unsigned long long key = b < B ? stage[(size_t)b * L] : kNoKey;
-        ord[q] = (unsigned)(key >> 32);
-        id[q] = key_id(key);
-        pos[q] = 0;
-    }
     unsigned res_ord = 0u;
     unsigned res_id = 0u;
-    for (int r = 0; r < m; ++r) {
-        unsigned bo = ord[0];
+    for (int b0 = 0; b0 < B; b0 += GROUP) {
+        const int Bc = min(GROUP, B - b0);
+        const int total = Bc * L;
+        const unsigned long long *src = pkeys_row + (size_t)b0 * L;
+        // everything this pass needs is requested before the first wait
+        for (int base = 0; base < total; base += U * kWave) {
+            unsigned long long kreg[U];
+            if (base + U * kWave <= total) {
 #pragma unroll
-        for (int q = 1; q < BQ; ++q) bo = ord[q] > bo ? ord[q] : bo;
-        const unsigned wmax = wave_max_u32(bo);
-        unsigned myid = 0xFFFFFFFFu;
-        int cnt = 0;
+                for (int u = 0; u < U; ++u) kreg[u] = acquire_u64(src + base + u * kWave + lane);
 #pragma unroll
-        for (int q = 0; q < BQ; ++q) {
-            if (ord[q] == wmax) {
-                myid = (unsigned)id[q] < myid ? (unsigned)id[q] : myid;
-                ++cnt;
+                for (int u = 0; u < U; ++u) stage[base + u * kWave + lane] = kreg[u];
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (base + u * kWave < total) kreg[u] = acquire_u64(src + min(base + u * kWave + lane, total - 1));
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int e = base + u * kWave + lane;
+                    if (e < total) stage[e] = kreg[u];
+                }
             }
         }
-        const unsigned long long holders = __ballot(cnt > 0);
-        const unsigned long long multi = __ballot(cnt > 1);
-        unsigned wid;
-        if (__popcll(holders) == 1 && multi == 0ull) {
-            wid = __builtin_amdgcn_readlane(myid, __ffsll((long long)holders) - 1);
-        } else {
-            wid = wave_min_u32(myid);
+        if constexpr (CARRY) {
+            // the previous pass's result (lane r holds rank r) joins as list number Bc
+            if (lane < L)
+                stage[total + lane] = (b0 > 0 && lane < m && res_ord != 0u)
+                                          ? (((unsigned long long)res_ord << 32) | (unsigned)(~res_id))
+                                          : kNoKey;
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // m rounds over the heads of the sorted lists
+        const int nl = Bc + (CARRY ? 1 : 0);
+        unsigned ord[BQ];
+        int id[BQ];
+        int pos[BQ];
 #pragma unroll
         for (int q = 0; q < BQ; ++q) {
-            if (ord[q] == wmax && (unsigned)id[q] == wid && wmax != 0u) {
-                const int b = lane + kWave * q;
-                pos[q] += 1;
-                const unsigned long long key = pos[q] < L ? stage[(size_t)b * L + pos[q]] : kNoKey;
-                ord[q] = (unsigned)(key >> 32);
-                id[q] = key_id(key);
+            const int b = lane + kWave * q;
+            const unsigned long long key = b < nl ? stage[(size_t)b * L] : kNoKey;
+            ord[q] = (unsigned)(key >> 32);
+            id[q] = key_id(key);
+            pos[q] = 0;
+        }
+        res_ord = 0u;
+        res_id = 0u;
+        for (int r = 0; r < m; ++r) {
+            unsigned bo = ord[0];
+#pragma unroll
+            for (int q = 1; q < BQ; ++q) bo = ord[q] > bo ? ord[q] : bo;
+            const unsigned wmax = wave_max_u32(bo);
+            unsigned myid = 0xFFFFFFFFu;
+            int cnt = 0;
+#pragma unroll
+            for (int q = 0; q < BQ; ++q) {
+                if (ord[q] == wmax) {
+                    myid = (unsigned)id[q] < myid ? (unsigned)id[q] : myid;
+                    ++cnt;
+                }
+            }
+            const unsigned long long holders = __ballot(cnt > 0);
+            const unsigned long long multi = __ballot(cnt > 1);
+            unsigned wid;
+            if (__popcll(holders) == 1 && multi == 0ull) {
+                wid = __builtin_amdgcn_readlane(myid, __ffsll((long long)holders) - 1);
+            } else {
+                wid = wave_min_u32(myid);
+            }
+#pragma unroll
+            for (int q = 0; q < BQ; ++q) {
+                if (ord[q] == wmax && (unsigned)id[q] == wid && wmax != 0u) {
+                    const int b = lane + kWave * q;
+                    pos[q] += 1;
+                    const unsigned long long key = pos[q] < L ? stage[(size_t)b * L + pos[q]] : kNoKey;
+                    ord[q] = (unsigned)(key >> 32);
+                    id[q] = key_id(key);
+                }
+            }
+            if (lane == r) {
+                res_ord = wmax;
+                res_id = wid;
             }
         }
-        if (lane == r) {
-            res_ord = wmax;
-            res_id = wid;
-        }
+        __builtin_amdgcn_wave_barrier();
     }
     if (lane < m) {
         out_ids_row[lane] = (int)res_id;
@@ -251,7 +277,6 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
         *lse_buf_i = lse;
         if (out_lse_i) *out_lse_i = lse;
     }
-    __builtin_amdgcn_wave_barrier();
 }
 
 // Last workgroup: waves split the hidden rows; `fin_conc` waves work at a time
@@ -264,7 +289,7 @@ __device__ __noinline__ void finalize_rows(const unsigned long long *__restrict_
     if (w >= fin_conc) return;
     unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * B * L;
     for (int i = w; i < n; i += fin_conc)
-        finalize_row(pms + (size_t)i * B, pkeys + (size_t)i * B * L, B, L, m, stage, out_ids + (size_t)i * m,
+        finalize_row<false>(pms + (size_t)i * B, pkeys + (size_t)i * B * L, B, L, m, stage, out_ids + (size_t)i * m,
                      out_logp + (size_t)i * m, out_lse ? out_lse + i : nullptr, lse_buf + i, lane);
 }
 

@@ -240,6 +240,77 @@ def test_step_llama1b_chain_and_full_vocab_control():
         check_step(oi, ol, ref, map_, 1)
 
 
+# ----------------------------------------------------------------------------- tree drafting (n > 8): matrix-core path
+@pytest.mark.parametrize("n,d", [(9, 2048), (16, 4096), (17, 2048), (33, 4096), (64, 4096), (100, 2048)])
+def test_step_many_rows_mid_size(n, d):
+    k, m = 4099, 8           # ragged last tile
+    W, map_ = synth.trimmed_head_direct(k, d, seed=200 + n, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=200 + n, dtype="bf16")
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+    check_step(oi, ol, ref, map_, m, lse)
+
+
+def test_step_llama8b_tree_64_nodes_full_size():
+    k, d, n, m = 32768, 4096, 64, 8
+    W, map_ = synth.trimmed_head_direct(k, d, seed=4000, dtype="bf16")
+    dW, dmap = to_dev(W), to_dev(map_)
+    ws = vt.StepWorkspace(n, k, d, m, dev())
+    near = 0
+    for step in range(3):     # consecutive steps with fresh hidden rows on one workspace
+        h = synth.hidden_rows(n, d, seed=4000 + step, dtype="bf16")
+        ref = oracle.draft_head_step(h, W, map_, m)
+        oi, ol, lse = vt.draft_head_step(to_dev(h), dW, dmap, m, ws=ws, return_lse=True)
+        torch.cuda.synchronize()
+        near += check_step(oi, ol, ref, map_, m, lse)
+    assert near <= 6          # near-tie rows are rare (a few per thousand rows at m = 8)
+
+
+def test_step_stress_256_nodes_sampled_rows():
+    k, d, n, m = 32768, 8192, 256, 16
+    W, map_ = synth.trimmed_head_direct(k, d, seed=5000, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=5000, dtype="bf16")
+    oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+    rows = [0, 1, 15, 16, 127, 128, 200, 255]      # the oracle recomputes these hidden rows one by one
+    ref = oracle.draft_head_step(np.ascontiguousarray(h[rows]), W, map_, m)
+    check_step(oi[rows], ol[rows], ref, map_, m, lse[rows])
+    # properties that hold for every row
+    ids = oi.cpu().numpy()
+    lp = ol.cpu().numpy()
+    assert np.all(np.isin(ids, map_)) and np.all(np.diff(lp, axis=1) <= 0) and np.all(lp <= 0)
+    assert all(len(set(r.tolist())) == m for r in ids)
+
+
+def test_step_many_rows_full_vocabulary_many_tiles():
+    k, d, n, m = 128256, 2048, 24, 8     # 1002 tiles: the merge runs in several passes
+    W, map_ = synth.trimmed_head_direct(k, d, seed=6000, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=6000, dtype="bf16")
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+    check_step(oi, ol, ref, map_, m, lse)
+
+
+def test_step_many_rows_exact_ties_and_full_logp():
+    k, d, n, m = 1000, 256, 20, 4
+    W, map_ = synth.trimmed_head_direct(k, d, seed=7000, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=7000, dtype="bf16")
+    z = oracle.logits(h, W)
+    j = int(np.argmax(z[3]))
+    for off in (1, 129, 500):
+        W[(j + off) % k] = W[j]
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse, full = run_step(h, W, map_, m, return_lse=True, return_full=True)
+    assert np.array_equal(oi.cpu().numpy()[3], ref["ids"][3])
+    check_step(oi, ol, ref, map_, m, lse)
+    _, logp_ref = oracle.log_softmax(ref["z"])
+    assert np.max(np.abs(full.cpu().numpy().astype(np.float64) - logp_ref)) <= LOGP_TOL
+    # unsupported on the matrix-core path: d not a multiple of 128
+    W2, map2 = synth.trimmed_head_direct(64, 200, seed=1, dtype="bf16")
+    with pytest.raises(vt.VocabTrimError) as e:
+        run_step(synth.hidden_rows(9, 200, seed=1, dtype="bf16"), W2, map2, 1)
+    assert e.value.status == 2
+
+
 def test_step_odd_shapes():
     # d not a multiple of the 512-column wave chunk; k tiny; m = k; fp32 with a ragged d
     for (k, d, n, m, dt) in ((1, 64, 1, 1, "bf16"), (7, 264, 3, 7, "bf16"), (64, 520, 8, 64, "bf16"),
