@@ -33,6 +33,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the step kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE),
 # scaled by the same counters on a plain copy of known size; see profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
+    # (workload, k, n, m): FETCH_SIZE 98717.8 x 1.99975 KiB + WRITE_SIZE 211.6 KiB per launch
+    # (profiles/head_gemv_kernel_llama3b_k32768_n8_m8.txt)
+    ("llama3b", 32768, 8, 8): 202_364_000,
 }
 
 
