@@ -55,6 +55,14 @@ __device__ __forceinline__ unsigned wave_allreduce_u32(unsigned v, Op op) {
     r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
     return op(r[0], r[1]);
 }
+// Same, restricted to the 16 lanes of a DPP row (four independent groups per wave).
+template <typename Op>
+__device__ __forceinline__ unsigned row16_allreduce_u32(unsigned v, Op op) {
+    v = op(v, dpp_mov<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = op(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = op(v, dpp_mov<0x141>(v));   // row_half_mirror
+    return op(v, dpp_mov<0x140>(v));   // row_mirror
+}
 struct OpMaxU32 {
     __device__ __forceinline__ unsigned operator()(unsigned a, unsigned b) const { return a > b ? a : b; }
 };

@@ -35,6 +35,18 @@ constexpr int kPrefetchUnits = 3;                    // units of W in flight per
 __device__ __forceinline__ void stream_load16(u32x4 &dst, unsigned voff, const void *sbase) {
     asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(voff), "s"(sbase) : "memory");
 }
+// h pieces stay cacheable: every workgroup re-reads them from L2
+__device__ __forceinline__ void cached_load16(u32x4 &dst, unsigned voff, const void *sbase) {
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(sbase) : "memory");
+}
+constexpr int kMaxPieces = 9;   // 16-byte pieces of an h chunk per thread
+template <int N>
+__device__ __forceinline__ void wait_pieces(u32x4 (&b)[kMaxPieces]) {
+    asm volatile("s_waitcnt vmcnt(%9)"
+                 : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7]),
+                   "+v"(b[8])
+                 : "n"(N));
+}
 template <int N>
 __device__ __forceinline__ void wait_unit(u32x4 (&b)[4]) {
     asm volatile("s_waitcnt vmcnt(%4)" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]) : "n"(N));
@@ -54,10 +66,6 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     const size_t rs = (size_t)a.d * 2;
     const int lrow = lane & 15, lgrp = lane >> 4;
 
-    // target ids of the tile rows this lane ranks in the epilogue
-    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
-    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
-
     // per-lane byte offsets of the 4 load instructions of a unit: instruction j covers rows 4j..4j+3
     // of this wave's 16 rows, 16 lanes x 16 B per row; rows past the end of W repeat the last row
     unsigned voff[4];
@@ -74,8 +82,6 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         for (int j = 0; j < 4; ++j) stream_load16(dst[j], voff[j], p);
     };
     u32x4 areg[kPrefetchUnits][4];
-#pragma unroll
-    for (int x = 0; x < kPrefetchUnits; ++x) load_unit(x, areg[x]);
 
     f32x4 acc[NT];
 #pragma unroll
@@ -88,32 +94,70 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     const int rd_off = lrow * kStagePitch + lgrp * 16;
     const int hrow_off = lrow * a.hpitch + lgrp * 16;
 
-    // Units are consumed in order; unit u sits in register slot u % kPrefetchUnits.  Every
-    // units_per_chunk units the next KC columns of all hidden rows replace the h chunk in LDS.
+    // ---- h chunks: KC columns of every hidden row (zero rows up to 16 * NT) live in LDS.  The next
+    // chunk is fetched into registers while the current one is consumed, so its L2 latency is hidden;
+    // two barriers per chunk swap it in.
     const int units_per_chunk = a.KC / kUnitCols;
+    const int nchunks = (a.d + a.KC - 1) / a.KC;
+    u32x4 hp[kMaxPieces];
+    // piece e = q * 512 + tid of a chunk is (hidden row e / ppr, 16-byte piece e % ppr); one division per
+    // chunk, then a carry per step
+    auto fetch_chunk = [&](int c) {
+        const int c0 = c * a.KC;
+        const int ppr = min(a.KC, a.d - c0) >> 3;        // pieces per row
+        const int step_r = (kStepWaves * kWave) / ppr, step_p = (kStepWaves * kWave) % ppr;
+        int r = (int)threadIdx.x / ppr, pc = (int)threadIdx.x % ppr;
+        const char *hbase = static_cast<const char *>(a.h) + (size_t)c0 * 2;
+#pragma unroll
+        for (int q = 0; q < kMaxPieces; ++q) {
+            hp[q] = u32x4{0u, 0u, 0u, 0u};
+            if (r < a.n) cached_load16(hp[q], (unsigned)((size_t)r * rs + (size_t)pc * 16), hbase);
+            r += step_r;
+            pc += step_p;
+            if (pc >= ppr) {
+                pc -= ppr;
+                ++r;
+            }
+        }
+    };
+    auto store_chunk = [&](int c) {
+        const int ppr = min(a.KC, a.d - c * a.KC) >> 3;
+        const int step_r = (kStepWaves * kWave) / ppr, step_p = (kStepWaves * kWave) % ppr;
+        int r = (int)threadIdx.x / ppr, pc = (int)threadIdx.x % ppr;
+#pragma unroll
+        for (int q = 0; q < kMaxPieces; ++q) {
+            if (r < 16 * NT) *reinterpret_cast<u32x4 *>(hbuf + (size_t)r * a.hpitch + pc * 16) = hp[q];
+            r += step_r;
+            pc += step_p;
+            if (pc >= ppr) {
+                pc -= ppr;
+                ++r;
+            }
+        }
+    };
+    fetch_chunk(0);                       // first: everything waits for it
+#pragma unroll
+    for (int x = 0; x < kPrefetchUnits; ++x) load_unit(x, areg[x]);
+    wait_pieces<4 * kPrefetchUnits>(hp);  // the W prefetch stays in flight
+    store_chunk(0);
+    __syncthreads();
+    // target ids of the tile rows this lane ranks in the epilogue (two layouts, see below)
+    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
+    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
+    int idq[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) idq[q] = a.map[row0 + min(lrow + 16 * q, rows_b - 1)];
+
+
+    // Units are consumed in order; unit u sits in register slot u % kPrefetchUnits.
     for (int u = 0; u < nunits;) {
 #pragma unroll
         for (int x = 0; x < kPrefetchUnits; ++x) {
             if (u < nunits) {   // uniform
                 const int uc = u % units_per_chunk;
-                if (uc == 0) {
-                    // ---- stage the next KC columns of every hidden row (zero rows up to 16 * NT)
-                    __syncthreads();
-                    const int c0 = u * kUnitCols;
-                    const int kc = min(a.KC, a.d - c0);
-                    const int pieces_per_row = kc >> 3;              // 16-byte pieces
-                    const int npieces = 16 * NT * pieces_per_row;
-                    for (int e = threadIdx.x; e < npieces; e += kStepWaves * kWave) {
-                        const int r = e / pieces_per_row, pc = e - r * pieces_per_row;
-                        u32x4 v = {0u, 0u, 0u, 0u};
-                        if (r < a.n)
-                            v = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.h) + (size_t)r * rs +
-                                                                 (size_t)(c0 + pc * 8) * 2);
-                        *reinterpret_cast<u32x4 *>(hbuf + (size_t)r * a.hpitch + pc * 16) = v;
-                    }
-                    __syncthreads();
-                }
-                // unit u's four loads are the oldest outstanding
+                const int c = u / units_per_chunk;
+                if (uc == 0 && c + 1 < nchunks) fetch_chunk(c + 1);
+                // unit u's four loads are the oldest outstanding of the W stream
                 wait_unit<4 * (kPrefetchUnits - 1)>(areg[x]);
                 unsigned char *sb = my_stage + (u & 1) * kStageUnitBytes;
 #pragma unroll
@@ -133,6 +177,16 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
                     }
                 }
                 ++u;
+                if ((uc == units_per_chunk - 1 || u == nunits) && c + 1 < nchunks) {
+                    // The next chunk's pieces were requested units_per_chunk units ago: only W loads
+                    // issued after them may still be outstanding (one unit per consumed unit).
+                    if (units_per_chunk >= kPrefetchUnits) wait_pieces<4 * kPrefetchUnits>(hp);
+                    else if (units_per_chunk == 2) wait_pieces<8>(hp);
+                    else wait_pieces<4>(hp);
+                    __syncthreads();       // every wave is done with the current chunk
+                    store_chunk(c + 1);
+                    __syncthreads();
+                }
             }
         }
     }
@@ -156,12 +210,19 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     }
     __syncthreads();
 
-    for (int i = w; i < a.n; i += kStepWaves) {
-        const float *zrow = zt + (size_t)i * tp;
-        float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
-        unsigned long long *pms_slot = a.pms + (size_t)i * a.nlists + blockIdx.x;
-        unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nlists + blockIdx.x) * a.L;
-        block_epilogue_small(zrow, 1, 0, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane);
+    if (a.L <= 16) {
+        // four hidden rows per wave and pass (16 lanes each)
+        for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
+            block_epilogue_rows4(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
+                                 a.pkeys, a.nlists, (int)blockIdx.x, lane);
+    } else {
+        for (int i = w; i < a.n; i += kStepWaves) {
+            const float *zrow = zt + (size_t)i * tp;
+            float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
+            unsigned long long *pms_slot = a.pms + (size_t)i * a.nlists + blockIdx.x;
+            unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nlists + blockIdx.x) * a.L;
+            block_epilogue_small(zrow, 1, 0, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane);
+        }
     }
 }
 

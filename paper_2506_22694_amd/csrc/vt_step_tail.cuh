@@ -112,6 +112,73 @@ __device__ __noinline__ void block_epilogue_large(const float *zrow, int S, int 
     block_epilogue_core<QMAX>(zrow, S, sstride, rows_b, L, idq, logp_full_row, pms_slot, pkeys_slot, lane);
 }
 
+// ------------------------------------------------------------------ four hidden rows per pass
+// Tiles of at most 128 logits per hidden row and L <= 16: the 16 lanes of DPP row g
+// rank hidden row i0 + g (8 logits per lane), so a wave finishes four hidden rows in
+// the time of one.  zt: logit tile [hidden row][tp]; idq: ids of tile rows gl + 16 q.
+__device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, int i0, int n, int rows_b, int L,
+                                                     const int (&idq)[8], float *__restrict__ logp_full, size_t k,
+                                                     int row0, unsigned long long *__restrict__ pms,
+                                                     unsigned long long *__restrict__ pkeys, int nlists, int blk,
+                                                     int lane) {
+    const int g = lane >> 4, gl = lane & 15;
+    const int i = i0 + g;
+    const bool active = i < n;
+    const float *zrow = zt + (size_t)(active ? i : 0) * tp;
+    unsigned ord[8];
+    int id[8];
+    float zq[8];
+    float lmax = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int t = gl + 16 * q;
+        ord[q] = 0u;
+        id[q] = idq[q];
+        zq[q] = -INFINITY;
+        if (active && t < rows_b) {
+            const float z = zrow[t];
+            if (logp_full) logp_full[(size_t)i * k + row0 + t] = z;
+            zq[q] = z;
+            ord[q] = orderable_f32(z);
+            lmax = fmaxf(lmax, z);
+        }
+    }
+    const float M = __uint_as_float(row16_allreduce_u32(__float_as_uint(lmax), OpMaxF32{}));
+    float ls = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) ls += __expf(zq[q] - M);
+    const float Ssum = __uint_as_float(row16_allreduce_u32(__float_as_uint(ls), OpAddF32{}));
+    unsigned res_ord = 0u, res_id = 0u;
+    for (int r = 0; r < L; ++r) {
+        unsigned bo = ord[0];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) bo = ord[q] > bo ? ord[q] : bo;
+        const unsigned wmax = row16_allreduce_u32(bo, OpMaxU32{});
+        unsigned myid = 0xFFFFFFFFu;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (ord[q] == wmax) myid = (unsigned)id[q] < myid ? (unsigned)id[q] : myid;
+        }
+        const unsigned wid = row16_allreduce_u32(myid, OpMinU32{});
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (ord[q] == wmax && (unsigned)id[q] == wid) ord[q] = 0u;
+        }
+        if (gl == r) {
+            res_ord = wmax;
+            res_id = wid;
+        }
+    }
+    if (active) {
+        const unsigned long long key =
+            res_ord == 0u ? kNoKey : (((unsigned long long)res_ord << 32) | (unsigned)(~res_id));
+        if (gl < L) publish_u64(pkeys + ((size_t)i * nlists + blk) * L + gl, key);
+        if (gl == 0)
+            publish_u64(pms + (size_t)i * nlists + blk,
+                        ((unsigned long long)__float_as_uint(Ssum) << 32) | __float_as_uint(M));
+    }
+}
+
 // ------------------------------------------------------------------ arrival
 // Two-level arrival counters (groups of 16 workgroups, then one counter for the
 // groups): same-address atomics are serialised at the memory side, so a single
