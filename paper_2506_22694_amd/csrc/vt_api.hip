@@ -85,11 +85,14 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         if (dtype != VT_BF16 || (d % 128) != 0 || n > 256) return p;
         int NT = 1;
         while (16 * NT < n) NT *= 2;
-        const size_t stage = vt::mfma_stage_bytes();
-        const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage) / (16 * (size_t)NT);
-        if (hmax < 272) return p;
-        int KC = (int)(((hmax - 16) / 2) / 128) * 128;
-        if (KC > d) KC = d;
+        const size_t stage = NT >= 8 ? vt::mfma_wide_lds_bytes() : vt::mfma_stage_bytes();
+        int KC = 128;   // NT >= 8: h is not staged at all (B-operands come from L2)
+        if (NT < 8) {
+            const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage) / (16 * (size_t)NT);
+            if (hmax < 272) return p;
+            KC = (int)(((hmax - 16) / 2) / 128) * 128;
+            if (KC > d) KC = d;
+        }
         p.mfma = true;
         p.NT = NT;
         p.KC = KC;
@@ -97,7 +100,7 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         p.nlists = (k + vt::kMfmaTileRows - 1) / vt::kMfmaTileRows;
         p.L = m < vt::kMfmaTileRows ? m : vt::kMfmaTileRows;
         p.nblocks = p.nlists;
-        p.lds = stage + (size_t)16 * NT * p.hpitch;
+        p.lds = NT >= 8 ? stage : stage + (size_t)16 * NT * p.hpitch;
         const size_t tile = (size_t)n * (vt::kMfmaTileRows + 1) * sizeof(float);
         if (tile > p.lds) p.lds = tile;
         if (p.lds > (size_t)vt::kMaxDynamicLds) return p;

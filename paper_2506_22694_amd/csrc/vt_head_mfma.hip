@@ -18,6 +18,7 @@
 #include "vt_device.h"
 #include "vt_step.h"
 #include "vt_step_tail.cuh"
+#include <type_traits>
 
 namespace vt {
 
@@ -226,6 +227,194 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     }
 }
 
+// ------------------------------------------------------------------ many hidden rows (n > 64)
+// With hundreds of hidden rows a chunk of h no longer fits LDS next to anything else, so the
+// roles are swapped: the unit of W (128 rows x 128 columns, loaded by the 8 waves as above, 16
+// rows each) is staged in LDS *shared* by the workgroup, double-buffered with one barrier per
+// unit, and every wave owns 16 * NTW hidden rows whose B-operands come straight from h (L2) into
+// registers, one unit ahead.  A wave multiplies all 128 rows of the tile (8 M-tiles) by its
+// hidden rows.
+template <int N, int CNT>
+__device__ __forceinline__ void wait_regs(u32x4 (&b)[CNT]) {
+    static_assert(CNT == 4 || CNT == 8, "register group size");
+    if constexpr (CNT == 4) {
+        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]) : "n"(N));
+    } else {
+        asm volatile("s_waitcnt vmcnt(%8)"
+                     : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
+                     : "n"(N));
+    }
+}
+
+template <int NTW>
+__global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const MfmaArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int kUbufBytes = kMfmaTileRows * kStagePitch;   // one staged unit of the whole tile
+    float *zt = reinterpret_cast<float *>(smem);                // logit tile, aliases the unit buffers afterwards
+    constexpr int PU = kPrefetchUnits;
+    constexpr int NB = 4 * NTW;                                  // B-operand loads per unit
+
+    const int lane = lane_id();
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int row0 = blockIdx.x * kMfmaTileRows;
+    const int rows_b = min(kMfmaTileRows, a.k - row0);
+    const size_t rs = (size_t)a.d * 2;
+    const int lrow = lane & 15, lgrp = lane >> 4;
+    const int nunits = a.d / kUnitCols;
+
+    // W: this wave loads rows 16w .. 16w+15 of the tile, 4 rows x 256 B per instruction
+    unsigned voff[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = min(16 * w + 4 * j + lgrp, rows_b - 1);
+        voff[j] = (unsigned)((size_t)r * rs + (size_t)lrow * 16);
+    }
+    const unsigned voff_dummy = (unsigned)lane * 16;
+    const char *Wt = static_cast<const char *>(a.W) + (size_t)row0 * rs;
+    // past the last unit the pipeline keeps its shape by reading the start of h (L2, in bounds)
+    auto load_unit = [&](int u, u32x4(&dst)[4]) {
+        const bool real = u < nunits;
+        const char *p = real ? Wt + (size_t)u * (kUnitCols * 2) : static_cast<const char *>(a.h);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) stream_load16(dst[j], real ? voff[j] : voff_dummy, p);
+    };
+    // h: B-operands of hidden rows 16 * (NTW * w + t) + lrow, k-group lgrp, four k-steps per unit
+    unsigned voffB[NTW];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) {
+        const int i = min(16 * (NTW * w + t) + lrow, a.n - 1);    // rows past n compute unused columns
+        voffB[t] = (unsigned)((size_t)i * rs + (size_t)lgrp * 16);
+    }
+    auto load_b = [&](int u, u32x4(&dst)[NB]) {
+        const char *p = static_cast<const char *>(a.h) + (size_t)min(u, nunits - 1) * (kUnitCols * 2);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+            for (int t = 0; t < NTW; ++t) cached_load16(dst[ks * NTW + t], voffB[t], p + ks * 64);
+        }
+    };
+
+    u32x4 areg[PU][4];
+    u32x4 breg[2][NB];
+    f32x4 acc[8][NTW];
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) {
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int wr_off = (16 * w + lgrp) * kStagePitch + lrow * 16;   // + 4 j rows
+    const int rd_off = lrow * kStagePitch + lgrp * 16;              // + 16 mt rows, + ks * 64
+
+    // ---- prologue: units 0 .. PU-1 and B(0) requested; unit 0 staged
+#pragma unroll
+    for (int x = 0; x < PU; ++x) load_unit(x, areg[x]);
+    load_b(0, breg[0]);
+    wait_regs<0, 4>(areg[0]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<u32x4 *>(smem + 4 * j * kStagePitch + wr_off) = areg[0][j];
+    load_unit(PU, areg[0]);
+    __syncthreads();
+    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
+    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
+    int idq[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) idq[q] = a.map[row0 + min(lrow + 16 * q, rows_b - 1)];
+
+    // ---- steady state.  Per iteration the wave issues NB B-loads, then 4 W-loads, always in this order,
+    // so the age of every outstanding load is known:
+    //   W(u+1) was issued PU iterations ago as the last 4 loads      -> (PU-1)*(NB+4) + NB younger loads
+    //   B(u)   was issued last iteration as the first NB loads       -> 4 + NB + 4 younger loads
+    constexpr int kWaitA = (PU - 1) * (NB + 4) + NB;
+    constexpr int kWaitB = 8 + NB;
+    static_assert(kWaitA <= 63, "vmcnt range");
+    auto iteration = [&](int u, auto par_tag, auto slot_tag) {
+        constexpr int PAR = decltype(par_tag)::value;      // u & 1
+        constexpr int SLOT = decltype(slot_tag)::value;    // (u + 1) % PU: register slot of unit u + 1
+        unsigned char *cur = smem + PAR * kUbufBytes;
+        unsigned char *nxt = smem + (PAR ^ 1) * kUbufBytes;
+        load_b(u + 1, breg[PAR ^ 1]);
+        wait_regs<kWaitA, 4>(areg[SLOT]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(nxt + 4 * j * kStagePitch + wr_off) = areg[SLOT][j];
+        load_unit(u + 1 + PU, areg[SLOT]);
+        if constexpr (NB == 4) wait_regs<kWaitB, 4>(breg[PAR]);
+        else wait_regs<kWaitB, 8>(breg[PAR]);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                const u32x4 av = *reinterpret_cast<const u32x4 *>(cur + 16 * mt * kStagePitch + rd_off + ks * 64);
+#pragma unroll
+                for (int t = 0; t < NTW; ++t)
+                    acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, breg[PAR][ks * NTW + t]),
+                        acc[mt][t], 0, 0, 0);
+            }
+        }
+        __syncthreads();   // unit u consumed by everyone, unit u + 1 staged by everyone
+    };
+    // the register slot of unit u + 1 cycles with period PU and the buffer parity with period 2:
+    // unroll over lcm(2, PU) = 6 iterations
+    static_assert(PU == 3, "the unrolled schedule below assumes three units in flight");
+    int u = 0;
+    for (; u + 6 <= nunits; u += 6) {
+        iteration(u + 0, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+        iteration(u + 1, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{});
+        iteration(u + 2, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        iteration(u + 3, std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+        iteration(u + 4, std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
+        iteration(u + 5, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+    }
+    if (u + 0 < nunits) iteration(u + 0, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+    if (u + 1 < nunits) iteration(u + 1, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{});
+    if (u + 2 < nunits) iteration(u + 2, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    if (u + 3 < nunits) iteration(u + 3, std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+    if (u + 4 < nunits) iteration(u + 4, std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
+    // loads past the end are still in flight: let them land before their registers die
+#pragma unroll
+    for (int x = 0; x < PU; ++x) wait_regs<0, 4>(areg[x]);
+    if constexpr (NB == 4) {
+        wait_regs<0, 4>(breg[0]);
+        wait_regs<0, 4>(breg[1]);
+    } else {
+        wait_regs<0, 8>(breg[0]);
+        wait_regs<0, 8>(breg[1]);
+    }
+
+    // ---- logits -> LDS tile zt[i][t] (the last barrier above freed the unit buffers)
+    const int tp = kMfmaTileRows + 1;
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) {
+        const int i = 16 * (NTW * w + t) + lrow;
+        if (i < a.n) {
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                float *dst = zt + (size_t)i * tp + 16 * mt + 4 * lgrp;
+                dst[0] = acc[mt][t].x;
+                dst[1] = acc[mt][t].y;
+                dst[2] = acc[mt][t].z;
+                dst[3] = acc[mt][t].w;
+            }
+        }
+    }
+    __syncthreads();
+
+    if (a.L <= 16) {
+        for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
+            block_epilogue_rows4(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
+                                 a.pkeys, a.nlists, (int)blockIdx.x, lane);
+    } else {
+        for (int i = w; i < a.n; i += kStepWaves) {
+            const float *zrow = zt + (size_t)i * tp;
+            float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
+            unsigned long long *pms_slot = a.pms + (size_t)i * a.nlists + blockIdx.x;
+            unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nlists + blockIdx.x) * a.L;
+            block_epilogue_small(zrow, 1, 0, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane);
+        }
+    }
+}
+
 // Merges the per-tile partials: one wave per hidden row.
 __global__ void __launch_bounds__(kStepWaves *kWave) step_finalize_kernel(const FinalizeArgs f) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -238,6 +427,24 @@ __global__ void __launch_bounds__(kStepWaves *kWave) step_finalize_kernel(const 
     finalize_row<true>(f.pms + (size_t)i * f.nlists, f.pkeys + (size_t)i * f.nlists * f.L, f.nlists, f.L, f.m, stage,
                  f.out_ids + (size_t)i * f.m, f.out_logp + (size_t)i * f.m, f.out_lse ? f.out_lse + i : nullptr,
                  f.lse_buf + i, lane);
+}
+
+template <int NTW>
+hipError_t launch_mfma_wide_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
+    auto kern = head_mfma_wide_kernel<NTW>;
+    static bool attr_set[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kMaxDynamicLds);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.nlists), dim3(kStepWaves * kWave), lds, st, a);
+    return hipGetLastError();
 }
 
 template <int NT>
@@ -261,14 +468,15 @@ hipError_t launch_mfma_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
 }  // namespace
 
 size_t mfma_stage_bytes() { return kStageBytes; }
+size_t mfma_wide_lds_bytes() { return 2 * (size_t)kMfmaTileRows * kStagePitch; }
 
 hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t st) {
     switch (NT) {
         case 1: return launch_mfma_inst<1>(a, lds, st);
         case 2: return launch_mfma_inst<2>(a, lds, st);
         case 4: return launch_mfma_inst<4>(a, lds, st);
-        case 8: return launch_mfma_inst<8>(a, lds, st);
-        case 16: return launch_mfma_inst<16>(a, lds, st);
+        case 8: return launch_mfma_wide_inst<1>(a, lds, st);
+        case 16: return launch_mfma_wide_inst<2>(a, lds, st);
         default: return hipErrorInvalidValue;
     }
 }

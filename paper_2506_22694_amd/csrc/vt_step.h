@@ -66,6 +66,7 @@ struct FinalizeArgs {
 };
 
 size_t mfma_stage_bytes();
+size_t mfma_wide_lds_bytes();   // NT >= 8: two shared unit buffers
 hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t st);
 hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t st);
 
