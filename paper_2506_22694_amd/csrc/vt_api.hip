@@ -34,7 +34,7 @@ struct StepPlan {
     int rpb = 0, nblocks = 0, tpitch = 0, L = 0, fin_conc = 0;
     size_t lds = 0;
     // workspace layout (byte offsets)
-    size_t off_lse = 0, off_pms = 0, off_pkeys = 0, bytes = 0;
+    size_t off_lse = 0, off_pms = 0, off_pkeys = 0, off_hpack = 0, bytes = 0;
 };
 
 using vt::kTicketBytes;
@@ -122,6 +122,8 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
     off = round_up(off + (size_t)p.nblocks * n * sizeof(unsigned long long), 256);
     p.off_pkeys = off;
     off = round_up(off + (size_t)n * p.nblocks * p.L * sizeof(unsigned long long), 256);
+    p.off_hpack = off;
+    if (p.mfma && p.NT >= 8) off = round_up(off + (size_t)d * p.NT * 32, 256);
     p.bytes = off;
     p.ok = true;
     return p;
@@ -284,6 +286,7 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
         a.pms = pms;
         a.pkeys = pkeys;
         a.out_logp_full = out_logp_full;
+        a.hpack = p.NT >= 8 ? static_cast<void *>(wsb + p.off_hpack) : nullptr;
         hipError_t e = vt::launch_head_mfma(p.NT, a, p.lds, st);
         if (e != hipSuccess) return device_status(e);
         vt::FinalizeArgs f;

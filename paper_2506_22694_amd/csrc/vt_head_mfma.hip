@@ -227,6 +227,24 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     }
 }
 
+// Re-lays h so that one B-operand load of the kernel below is 1 KiB of consecutive bytes: piece
+// (unit u, k-step ks, 16-row group g, lane) holds the 8 columns 128 u + 32 ks + 8 (lane / 16) .. of
+// hidden row 16 g + lane % 16 (rows past n repeat row n - 1; their products are never read).
+// Read in place, hidden rows lie d * 2 bytes apart and a load touches 16 of them, which the L2
+// serves at a fraction of the rate of consecutive lines.
+__global__ void __launch_bounds__(256) pack_h_kernel(const u32x4 *__restrict__ h, u32x4 *__restrict__ hp, int n,
+                                                     int d, int groups, long long pieces) {
+    const long long x = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (x >= pieces) return;
+    const int lane = (int)(x & 63);
+    const long long y = x >> 6;
+    const int g = (int)(y % groups);
+    const long long z = y / groups;          // 4 u + ks
+    const int i = min(16 * g + (lane & 15), n - 1);
+    const long long col16 = z * 4 + (lane >> 4);   // 16-byte column piece of the row
+    hp[x] = h[(long long)i * (d / 8) + col16];
+}
+
 // ------------------------------------------------------------------ many hidden rows (n > 64)
 // With hundreds of hidden rows a chunk of h no longer fits LDS next to anything else, so the
 // roles are swapped: the unit of W (128 rows x 128 columns, loaded by the 8 waves as above, 16
@@ -278,19 +296,15 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
 #pragma unroll
         for (int j = 0; j < 4; ++j) stream_load16(dst[j], real ? voff[j] : voff_dummy, p);
     };
-    // h: B-operands of hidden rows 16 * (NTW * w + t) + lrow, k-group lgrp, four k-steps per unit
-    unsigned voffB[NTW];
-#pragma unroll
-    for (int t = 0; t < NTW; ++t) {
-        const int i = min(16 * (NTW * w + t) + lrow, a.n - 1);    // rows past n compute unused columns
-        voffB[t] = (unsigned)((size_t)i * rs + (size_t)lgrp * 16);
-    }
+    // h: B-operands of hidden rows 16 * (NTW * w + t) + lrow, k-group lgrp, four k-steps per unit,
+    // from the re-laid copy: 1 KiB per (unit, k-step, 16-row group)
+    const char *hpk = static_cast<const char *>(a.hpack) + (size_t)(NTW * w) * 1024;
     auto load_b = [&](int u, u32x4(&dst)[NB]) {
-        const char *p = static_cast<const char *>(a.h) + (size_t)min(u, nunits - 1) * (kUnitCols * 2);
+        const char *p = hpk + (size_t)min(u, nunits - 1) * (4 * 8 * NTW * 1024);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
-            for (int t = 0; t < NTW; ++t) cached_load16(dst[ks * NTW + t], voffB[t], p + ks * 64);
+            for (int t = 0; t < NTW; ++t) cached_load16(dst[ks * NTW + t], voff_dummy, p + (ks * 8 * NTW + t) * 1024);
         }
     };
 
@@ -429,6 +443,14 @@ __global__ void __launch_bounds__(kStepWaves *kWave) step_finalize_kernel(const 
                  f.lse_buf + i, lane);
 }
 
+hipError_t launch_pack_h_impl(const MfmaArgs &a, int groups, hipStream_t st) {
+    const long long pieces = (long long)(a.d / 128) * 4 * groups * 64;
+    const unsigned blocks = (unsigned)((pieces + 255) / 256);
+    hipLaunchKernelGGL(pack_h_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const u32x4 *>(a.h),
+                       static_cast<u32x4 *>(a.hpack), a.n, a.d, groups, pieces);
+    return hipGetLastError();
+}
+
 template <int NTW>
 hipError_t launch_mfma_wide_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
     auto kern = head_mfma_wide_kernel<NTW>;
@@ -475,8 +497,13 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
         case 1: return launch_mfma_inst<1>(a, lds, st);
         case 2: return launch_mfma_inst<2>(a, lds, st);
         case 4: return launch_mfma_inst<4>(a, lds, st);
-        case 8: return launch_mfma_wide_inst<1>(a, lds, st);
-        case 16: return launch_mfma_wide_inst<2>(a, lds, st);
+        case 8:
+        case 16: {
+            if (a.hpack == nullptr) return hipErrorInvalidValue;
+            const hipError_t e = launch_pack_h_impl(a, NT, st);
+            if (e != hipSuccess) return e;
+            return NT == 8 ? launch_mfma_wide_inst<1>(a, lds, st) : launch_mfma_wide_inst<2>(a, lds, st);
+        }
         default: return hipErrorInvalidValue;
     }
 }

@@ -51,6 +51,7 @@ struct MfmaArgs {
     unsigned long long *pms;    // [n, nlists]
     unsigned long long *pkeys;  // [n, nlists, L]
     float *out_logp_full;     // [n, k] or null
+    void *hpack;              // more than 64 hidden rows: h re-laid in operand order, d * NT * 32 bytes
 };
 
 struct FinalizeArgs {
