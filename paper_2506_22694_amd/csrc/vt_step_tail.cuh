@@ -91,7 +91,7 @@ __device__ __forceinline__ void block_epilogue_core(const float *zrow, int S, in
 }
 
 // small tiles (<= 128 rows): ids were prefetched by the caller
-__device__ __noinline__ void block_epilogue_small(const float *zrow, int S, int sstride, int rows_b, int L, int id0,
+__device__ __forceinline__ void block_epilogue_small(const float *zrow, int S, int sstride, int rows_b, int L, int id0,
                                                   int id1, float *__restrict__ logp_full_row,
                                                   unsigned long long *__restrict__ pms_slot,
                                                   unsigned long long *__restrict__ pkeys_slot, int lane) {
@@ -100,7 +100,7 @@ __device__ __noinline__ void block_epilogue_small(const float *zrow, int S, int 
 }
 
 // large tiles (<= 1024 rows): ids are read here
-__device__ __noinline__ void block_epilogue_large(const float *zrow, int S, int sstride, int rows_b, int L,
+__device__ __forceinline__ void block_epilogue_large(const float *zrow, int S, int sstride, int rows_b, int L,
                                                   const int *__restrict__ map_tile,
                                                   float *__restrict__ logp_full_row,
                                                   unsigned long long *__restrict__ pms_slot,
@@ -298,6 +298,11 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
         res_ord = 0u;
         res_id = 0u;
         for (int r = 0; r < m; ++r) {
+            // the successor of every head is read now, so that a pop below costs no LDS round trip
+            unsigned long long succ[BQ];
+#pragma unroll
+            for (int q = 0; q < BQ; ++q)
+                succ[q] = stage[(size_t)min(lane + kWave * q, nl - 1) * L + min(pos[q] + 1, L - 1)];
             unsigned bo = ord[0];
 #pragma unroll
             for (int q = 1; q < BQ; ++q) bo = ord[q] > bo ? ord[q] : bo;
@@ -321,13 +326,11 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
             }
 #pragma unroll
             for (int q = 0; q < BQ; ++q) {
-                if (ord[q] == wmax && (unsigned)id[q] == wid && wmax != 0u) {
-                    const int b = lane + kWave * q;
-                    pos[q] += 1;
-                    const unsigned long long key = pos[q] < L ? stage[(size_t)b * L + pos[q]] : kNoKey;
-                    ord[q] = (unsigned)(key >> 32);
-                    id[q] = key_id(key);
-                }
+                const bool win = ord[q] == wmax && (unsigned)id[q] == wid && wmax != 0u;
+                const unsigned long long key = pos[q] + 1 < L ? succ[q] : kNoKey;
+                ord[q] = win ? (unsigned)(key >> 32) : ord[q];
+                id[q] = win ? key_id(key) : id[q];
+                pos[q] += win ? 1 : 0;
             }
             if (lane == r) {
                 res_ord = wmax;
@@ -348,7 +351,7 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
 
 // Last workgroup: waves split the hidden rows; `fin_conc` waves work at a time
 // (LDS staging budget).
-__device__ __noinline__ void finalize_rows(const unsigned long long *__restrict__ pms,
+__device__ __forceinline__ void finalize_rows(const unsigned long long *__restrict__ pms,
                                            const unsigned long long *__restrict__ pkeys, int B, int L, int n, int m,
                                            int fin_conc, int *__restrict__ out_ids, float *__restrict__ out_logp,
                                            float *__restrict__ out_lse, float *__restrict__ lse_buf,
