@@ -91,6 +91,8 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
             const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage) / (16 * (size_t)NT);
             if (hmax < 272) return p;
             KC = (int)(((hmax - 16) / 2) / 128) * 128;
+            const int kc_regs = (vt::kMfmaChunkPieces * vt::kStepWaves * 64 * 16) / (16 * NT * 2) / 128 * 128;
+            if (KC > kc_regs) KC = kc_regs;   // the chunk must fit the register prefetch
             if (KC > d) KC = d;
         }
         p.mfma = true;

@@ -40,7 +40,7 @@ __device__ __forceinline__ void stream_load16(u32x4 &dst, unsigned voff, const v
 __device__ __forceinline__ void cached_load16(u32x4 &dst, unsigned voff, const void *sbase) {
     asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(sbase) : "memory");
 }
-constexpr int kMaxPieces = 9;   // 16-byte pieces of an h chunk per thread
+constexpr int kMaxPieces = kMfmaChunkPieces;   // 16-byte pieces of an h chunk per thread
 template <int N>
 __device__ __forceinline__ void wait_pieces(u32x4 (&b)[kMaxPieces]) {
     asm volatile("s_waitcnt vmcnt(%9)"

@@ -38,6 +38,8 @@ struct StepArgs {
 
 // ---- matrix-core path (n > 8) ----
 constexpr int kMfmaTileRows = 128;     // rows of W_trim per workgroup (16 per wave)
+constexpr int kMfmaChunkPieces = 9;    // an h chunk is prefetched through registers: at most this many
+                                       // 16-byte pieces per thread, i.e. 16 * NT * KC * 2 <= 9 * 512 * 16 bytes
 
 struct MfmaArgs {
     const void *h;            // [n, d] bf16
