@@ -59,6 +59,10 @@ def parse():
     p.add_argument("--sweep", action="store_true", help="also time the k / n sweep (table on stderr)")
     p.add_argument("--configs", action="store_true",
                    help="also time the other workloads' draft steps (1B chain + full-vocab control, 8B tree, stress)")
+    p.add_argument("--tree-run", action="store_true",
+                   help="also time 1000 consecutive draft steps of the 8B-shaped tree workload (n=64, d=4096) as one span")
+    p.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing of the headline step")
+    p.add_argument("--no-full-vocab", action="store_true", help="skip the k = V control step (trimmed-vs-full ratio)")
     p.add_argument("--pmc-copy", action="store_true",
                    help="only run plain device copies of the W_trim size (counter calibration under rocprofv3)")
     return p.parse_args()
@@ -123,23 +127,36 @@ def main():
         counts = torch.zeros(V, dtype=torch.int64, device=dev)
         ws_c = torch.empty(vt.load_library().vt_count_tokens_ws_bytes(V, ids.numel()), dtype=torch.uint8, device=dev)
 
-        def do_count(_):
-            counts.zero_()
-            vt.count_tokens(ids, V, counts=counts, ws=ws_c)
-        do_count(0)
-        us_count = time_region(do_count, 10)
-        us_zero = time_region(lambda _: counts.zero_(), 10)
-        us_count -= us_zero
-        us_select = time_region(lambda _: vt.build_trimmed_head(counts, None, k), 10)
-        map_, W_trim = vt.build_trimmed_head(counts, W_full, k)
-        us_build = time_region(lambda _: vt.build_trimmed_head(counts, W_full, k), 5)
+        def median_us(fn, reps):
+            # one event pair per call: the median is robust against allocator hiccups of a single call
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            torch.cuda.synchronize()
+            for a, b in evs:
+                a.record(stream)
+                fn()
+                b.record(stream)
+            torch.cuda.synchronize()
+            t = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+            return t[len(t) // 2]
+
+        ws_b = torch.empty(vt.load_library().vt_build_trimmed_head_ws_bytes(V, d, k), dtype=torch.uint8, device=dev)
+        vt.count_tokens(ids, V, counts=counts, ws=ws_c)
+        counts_once = counts.clone()
+        us_count = median_us(lambda: vt.count_tokens(ids, V, counts=counts, ws=ws_c), 15)
+        counts.copy_(counts_once)
+        for _ in range(3):
+            vt.build_trimmed_head(counts, W_full, k, ws=ws_b)
+        us_select = median_us(lambda: vt.build_trimmed_head(counts, None, k, ws=ws_b), 15)
+        us_build = median_us(lambda: vt.build_trimmed_head(counts, W_full, k, ws=ws_b), 9)
+        map_, W_trim = vt.build_trimmed_head(counts, W_full, k, ws=ws_b)
         us_gather = us_build - us_select
         calib = {
             "count_us": round(us_count, 2), "count_ids": wl.n_ids,
             "count_gids_per_s": round(wl.n_ids / us_count / 1e3, 2),
             "count_id_stream_gbps": round(wl.n_ids * 4 / us_count / 1e3, 1),
             "select_us": round(us_select, 2),
-            "gather_us": round(us_gather, 2),
+            "build_us": round(us_build, 2),
+            "gather_us": round(us_gather, 2),   # build minus select (medians)
             "gather_gbps": round(2 * step_bytes / us_gather / 1e3, 1),
             "gather_frac_of_hbm_peak": round(2 * step_bytes / us_gather / 1e3 / HBM_PEAK_GBPS, 4),
         }
@@ -173,6 +190,87 @@ def main():
     log(f"step n={n} m={m} k={k} d={d}: cold {us_cold:.2f} us/step (back-to-back), "
         f"per-launch avg {us_kernel:.2f} us (p10 {per[len(per)//10]:.2f}, p50 {per[len(per)//2]:.2f}, "
         f"p90 {per[len(per)*9//10]:.2f}), warm single buffer {us_warm:.2f} us")
+
+    # ------------------------------------------------------------------ the same steps replayed from a HIP graph
+    # (launch overhead factored out; every replay is checked against the eager result)
+    graph_us = None
+    if not args.no_graph:
+        step(0)
+        torch.cuda.synchronize()
+        want_ids, want_lp = out_ids.clone(), out_logp.clone()
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream(dev)
+        side.wait_stream(stream)
+        nrep = 10 * len(copies)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for r in range(nrep):
+                    vt.draft_head_step(h, copies[r % len(copies)], map_, m, ws=ws, out_ids=out_ids, out_logp=out_logp)
+        torch.cuda.synchronize()
+        ok = True
+        t_best = None
+        for _ in range(5):
+            out_ids.zero_()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            g.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e3 / nrep
+            t_best = t if t_best is None else min(t_best, t)
+            ok = ok and torch.equal(out_ids, want_ids) and torch.equal(out_logp, want_lp)
+        if not ok:
+            log("HIP-graph replay disagrees with the eager step; its timing is dropped")
+        else:
+            graph_us = round(t_best, 3)
+            log(f"HIP-graph replay of {nrep} steps: {graph_us} us/step")
+
+    # ------------------------------------------------------------------ k = V control: what trimming saves
+    full = None
+    if not args.no_full_vocab:
+        Wf_np, mapf_np = synth.trimmed_head_direct(V, d, wl.seed + 17, "bf16")
+        Wf = [to_dev_bf16(Wf_np)]
+        Wf.append(Wf[0].clone())
+        mapf = torch.from_numpy(mapf_np).to(dev)
+        wsf = vt.StepWorkspace(n, V, d, m, dev)
+        ff = lambda r: vt.draft_head_step(h, Wf[r % 2], mapf, m, ws=wsf)
+        for r in range(6):
+            ff(r)
+        us_full = time_region(ff, max(20, args.steps // 3))
+        full = {"k": V, "us": round(us_full, 2), "gbps": round(V * d * 2 / us_full / 1e3, 1),
+                "frac_of_hbm_peak": round(V * d * 2 / us_full / 1e3 / HBM_PEAK_GBPS, 4),
+                "trimmed_speedup": round(us_full / us_cold, 3), "byte_ratio": round(V / k, 3)}
+        log("full-vocabulary control:", full)
+        del Wf, wsf
+
+    # ------------------------------------------------------------------ 8B-shaped tree drafting: 1000 steps, one span
+    tree = None
+    if args.tree_run:
+        dd, kk, nn, mm, nsteps = 4096, 32768, 64, 8, 1000
+        Wk_np, mapk_np = synth.trimmed_head_direct(kk, dd, 4000, "bf16")
+        cps = [to_dev_bf16(Wk_np)]
+        cps += [cps[0].clone() for _ in range(3)]
+        mapk = torch.from_numpy(mapk_np).to(dev)
+        hs = [to_dev_bf16(synth.hidden_rows(nn, dd, 4000 + j, "bf16")) for j in range(16)]
+        wsk = vt.StepWorkspace(nn, kk, dd, mm, dev)
+        ids_all = torch.empty((16, nn, mm), dtype=torch.int32, device=dev)
+        lp_all = torch.empty((16, nn, mm), dtype=torch.float32, device=dev)
+        ft = lambda r: vt.draft_head_step(hs[r % 16], cps[r % 4], mapk, mm, ws=wsk, out_ids=ids_all[r % 16],
+                                          out_logp=lp_all[r % 16])
+        for r in range(32):
+            ft(r)
+        us_tree = time_region(ft, nsteps)
+        # reproducibility: the 16 distinct results, folded into one number
+        wgt = torch.arange(1, 16 * nn * mm + 1, device=dev, dtype=torch.int64)
+        checksum = int((ids_all.flatten().to(torch.int64) * wgt).sum().item() % (2**61 - 1))
+        tree = {"workload": "llama8b tree: d=4096 k=32768 n=64 top-8, 16 h blocks cycled, 4 W_trim copies",
+                "steps": nsteps, "us_per_step": round(us_tree, 2), "total_ms": round(us_tree * nsteps / 1e3, 2),
+                "gbps": round(kk * dd * 2 / us_tree / 1e3, 1),
+                "frac_of_hbm_peak": round(kk * dd * 2 / us_tree / 1e3 / HBM_PEAK_GBPS, 4),
+                "tflops": round(2.0 * nn * kk * dd / us_tree / 1e6, 1), "ids_checksum": checksum}
+        log("tree run:", tree)
+        del cps, hs
 
     sweep = None
     if args.sweep:
@@ -236,8 +334,15 @@ def main():
             oracle.draft_head_step(h_host, W_host, map_host, m)
             reps += 1
         us_cpu = (time.time() - t0) / reps * 1e6
-        cpu = {"value": round(us_cpu, 1), "unit": "us", "cores": oracle.get_threads(), "kind": "oracle",
-               "sample": f"{reps} full draft steps of the same workload (n={n}, k={k}, d={d}, m={m}), fp64"}
+        cores = oracle.get_threads()
+        oracle.set_threads(1)
+        t1 = time.time()
+        oracle.draft_head_step(h_host, W_host, map_host, m)
+        us_cpu_1t = (time.time() - t1) * 1e6
+        oracle.set_threads(cores)
+        cpu = {"value": round(us_cpu, 1), "unit": "us", "cores": cores, "kind": "oracle",
+               "sample": f"{reps} full draft steps of the same workload (n={n}, k={k}, d={d}, m={m}), fp64",
+               "one_thread_us": round(us_cpu_1t, 1)}
         log("cpu_baseline:", cpu)
 
     gbps_cold = step_bytes / us_cold / 1e3
@@ -268,7 +373,11 @@ def main():
                      "avg_launch_us": round(us_kernel, 3)},
         "cpu_baseline": cpu,
         "calibration": calib,
+        "hip_graph_us_per_step": graph_us,
+        "full_vocab_control": full,
     }
+    if tree is not None:
+        out["tree_run"] = tree
     if sweep is not None:
         out["sweep"] = sweep
     if others is not None:

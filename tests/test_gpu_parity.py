@@ -404,3 +404,40 @@ def test_error_statuses_on_device():
     with pytest.raises(vt.VocabTrimError) as e:
         vt.build_trimmed_head(torch.zeros(10, dtype=torch.int64, device=dev()), None, 11)
     assert e.value.status == 2
+
+
+def test_step_hip_graph_replays_match_eager():
+    # the step is a plain sequence of kernel launches on the caller's stream (no allocation, no memset):
+    # captured once, every replay -- with eager steps and synchronisations in between -- gives the eager result
+    for (k, d, n, m) in ((32768, 3072, 8, 8), (4096, 1024, 40, 4)):
+        W, map_ = synth.trimmed_head_direct(k, d, seed=21, dtype="bf16")
+        dW, dmap = to_dev(W), to_dev(map_)
+        hs = [to_dev(synth.hidden_rows(n, d, seed=21 + j, dtype="bf16")) for j in range(2)]
+        ws = vt.StepWorkspace(n, k, d, m, dev())
+        oi = torch.empty((n, m), dtype=torch.int32, device=dev())
+        ol = torch.empty((n, m), dtype=torch.float32, device=dev())
+        h_in = hs[0].clone()
+        vt.draft_head_step(h_in, dW, dmap, m, ws=ws, out_ids=oi, out_logp=ol)    # warm-up outside the capture
+        torch.cuda.synchronize()
+        want = []
+        for j in range(2):
+            a, b = vt.draft_head_step(hs[j], dW, dmap, m)
+            want.append((a.clone(), b.clone()))
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream(dev())
+        side.wait_stream(torch.cuda.current_stream(dev()))
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                vt.draft_head_step(h_in, dW, dmap, m, ws=ws, out_ids=oi, out_logp=ol)
+        torch.cuda.synchronize()
+        for rep in range(6):
+            j = rep % 2
+            h_in.copy_(hs[j])
+            oi.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(oi, want[j][0]) and torch.equal(ol, want[j][1]), (k, n, rep)
+            # eager work on the same workspace between replays
+            a, b = vt.draft_head_step(hs[1 - j], dW, dmap, m, ws=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(a, want[1 - j][0])
