@@ -33,9 +33,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the step kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE),
 # scaled by the same counters on a plain copy of known size; see profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # (workload, k, n, m): FETCH_SIZE 98717.8 x 1.99975 KiB + WRITE_SIZE 211.6 KiB per launch
+    # (workload, k, n, m): FETCH_SIZE 98722.7 x 1.99975 KiB + WRITE_SIZE 201.6 KiB per launch
     # (profiles/head_gemv_kernel_llama3b_k32768_n8_m8.txt)
-    ("llama3b", 32768, 8, 8): 202_364_000,
+    ("llama3b", 32768, 8, 8): 202_365_000,
 }
 
 
@@ -127,28 +127,18 @@ def main():
         counts = torch.zeros(V, dtype=torch.int64, device=dev)
         ws_c = torch.empty(vt.load_library().vt_count_tokens_ws_bytes(V, ids.numel()), dtype=torch.uint8, device=dev)
 
-        def median_us(fn, reps):
-            # one event pair per call: the median is robust against allocator hiccups of a single call
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-            torch.cuda.synchronize()
-            for a, b in evs:
-                a.record(stream)
-                fn()
-                b.record(stream)
-            torch.cuda.synchronize()
-            t = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
-            return t[len(t) // 2]
-
+        # back-to-back calls with every buffer pre-allocated, so that the stream never waits for the host
         ws_b = torch.empty(vt.load_library().vt_build_trimmed_head_ws_bytes(V, d, k), dtype=torch.uint8, device=dev)
+        map_ = torch.empty(k, dtype=torch.int32, device=dev)
+        W_trim = torch.empty((k, d), dtype=torch.bfloat16, device=dev)
         vt.count_tokens(ids, V, counts=counts, ws=ws_c)
         counts_once = counts.clone()
-        us_count = median_us(lambda: vt.count_tokens(ids, V, counts=counts, ws=ws_c), 15)
+        us_count = time_region(lambda _: vt.count_tokens(ids, V, counts=counts, ws=ws_c), 20)
         counts.copy_(counts_once)
         for _ in range(3):
-            vt.build_trimmed_head(counts, W_full, k, ws=ws_b)
-        us_select = median_us(lambda: vt.build_trimmed_head(counts, None, k, ws=ws_b), 15)
-        us_build = median_us(lambda: vt.build_trimmed_head(counts, W_full, k, ws=ws_b), 9)
-        map_, W_trim = vt.build_trimmed_head(counts, W_full, k, ws=ws_b)
+            vt.build_trimmed_head(counts, W_full, k, ws=ws_b, out_map=map_, out_W=W_trim)
+        us_select = time_region(lambda _: vt.build_trimmed_head(counts, None, k, ws=ws_b, out_map=map_), 20)
+        us_build = time_region(lambda _: vt.build_trimmed_head(counts, W_full, k, ws=ws_b, out_map=map_, out_W=W_trim), 10)
         us_gather = us_build - us_select
         calib = {
             "count_us": round(us_count, 2), "count_ids": wl.n_ids,
@@ -156,7 +146,7 @@ def main():
             "count_id_stream_gbps": round(wl.n_ids * 4 / us_count / 1e3, 1),
             "select_us": round(us_select, 2),
             "build_us": round(us_build, 2),
-            "gather_us": round(us_gather, 2),   # build minus select (medians)
+            "gather_us": round(us_gather, 2),   # build minus select
             "gather_gbps": round(2 * step_bytes / us_gather / 1e3, 1),
             "gather_frac_of_hbm_peak": round(2 * step_bytes / us_gather / 1e3 / HBM_PEAK_GBPS, 4),
         }

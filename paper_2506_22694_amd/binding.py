@@ -128,10 +128,11 @@ def count_tokens(ids: torch.Tensor, V: int, counts: torch.Tensor | None = None,
 
 
 # --------------------------------------------------------------------------- Eq. 1
-def build_trimmed_head(counts: torch.Tensor, W: torch.Tensor | None, k: int, ws: torch.Tensor | None = None):
+def build_trimmed_head(counts: torch.Tensor, W: torch.Tensor | None, k: int, ws: torch.Tensor | None = None,
+                       out_map: torch.Tensor | None = None, out_W: torch.Tensor | None = None):
     """Top-k ids by count (ties -> lower id), ascending, and the gathered head rows.
 
-    Returns (map int32 [k], W_trim [k,d] or None).
+    Returns (map int32 [k], W_trim [k,d] or None); `out_map` / `out_W` supply the result tensors.
     """
     L = load_library()
     _require_cuda(counts, W, ws)
@@ -139,10 +140,15 @@ def build_trimmed_head(counts: torch.Tensor, W: torch.Tensor | None, k: int, ws:
         raise TypeError("counts must be int64")
     dev = counts.device
     V = counts.numel()
-    map_ = torch.empty(k, dtype=torch.int32, device=dev)
+    _require_cuda(out_map, out_W)
+    if out_map is not None and (out_map.dtype != torch.int32 or out_map.numel() != k):
+        raise ValueError("out_map must be int32 [k]")
+    map_ = out_map if out_map is not None else torch.empty(k, dtype=torch.int32, device=dev)
     if W is not None:
         d = W.shape[1]
-        W_trim = torch.empty((k, d), dtype=W.dtype, device=dev)
+        if out_W is not None and (out_W.dtype != W.dtype or tuple(out_W.shape) != (k, d)):
+            raise ValueError("out_W must be [k, d] of W's element type")
+        W_trim = out_W if out_W is not None else torch.empty((k, d), dtype=W.dtype, device=dev)
         wt = _dtype_code(W)
     else:
         d, W_trim, wt = 8, None, VT_BF16

@@ -10,6 +10,7 @@ namespace vt {
 constexpr int kHistBinsPerBlock = 32768;   // uint32 bins privatised in LDS per workgroup (128 KiB)
 constexpr int kHistMaxChunks = 64;         // id-stream chunks (partial histograms) per launch
 constexpr int kHistThreads = 1024;
+constexpr int kHistUnroll = 4;            // 16-byte id vectors in flight per thread
 
 int hist_num_ranges(int V);
 int hist_num_chunks(int64_t n_ids);

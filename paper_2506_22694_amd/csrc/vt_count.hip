@@ -50,8 +50,7 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
         }
     };
     const u32x4 *vp = reinterpret_cast<const u32x4 *>(static_cast<const char *>(ids_v) + (size_t)head * IDB);
-    for (long long v = v0 + threadIdx.x; v < v1; v += kHistThreads) {
-        const u32x4 q = __builtin_nontemporal_load(vp + v);
+    auto tally_vec = [&](const u32x4 q) {
         if constexpr (IDS64) {
             tally((long long)(((unsigned long long)q.y << 32) | q.x));
             tally((long long)(((unsigned long long)q.w << 32) | q.z));
@@ -61,7 +60,18 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
             tally((long long)(int)q.z);
             tally((long long)(int)q.w);
         }
+    };
+    // kHistUnroll vectors per thread are requested before the first is counted: one 16-byte load per
+    // thread in flight (16 KiB per CU) is far below what the memory latency needs
+    long long v = v0 + threadIdx.x;
+    for (; v + (long long)(kHistUnroll - 1) * kHistThreads < v1; v += (long long)kHistUnroll * kHistThreads) {
+        u32x4 q[kHistUnroll];
+#pragma unroll
+        for (int u = 0; u < kHistUnroll; ++u) q[u] = __builtin_nontemporal_load(vp + v + (long long)u * kHistThreads);
+#pragma unroll
+        for (int u = 0; u < kHistUnroll; ++u) tally_vec(q[u]);
     }
+    for (; v < v1; v += kHistThreads) tally_vec(__builtin_nontemporal_load(vp + v));
     if (chunk == 0 && (int)threadIdx.x < head) {   // scalar head
         if constexpr (IDS64) tally(static_cast<const long long *>(ids_v)[threadIdx.x]);
         else tally((long long)static_cast<const int *>(ids_v)[threadIdx.x]);
@@ -88,7 +98,15 @@ __global__ void __launch_bounds__(256) hist_reduce_kernel(const unsigned *__rest
     const int v = blockIdx.x * 256 + threadIdx.x;
     if (v >= V) return;
     long long s = 0;
-    for (int c = 0; c < nchunks; ++c) s += (long long)partial[(size_t)c * V + v];
+    int c = 0;
+    for (; c + 8 <= nchunks; c += 8) {
+        unsigned t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = partial[(size_t)(c + u) * V + v];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (long long)t[u];
+    }
+    for (; c < nchunks; ++c) s += (long long)partial[(size_t)c * V + v];
     counts[v] += s;
 }
 
