@@ -14,6 +14,8 @@ import subprocess
 
 import numpy as np
 
+from .tree import tree_expand, tree_rerank  # noqa: F401  (numpy-only oracle of the tree selection steps)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "vt_oracle.c")
 _LIB = os.path.join(_HERE, "libvt_oracle.so")

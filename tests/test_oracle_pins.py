@@ -329,3 +329,71 @@ def test_bf16_rounding_is_nearest_even():
     assert np.array_equal(synth.f32_to_bf16_bits(x), ref)
     assert np.array_equal(synth.bf16_bits_to_f32(ref),
                           torch.from_numpy(ref.view(np.int16)).view(torch.bfloat16).float().numpy())
+
+
+# ----------------------------------------------------------------------------- draft-tree selection (Sec. 4.1)
+def _brute_topk(scores, K):
+    """K rounds of 'take the best remaining': no sort, no key function."""
+    left = list(range(len(scores)))
+    out = []
+    for _ in range(K):
+        best = left[0]
+        for c in left[1:]:
+            if scores[c] > scores[best]:      # strict: the earlier index keeps a tie
+                best = c
+        out.append(best)
+        left.remove(best)
+    return out
+
+
+def test_tree_expand_matches_round_by_round_extraction():
+    rng = np.random.default_rng(11)
+    for (n, m, K) in ((1, 1, 1), (8, 8, 8), (3, 5, 15), (16, 4, 7)):
+        cum = rng.normal(-3, 1, size=n).astype(np.float32)
+        lp = -np.abs(rng.normal(0, 2, size=(n, m))).astype(np.float32)
+        ids = rng.integers(0, 128256, size=(n, m)).astype(np.int32)
+        parent, token, score = oracle.tree_expand(cum, lp, ids, K)
+        flat = [np.float32(cum[c // m]) + np.float32(lp[c // m, c % m]) for c in range(n * m)]
+        want = _brute_topk(flat, K)
+        assert parent.tolist() == [c // m for c in want]
+        assert token.tolist() == [int(ids[c // m, c % m]) for c in want]
+        assert score.tolist() == [float(flat[c]) for c in want]
+        assert all(score[r] >= score[r + 1] for r in range(K - 1))
+
+
+def test_tree_expand_worked_example_and_ties():
+    # two frontier nodes, three children each; by hand: scores
+    #   node 0: -1.0 + (-0.5, -1.5, -3.0) = -1.5, -2.5, -4.0
+    #   node 1: -2.0 + (-0.5, -0.5, -2.5) = -2.5, -2.5, -4.5
+    cum = np.array([-1.0, -2.0], dtype=np.float32)
+    lp = np.array([[-0.5, -1.5, -3.0], [-0.5, -0.5, -2.5]], dtype=np.float32)
+    ids = np.array([[10, 11, 12], [20, 21, 22]], dtype=np.int32)
+    parent, token, score = oracle.tree_expand(cum, lp, ids, 4)
+    # three candidates tie at -2.5: flat indices 1, 3, 4 in that order
+    assert parent.tolist() == [0, 0, 1, 1] and token.tolist() == [10, 11, 20, 21]
+    assert score.tolist() == [-1.5, -2.5, -2.5, -2.5]
+    # signed zeros compare equal: the lower index wins
+    p2, t2, _ = oracle.tree_expand(np.array([0.0], dtype=np.float32), np.array([[-0.0, 0.0]], dtype=np.float32),
+                                   np.array([[7, 8]], dtype=np.int32), 1)
+    assert p2.tolist() == [0] and t2.tolist() == [7]
+    # the score is a single fp32 addition: 1 + 2^-24 rounds to 1 in fp32 (it would not in fp64)
+    _, _, s3 = oracle.tree_expand(np.array([1.0], dtype=np.float32), np.array([[2.0 ** -24]], dtype=np.float32),
+                                  np.array([[0]], dtype=np.int32), 1)
+    assert s3[0] == np.float32(1.0)
+
+
+def test_tree_rerank_properties():
+    rng = np.random.default_rng(12)
+    for (N, T) in ((1, 1), (136, 32), (392, 60), (50, 50)):
+        cum = rng.normal(-5, 2, size=N).astype(np.float32)
+        cum[::7] = cum[0]                      # plant ties
+        idx = oracle.tree_rerank(cum, T)
+        assert idx.tolist() == sorted(_brute_topk(cum.tolist(), T))
+        assert np.all(np.diff(idx) > 0)
+        kept = set(idx.tolist())
+        worst_kept = min(cum[i] for i in kept)
+        assert all(cum[i] <= worst_kept for i in range(N) if i not in kept)
+    # T = N keeps everything, in index order
+    assert oracle.tree_rerank(np.array([3, 1, 2], dtype=np.float32), 3).tolist() == [0, 1, 2]
+    # all equal: the lowest indices
+    assert oracle.tree_rerank(np.zeros(10, dtype=np.float32), 4).tolist() == [0, 1, 2, 3]
