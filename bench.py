@@ -262,6 +262,51 @@ def main():
         log("tree run:", tree)
         del cps, hs
 
+    # ------------------------------------------------------------------ draft-tree selection behind the step
+    # (the paper's tree: 8 frontier nodes x top-8 -> keep 8 per level; rerank 8 + 64 + 64 nodes -> 32; the
+    # depth-7 ablation reranks 392 -> 60).  Replayed from a HIP graph: these kernels run a few microseconds,
+    # less than a Python call.
+    tree_sel = None
+    if not args.no_graph:
+        def replay_us(fn, reps=50):
+            fn()
+            torch.cuda.synchronize()
+            g2 = torch.cuda.CUDAGraph()
+            s2 = torch.cuda.Stream(dev)
+            s2.wait_stream(stream)
+            with torch.cuda.stream(s2):
+                with torch.cuda.graph(g2, stream=s2):
+                    for _ in range(reps):
+                        fn()
+            torch.cuda.synchronize()
+            best = None
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                g2.replay()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                t = e0.elapsed_time(e1) * 1e3 / reps
+                best = t if best is None else min(best, t)
+            return round(best, 3)
+
+        step(0)
+        cum8 = torch.linspace(-0.5, -4.0, n, device=dev)
+        o3 = (torch.empty(8, dtype=torch.int32, device=dev), torch.empty(8, dtype=torch.int32, device=dev),
+              torch.empty(8, dtype=torch.float32, device=dev))
+        gen = torch.Generator(device="cpu").manual_seed(5)
+        c136 = (torch.randn(136, generator=gen) * 2 - 6).to(dev)
+        c392 = (torch.randn(392, generator=gen) * 2 - 6).to(dev)
+        o60 = torch.empty(60, dtype=torch.int32, device=dev)
+        tree_sel = {
+            "expand_n8_m8_K8_us": replay_us(lambda: vt.tree_expand(cum8, out_logp, out_ids, min(8, n * m), out=o3)),
+            "rerank_N136_T32_us": replay_us(lambda: vt.tree_rerank(c136, 32, out=o60)),
+            "rerank_N392_T60_us": replay_us(lambda: vt.tree_rerank(c392, 60, out=o60)),
+            "step_plus_expand_us": replay_us(lambda: (step(0), vt.tree_expand(cum8, out_logp, out_ids, min(8, n * m),
+                                                                             out=o3)), reps=30),
+        }
+        log("tree selection (HIP-graph replay):", tree_sel)
+
     sweep = None
     if args.sweep:
         sweep = []
@@ -365,6 +410,7 @@ def main():
         "calibration": calib,
         "hip_graph_us_per_step": graph_us,
         "full_vocab_control": full,
+        "tree_selection": tree_sel,
     }
     if tree is not None:
         out["tree_run"] = tree

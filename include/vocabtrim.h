@@ -154,6 +154,42 @@ size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m);
  * allocating the workspace, and again only if a step was aborted mid-flight. */
 int vt_draft_head_step_ws_init(void *ws, size_t ws_bytes, void *stream);
 
+/* ------------------------------------------------------------------------
+ * Draft-tree growth on top of the draft step (experimental settings, "Draft
+ * Tree": EAGLE-2 style tree of depth 3 with top-K = 8 per level and at most
+ * 32 draft tokens; the depth ablation keeps 60).  Selection arithmetic only;
+ * verification against a target model is the caller's.
+ *
+ * vt_tree_expand -- one level: candidate (i, j) = token step_ids[i, j] under
+ *   frontier node i scores parent_cum[i] + step_logp[i, j] (ONE fp32 addition);
+ *   the K best candidates, best first, are the next frontier.  Equal scores
+ *   (-0.0 == +0.0) go to the lower flat index i * m + j.
+ *     parent_cum  [n] fp32, device: cumulative log-prob of the frontier nodes
+ *     step_logp   [n, m] fp32, device  (vt_draft_head_step's out_logp)
+ *     step_ids    [n, m] int32, device (vt_draft_head_step's out_ids)
+ *     n, m        1 <= n, 1 <= m, n * m <= VT_TREE_MAX_CANDIDATES
+ *     K           1 <= K <= n * m
+ *     out_parent  [K] int32, device, out: frontier index i of each survivor
+ *     out_token   [K] int32, device, out: its token id
+ *     out_cum     [K] fp32, device, out: its cumulative log-prob (a sum of -0.0 is
+ *                 returned as +0.0)
+ *
+ * vt_tree_rerank -- the T best of N cumulative scores; their node indices in
+ *   ASCENDING order (parents before children when nodes are numbered in the
+ *   order they were drafted).  Equal scores go to the lower index.
+ *     cum      [N] fp32, device;  1 <= N <= VT_TREE_MAX_CANDIDATES
+ *     T        1 <= T <= min(N, VT_TREE_MAX_KEEP)
+ *     out_idx  [T] int32, device, out
+ *
+ * Neither call needs a workspace; both enqueue one small kernel on `stream`.
+ * ---------------------------------------------------------------------- */
+#define VT_TREE_MAX_CANDIDATES 16384
+#define VT_TREE_MAX_KEEP 1024
+int vt_tree_expand(const float *parent_cum, const float *step_logp, const int32_t *step_ids, int32_t n,
+                   int32_t m, int32_t K, int32_t *out_parent, int32_t *out_token, float *out_cum,
+                   void *stream);
+int vt_tree_rerank(const float *cum, int32_t N, int32_t T, int32_t *out_idx, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,9 @@ EXPORTS = (
     "vt_count_tokens", "vt_count_tokens_ws_bytes",
     "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes",
     "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
+    "vt_tree_expand", "vt_tree_rerank",
 )
+VT_TREE_MAX_CANDIDATES, VT_TREE_MAX_KEEP = 16384, 1024
 
 _lib = None
 
@@ -58,6 +60,10 @@ def load_library() -> ctypes.CDLL:
     L.vt_draft_head_step_ws_bytes.restype = sz
     L.vt_draft_head_step_ws_init.argtypes = [vp, sz, vp]
     L.vt_draft_head_step_ws_init.restype = ci
+    L.vt_tree_expand.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
+    L.vt_tree_expand.restype = ci
+    L.vt_tree_rerank.argtypes = [vp, i32, i32, vp, vp]
+    L.vt_tree_rerank.restype = ci
     _lib = L
     return L
 
@@ -204,3 +210,45 @@ def draft_head_step(h: torch.Tensor, W_trim: torch.Tensor, map_: torch.Tensor, m
     if return_full:
         res.append(full)
     return tuple(res)
+
+
+# --------------------------------------------------------------------------- draft-tree selection (Sec. 4.1)
+def tree_expand(parent_cum: torch.Tensor, step_logp: torch.Tensor, step_ids: torch.Tensor, K: int, out=None):
+    """Next frontier of the draft tree: (parent int32 [K], token int32 [K], cum fp32 [K]), best first.
+
+    `out` = (parent, token, cum) supplies the result tensors."""
+    L = load_library()
+    _require_cuda(parent_cum, step_logp, step_ids)
+    if parent_cum.dtype != torch.float32 or step_logp.dtype != torch.float32 or step_ids.dtype != torch.int32:
+        raise TypeError("parent_cum / step_logp must be float32 and step_ids int32")
+    n, m = step_logp.shape
+    if tuple(step_ids.shape) != (n, m) or parent_cum.numel() != n:
+        raise ValueError("shape mismatch between parent_cum, step_logp and step_ids")
+    dev = step_logp.device
+    if out is not None:
+        parent, token, cum = out
+        _require_cuda(parent, token, cum)
+        if (parent.dtype, token.dtype, cum.dtype) != (torch.int32, torch.int32, torch.float32) or \
+                min(parent.numel(), token.numel(), cum.numel()) < K:
+            raise ValueError("out must be (int32 [K], int32 [K], float32 [K])")
+    else:
+        parent = torch.empty(K, dtype=torch.int32, device=dev)
+        token = torch.empty(K, dtype=torch.int32, device=dev)
+        cum = torch.empty(K, dtype=torch.float32, device=dev)
+    _check(L.vt_tree_expand(_ptr(parent_cum), _ptr(step_logp), _ptr(step_ids), n, m, K, _ptr(parent), _ptr(token),
+                            _ptr(cum), _stream(dev)))
+    return parent, token, cum
+
+
+def tree_rerank(cum: torch.Tensor, T: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Indices (int32 [T], ascending) of the T best cumulative scores."""
+    L = load_library()
+    _require_cuda(cum)
+    if cum.dtype != torch.float32 or cum.dim() != 1:
+        raise TypeError("cum must be a float32 vector")
+    if out is None:
+        out = torch.empty(T, dtype=torch.int32, device=cum.device)
+    elif not out.is_cuda or out.dtype != torch.int32 or out.numel() < T:
+        raise ValueError("out must be a device int32 tensor of at least T elements")
+    _check(L.vt_tree_rerank(_ptr(cum), cum.numel(), T, _ptr(out), _stream(cum.device)))
+    return out

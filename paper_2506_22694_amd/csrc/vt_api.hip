@@ -6,6 +6,7 @@
 
 #include "vt_build.h"
 #include "vt_step.h"
+#include "vt_tree.h"
 
 namespace {
 
@@ -310,6 +311,42 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
     if (out_logp_full != nullptr)
         vt::launch_sub_lse(out_logp_full, lse_buf, n, k, st);
     return launch_status();
+}
+
+int vt_tree_expand(const float *parent_cum, const float *step_logp, const int32_t *step_ids, int32_t n, int32_t m,
+                   int32_t K, int32_t *out_parent, int32_t *out_token, float *out_cum, void *stream) {
+    if (!parent_cum || !step_logp || !step_ids || !out_parent || !out_token || !out_cum) return VT_ERR_NULL;
+    if (n < 1 || m < 1 || (int64_t)n * m > VT_TREE_MAX_CANDIDATES || K < 1 || K > n * m) return VT_ERR_SHAPE;
+    vt::TreeArgs a;
+    a.parent_cum = parent_cum;
+    a.vals = step_logp;
+    a.ids = step_ids;
+    a.N = n * m;
+    a.m = m;
+    a.K = K;
+    a.index_order = 0;
+    a.out_a = out_parent;
+    a.out_token = out_token;
+    a.out_score = out_cum;
+    return device_status(vt::launch_tree_select(a, static_cast<hipStream_t>(stream)));
+}
+
+int vt_tree_rerank(const float *cum, int32_t N, int32_t T, int32_t *out_idx, void *stream) {
+    if (!cum || !out_idx) return VT_ERR_NULL;
+    if (N < 1 || N > VT_TREE_MAX_CANDIDATES || T < 1 || T > N || T > VT_TREE_MAX_KEEP) return VT_ERR_SHAPE;
+    static_assert(VT_TREE_MAX_CANDIDATES == vt::kTreeMaxN && VT_TREE_MAX_KEEP == vt::kTreeMaxKeepSorted, "limits");
+    vt::TreeArgs a;
+    a.parent_cum = nullptr;
+    a.vals = cum;
+    a.ids = nullptr;
+    a.N = N;
+    a.m = 1;
+    a.K = T;
+    a.index_order = 1;
+    a.out_a = out_idx;
+    a.out_token = nullptr;
+    a.out_score = nullptr;
+    return device_status(vt::launch_tree_select(a, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

@@ -115,6 +115,24 @@ def test_draft_head_step_argument_errors(lib):
     assert lib.vt_draft_head_step_ws_init(A, 8, None) == 5
 
 
+def test_tree_selection_argument_errors(lib):
+    f = lib.vt_tree_expand
+    ok = (A, A, A, 8, 8, 8, A, A, A, None)
+    for pos in (0, 1, 2, 6, 7, 8):
+        bad = list(ok)
+        bad[pos] = None
+        assert f(*bad) == 1, pos
+    assert f(A, A, A, 0, 8, 1, A, A, A, None) == 2
+    assert f(A, A, A, 8, 0, 1, A, A, A, None) == 2
+    assert f(A, A, A, 8, 8, 0, A, A, A, None) == 2
+    assert f(A, A, A, 8, 8, 65, A, A, A, None) == 2          # K > n * m
+    assert f(A, A, A, 257, 64, 8, A, A, A, None) == 2        # n * m above the limit
+    g = lib.vt_tree_rerank
+    assert g(None, 10, 5, A, None) == 1 and g(A, 10, 5, None, None) == 1
+    assert g(A, 0, 1, A, None) == 2 and g(A, 10, 0, A, None) == 2 and g(A, 10, 11, A, None) == 2
+    assert g(A, 16385, 8, A, None) == 2 and g(A, 4096, 1025, A, None) == 2
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):

@@ -441,3 +441,56 @@ def test_step_hip_graph_replays_match_eager():
             a, b = vt.draft_head_step(hs[1 - j], dW, dmap, m, ws=ws)
             torch.cuda.synchronize()
             assert torch.equal(a, want[1 - j][0])
+
+
+# ----------------------------------------------------------------------------- draft-tree selection (Sec. 4.1)
+def _tree_inputs(n, m, seed, ties=False):
+    rng = np.random.default_rng(seed)
+    cum = rng.normal(-3, 1.5, size=n).astype(np.float32)
+    lp = -np.sort(np.abs(rng.normal(0, 2.5, size=(n, m))).astype(np.float32), axis=1)   # descending per row
+    ids = rng.integers(0, 128256, size=(n, m)).astype(np.int32)
+    if ties:
+        cum[:] = np.round(cum)
+        lp[:] = np.round(lp)
+        lp[0, 0] = -0.0
+    return cum, lp, ids
+
+
+@pytest.mark.parametrize("n,m,K", [(1, 1, 1), (8, 8, 8), (8, 8, 64), (3, 5, 7), (16, 64, 32), (64, 8, 8),
+                                   (100, 10, 37), (33, 64, 500), (256, 16, 16), (256, 64, 64), (250, 60, 1000)])
+def test_tree_expand_exact(n, m, K):
+    for ties in (False, True):
+        cum, lp, ids = _tree_inputs(n, m, seed=n * 1000 + m + K, ties=ties)
+        parent, token, score = vt.tree_expand(to_dev(cum), to_dev(lp), to_dev(ids), K)
+        torch.cuda.synchronize()
+        rp, rt, rs = oracle.tree_expand(cum, lp, ids, K)
+        assert np.array_equal(parent.cpu().numpy(), rp), (n, m, K, ties)
+        assert np.array_equal(token.cpu().numpy(), rt)
+        assert np.array_equal(score.cpu().numpy(), rs)   # the same fp32 sum (a -0.0 comes back as +0.0)
+
+
+@pytest.mark.parametrize("N,T", [(1, 1), (64, 8), (136, 32), (392, 60), (1000, 1000), (1024, 17), (1025, 32),
+                                 (5000, 1024), (16384, 60), (16384, 1024), (3000, 1)])
+def test_tree_rerank_exact(N, T):
+    rng = np.random.default_rng(N + T)
+    for ties in (False, True):
+        cum = rng.normal(-6, 2, size=N).astype(np.float32)
+        if ties:
+            cum = np.round(cum)
+        idx = vt.tree_rerank(to_dev(cum), T)
+        torch.cuda.synchronize()
+        assert np.array_equal(idx.cpu().numpy(), oracle.tree_rerank(cum, T)), (N, T, ties)
+
+
+def test_tree_after_draft_step_end_to_end():
+    # the paper's tree shape: 8 frontier nodes, top-8 each, keep 8; fed by the real draft step
+    k, d, n, m = 32768, 3072, 8, 8
+    W, map_ = synth.trimmed_head_direct(k, d, seed=31, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=31, dtype="bf16")
+    oi, ol = run_step(h, W, map_, m)
+    cum = np.linspace(-0.5, -4.0, n).astype(np.float32)
+    parent, token, score = vt.tree_expand(to_dev(cum), ol, oi, 8)
+    torch.cuda.synchronize()
+    rp, rt, rs = oracle.tree_expand(cum, ol.cpu().numpy(), oi.cpu().numpy(), 8)
+    assert np.array_equal(parent.cpu().numpy(), rp) and np.array_equal(token.cpu().numpy(), rt)
+    assert np.array_equal(score.cpu().numpy(), rs)
