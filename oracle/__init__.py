@@ -14,6 +14,7 @@ import subprocess
 
 import numpy as np
 
+from .selection import choose_k_min_count, choose_k_top_p, rank_order  # noqa: F401
 from .tree import tree_expand, tree_rerank  # noqa: F401  (numpy-only oracle of the tree selection steps)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -397,3 +397,51 @@ def test_tree_rerank_properties():
     assert oracle.tree_rerank(np.array([3, 1, 2], dtype=np.float32), 3).tolist() == [0, 1, 2]
     # all equal: the lowest indices
     assert oracle.tree_rerank(np.zeros(10, dtype=np.float32), 4).tolist() == [0, 1, 2, 3]
+
+
+# ----------------------------------------------------------------------------- Sec. 3.2: other selection criteria
+def test_rank_order_prefixes_are_the_top_k_selections():
+    rng = np.random.default_rng(31)
+    for V in (1, 2, 9, 40):
+        for hi in (3, 10**12):
+            c = rng.integers(0, hi, size=V).astype(np.int64)
+            ro = oracle.rank_order(c)
+            assert sorted(ro.tolist()) == list(range(V))
+            for j in range(V - 1):                       # adjacent pairs obey (count desc, id asc)
+                a, b = int(ro[j]), int(ro[j + 1])
+                assert c[a] > c[b] or (c[a] == c[b] and a < b)
+            for k in range(1, V + 1):                    # every prefix is Eq. 1's Top-K(c, k)
+                assert sorted(ro[:k].tolist()) == _selected_by_definition(c.tolist(), k)
+                assert np.array_equal(oracle.select(c, k, return_rank_order=True)[1], ro[:k])
+
+
+def test_choose_k_worked_examples():
+    c = np.array([5, 0, 50, 20, 20, 5], dtype=np.int64)          # total 100; sorted: 50 20 20 5 5 0
+    assert oracle.choose_k_top_p(c, 0.5) == (1, 50, 100)
+    assert oracle.choose_k_top_p(c, 0.51) == (2, 70, 100)
+    assert oracle.choose_k_top_p(c, 0.9) == (3, 90, 100)
+    assert oracle.choose_k_top_p(c, 0.95) == (4, 95, 100)
+    assert oracle.choose_k_top_p(c, 1.0) == (5, 100, 100)        # the zero-count id is never needed
+    assert oracle.choose_k_top_p(c, 0.0) == (1, 50, 100)         # k >= 1
+    assert oracle.choose_k_top_p(np.zeros(4, dtype=np.int64), 0.9) == (1, 0, 0)
+    assert oracle.choose_k_min_count(c, 5) == (5, 100, 100)
+    assert oracle.choose_k_min_count(c, 6) == (3, 90, 100)
+    assert oracle.choose_k_min_count(c, 51) == (0, 0, 100)
+    assert oracle.choose_k_min_count(c, 0) == (6, 100, 100)
+
+
+def test_choose_k_against_library_cumsum_and_the_stated_zipf_coverage():
+    ids = synth.zipf_ids(2_000_000, 128256, 1.1, seed=2000, permute=True)
+    c = np.bincount(ids, minlength=128256).astype(np.int64)
+    srt = np.sort(c)[::-1]
+    cs = np.cumsum(srt)
+    for P in (0.1, 0.5, 0.9, 0.94, 0.999, 1.0):
+        k, cov, tot = oracle.choose_k_top_p(c, P)
+        assert tot == 2_000_000 and cov == cs[k - 1]
+        assert cs[k - 1] >= P * tot and (k == 1 or cs[k - 2] < P * tot)
+    for f in (1, 2, 14, 1000):
+        k, cov, tot = oracle.choose_k_min_count(c, f)
+        assert k == int((c >= f).sum()) and cov == int(c[c >= f].sum())
+    # finite Zipf(1.1) over 128256 ids: the 32768 most frequent carry about 94 % of the mass
+    cov32k = cs[32767] / cs[-1]
+    assert 0.93 < cov32k < 0.95
