@@ -118,6 +118,40 @@ int vt_build_trimmed_head(const int64_t *counts, int32_t V, const void *W, int w
 size_t vt_build_trimmed_head_ws_bytes(int32_t V, int32_t d, int32_t k);
 
 /* ------------------------------------------------------------------------
+ * The same build with the rows in FREQUENCY-RANK order: map (and W_trim's
+ * rows) sorted by (count descending, id ascending), the order in which
+ * Top-K(c, k) takes ids.  Every prefix of the result is the trimmed head for
+ * a smaller k, so one build at the largest k of interest serves a whole
+ * ablation over k by pointer arithmetic; the draft step breaks ties of equal
+ * logits by target id, so it accepts either order.  Arguments, errors and
+ * workspace size as for vt_build_trimmed_head.
+ * ---------------------------------------------------------------------- */
+int vt_build_trimmed_head_by_rank(const int64_t *counts, int32_t V, const void *W, int w_type, int32_t d,
+                                  int32_t k, int32_t *map, void *W_trim, void *ws, size_t ws_bytes,
+                                  void *stream);
+
+/* ------------------------------------------------------------------------
+ * Choosing k from the counts instead of fixing it (the method section notes
+ * that Top-P over the counts or a minimum-frequency threshold can replace a
+ * fixed k):
+ *
+ *   VT_K_TOP_P      smallest k >= 1 whose k most frequent ids carry at least
+ *                   p of all counted tokens: S_k >= ceil(p * S_V), S_k = sum of
+ *                   the k largest counts, p * S_V one fp64 product; 0 <= p <= 1
+ *   VT_K_MIN_COUNT  k = number of ids with count >= min_count (may be 0)
+ *
+ *   counts  [V] int64, device (values >= 0)
+ *   out     [3] int64, device, out: k, S_k (tokens covered), S_V (all tokens);
+ *           S_k / S_V is the coverage of the calibration set.  The caller reads
+ *           k back (one small copy) before sizing W_trim for the build.
+ *   ws      >= vt_choose_k_ws_bytes(V) bytes; no initialisation
+ * ---------------------------------------------------------------------- */
+typedef enum { VT_K_TOP_P = 0, VT_K_MIN_COUNT = 1 } vt_kmode;
+int vt_choose_k(const int64_t *counts, int32_t V, int mode, double p, int64_t min_count, int64_t *out,
+                void *ws, size_t ws_bytes, void *stream);
+size_t vt_choose_k_ws_bytes(int32_t V);
+
+/* ------------------------------------------------------------------------
  * Algorithm 2, drafting lines -- one draft step of the trimmed LM head.
  *
  *   z[i, j]   = sum_t h[i, t] * W_trim[j, t]            (never stored unless asked)

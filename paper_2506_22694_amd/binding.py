@@ -22,7 +22,8 @@ VT_MAX_TOP_M = 64
 EXPORTS = (
     "vt_status_string", "vt_last_device_error",
     "vt_count_tokens", "vt_count_tokens_ws_bytes",
-    "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes",
+    "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes", "vt_build_trimmed_head_by_rank",
+    "vt_choose_k", "vt_choose_k_ws_bytes",
     "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
     "vt_tree_expand", "vt_tree_rerank",
 )
@@ -54,6 +55,12 @@ def load_library() -> ctypes.CDLL:
     L.vt_build_trimmed_head.restype = ci
     L.vt_build_trimmed_head_ws_bytes.argtypes = [i32, i32, i32]
     L.vt_build_trimmed_head_ws_bytes.restype = sz
+    L.vt_build_trimmed_head_by_rank.argtypes = [vp, i32, vp, ci, i32, i32, vp, vp, vp, sz, vp]
+    L.vt_build_trimmed_head_by_rank.restype = ci
+    L.vt_choose_k.argtypes = [vp, i32, ci, ctypes.c_double, i64, vp, vp, sz, vp]
+    L.vt_choose_k.restype = ci
+    L.vt_choose_k_ws_bytes.argtypes = [i32]
+    L.vt_choose_k_ws_bytes.restype = sz
     L.vt_draft_head_step.argtypes = [vp, ci, i32, vp, ci, i32, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     L.vt_draft_head_step.restype = ci
     L.vt_draft_head_step_ws_bytes.argtypes = [i32, i32, i32, i32]
@@ -135,11 +142,15 @@ def count_tokens(ids: torch.Tensor, V: int, counts: torch.Tensor | None = None,
 
 # --------------------------------------------------------------------------- Eq. 1
 def build_trimmed_head(counts: torch.Tensor, W: torch.Tensor | None, k: int, ws: torch.Tensor | None = None,
-                       out_map: torch.Tensor | None = None, out_W: torch.Tensor | None = None):
-    """Top-k ids by count (ties -> lower id), ascending, and the gathered head rows.
+                       out_map: torch.Tensor | None = None, out_W: torch.Tensor | None = None, order: str = "id"):
+    """Top-k ids by count (ties -> lower id) and the gathered head rows.
 
-    Returns (map int32 [k], W_trim [k,d] or None); `out_map` / `out_W` supply the result tensors.
+    order="id": ascending target id; order="rank": (count descending, id ascending), every prefix being
+    the build for a smaller k.  Returns (map int32 [k], W_trim [k,d] or None); `out_map` / `out_W` supply
+    the result tensors.
     """
+    if order not in ("id", "rank"):
+        raise ValueError("order must be 'id' or 'rank'")
     L = load_library()
     _require_cuda(counts, W, ws)
     if counts.dtype != torch.int64:
@@ -160,9 +171,33 @@ def build_trimmed_head(counts: torch.Tensor, W: torch.Tensor | None, k: int, ws:
         d, W_trim, wt = 8, None, VT_BF16
     if ws is None:
         ws = _scratch(L.vt_build_trimmed_head_ws_bytes(V, d, k), dev)
-    _check(L.vt_build_trimmed_head(_ptr(counts), V, _ptr(W), wt, d, k, _ptr(map_), _ptr(W_trim), _ptr(ws),
-                                   ws.numel(), _stream(dev)))
+    fn = L.vt_build_trimmed_head if order == "id" else L.vt_build_trimmed_head_by_rank
+    _check(fn(_ptr(counts), V, _ptr(W), wt, d, k, _ptr(map_), _ptr(W_trim), _ptr(ws), ws.numel(), _stream(dev)))
     return map_, W_trim
+
+
+VT_K_TOP_P, VT_K_MIN_COUNT = 0, 1
+
+
+def choose_k(counts: torch.Tensor, top_p: float | None = None, min_count: int | None = None,
+             ws: torch.Tensor | None = None):
+    """k from the counts (Top-P mass or minimum count).  Returns host ints (k, covered, total); synchronises."""
+    L = load_library()
+    _require_cuda(counts, ws)
+    if counts.dtype != torch.int64:
+        raise TypeError("counts must be int64")
+    if (top_p is None) == (min_count is None):
+        raise ValueError("give exactly one of top_p and min_count")
+    dev = counts.device
+    V = counts.numel()
+    if ws is None:
+        ws = _scratch(L.vt_choose_k_ws_bytes(V), dev)
+    out = torch.empty(3, dtype=torch.int64, device=dev)
+    mode = VT_K_TOP_P if top_p is not None else VT_K_MIN_COUNT
+    _check(L.vt_choose_k(_ptr(counts), V, mode, float(top_p or 0.0), int(min_count or 0), _ptr(out), _ptr(ws),
+                         ws.numel(), _stream(dev)))
+    k, cov, tot = (int(x) for x in out.cpu().tolist())
+    return k, cov, tot
 
 
 # --------------------------------------------------------------------------- Alg. 2, drafting lines

@@ -177,8 +177,9 @@ int vt_count_tokens(const void *ids, int id_type, int64_t n_ids, int32_t V, int6
 size_t vt_build_trimmed_head_ws_bytes(int32_t V, int32_t d, int32_t k) {
     (void)V;
     (void)d;
-    (void)k;
-    return 256;   // the select kernel keeps its state in LDS; a token amount keeps the contract uniform
+    if (k < 1) return 256;
+    // rank-ordered build: the id-ordered selection, then the sort's ping-pong buffers
+    return 256 + round_up((size_t)k * sizeof(int32_t), 256) + vt::rank_sort_scratch_bytes(k);
 }
 
 int vt_build_trimmed_head(const int64_t *counts, int32_t V, const void *W, int w_type, int32_t d, int32_t k,
@@ -196,6 +197,55 @@ int vt_build_trimmed_head(const int64_t *counts, int32_t V, const void *W, int w
     hipStream_t st = static_cast<hipStream_t>(stream);
     vt::launch_select_topk(reinterpret_cast<const long long *>(counts), V, k, map, st);
     if (W != nullptr) vt::launch_gather_rows(W, row_bytes, map, k, W_trim, st);
+    return launch_status();
+}
+
+int vt_build_trimmed_head_by_rank(const int64_t *counts, int32_t V, const void *W, int w_type, int32_t d, int32_t k,
+                                  int32_t *map, void *W_trim, void *ws, size_t ws_bytes, void *stream) {
+    if (w_type != VT_F32 && w_type != VT_BF16) return VT_ERR_DTYPE;
+    if (V <= 0 || d <= 0 || k < 1 || k > V) return VT_ERR_SHAPE;
+    if (counts == nullptr || map == nullptr) return VT_ERR_NULL;
+    if ((W == nullptr) != (W_trim == nullptr)) return VT_ERR_NULL;
+    const size_t row_bytes = (size_t)d * elem_size(w_type);
+    if (!aligned(counts, 8) || !aligned(map, 4)) return VT_ERR_ALIGN;
+    if (W != nullptr && ((row_bytes & 15) != 0 || !aligned(W, 16) || !aligned(W_trim, 16))) return VT_ERR_ALIGN;
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < vt_build_trimmed_head_ws_bytes(V, d, k))
+        return VT_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *wsb = static_cast<char *>(ws);
+    int *by_id = reinterpret_cast<int *>(wsb + 256);
+    void *scratch = wsb + 256 + round_up((size_t)k * sizeof(int32_t), 256);
+    const long long *c = reinterpret_cast<const long long *>(counts);
+    vt::launch_select_topk(c, V, k, by_id, st);
+    vt::launch_rank_sort(c, by_id, k, scratch, map, nullptr, st);
+    if (W != nullptr) vt::launch_gather_rows(W, row_bytes, map, k, W_trim, st);
+    return launch_status();
+}
+
+size_t vt_choose_k_ws_bytes(int32_t V) {
+    if (V < 1) return 256;
+    return round_up((size_t)V * sizeof(int32_t), 256) + round_up((size_t)V * sizeof(int64_t), 256) +
+           vt::rank_sort_scratch_bytes(V);
+}
+
+int vt_choose_k(const int64_t *counts, int32_t V, int mode, double p, int64_t min_count, int64_t *out, void *ws,
+                size_t ws_bytes, void *stream) {
+    if (mode != VT_K_TOP_P && mode != VT_K_MIN_COUNT) return VT_ERR_DTYPE;
+    if (V <= 0) return VT_ERR_SHAPE;
+    if (mode == VT_K_TOP_P && !(p >= 0.0 && p <= 1.0)) return VT_ERR_SHAPE;
+    if (counts == nullptr || out == nullptr) return VT_ERR_NULL;
+    if (!aligned(counts, 8) || !aligned(out, 8)) return VT_ERR_ALIGN;
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < vt_choose_k_ws_bytes(V)) return VT_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *wsb = static_cast<char *>(ws);
+    int *ids = reinterpret_cast<int *>(wsb);
+    long long *sorted = reinterpret_cast<long long *>(wsb + round_up((size_t)V * sizeof(int32_t), 256));
+    void *scratch = wsb + round_up((size_t)V * sizeof(int32_t), 256) + round_up((size_t)V * sizeof(int64_t), 256);
+    const long long *c = reinterpret_cast<const long long *>(counts);
+    vt::launch_rank_sort(c, nullptr, V, scratch, ids, sorted, st);
+    vt::launch_choose_k(sorted, V, mode, p, (long long)min_count, reinterpret_cast<long long *>(out), st);
     return launch_status();
 }
 

@@ -24,4 +24,14 @@ constexpr int kSelectThreads = 1024;
 void launch_select_topk(const long long *counts, int V, int k, int *map, hipStream_t st);
 void launch_gather_rows(const void *W, size_t row_bytes, const int *map, int k, void *W_trim, hipStream_t st);
 
+// ---- Sec. 3.2: frequency-rank order, Top-P / minimum-count choice of k ----
+constexpr int kRankSortThreads = 1024;
+size_t rank_sort_scratch_bytes(int n);
+// ids_in: [n] ascending ids to sort (null = 0 .. n-1); out_ids [n]; out_counts [n] or null
+void launch_rank_sort(const long long *counts, const int *ids_in, int n, void *scratch, int *out_ids,
+                      long long *out_counts, hipStream_t st);
+// out: [3] = k, mass of the k largest counts, total mass
+void launch_choose_k(const long long *sorted_counts, int V, int mode, double P, long long f_min, long long *out,
+                     hipStream_t st);
+
 }  // namespace vt

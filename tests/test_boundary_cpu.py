@@ -133,6 +133,23 @@ def test_tree_selection_argument_errors(lib):
     assert g(A, 16385, 8, A, None) == 2 and g(A, 4096, 1025, A, None) == 2
 
 
+def test_choose_k_and_ranked_build_argument_errors(lib):
+    f = lib.vt_choose_k
+    big = 1 << 30
+    assert f(A, 100, 2, 0.5, 0, A, A, big, None) == 3            # unknown mode
+    assert f(A, 0, 0, 0.5, 0, A, A, big, None) == 2
+    assert f(A, 100, 0, 1.5, 0, A, A, big, None) == 2            # p outside [0, 1]
+    assert f(A, 100, 0, float("nan"), 0, A, A, big, None) == 2
+    assert f(None, 100, 0, 0.5, 0, A, A, big, None) == 1 and f(A, 100, 0, 0.5, 0, None, A, big, None) == 1
+    assert f(A, 100, 0, 0.5, 0, A, A, 16, None) == 5
+    assert lib.vt_choose_k_ws_bytes(128256) >= 128256 * (4 + 8 + 24)
+    g = lib.vt_build_trimmed_head_by_rank
+    assert g(A, 100, A, 1, 64, 0, A, A, A, big, None) == 2
+    assert g(A, 100, A, 1, 64, 10, None, A, A, big, None) == 1
+    assert g(A, 100, A, 1, 64, 10, A, A, A, 256, None) == 5      # the sort needs room
+    assert lib.vt_build_trimmed_head_ws_bytes(128256, 3072, 32768) >= 256 + 32768 * 28
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):

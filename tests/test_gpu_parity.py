@@ -494,3 +494,68 @@ def test_tree_after_draft_step_end_to_end():
     rp, rt, rs = oracle.tree_expand(cum, ol.cpu().numpy(), oi.cpu().numpy(), 8)
     assert np.array_equal(parent.cpu().numpy(), rp) and np.array_equal(token.cpu().numpy(), rt)
     assert np.array_equal(score.cpu().numpy(), rs)
+
+
+# ----------------------------------------------------------------------------- Sec. 3.2: rank order, Top-P, minimum count
+def test_build_by_rank_llama_k_sweep_and_prefix_property(llama_counts):
+    c = torch.from_numpy(llama_counts).to(dev())
+    ro = oracle.rank_order(llama_counts)
+    for k in (1, 100, 8192, 32768, 128256):
+        map_, _ = vt.build_trimmed_head(c, None, k, order="rank")
+        assert np.array_equal(map_.cpu().numpy(), ro[:k]), k
+    # gathered rows follow the same order; a prefix of the k = 32768 build is the k = 8192 build
+    V, d = 128256, 256
+    W = synth.head_weights(V, d, seed=3001, dtype="bf16")
+    dW = to_dev(W)
+    m32, W32 = vt.build_trimmed_head(c, dW, 32768, order="rank")
+    m8, W8 = vt.build_trimmed_head(c, dW, 8192, order="rank")
+    assert torch.equal(m32[:8192], m8) and torch.equal(W32[:8192].view(torch.int16), W8.view(torch.int16))
+    assert np.array_equal(from_bf16(W32), oracle.gather(W, ro[:32768]))
+
+
+def test_build_by_rank_adversarial_counts():
+    rng = np.random.default_rng(4)
+    cases = [np.zeros(1000, dtype=np.int64), np.full(777, 9, dtype=np.int64),
+             rng.integers(0, 3, size=4099).astype(np.int64), rng.integers(0, 2**62, size=5000).astype(np.int64),
+             (np.arange(3000, dtype=np.int64) * 2**33)[::-1].copy(), np.arange(70000, dtype=np.int64) % 17,
+             np.array([5], dtype=np.int64)]
+    for c in cases:
+        V = c.size
+        ro = oracle.rank_order(c)
+        for k in sorted(kk for kk in {1, 2, V // 3 + 1, V - 1, V} if 1 <= kk <= V):
+            map_, _ = vt.build_trimmed_head(to_dev(c), None, k, order="rank")
+            assert np.array_equal(map_.cpu().numpy(), ro[:k]), (V, k)
+
+
+def test_step_on_rank_ordered_head_matches_id_ordered(llama_counts):
+    # the draft step only needs map[j] to name row j: both row orders give the same tokens and log-probs
+    V, d, k, n, m = 128256, 1024, 16384, 4, 8
+    W = synth.head_weights(V, d, seed=3002, dtype="bf16")
+    c = torch.from_numpy(llama_counts).to(dev())
+    dW = to_dev(W)
+    h = to_dev(synth.hidden_rows(n, d, seed=3002, dtype="bf16"))
+    mi, Wi = vt.build_trimmed_head(c, dW, k, order="id")
+    mr, Wr = vt.build_trimmed_head(c, dW, k, order="rank")
+    a = vt.draft_head_step(h, Wi, mi, m)
+    b = vt.draft_head_step(h, Wr, mr, m)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0])
+    assert float((a[1] - b[1]).abs().max()) <= 1e-5
+    ref = oracle.draft_head_step(from_bf16(h), from_bf16(Wr), mr.cpu().numpy(), m)
+    check_step(b[0], b[1], ref, mr.cpu().numpy(), m)
+
+
+def test_choose_k_top_p_and_min_count(llama_counts):
+    c = torch.from_numpy(llama_counts).to(dev())
+    for P in (0.0, 0.1, 0.5, 0.9, 0.94, 0.999, 1.0):
+        assert vt.choose_k(c, top_p=P) == oracle.choose_k_top_p(llama_counts, P), P
+    for f in (0, 1, 2, 14, 1000, 10**7):
+        assert vt.choose_k(c, min_count=f) == oracle.choose_k_min_count(llama_counts, f), f
+    rng = np.random.default_rng(6)
+    cases = [np.zeros(50, dtype=np.int64), np.array([7], dtype=np.int64), np.full(3000, 2, dtype=np.int64),
+             rng.integers(0, 2**40, size=70001).astype(np.int64), rng.integers(0, 3, size=1025).astype(np.int64)]
+    for cc in cases:
+        for P in (0.0, 0.3, 0.77, 1.0):
+            assert vt.choose_k(to_dev(cc), top_p=P) == oracle.choose_k_top_p(cc, P), (cc.size, P)
+        for f in (0, 1, 2, 3, 2**39):
+            assert vt.choose_k(to_dev(cc), min_count=f) == oracle.choose_k_min_count(cc, f), (cc.size, f)
