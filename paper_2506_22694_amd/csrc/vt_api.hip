@@ -111,7 +111,9 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         p.fin_stage_keys = (group + 1) * p.L;
         int fc = (int)(vt::kFinalizeLdsBytes / ((size_t)p.fin_stage_keys * sizeof(unsigned long long)));
         if (fc < 1) return p;
-        p.fin_conc = fc < vt::kStepWaves ? fc : vt::kStepWaves;
+        // one hidden row per workgroup: n <= 256 rows spread over as many CUs, and a merging wave has its
+        // SIMD to itself (the selection rounds are bound by instruction issue)
+        p.fin_conc = 1;
         p.fin_lds = (size_t)p.fin_conc * p.fin_stage_keys * sizeof(unsigned long long);
     } else {
         const size_t fin = (size_t)p.fin_conc * stage;

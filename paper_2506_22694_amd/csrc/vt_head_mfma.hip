@@ -521,7 +521,7 @@ hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t s
         attr_set[dev] = true;
     }
     const int grid = (f.n + f.conc - 1) / f.conc;
-    hipLaunchKernelGGL(step_finalize_kernel, dim3(grid), dim3(kStepWaves * kWave), lds, st, f);
+    hipLaunchKernelGGL(step_finalize_kernel, dim3(grid), dim3(f.conc * kWave), lds, st, f);
     return hipGetLastError();
 }
 
