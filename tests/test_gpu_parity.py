@@ -121,6 +121,17 @@ def test_count_chunked_unaligned_int64_and_invalid():
             assert np.array_equal(c.cpu().numpy(), oracle.count(ids32[lo:hi], V)[0]), (lo, hi)
 
 
+def test_count_stress_100m_ids_exact():
+    # the stress workload's calibration stream: 10^8 ids, Zipf(1.05), permuted ranks (400 MB of int32)
+    wl = synth.WORKLOADS["stress"]
+    ids = synth.zipf_ids(wl.n_ids, wl.V, wl.zipf_s, wl.seed, wl.permute)
+    assert ids.size == 100_000_000
+    c = vt.count_tokens(to_dev(ids), wl.V)
+    ref, _ = oracle.count(ids, wl.V)
+    assert np.array_equal(c.cpu().numpy(), ref)
+    assert int(ref.max()) > 9_000_000          # the hottest id holds about a tenth of the stream
+
+
 def test_count_all_tokens_identical_and_small_vocab():
     ids = np.full(1_000_000, 17, dtype=np.int32)
     c = vt.count_tokens(to_dev(ids), 40_000)
