@@ -181,6 +181,15 @@ def main():
         f"per-launch avg {us_kernel:.2f} us (p10 {per[len(per)//10]:.2f}, p50 {per[len(per)//2]:.2f}, "
         f"p90 {per[len(per)*9//10]:.2f}), warm single buffer {us_warm:.2f} us")
 
+    # ------------------------------------------------------------------ what merely streaming the same bytes takes
+    from paper_2506_22694_amd.binding import stream_read_reference
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for r in range(10):
+        stream_read_reference(copies[r % len(copies)], sink)
+    us_read = time_region(lambda r: stream_read_reference(copies[r % len(copies)], sink), args.steps)
+    log(f"plain streaming read of the same {step_bytes} B, same rotation: {us_read:.2f} us per launch "
+        f"({step_bytes / us_read / 1e3:.0f} GB/s)")
+
     # ------------------------------------------------------------------ the same steps replayed from a HIP graph
     # (launch overhead factored out; every replay is checked against the eager result)
     graph_us = None
@@ -402,6 +411,8 @@ def main():
         "hbm_gbps": round(gbps_cold, 1),
         "frac_of_hbm_peak": round(gbps_cold / HBM_PEAK_GBPS, 4),
         "warm_single_buffer_us": round(us_warm, 3),
+        "plain_read_same_bytes_us": round(us_read, 3),
+        "plain_read_gbps": round(step_bytes / us_read / 1e3, 1),
         "roofline": {"bound": "hbm", "achieved": round(gbps_kernel, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps_kernel / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel": "head_gemv_kernel", "algorithmic_bytes": step_bytes,

@@ -224,6 +224,18 @@ int vt_tree_expand(const float *parent_cum, const float *step_logp, const int32_
                    void *stream);
 int vt_tree_rerank(const float *cum, int32_t N, int32_t T, int32_t *out_idx, void *stream);
 
+/* ------------------------------------------------------------------------
+ * Measurement reference (not part of the method): reads `bytes` bytes at `p`
+ * once, in the launch and load shape of the small-n draft step (*sink is
+ * written only if a lane's fold of its words hits one fixed value, which keeps
+ * the loads alive at no cost).  Its duration is what the device needs to merely
+ * stream the bytes a draft step has to stream; the benchmark reports it next
+ * to the step.
+ *   p      device, 16-byte aligned;  bytes > 0, a multiple of 16
+ *   sink   [1] uint32, device
+ * ---------------------------------------------------------------------- */
+int vt_stream_read_reference(const void *p, size_t bytes, uint32_t *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

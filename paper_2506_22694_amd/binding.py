@@ -25,7 +25,7 @@ EXPORTS = (
     "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes", "vt_build_trimmed_head_by_rank",
     "vt_choose_k", "vt_choose_k_ws_bytes",
     "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
-    "vt_tree_expand", "vt_tree_rerank",
+    "vt_tree_expand", "vt_tree_rerank", "vt_stream_read_reference",
 )
 VT_TREE_MAX_CANDIDATES, VT_TREE_MAX_KEEP = 16384, 1024
 
@@ -71,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     L.vt_tree_expand.restype = ci
     L.vt_tree_rerank.argtypes = [vp, i32, i32, vp, vp]
     L.vt_tree_rerank.restype = ci
+    L.vt_stream_read_reference.argtypes = [vp, sz, vp, vp]
+    L.vt_stream_read_reference.restype = ci
     _lib = L
     return L
 
@@ -287,3 +289,11 @@ def tree_rerank(cum: torch.Tensor, T: int, out: torch.Tensor | None = None) -> t
         raise ValueError("out must be a device int32 tensor of at least T elements")
     _check(L.vt_tree_rerank(_ptr(cum), cum.numel(), T, _ptr(out), _stream(cum.device)))
     return out
+
+
+# --------------------------------------------------------------------------- measurement reference
+def stream_read_reference(t: torch.Tensor, sink: torch.Tensor) -> None:
+    """Reads every byte of `t` once on the device (plain streaming read; timing reference only)."""
+    L = load_library()
+    _require_cuda(t, sink)
+    _check(L.vt_stream_read_reference(_ptr(t), t.numel() * t.element_size(), _ptr(sink), _stream(t.device)))

@@ -401,4 +401,13 @@ int vt_tree_rerank(const float *cum, int32_t N, int32_t T, int32_t *out_idx, voi
     return device_status(vt::launch_tree_select(a, static_cast<hipStream_t>(stream)));
 }
 
+int vt_stream_read_reference(const void *p, size_t bytes, uint32_t *sink, void *stream) {
+    if (p == nullptr || sink == nullptr) return VT_ERR_NULL;
+    if (bytes == 0 || (bytes & 15) != 0) return VT_ERR_SHAPE;
+    if (!aligned(p, 16) || !aligned(sink, 4)) return VT_ERR_ALIGN;
+    (void)hipGetLastError();
+    vt::launch_stream_read(p, bytes, sink, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
 }  // extern "C"

@@ -84,5 +84,6 @@ hipError_t launch_head_gemv_np8(bool bf16, int CS, const StepArgs &a, size_t lds
 void launch_sub_lse(float *logp_full, const float *lse, int n, int k, hipStream_t st);
 // zero the arrival counters
 void launch_ws_clear(unsigned *p, int nwords, hipStream_t st);
+void launch_stream_read(const void *p, size_t bytes, unsigned *sink, hipStream_t st);
 
 }  // namespace vt

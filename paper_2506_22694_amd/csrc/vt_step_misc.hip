@@ -27,4 +27,36 @@ void launch_ws_clear(unsigned *p, int nwords, hipStream_t st) {
     hipLaunchKernelGGL(ws_clear_kernel, dim3(1), dim3(64), 0, st, p, nwords);
 }
 
+// Measurement reference: a kernel that only reads `nvec` 16-byte vectors once, in the launch shape
+// and load shape of the small-n draft step (256 workgroups of 8 waves, 1 KiB per wave load,
+// streaming hint, 8 loads in flight per lane) and folds them into a word per lane.  Its duration is
+// what this machine takes to merely stream the bytes the step has to stream.
+__global__ void __launch_bounds__(512) stream_read_kernel(const u32x4 *__restrict__ p, size_t nvec,
+                                                          unsigned *__restrict__ sink) {
+    const size_t per_block = (nvec + gridDim.x - 1) / gridDim.x;
+    const size_t b0 = (size_t)blockIdx.x * per_block;
+    const size_t b1 = b0 + per_block < nvec ? b0 + per_block : nvec;
+    unsigned acc = 0u;
+    size_t i = b0 + threadIdx.x;
+    for (; i + 7 * 512 < b1; i += 8 * 512) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + i + (size_t)u * 512);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < b1; i += 512) {
+        const u32x4 v = __builtin_nontemporal_load(p + i);
+        acc += v.x ^ v.y ^ v.z ^ v.w;
+    }
+    // the fold is stored only if it hits one particular value: enough to keep the loads alive, and no
+    // store or atomic traffic is added to what is being timed
+    if (acc == 0x9E3779B9u) *sink = acc;
+}
+
+void launch_stream_read(const void *p, size_t bytes, unsigned *sink, hipStream_t st) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(256), dim3(512), 0, st, static_cast<const u32x4 *>(p), bytes / 16,
+                       sink);
+}
+
 }  // namespace vt
