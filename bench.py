@@ -343,6 +343,7 @@ def main():
     if args.configs:
         others = []
         cases = [("llama1b chain", 2048, 32768, 1, 1), ("llama1b full-vocab control", 2048, 128256, 1, 1),
+                 ("task head (xLAM-sized vocabulary)", 3072, 5000, 8, 8),
                  ("llama3b full-vocab control", 3072, 128256, 8, 8),
                  ("llama8b tree", 4096, 32768, 64, 8), ("stress", 8192, 32768, 256, 16)]
         for name, dd, kk, nn, mm in cases:

@@ -570,3 +570,28 @@ def test_choose_k_top_p_and_min_count(llama_counts):
             assert vt.choose_k(to_dev(cc), top_p=P) == oracle.choose_k_top_p(cc, P), (cc.size, P)
         for f in (0, 1, 2, 3, 2**39):
             assert vt.choose_k(to_dev(cc), min_count=f) == oracle.choose_k_min_count(cc, f), (cc.size, f)
+
+
+def test_two_task_heads_from_one_head_swapped_per_step():
+    # future-work remark of the conclusion / xLAM rows of Table 1: a small task-specific vocabulary next to
+    # the general one.  Two calibration streams over the same V give two (map, W_trim) pairs from one W;
+    # consecutive steps alternate between them on one workspace.
+    V, d, n, m = 128256, 1024, 4, 8
+    W = synth.head_weights(V, d, seed=3003, dtype="bf16")
+    dW = to_dev(W)
+    heads = []
+    for (seed, n_ids, s, k) in ((41, 2_000_000, 1.1, 32768), (42, 300_000, 1.4, 5000)):
+        ids = synth.zipf_ids(n_ids, V, s, seed=seed, permute=True)
+        c = vt.count_tokens(to_dev(ids), V)
+        map_, Wt = vt.build_trimmed_head(c, dW, k)
+        c_ref, _ = oracle.count(ids, V)
+        assert np.array_equal(map_.cpu().numpy(), oracle.select(c_ref, k))
+        heads.append((map_, Wt, oracle.gather(W, map_.cpu().numpy())))
+    ws = vt.StepWorkspace(n, 32768, d, m, dev())          # sized for the larger head, shared by both
+    for step in range(6):
+        map_, Wt, Wt_ref = heads[step % 2]
+        h = synth.hidden_rows(n, d, seed=500 + step, dtype="bf16")
+        oi, ol = vt.draft_head_step(to_dev(h), Wt, map_, m, ws=ws)
+        torch.cuda.synchronize()
+        ref = oracle.draft_head_step(h, Wt_ref, map_.cpu().numpy(), m)
+        check_step(oi, ol, ref, map_.cpu().numpy(), m)
