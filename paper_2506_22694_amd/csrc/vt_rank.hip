@@ -18,6 +18,7 @@ namespace vt {
 namespace {
 
 constexpr int kSortWaves = kRankSortThreads / kWave;   // 16
+constexpr int kRankUnroll = 8;                         // segment iterations whose loads are in flight together
 
 // lanes of the wave whose `dgt` (0..16) equals this lane's
 __device__ __forceinline__ unsigned long long match_digit(int dgt) {
@@ -82,13 +83,25 @@ __global__ void __launch_bounds__(kRankSortThreads) rank_sort_kernel(const long 
         if (lane < 16) cnt[w * 16 + lane] = 0u;
         __builtin_amdgcn_wave_barrier();
         // ---- how many elements of each digit this wave holds (digit 0 = largest hex digit: descending order)
-        for (int j0 = s0; j0 < s1; j0 += kWave) {
-            const int j = j0 + lane;
-            const bool in = j < s1;
-            const unsigned long long key = in ? ld64(ks + j) : 0ull;
-            const int dgt = in ? 15 - (int)((key >> sh) & 15ull) : 16;
-            const unsigned long long m = match_digit(dgt);
-            if (in && lanes_below(m) == 0) cnt[w * 16 + dgt] = cnt[w * 16 + dgt] + (unsigned)__popcll(m);
+        // kRankUnroll iterations' keys are requested together: the device-scope loads take about a
+        // microsecond each and nothing else hides them
+        for (int j0 = s0; j0 < s1; j0 += kRankUnroll * kWave) {
+            unsigned long long keyu[kRankUnroll];
+#pragma unroll
+            for (int u = 0; u < kRankUnroll; ++u) {
+                const int j = j0 + u * kWave + lane;
+                keyu[u] = j < s1 ? ld64(ks + j) : 0ull;
+            }
+#pragma unroll
+            for (int u = 0; u < kRankUnroll; ++u) {
+                const int j = j0 + u * kWave + lane;
+                if (j0 + u * kWave < s1) {                      // wave-uniform
+                    const bool in = j < s1;
+                    const int dgt = in ? 15 - (int)((keyu[u] >> sh) & 15ull) : 16;
+                    const unsigned long long m = match_digit(dgt);
+                    if (in && lanes_below(m) == 0) cnt[w * 16 + dgt] = cnt[w * 16 + dgt] + (unsigned)__popcll(m);
+                }
+            }
         }
         __syncthreads();
         // ---- exclusive prefix over (digit, wave): the first output slot of every (wave, digit) run
@@ -115,22 +128,33 @@ __global__ void __launch_bounds__(kRankSortThreads) rank_sort_kernel(const long 
         }
         __syncthreads();
         // ---- stable scatter
-        for (int j0 = s0; j0 < s1; j0 += kWave) {
-            const int j = j0 + lane;
-            const bool in = j < s1;
-            const unsigned long long key = in ? ld64(ks + j) : 0ull;
-            const int idv = in ? ld32(is + j) : 0;
-            const int dgt = in ? 15 - (int)((key >> sh) & 15ull) : 16;
-            const unsigned long long m = match_digit(dgt);
-            const int below = lanes_below(m);
-            const unsigned base = in ? cnt[w * 16 + dgt] : 0u;
-            __builtin_amdgcn_wave_barrier();           // every lane has read its base before a leader moves it
-            if (in) {
-                st64(kd + base + below, key);
-                st32(id_ + base + below, idv);
-                if (below == 0) cnt[w * 16 + dgt] = base + (unsigned)__popcll(m);
+        for (int j0 = s0; j0 < s1; j0 += kRankUnroll * kWave) {
+            unsigned long long keyu[kRankUnroll];
+            int idu[kRankUnroll];
+#pragma unroll
+            for (int u = 0; u < kRankUnroll; ++u) {
+                const int j = j0 + u * kWave + lane;
+                keyu[u] = j < s1 ? ld64(ks + j) : 0ull;
+                idu[u] = j < s1 ? ld32(is + j) : 0;
             }
-            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int u = 0; u < kRankUnroll; ++u) {
+                const int j = j0 + u * kWave + lane;
+                if (j0 + u * kWave < s1) {                      // wave-uniform
+                    const bool in = j < s1;
+                    const int dgt = in ? 15 - (int)((keyu[u] >> sh) & 15ull) : 16;
+                    const unsigned long long m = match_digit(dgt);
+                    const int below = lanes_below(m);
+                    const unsigned base = in ? cnt[w * 16 + dgt] : 0u;
+                    __builtin_amdgcn_wave_barrier();       // every lane has read its base before a leader moves it
+                    if (in) {
+                        st64(kd + base + below, keyu[u]);
+                        st32(id_ + base + below, idu[u]);
+                        if (below == 0) cnt[w * 16 + dgt] = base + (unsigned)__popcll(m);
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
         }
         __syncthreads();   // the pass is complete (and visible to the whole workgroup) before the next reads it
         unsigned long long *tk = ks;
