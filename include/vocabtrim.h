@@ -163,6 +163,9 @@ size_t vt_choose_k_ws_bytes(int32_t V);
  *
  *   h              [n, d] row-major, h_type, device
  *   n              hidden rows this step (chain drafting: 1; tree drafting: nodes), 1 <= n
+ *                  (one launch covers n <= 8, and n <= 256 for bf16 with d a multiple of
+ *                  128; other shapes run as consecutive groups of rows, each streaming
+ *                  W_trim again)
  *   W_trim         [k, d] row-major, w_type (== h_type), device
  *   map            [k] int32 target ids, device
  *   m              tokens kept per row, 1 <= m <= min(k, VT_MAX_TOP_M)

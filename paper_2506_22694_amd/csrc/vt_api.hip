@@ -134,6 +134,21 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
     return p;
 }
 
+// Hidden rows handled per launch group.  A step whose n no single plan covers (more than 256 rows; more
+// than 8 rows in fp32 or with d not a multiple of 128; very long fp32 rows) runs as consecutive groups
+// of `chunk` rows, each streaming W_trim again -- slower, but every shape has an answer.
+int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, int d, const int32_t *map, int m,
+                   int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws,
+                   hipStream_t st);
+
+int pick_chunk(int n, int k, int d, int m, int dtype) {
+    if (plan_step(n, k, d, m, dtype).ok) return n;
+    for (int c : {256, 8, 4, 2, 1}) {
+        if (c < n && plan_step(c, k, d, m, dtype).ok && (n % c == 0 || plan_step(n % c, k, d, m, dtype).ok)) return c;
+    }
+    return 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -253,11 +268,18 @@ int vt_choose_k(const int64_t *counts, int32_t V, int mode, double p, int64_t mi
 
 // ------------------------------------------------------------------ Algorithm 2, drafting lines
 size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m) {
-    // sized for either element type (the layout does not depend on it)
-    const StepPlan p = plan_step(n, k, d, m, VT_BF16);
-    const StepPlan q = plan_step(n, k, d, m, VT_F32);
-    size_t b = p.ok ? p.bytes : 0;
-    if (q.ok && q.bytes > b) b = q.bytes;
+    // sized for either element type
+    size_t b = 0;
+    for (int dtype : {VT_BF16, VT_F32}) {
+        const int c = pick_chunk(n, k, d, m, dtype);
+        if (c == 0) continue;
+        const StepPlan p = plan_step(c, k, d, m, dtype);
+        if (p.bytes > b) b = p.bytes;
+        if (n % c != 0) {
+            const StepPlan r = plan_step(n % c, k, d, m, dtype);
+            if (r.ok && r.bytes > b) b = r.bytes;
+        }
+    }
     return b;
 }
 
@@ -283,13 +305,34 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
         !aligned(out_ids, 4) || !aligned(out_logp, 4) || (out_lse && !aligned(out_lse, 4)) ||
         (out_logp_full && !aligned(out_logp_full, 4)))
         return VT_ERR_ALIGN;
-    const StepPlan p = plan_step(n, k, d, m, w_type);
-    if (!p.ok) return VT_ERR_SHAPE;
-    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < p.bytes) return VT_ERR_WORKSPACE;
-
-    char *wsb = static_cast<char *>(ws);
+    const int chunk = pick_chunk(n, k, d, m, w_type);
+    if (chunk == 0) return VT_ERR_SHAPE;
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < vt_draft_head_step_ws_bytes(n, k, d, m))
+        return VT_ERR_WORKSPACE;
     (void)hipGetLastError();
     hipStream_t st = static_cast<hipStream_t>(stream);
+    for (int i0 = 0; i0 < n; i0 += chunk) {
+        const int nc = n - i0 < chunk ? n - i0 : chunk;
+        const int rc = run_step_group(static_cast<const char *>(h) + (size_t)i0 * row_bytes, nc, W_trim, w_type, k, d, map,
+                                      m, out_ids + (size_t)i0 * m, out_logp + (size_t)i0 * m,
+                                      out_lse ? out_lse + i0 : nullptr,
+                                      out_logp_full ? out_logp_full + (size_t)i0 * k : nullptr, ws, st);
+        if (rc != VT_OK) return rc;
+    }
+    return launch_status();
+}
+
+}  // extern "C"
+
+namespace {
+
+// One launch group of the draft step: n rows that a single plan covers.  Arguments are validated.
+int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, int d, const int32_t *map, int m,
+                   int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws,
+                   hipStream_t st) {
+    const StepPlan p = plan_step(n, k, d, m, w_type);
+    if (!p.ok) return VT_ERR_SHAPE;
+    char *wsb = static_cast<char *>(ws);
     unsigned long long *pms = reinterpret_cast<unsigned long long *>(wsb + p.off_pms);
     unsigned long long *pkeys = reinterpret_cast<unsigned long long *>(wsb + p.off_pkeys);
     float *lse_buf = reinterpret_cast<float *>(wsb + p.off_lse);
@@ -362,8 +405,12 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
     }
     if (out_logp_full != nullptr)
         vt::launch_sub_lse(out_logp_full, lse_buf, n, k, st);
-    return launch_status();
+    return VT_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int vt_tree_expand(const float *parent_cum, const float *step_logp, const int32_t *step_ids, int32_t n, int32_t m,
                    int32_t K, int32_t *out_parent, int32_t *out_token, float *out_cum, void *stream) {

@@ -315,11 +315,20 @@ def test_step_many_rows_exact_ties_and_full_logp():
     check_step(oi, ol, ref, map_, m, lse)
     _, logp_ref = oracle.log_softmax(ref["z"])
     assert np.max(np.abs(full.cpu().numpy().astype(np.float64) - logp_ref)) <= LOGP_TOL
-    # unsupported on the matrix-core path: d not a multiple of 128
-    W2, map2 = synth.trimmed_head_direct(64, 200, seed=1, dtype="bf16")
-    with pytest.raises(vt.VocabTrimError) as e:
-        run_step(synth.hidden_rows(9, 200, seed=1, dtype="bf16"), W2, map2, 1)
-    assert e.value.status == 2
+
+
+def test_step_shapes_no_single_launch_covers_run_as_row_groups():
+    # more than 8 rows with d not a multiple of 128, or in fp32, or more than 256 rows: the step runs as
+    # consecutive groups of rows on one workspace; results (incl. lse and the full log-softmax) as for one launch
+    for (k, d, n, m, dt) in ((64, 200, 9, 1, "bf16"), (1000, 256, 20, 4, "f32"), (3000, 256, 300, 8, "bf16"),
+                             (500, 72, 17, 5, "bf16"), (2000, 8192, 8, 3, "f32")):
+        W, map_ = synth.trimmed_head_direct(k, d, seed=k + n, dtype=dt)
+        h = synth.hidden_rows(n, d, seed=k + n, dtype=dt)
+        ref = oracle.draft_head_step(h, W, map_, m)
+        oi, ol, lse, full = run_step(h, W, map_, m, return_lse=True, return_full=True)
+        check_step(oi, ol, ref, map_, m, lse)
+        _, logp_ref = oracle.log_softmax(ref["z"])
+        assert np.max(np.abs(full.cpu().numpy().astype(np.float64) - logp_ref)) <= LOGP_TOL, (k, d, n)
 
 
 def test_step_odd_shapes():
