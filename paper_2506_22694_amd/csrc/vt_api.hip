@@ -192,11 +192,10 @@ int vt_count_tokens(const void *ids, int id_type, int64_t n_ids, int32_t V, int6
 
 // ------------------------------------------------------------------ Eq. 1
 size_t vt_build_trimmed_head_ws_bytes(int32_t V, int32_t d, int32_t k) {
-    (void)V;
     (void)d;
-    if (k < 1) return 256;
-    // rank-ordered build: the id-ordered selection, then the sort's ping-pong buffers
-    return 256 + round_up((size_t)k * sizeof(int32_t), 256) + vt::rank_sort_scratch_bytes(k);
+    (void)k;
+    // rank-ordered build: the buffers of a sort of all V (count, id) pairs
+    return 256 + vt::rank_sort_scratch_bytes(V > 0 ? V : 1);
 }
 
 int vt_build_trimmed_head(const int64_t *counts, int32_t V, const void *W, int w_type, int32_t d, int32_t k,
@@ -230,12 +229,9 @@ int vt_build_trimmed_head_by_rank(const int64_t *counts, int32_t V, const void *
         return VT_ERR_WORKSPACE;
     (void)hipGetLastError();
     hipStream_t st = static_cast<hipStream_t>(stream);
-    char *wsb = static_cast<char *>(ws);
-    int *by_id = reinterpret_cast<int *>(wsb + 256);
-    void *scratch = wsb + 256 + round_up((size_t)k * sizeof(int32_t), 256);
-    const long long *c = reinterpret_cast<const long long *>(counts);
-    vt::launch_select_topk(c, V, k, by_id, st);
-    vt::launch_rank_sort(c, by_id, k, scratch, map, nullptr, st);
+    // the k best ids in rank order are the first k of the full rank order
+    vt::launch_rank_sort(reinterpret_cast<const long long *>(counts), V, static_cast<char *>(ws) + 256, map, k,
+                         nullptr, st);
     if (W != nullptr) vt::launch_gather_rows(W, row_bytes, map, k, W_trim, st);
     return launch_status();
 }
@@ -261,7 +257,7 @@ int vt_choose_k(const int64_t *counts, int32_t V, int mode, double p, int64_t mi
     long long *sorted = reinterpret_cast<long long *>(wsb + round_up((size_t)V * sizeof(int32_t), 256));
     void *scratch = wsb + round_up((size_t)V * sizeof(int32_t), 256) + round_up((size_t)V * sizeof(int64_t), 256);
     const long long *c = reinterpret_cast<const long long *>(counts);
-    vt::launch_rank_sort(c, nullptr, V, scratch, ids, sorted, st);
+    vt::launch_rank_sort(c, V, scratch, ids, V, sorted, st);
     vt::launch_choose_k(sorted, V, mode, p, (long long)min_count, reinterpret_cast<long long *>(out), st);
     return launch_status();
 }

@@ -27,9 +27,10 @@ void launch_gather_rows(const void *W, size_t row_bytes, const int *map, int k, 
 // ---- Sec. 3.2: frequency-rank order, Top-P / minimum-count choice of k ----
 constexpr int kRankSortThreads = 1024;
 size_t rank_sort_scratch_bytes(int n);
-// ids_in: [n] ascending ids to sort (null = 0 .. n-1); out_ids [n]; out_counts [n] or null
-void launch_rank_sort(const long long *counts, const int *ids_in, int n, void *scratch, int *out_ids,
-                      long long *out_counts, hipStream_t st);
+// sorts all n ids by (count desc, id asc); out_ids [n_ids] receives the first n_ids of them, out_counts [n] (or
+// null) all sorted counts
+void launch_rank_sort(const long long *counts, int n, void *scratch, int *out_ids, int n_ids, long long *out_counts,
+                      hipStream_t st);
 // out: [3] = k, mass of the k largest counts, total mass
 void launch_choose_k(const long long *sorted_counts, int V, int mode, double P, long long f_min, long long *out,
                      hipStream_t st);

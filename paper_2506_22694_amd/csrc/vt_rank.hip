@@ -1,13 +1,22 @@
 // Frequency-rank order and the alternative choices of k (Sec. 3.2: besides a fixed k, Top-P over
 // the counts or a minimum-frequency threshold select the trimmed vocabulary).
 //
-// rank_sort_kernel: stable LSD radix sort of (count, id) pairs by count, descending, 4 bits per
-//   pass; the ids arrive ascending, so equal counts stay in ascending-id order -- the order in
-//   which Top-K(c, k) takes ids, every prefix being the selection for a smaller k.  Only as many
-//   passes as the largest count has hex digits (6 for 10^7 calibration tokens).  One workgroup;
-//   a wave owns a contiguous segment and walks it 64 elements at a time, so loads are coalesced
-//   and "earlier in the input" is (iteration, lane) order: lanes with equal digits find each other
-//   with five ballots and rank themselves with a population count.
+// Rank order = all V ids sorted by (count descending, id ascending), the order in which
+// Top-K(c, k) takes ids; every prefix is the selection for a smaller k.
+//
+// rsort_*: stable LSD radix sort of the (count, id) pairs over the whole device, 8 bits per pass.
+//   The ids start ascending and every pass is stable, so equal counts stay in ascending-id order.
+//   One workgroup per 1024 consecutive elements; a wave takes 64 consecutive elements, lanes with
+//   equal digits find each other with nine ballots and rank themselves by population count, so
+//   "earlier in the input" is (workgroup, wave, lane) order and no per-thread histogram is needed.
+//     rsort_init     keys/ids from the counts, and the digit totals of all eight byte positions
+//     rsort_hist     per-workgroup digit histogram of one pass
+//     rsort_scatter  every workgroup derives its own output offsets from the histogram table
+//                    (sum over earlier digits and over earlier workgroups), then scatters
+//   A pass whose digit is the same for every key moves nothing and is skipped: each kernel
+//   derives that, and which buffer currently holds the data, from the digit totals alone, so the
+//   host enqueues a fixed sequence without reading anything back.  With 10^7 calibration tokens
+//   three of the eight passes do work.
 // choose_k_kernel: prefix sums over the sorted counts; the smallest prefix whose mass reaches
 //   ceil(P * total), or the number of counts >= f_min.
 #include "vt_build.h"
@@ -17,14 +26,24 @@ namespace vt {
 
 namespace {
 
-constexpr int kSortWaves = kRankSortThreads / kWave;   // 16
-constexpr int kRankUnroll = 8;                         // segment iterations whose loads are in flight together
+inline size_t round256(size_t x) { return (x + 255) / 256 * 256; }
 
-// lanes of the wave whose `dgt` (0..16) equals this lane's
-__device__ __forceinline__ unsigned long long match_digit(int dgt) {
+constexpr int kSortWaves = kRankSortThreads / kWave;   // 16
+constexpr int kDigits = 256;
+constexpr int kPasses = 8;
+
+struct SortBufs {
+    unsigned long long *keys[2];
+    int *ids[2];
+    unsigned *gtot;      // [kPasses][kDigits] digit totals over all elements
+    unsigned *hist;      // [kDigits][nblk] per-workgroup digit counts of the current pass, descending digit first
+};
+
+// lanes of the wave whose `dgt` (0..256, 256 = not an element) equals this lane's
+__device__ __forceinline__ unsigned long long match_digit9(int dgt) {
     unsigned long long m = ~0ull;
 #pragma unroll
-    for (int b = 0; b < 5; ++b) {
+    for (int b = 0; b < 9; ++b) {
         const bool bit = (dgt >> b) & 1;
         const unsigned long long B = __ballot(bit);
         m &= bit ? B : ~B;
@@ -35,140 +54,129 @@ __device__ __forceinline__ int lanes_below(unsigned long long m) {
     return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
 }
 
-// The ping-pong buffers are written by one wave and read by another in the next pass: device-scope
-// relaxed atomics go to the L2 both ways, so no stale line of this CU's vector cache is ever read.
-__device__ __forceinline__ unsigned long long ld64(const unsigned long long *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// A pass is idle iff one digit bin holds all n elements.  Every wave of every kernel evaluates this
+// the same way from the digit totals (call with all 64 lanes active).
+__device__ __forceinline__ bool pass_active(const unsigned *__restrict__ gtot, int p, int n) {
+    bool idle = false;
+    for (int d = (int)threadIdx.x & 63; d < kDigits; d += kWave) idle |= gtot[p * kDigits + d] == (unsigned)n;
+    return __ballot(idle) == 0ull;
 }
-__device__ __forceinline__ int ld32(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void st64(unsigned long long *p, unsigned long long v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Buffer (0 or 1) that holds the data before pass p: the parity of the active passes before it.
+__device__ __forceinline__ int source_buffer(const unsigned *__restrict__ gtot, int p, int n) {
+    int moved = 0;
+    for (int q = 0; q < p; ++q) moved += pass_active(gtot, q, n) ? 1 : 0;
+    return moved & 1;
 }
-__device__ __forceinline__ void st32(int *p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+__global__ void __launch_bounds__(256) rsort_zero_kernel(unsigned *gtot) {
+    for (int i = threadIdx.x; i < kPasses * kDigits; i += 256) gtot[i] = 0u;
+}
+
+__global__ void __launch_bounds__(kRankSortThreads) rsort_init_kernel(const long long *__restrict__ counts, int n,
+                                                                      SortBufs b) {
+    __shared__ unsigned h[kPasses * kDigits];
+    for (int i = threadIdx.x; i < kPasses * kDigits; i += kRankSortThreads) h[i] = 0u;
+    __syncthreads();
+    const int j = blockIdx.x * kRankSortThreads + threadIdx.x;
+    if (j < n) {
+        const unsigned long long c = (unsigned long long)counts[j];
+        b.keys[0][j] = c;
+        b.ids[0][j] = j;
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) atomicAdd(&h[p * kDigits + (int)((c >> (8 * p)) & 255ull)], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kPasses * kDigits; i += kRankSortThreads) {
+        if (h[i] != 0u) atomicAdd(&b.gtot[i], h[i]);
+    }
+}
+
+__global__ void __launch_bounds__(kRankSortThreads) rsort_hist_kernel(int n, int p, SortBufs b) {
+    __shared__ unsigned h[kDigits];
+    if (!pass_active(b.gtot, p, n)) return;
+    const int src = source_buffer(b.gtot, p, n);
+    if (threadIdx.x < kDigits) h[threadIdx.x] = 0u;
+    __syncthreads();
+    const int j = blockIdx.x * kRankSortThreads + threadIdx.x;
+    if (j < n) atomicAdd(&h[255 - (int)((b.keys[src][j] >> (8 * p)) & 255ull)], 1u);
+    __syncthreads();
+    if (threadIdx.x < kDigits) b.hist[threadIdx.x * gridDim.x + blockIdx.x] = h[threadIdx.x];
+}
+
+__global__ void __launch_bounds__(kRankSortThreads) rsort_scatter_kernel(int n, int p, SortBufs b) {
+    __shared__ unsigned wcnt[kSortWaves * kDigits];   // [wave][digit]: elements of that digit in earlier waves
+    __shared__ unsigned part[4 * kDigits];            // sums over a quarter of the earlier workgroups
+    __shared__ unsigned offs[kDigits];                // first output slot of this workgroup's run of each digit
+    if (!pass_active(b.gtot, p, n)) return;
+    const int src = source_buffer(b.gtot, p, n);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int nblk = gridDim.x, blk = blockIdx.x;
+
+    for (int i = tid; i < kSortWaves * kDigits; i += kRankSortThreads) wcnt[i] = 0u;
+    // this workgroup's offsets: (elements with an earlier digit anywhere) + (same digit, earlier workgroups)
+    {
+        const int d = tid >> 2, q = tid & 3;
+        unsigned before = 0;
+        const int b0 = nblk * q / 4, b1 = nblk * (q + 1) / 4;
+        for (int x = b0; x < b1 && x < blk; ++x) before += b.hist[d * nblk + x];
+        part[q * kDigits + d] = before;
+    }
+    unsigned tot = 0, inc = 0;
+    if (tid < kDigits) {
+        tot = b.gtot[p * kDigits + (255 - tid)];      // digit totals in descending-digit order
+        inc = tot;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {         // inclusive scan inside each of the four waves
+            const unsigned t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
+        }
+        offs[tid] = inc;
+    }
+    __syncthreads();
+    unsigned my_off = 0;
+    if (tid < kDigits) {
+        unsigned carry = 0;
+        for (int ww = 0; ww < w; ++ww) carry += offs[ww * kWave + kWave - 1];
+        my_off = carry + inc - tot + part[tid] + part[kDigits + tid] + part[2 * kDigits + tid] + part[3 * kDigits + tid];
+    }
+    __syncthreads();
+    if (tid < kDigits) offs[tid] = my_off;
+
+    // ---- ranks inside the workgroup
+    const int j = blk * kRankSortThreads + tid;
+    const bool in = j < n;
+    const unsigned long long key = in ? b.keys[src][j] : 0ull;
+    const int idv = in ? b.ids[src][j] : 0;
+    const int dgt = in ? 255 - (int)((key >> (8 * p)) & 255ull) : 256;
+    const unsigned long long m = match_digit9(dgt);
+    const int below = lanes_below(m);
+    if (in && below == 0) wcnt[w * kDigits + dgt] = (unsigned)__popcll(m);
+    __syncthreads();
+    if (tid < kDigits) {
+        unsigned run = 0;
+        for (int ww = 0; ww < kSortWaves; ++ww) {
+            const unsigned c = wcnt[ww * kDigits + tid];
+            wcnt[ww * kDigits + tid] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    if (in) {
+        const unsigned pos = offs[dgt] + wcnt[w * kDigits + dgt] + (unsigned)below;
+        b.keys[src ^ 1][pos] = key;
+        b.ids[src ^ 1][pos] = idv;
+    }
+}
+
+__global__ void __launch_bounds__(256) rsort_out_kernel(int n, int n_ids, SortBufs b, int *__restrict__ out_ids,
+                                                        long long *__restrict__ out_counts) {
+    const int src = source_buffer(b.gtot, kPasses, n);
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j < n_ids) out_ids[j] = b.ids[src][j];
+    if (out_counts != nullptr && j < n) out_counts[j] = (long long)b.keys[src][j];
+}
 
 }  // namespace
-
-__global__ void __launch_bounds__(kRankSortThreads) rank_sort_kernel(const long long *__restrict__ counts,
-                                                                     const int *__restrict__ ids_in, int n,
-                                                                     unsigned long long *kA, unsigned long long *kB,
-                                                                     int *iA, int *iB, int *__restrict__ out_ids,
-                                                                     long long *__restrict__ out_counts) {
-    __shared__ unsigned cnt_s[kSortWaves * 16];
-    __shared__ unsigned long long s_max[kSortWaves];
-    volatile unsigned *cnt = cnt_s;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int seg = ((n + kSortWaves - 1) / kSortWaves + kWave - 1) / kWave * kWave;
-    const int s0 = w * seg, s1 = min(n, s0 + seg);
-
-    unsigned long long mx = 0;
-    for (int j = s0 + lane; j < s1; j += kWave) {
-        const int id = ids_in != nullptr ? ids_in[j] : j;
-        const unsigned long long c = (unsigned long long)counts[id];
-        st64(kA + j, c);
-        st32(iA + j, id);
-        mx = c > mx ? c : mx;
-    }
-    mx = wave_max_u64(mx);
-    if (lane == 0) s_max[w] = mx;
-    __syncthreads();
-    mx = 0;
-    for (int q = 0; q < kSortWaves; ++q) mx = s_max[q] > mx ? s_max[q] : mx;
-    const int nbits = mx == 0 ? 0 : 64 - __clzll((long long)mx);
-    const int npass = (nbits + 3) / 4;
-
-    unsigned long long *ks = kA, *kd = kB;
-    int *is = iA, *id_ = iB;
-    for (int p = 0; p < npass; ++p) {
-        const int sh = 4 * p;
-        if (lane < 16) cnt[w * 16 + lane] = 0u;
-        __builtin_amdgcn_wave_barrier();
-        // ---- how many elements of each digit this wave holds (digit 0 = largest hex digit: descending order)
-        // kRankUnroll iterations' keys are requested together: the device-scope loads take about a
-        // microsecond each and nothing else hides them
-        for (int j0 = s0; j0 < s1; j0 += kRankUnroll * kWave) {
-            unsigned long long keyu[kRankUnroll];
-#pragma unroll
-            for (int u = 0; u < kRankUnroll; ++u) {
-                const int j = j0 + u * kWave + lane;
-                keyu[u] = j < s1 ? ld64(ks + j) : 0ull;
-            }
-#pragma unroll
-            for (int u = 0; u < kRankUnroll; ++u) {
-                const int j = j0 + u * kWave + lane;
-                if (j0 + u * kWave < s1) {                      // wave-uniform
-                    const bool in = j < s1;
-                    const int dgt = in ? 15 - (int)((keyu[u] >> sh) & 15ull) : 16;
-                    const unsigned long long m = match_digit(dgt);
-                    if (in && lanes_below(m) == 0) cnt[w * 16 + dgt] = cnt[w * 16 + dgt] + (unsigned)__popcll(m);
-                }
-            }
-        }
-        __syncthreads();
-        // ---- exclusive prefix over (digit, wave): the first output slot of every (wave, digit) run
-        if (w == 0) {
-            const int dgt = lane >> 2, wv0 = (lane & 3) * 4;
-            unsigned v[4], s = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                v[q] = cnt[(wv0 + q) * 16 + dgt];
-                s += v[q];
-            }
-            unsigned inc = s;
-#pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const unsigned t = __shfl_up(inc, o);
-                if (lane >= o) inc += t;
-            }
-            unsigned run = inc - s;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                cnt[(wv0 + q) * 16 + dgt] = run;
-                run += v[q];
-            }
-        }
-        __syncthreads();
-        // ---- stable scatter
-        for (int j0 = s0; j0 < s1; j0 += kRankUnroll * kWave) {
-            unsigned long long keyu[kRankUnroll];
-            int idu[kRankUnroll];
-#pragma unroll
-            for (int u = 0; u < kRankUnroll; ++u) {
-                const int j = j0 + u * kWave + lane;
-                keyu[u] = j < s1 ? ld64(ks + j) : 0ull;
-                idu[u] = j < s1 ? ld32(is + j) : 0;
-            }
-#pragma unroll
-            for (int u = 0; u < kRankUnroll; ++u) {
-                const int j = j0 + u * kWave + lane;
-                if (j0 + u * kWave < s1) {                      // wave-uniform
-                    const bool in = j < s1;
-                    const int dgt = in ? 15 - (int)((keyu[u] >> sh) & 15ull) : 16;
-                    const unsigned long long m = match_digit(dgt);
-                    const int below = lanes_below(m);
-                    const unsigned base = in ? cnt[w * 16 + dgt] : 0u;
-                    __builtin_amdgcn_wave_barrier();       // every lane has read its base before a leader moves it
-                    if (in) {
-                        st64(kd + base + below, keyu[u]);
-                        st32(id_ + base + below, idu[u]);
-                        if (below == 0) cnt[w * 16 + dgt] = base + (unsigned)__popcll(m);
-                    }
-                    __builtin_amdgcn_wave_barrier();
-                }
-            }
-        }
-        __syncthreads();   // the pass is complete (and visible to the whole workgroup) before the next reads it
-        unsigned long long *tk = ks;
-        ks = kd;
-        kd = tk;
-        int *ti = is;
-        is = id_;
-        id_ = ti;
-    }
-    for (int j = tid; j < n; j += kRankSortThreads) {
-        out_ids[j] = ld32(is + j);
-        if (out_counts != nullptr) out_counts[j] = (long long)ld64(ks + j);
-    }
-}
 
 // sc: counts sorted descending.  out[0] = k, out[1] = mass of the k largest counts, out[2] = total mass.
 //   mode 0: smallest k >= 1 with S_k >= ceil(P * total);  mode 1: k = #{c >= f_min}.
@@ -259,21 +267,32 @@ __global__ void __launch_bounds__(kRankSortThreads) choose_k_kernel(const long l
     }
 }
 
-void launch_rank_sort(const long long *counts, const int *ids_in, int n, void *scratch, int *out_ids,
-                      long long *out_counts, hipStream_t st) {
-    char *p = static_cast<char *>(scratch);
-    const size_t kb = ((size_t)n * 8 + 255) / 256 * 256, ib = ((size_t)n * 4 + 255) / 256 * 256;
-    unsigned long long *kA = reinterpret_cast<unsigned long long *>(p);
-    unsigned long long *kB = reinterpret_cast<unsigned long long *>(p + kb);
-    int *iA = reinterpret_cast<int *>(p + 2 * kb);
-    int *iB = reinterpret_cast<int *>(p + 2 * kb + ib);
-    hipLaunchKernelGGL(rank_sort_kernel, dim3(1), dim3(kRankSortThreads), 0, st, counts, ids_in, n, kA, kB, iA, iB,
-                       out_ids, out_counts);
+size_t rank_sort_scratch_bytes(int n) {
+    const size_t kb = round256((size_t)n * 8), ib = round256((size_t)n * 4);
+    const size_t nblk = ((size_t)n + kRankSortThreads - 1) / kRankSortThreads;
+    return 2 * kb + 2 * ib + round256(kPasses * kDigits * 4) + round256(kDigits * nblk * 4);
 }
 
-size_t rank_sort_scratch_bytes(int n) {
-    const size_t kb = ((size_t)n * 8 + 255) / 256 * 256, ib = ((size_t)n * 4 + 255) / 256 * 256;
-    return 2 * kb + 2 * ib;
+// Sorts all n ids by (count desc, id asc); writes the first n_ids of them and, if asked, all sorted counts.
+void launch_rank_sort(const long long *counts, int n, void *scratch, int *out_ids, int n_ids, long long *out_counts,
+                      hipStream_t st) {
+    char *p = static_cast<char *>(scratch);
+    const size_t kb = round256((size_t)n * 8), ib = round256((size_t)n * 4);
+    const int nblk = (n + kRankSortThreads - 1) / kRankSortThreads;
+    SortBufs b;
+    b.keys[0] = reinterpret_cast<unsigned long long *>(p);
+    b.keys[1] = reinterpret_cast<unsigned long long *>(p + kb);
+    b.ids[0] = reinterpret_cast<int *>(p + 2 * kb);
+    b.ids[1] = reinterpret_cast<int *>(p + 2 * kb + ib);
+    b.gtot = reinterpret_cast<unsigned *>(p + 2 * kb + 2 * ib);
+    b.hist = reinterpret_cast<unsigned *>(p + 2 * kb + 2 * ib + round256(kPasses * kDigits * 4));
+    hipLaunchKernelGGL(rsort_zero_kernel, dim3(1), dim3(256), 0, st, b.gtot);
+    hipLaunchKernelGGL(rsort_init_kernel, dim3(nblk), dim3(kRankSortThreads), 0, st, counts, n, b);
+    for (int pass = 0; pass < kPasses; ++pass) {
+        hipLaunchKernelGGL(rsort_hist_kernel, dim3(nblk), dim3(kRankSortThreads), 0, st, n, pass, b);
+        hipLaunchKernelGGL(rsort_scatter_kernel, dim3(nblk), dim3(kRankSortThreads), 0, st, n, pass, b);
+    }
+    hipLaunchKernelGGL(rsort_out_kernel, dim3((n + 255) / 256), dim3(256), 0, st, n, n_ids, b, out_ids, out_counts);
 }
 
 void launch_choose_k(const long long *sorted_counts, int V, int mode, double P, long long f_min, long long *out,
