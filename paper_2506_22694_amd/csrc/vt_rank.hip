@@ -82,8 +82,24 @@ __global__ void __launch_bounds__(kRankSortThreads) rsort_init_kernel(const long
         const unsigned long long c = (unsigned long long)counts[j];
         b.keys[0][j] = c;
         b.ids[0][j] = j;
+    }
+    // the upper bytes are the same in nearly every key (zero): when a whole wave agrees on a digit one lane
+    // adds for all, instead of 64 LDS atomics queueing on one address
+    {
+        const unsigned long long c = j < n ? (unsigned long long)counts[j] : 0ull;
+        const unsigned long long live = __ballot(j < n);
 #pragma unroll
-        for (int p = 0; p < kPasses; ++p) atomicAdd(&h[p * kDigits + (int)((c >> (8 * p)) & 255ull)], 1u);
+        for (int p = 0; p < kPasses; ++p) {
+            const int dg = (int)((c >> (8 * p)) & 255ull);
+            const int first = __builtin_amdgcn_readfirstlane(dg);
+            const unsigned long long same = __ballot(j < n && dg == first);
+            if (same == live && live != 0ull) {
+                if ((threadIdx.x & 63) == (unsigned)(__ffsll((long long)live) - 1))
+                    atomicAdd(&h[p * kDigits + dg], (unsigned)__popcll(live));
+            } else if (j < n) {
+                atomicAdd(&h[p * kDigits + dg], 1u);
+            }
+        }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < kPasses * kDigits; i += kRankSortThreads) {
@@ -118,7 +134,17 @@ __global__ void __launch_bounds__(kRankSortThreads) rsort_scatter_kernel(int n, 
         const int d = tid >> 2, q = tid & 3;
         unsigned before = 0;
         const int b0 = nblk * q / 4, b1 = nblk * (q + 1) / 4;
-        for (int x = b0; x < b1 && x < blk; ++x) before += b.hist[d * nblk + x];
+        const int b1c = b1 < blk ? b1 : blk;
+        const unsigned *row = b.hist + (size_t)d * nblk;
+        int x = b0;
+        for (; x + 8 <= b1c; x += 8) {          // eight independent loads at a time
+            unsigned t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = row[x + u];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) before += t[u];
+        }
+        for (; x < b1c; ++x) before += row[x];
         part[q * kDigits + d] = before;
     }
     unsigned tot = 0, inc = 0;
@@ -189,7 +215,17 @@ __global__ void __launch_bounds__(kRankSortThreads) choose_k_kernel(const long l
     const int seg = ((V + kSortWaves - 1) / kSortWaves + kWave - 1) / kWave * kWave;
     const int s0 = w * seg, s1 = min(V, s0 + seg);
     long long s = 0;
-    for (int j = s0 + lane; j < s1; j += kWave) s += sc[j];
+    {
+        int j = s0 + lane;
+        for (; j + 7 * kWave < s1; j += 8 * kWave) {     // eight independent loads at a time
+            long long t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = sc[j + u * kWave];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += t[u];
+        }
+        for (; j < s1; j += kWave) s += sc[j];
+    }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
     if (lane == 0) wsum[w] = s;
