@@ -239,7 +239,7 @@ int vt_build_trimmed_head_by_rank(const int64_t *counts, int32_t V, const void *
 size_t vt_choose_k_ws_bytes(int32_t V) {
     if (V < 1) return 256;
     return round_up((size_t)V * sizeof(int32_t), 256) + round_up((size_t)V * sizeof(int64_t), 256) +
-           vt::rank_sort_scratch_bytes(V);
+           vt::choose_k_scratch_bytes(V) + vt::rank_sort_scratch_bytes(V);
 }
 
 int vt_choose_k(const int64_t *counts, int32_t V, int mode, double p, int64_t min_count, int64_t *out, void *ws,
@@ -255,10 +255,11 @@ int vt_choose_k(const int64_t *counts, int32_t V, int mode, double p, int64_t mi
     char *wsb = static_cast<char *>(ws);
     int *ids = reinterpret_cast<int *>(wsb);
     long long *sorted = reinterpret_cast<long long *>(wsb + round_up((size_t)V * sizeof(int32_t), 256));
-    void *scratch = wsb + round_up((size_t)V * sizeof(int32_t), 256) + round_up((size_t)V * sizeof(int64_t), 256);
+    char *bsum = wsb + round_up((size_t)V * sizeof(int32_t), 256) + round_up((size_t)V * sizeof(int64_t), 256);
+    void *scratch = bsum + vt::choose_k_scratch_bytes(V);
     const long long *c = reinterpret_cast<const long long *>(counts);
     vt::launch_rank_sort(c, V, scratch, ids, V, sorted, st);
-    vt::launch_choose_k(sorted, V, mode, p, (long long)min_count, reinterpret_cast<long long *>(out), st);
+    vt::launch_choose_k(sorted, V, mode, p, (long long)min_count, bsum, reinterpret_cast<long long *>(out), st);
     return launch_status();
 }
 

@@ -31,8 +31,9 @@ size_t rank_sort_scratch_bytes(int n);
 // null) all sorted counts
 void launch_rank_sort(const long long *counts, int n, void *scratch, int *out_ids, int n_ids, long long *out_counts,
                       hipStream_t st);
-// out: [3] = k, mass of the k largest counts, total mass
-void launch_choose_k(const long long *sorted_counts, int V, int mode, double P, long long f_min, long long *out,
-                     hipStream_t st);
+// out: [3] = k, mass of the k largest counts, total mass; scratch: choose_k_scratch_bytes(V)
+size_t choose_k_scratch_bytes(int V);
+void launch_choose_k(const long long *sorted_counts, int V, int mode, double P, long long f_min, void *scratch,
+                     long long *out, hipStream_t st);
 
 }  // namespace vt

@@ -17,8 +17,8 @@
 //   derives that, and which buffer currently holds the data, from the digit totals alone, so the
 //   host enqueues a fixed sequence without reading anything back.  With 10^7 calibration tokens
 //   three of the eight passes do work.
-// choose_k_kernel: prefix sums over the sorted counts; the smallest prefix whose mass reaches
-//   ceil(P * total), or the number of counts >= f_min.
+// choose_*: prefix sums over the sorted counts (per-workgroup sums, then every workgroup places itself in the
+//   running mass); the smallest prefix whose mass reaches ceil(P * total), or the number of counts >= f_min.
 #include "vt_build.h"
 #include "vt_device.h"
 
@@ -206,100 +206,98 @@ __global__ void __launch_bounds__(256) rsort_out_kernel(int n, int n_ids, SortBu
 
 // sc: counts sorted descending.  out[0] = k, out[1] = mass of the k largest counts, out[2] = total mass.
 //   mode 0: smallest k >= 1 with S_k >= ceil(P * total);  mode 1: k = #{c >= f_min}.
-__global__ void __launch_bounds__(kRankSortThreads) choose_k_kernel(const long long *__restrict__ sc, int V, int mode,
-                                                                    double P, long long f_min,
-                                                                    long long *__restrict__ out) {
-    __shared__ long long wsum[kSortWaves], wkept[kSortWaves];
-    __shared__ long long s_k, s_cov;
+// Two launches over the whole device, one workgroup per 1024 counts: the first writes each workgroup's sum
+// (and clears `out`), the second lets every workgroup place itself in the running mass.
+__global__ void __launch_bounds__(kRankSortThreads) choose_sum_kernel(const long long *__restrict__ sc, int V,
+                                                                      long long *__restrict__ bsum,
+                                                                      long long *__restrict__ out) {
+    __shared__ long long wsum[kSortWaves];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int seg = ((V + kSortWaves - 1) / kSortWaves + kWave - 1) / kWave * kWave;
-    const int s0 = w * seg, s1 = min(V, s0 + seg);
-    long long s = 0;
-    {
-        int j = s0 + lane;
-        for (; j + 7 * kWave < s1; j += 8 * kWave) {     // eight independent loads at a time
-            long long t[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = sc[j + u * kWave];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) s += t[u];
-        }
-        for (; j < s1; j += kWave) s += sc[j];
-    }
+    const int j = blockIdx.x * kRankSortThreads + tid;
+    long long s = j < V ? sc[j] : 0;
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
     if (lane == 0) wsum[w] = s;
+    __syncthreads();
     if (tid == 0) {
-        s_k = -1;
-        s_cov = 0;
+        long long t = 0;
+        for (int q = 0; q < kSortWaves; ++q) t += wsum[q];
+        bsum[blockIdx.x] = t;
+        if (blockIdx.x == 0) {
+            out[0] = 0;
+            out[1] = 0;
+            out[2] = 0;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kRankSortThreads) choose_k_kernel(const long long *__restrict__ sc, int V, int mode,
+                                                                    double P, long long f_min,
+                                                                    const long long *__restrict__ bsum,
+                                                                    long long *__restrict__ out) {
+    __shared__ long long red[2 * kSortWaves];
+    __shared__ long long wsum[kSortWaves];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int nblk = gridDim.x, blk = blockIdx.x;
+    // mass before this workgroup, and in total
+    long long before = 0, total = 0;
+    for (int x = tid; x < nblk; x += kRankSortThreads) {
+        const long long v = bsum[x];
+        total += v;
+        if (x < blk) before += v;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        before += __shfl_xor(before, o);
+        total += __shfl_xor(total, o);
+    }
+    if (lane == 0) {
+        red[w] = before;
+        red[kSortWaves + w] = total;
     }
     __syncthreads();
-    long long total = 0, before = 0;
+    before = 0;
+    total = 0;
     for (int q = 0; q < kSortWaves; ++q) {
-        if (q < w) before += wsum[q];
-        total += wsum[q];
+        before += red[q];
+        total += red[kSortWaves + q];
     }
+    const int j = blk * kRankSortThreads + tid;
+    const long long c = j < V ? sc[j] : 0;
+    if (blk == 0 && tid == 0) out[2] = total;
+
     if (mode == 0) {
-        long long target = (long long)ceil(P * (double)total);     // one fp64 product, then its ceiling
-        // exactly one wave holds the element that takes the running mass from below the target to at least
-        // the target (wave 0 also when the target is 0: k >= 1)
-        const bool mine = (w == 0 || before < target) && before + wsum[w] >= target && s1 > s0;
-        if (mine) {
-            long long run = before;
-            for (int j0 = s0; j0 < s1; j0 += kWave) {
-                const int j = j0 + lane;
-                const long long c = j < s1 ? sc[j] : 0;
-                long long inc = c;
+        const long long target = (long long)ceil(P * (double)total);     // one fp64 product, then its ceiling
+        // inclusive prefix of c inside the workgroup: wave scan, then the earlier waves' sums
+        long long inc = c;
 #pragma unroll
-                for (int o = 1; o < kWave; o <<= 1) {
-                    const long long t = __shfl_up(inc, o);
-                    if (lane >= o) inc += t;
-                }
-                const bool hit = j < s1 && run + inc >= target;
-                const unsigned long long b = __ballot(hit);
-                if (b != 0ull) {
-                    const int first = __ffsll((long long)b) - 1;
-                    if (lane == first) {
-                        s_k = j + 1;
-                        s_cov = run + inc;
-                    }
-                    break;
-                }
-                run += __shfl(inc, kWave - 1);
-            }
+        for (int o = 1; o < kWave; o <<= 1) {
+            const long long t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
+        }
+        if (lane == kWave - 1) wsum[w] = inc;
+        __syncthreads();
+        long long run = before;
+        for (int q = 0; q < w; ++q) run += wsum[q];
+        const long long upto = run + inc;          // S_{j+1}
+        const long long prev = upto - c;           // S_j
+        // exactly one element takes the mass from below the target to at least the target
+        // (element 0 also when the target is 0: k >= 1)
+        if (j < V && upto >= target && (j == 0 || prev < target)) {
+            out[0] = j + 1;
+            out[1] = upto;
         }
     } else {
-        // counts are sorted: k = index of the first count below f_min
-        long long kept = 0, cov = 0;
-        for (int j = s0 + lane; j < s1; j += kWave) {
-            const long long c = sc[j];
-            if (c >= f_min) {
-                kept += 1;
-                cov += c;
-            }
-        }
+        long long kept = (j < V && c >= f_min) ? 1 : 0, cov = kept ? c : 0;
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) {
             kept += __shfl_xor(kept, o);
             cov += __shfl_xor(cov, o);
         }
-        if (lane == 0) {
-            atomicAdd(reinterpret_cast<unsigned long long *>(&s_cov), (unsigned long long)cov);
-            wkept[w] = kept;
+        if (lane == 0 && kept != 0) {
+            atomicAdd(reinterpret_cast<unsigned long long *>(&out[0]), (unsigned long long)kept);
+            atomicAdd(reinterpret_cast<unsigned long long *>(&out[1]), (unsigned long long)cov);
         }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        if (mode == 0) {
-            out[0] = s_k;
-            out[1] = s_cov;
-        } else {
-            long long k = 0;
-            for (int q = 0; q < kSortWaves; ++q) k += wkept[q];
-            out[0] = k;
-            out[1] = s_cov;
-        }
-        out[2] = total;
     }
 }
 
@@ -331,9 +329,17 @@ void launch_rank_sort(const long long *counts, int n, void *scratch, int *out_id
     hipLaunchKernelGGL(rsort_out_kernel, dim3((n + 255) / 256), dim3(256), 0, st, n, n_ids, b, out_ids, out_counts);
 }
 
-void launch_choose_k(const long long *sorted_counts, int V, int mode, double P, long long f_min, long long *out,
-                     hipStream_t st) {
-    hipLaunchKernelGGL(choose_k_kernel, dim3(1), dim3(kRankSortThreads), 0, st, sorted_counts, V, mode, P, f_min, out);
+size_t choose_k_scratch_bytes(int V) {
+    return round256((((size_t)V + kRankSortThreads - 1) / kRankSortThreads) * sizeof(long long));
+}
+
+void launch_choose_k(const long long *sorted_counts, int V, int mode, double P, long long f_min, void *scratch,
+                     long long *out, hipStream_t st) {
+    const int nblk = (V + kRankSortThreads - 1) / kRankSortThreads;
+    long long *bsum = static_cast<long long *>(scratch);
+    hipLaunchKernelGGL(choose_sum_kernel, dim3(nblk), dim3(kRankSortThreads), 0, st, sorted_counts, V, bsum, out);
+    hipLaunchKernelGGL(choose_k_kernel, dim3(nblk), dim3(kRankSortThreads), 0, st, sorted_counts, V, mode, P, f_min,
+                       bsum, out);
 }
 
 }  // namespace vt
