@@ -194,8 +194,9 @@ int vt_count_tokens(const void *ids, int id_type, int64_t n_ids, int32_t V, int6
 size_t vt_build_trimmed_head_ws_bytes(int32_t V, int32_t d, int32_t k) {
     (void)d;
     (void)k;
-    // rank-ordered build: the buffers of a sort of all V (count, id) pairs
-    return 256 + vt::rank_sort_scratch_bytes(V > 0 ? V : 1);
+    // the larger of: selection histograms (id order), buffers of a sort of all V (count, id) pairs (rank order)
+    const size_t a = vt::select_scratch_bytes(V > 0 ? V : 1), b = vt::rank_sort_scratch_bytes(V > 0 ? V : 1);
+    return 256 + round_up(a > b ? a : b, 256);
 }
 
 int vt_build_trimmed_head(const int64_t *counts, int32_t V, const void *W, int w_type, int32_t d, int32_t k,
@@ -211,7 +212,7 @@ int vt_build_trimmed_head(const int64_t *counts, int32_t V, const void *W, int w
         return VT_ERR_WORKSPACE;
     (void)hipGetLastError();
     hipStream_t st = static_cast<hipStream_t>(stream);
-    vt::launch_select_topk(reinterpret_cast<const long long *>(counts), V, k, map, st);
+    vt::launch_select_topk(reinterpret_cast<const long long *>(counts), V, k, static_cast<char *>(ws) + 256, map, st);
     if (W != nullptr) vt::launch_gather_rows(W, row_bytes, map, k, W_trim, st);
     return launch_status();
 }

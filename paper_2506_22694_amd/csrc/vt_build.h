@@ -20,8 +20,9 @@ hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V
 
 // ---- Eq. 1 ----
 constexpr int kSelectThreads = 1024;
-// scratch: a few words (threshold, tie budget)
-void launch_select_topk(const long long *counts, int V, int k, int *map, hipStream_t st);
+// scratch: select_scratch_bytes(V) of device memory, no initialisation
+size_t select_scratch_bytes(int V);
+void launch_select_topk(const long long *counts, int V, int k, void *scratch, int *map, hipStream_t st);
 void launch_gather_rows(const void *W, size_t row_bytes, const int *map, int k, void *W_trim, hipStream_t st);
 
 // ---- Sec. 3.2: frequency-rank order, Top-P / minimum-count choice of k ----

@@ -1,9 +1,17 @@
 // Eq. 1 of the paper: V_trim = V[Top-K(c, k)], W_trim = W[Top-K(c, k), :].
 //
-// select_topk_kernel: radix select of the k-th largest count (threshold T and the
-//   number r of T-valued ids to keep; ties go to the lower id), then an
-//   id-ordered compaction that emits the selected ids already ascending -- no sort.
-//   One workgroup of 1024 threads: V is ~1e5 and the job is latency-bound.
+// Selection = radix select of the k-th largest count, most significant byte first (threshold T
+// and the number r of T-valued ids to keep; ties go to the lower id), then an id-ordered
+// compaction that emits the selected ids already ascending -- no sort.  All of it runs over the
+// whole device, one workgroup per 1024 ids, as a fixed sequence of small launches:
+//   sel_zero, sel_init   digit totals of all eight byte positions of the counts
+//   sel_hist (p = 6..0)  histogram of byte p among the ids whose higher bytes equal the prefix chosen
+//                        so far; a byte position on which all counts agree needs none (with 10^7
+//                        calibration tokens two of the seven launches do work, the others return at
+//                        once), and the highest position that varies uses the totals as they are
+//   sel_count, sel_write per-workgroup numbers of ids above / at the threshold, then the compaction
+// No launch depends on host knowledge of the data: every workgroup re-derives the prefix, the
+// remaining k and finally (T, r) from the histograms written by the launches before it.
 // gather_rows_kernel: W_trim[j, :] = W[map[j], :], a pure copy at HBM speed.
 #include "vt_build.h"
 #include "vt_device.h"
@@ -12,116 +20,243 @@ namespace vt {
 
 namespace {
 constexpr int kSelWaves = kSelectThreads / kWave;   // 16
-constexpr int kDigitBits = 8;
-constexpr int kDigits = 1 << kDigitBits;
-}  // namespace
+constexpr int kDigits = 256;
+constexpr int kBytes = 8;
 
-__global__ void __launch_bounds__(kSelectThreads) select_topk_kernel(const long long *__restrict__ counts, int V,
-                                                                     int k, int *__restrict__ map) {
-    // 32 histogram copies indexed by lane: at most two lanes of one instruction share an address
-    constexpr int kCopies = 32;
-    __shared__ unsigned hist[kDigits * kCopies];
-    __shared__ unsigned tot[kDigits];
-    __shared__ unsigned long long s_wave[kSelWaves];
-    __shared__ unsigned long long s_prefix;
-    __shared__ int s_kk;
-    __shared__ int s_gt[kSelWaves + 1], s_eq[kSelWaves + 1];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+struct SelBufs {
+    unsigned *gtot;    // [kBytes][kDigits] digit totals over all ids
+    unsigned *chist;   // [kBytes][kDigits] digit totals among the ids that match the prefix above that byte
+    unsigned *tab;     // [nblk][2] ids above / at the threshold per workgroup
+};
 
-    // ---- largest count -> number of significant digits
-    unsigned long long mx = 0;
-    for (int v = tid; v < V; v += kSelectThreads) {
-        const unsigned long long c = (unsigned long long)counts[v];
-        mx = c > mx ? c : mx;
-    }
-    mx = wave_max_u64(mx);
-    if (lane == 0) s_wave[w] = mx;
+// Every kernel first copies both histogram tables (16 KiB, contiguous in the scratch) into LDS: the walk
+// below reads them a few words at a time with each read depending on the previous choice.
+__device__ __forceinline__ void stage_tables(const SelBufs &b, unsigned *hs) {
+    for (int i = threadIdx.x; i < 2 * kBytes * kDigits; i += kSelectThreads) hs[i] = b.gtot[i];
     __syncthreads();
-    mx = 0;
-    for (int q = 0; q < kSelWaves; ++q) mx = s_wave[q] > mx ? s_wave[q] : mx;
-    const int nbits = mx == 0 ? 0 : 64 - __clzll((long long)mx);
-    const int ndig = (nbits + kDigitBits - 1) / kDigitBits;
-    if (tid == 0) {
-        s_prefix = 0;
-        s_kk = k;
-    }
-    __syncthreads();
+}
 
-    // ---- radix select, most significant digit first
-    for (int p = ndig - 1; p >= 0; --p) {
-        const int sh = p * kDigitBits;
-        for (int b = tid; b < kDigits * kCopies; b += kSelectThreads) hist[b] = 0u;
-        __syncthreads();
-        const unsigned long long prefix = s_prefix;
-        for (int v = tid; v < V; v += kSelectThreads) {
-            const unsigned long long c = (unsigned long long)counts[v];
-            const unsigned long long hi = (sh + kDigitBits >= 64) ? 0ull : (c >> (sh + kDigitBits));
-            if (hi == prefix) atomicAdd(&hist[(unsigned)((c >> sh) & (kDigits - 1)) * kCopies + (lane & (kCopies - 1))], 1u);
+// true iff every count has the same byte p (one bin holds all V).  All 64 lanes must call.
+__device__ __forceinline__ bool byte_idle(const unsigned *__restrict__ gtot, int p, int V) {
+    bool idle = false;
+    for (int d = lane_id(); d < kDigits; d += kWave) idle |= gtot[p * kDigits + d] == (unsigned)V;
+    return __ballot(idle) != 0ull;
+}
+
+// Walks the byte positions from 7 down to `stop + 1`, choosing at each the digit in which the k-th
+// largest count lies.  Returns the chosen bytes as `prefix` (aligned at bit 8 * (stop + 1)) and the
+// number `krem` of ids still to take among those that match the prefix; `top` = highest byte position
+// on which the counts differ (-1 if none).  All 64 lanes of the calling wave take part and get the
+// same result.
+struct SelState {
+    unsigned long long prefix;
+    int krem;
+    int top;
+};
+__device__ __forceinline__ SelState sel_state(const unsigned *hs, int V, int k, int stop) {
+    const unsigned *gtot = hs, *chist = hs + kBytes * kDigits;
+    const int lane = lane_id();
+    SelState s;
+    s.prefix = 0ull;
+    s.krem = k;
+    s.top = -1;
+    for (int q = kBytes - 1; q > stop; --q) {
+        const bool idle = byte_idle(gtot, q, V);
+        if (!idle && s.top < 0) s.top = q;
+        const unsigned *H = (idle || q == s.top) ? gtot + q * kDigits : chist + q * kDigits;
+        // lane l holds digits 255 - 4 l .. 252 - 4 l (descending); inclusive scan over lanes
+        unsigned v[4], sum = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[i] = H[255 - (4 * lane + i)];
+            sum += v[i];
         }
-        __syncthreads();
-        if (tid < kDigits) {
-            unsigned s = 0;
-            for (int q = 0; q < kCopies; ++q) s += hist[tid * kCopies + ((q + tid) & (kCopies - 1))];
-            tot[tid] = s;
+        unsigned inc = sum;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const unsigned t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
         }
-        __syncthreads();
-        if (tid == 0) {
-            int kk = s_kk;
-            unsigned cum = 0;
-            int dg = kDigits - 1;
-            for (; dg > 0; --dg) {
-                if (cum + tot[dg] >= (unsigned)kk) break;
-                cum += tot[dg];
+        const unsigned long long hit = __ballot(inc >= (unsigned)s.krem);
+        // hit is never empty: the candidates number at least krem
+        const int first = __ffsll((long long)hit) - 1;
+        unsigned above = inc - sum;        // ids in higher digits, as seen by this lane
+        int dsel = 0;
+        unsigned asel = 0;
+        bool found = false;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (!found && above + v[i] >= (unsigned)s.krem) {
+                dsel = 255 - (4 * lane + i);
+                asel = above;
+                found = true;
             }
-            s_kk = kk - (int)cum;
-            s_prefix = (prefix << kDigitBits) | (unsigned)dg;
+            above += v[i];
         }
-        __syncthreads();
+        const int d = __builtin_amdgcn_readlane(dsel, first);
+        const unsigned a = (unsigned)__builtin_amdgcn_readlane((int)asel, first);
+        s.prefix = (s.prefix << 8) | (unsigned long long)d;
+        s.krem -= (int)a;
     }
-    const unsigned long long T = s_prefix;   // the k-th largest count
-    const int r = s_kk;                      // how many ids with count == T are kept (lowest ids)
+    return s;
+}
 
-    // ---- id-ordered compaction; wave w owns a contiguous id range
-    const int span = ((V + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-    const int v0 = w * span, v1 = min(V, v0 + span);
-    int ngt = 0, neq = 0;
-    for (int v = v0 + lane; v < v0 + span; v += kWave) {
-        const bool in = v < v1;
-        const unsigned long long c = in ? (unsigned long long)counts[v] : 0ull;
-        ngt += __popcll(__ballot(in && c > T));
-        neq += __popcll(__ballot(in && c == T));
+__global__ void __launch_bounds__(256) sel_zero_kernel(unsigned *p, int nwords) {
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < nwords; i += gridDim.x * 256) p[i] = 0u;
+}
+
+__global__ void __launch_bounds__(kSelectThreads) sel_init_kernel(const long long *__restrict__ counts, int V,
+                                                                  SelBufs b) {
+    __shared__ unsigned h[kBytes * kDigits];
+    for (int i = threadIdx.x; i < kBytes * kDigits; i += kSelectThreads) h[i] = 0u;
+    __syncthreads();
+    const int j = blockIdx.x * kSelectThreads + threadIdx.x;
+    const bool in = j < V;
+    const unsigned long long c = in ? (unsigned long long)counts[j] : 0ull;
+    const unsigned long long live = __ballot(in);
+    // the upper bytes are the same in nearly every count (zero): when a whole wave agrees on a digit one
+    // lane adds for all, instead of 64 LDS atomics queueing on one address
+#pragma unroll
+    for (int p = 0; p < kBytes; ++p) {
+        const int dg = (int)((c >> (8 * p)) & 255ull);
+        const int first = __builtin_amdgcn_readfirstlane(dg);
+        const unsigned long long same = __ballot(in && dg == first);
+        if (same == live && live != 0ull) {
+            if (lane_id() == __ffsll((long long)live) - 1) atomicAdd(&h[p * kDigits + dg], (unsigned)__popcll(live));
+        } else if (in) {
+            atomicAdd(&h[p * kDigits + dg], 1u);
+        }
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kBytes * kDigits; i += kSelectThreads) {
+        if (h[i] != 0u) atomicAdd(&b.gtot[i], h[i]);
+    }
+}
+
+__global__ void __launch_bounds__(kSelectThreads) sel_hist_kernel(const long long *__restrict__ counts, int V, int k,
+                                                                  int p, SelBufs b) {
+    __shared__ unsigned h[kDigits];
+    __shared__ unsigned hs[2 * kBytes * kDigits];
+    stage_tables(b, hs);
+    if (byte_idle(hs, p, V)) return;
+    const SelState s = sel_state(hs, V, k, p);
+    if (s.top < 0 || p >= s.top) return;          // the highest varying byte uses the totals themselves
+    if (threadIdx.x < kDigits) h[threadIdx.x] = 0u;
+    __syncthreads();
+    const int j = blockIdx.x * kSelectThreads + threadIdx.x;
+    if (j < V) {
+        const unsigned long long c = (unsigned long long)counts[j];
+        if ((c >> (8 * (p + 1))) == s.prefix) atomicAdd(&h[(int)((c >> (8 * p)) & 255ull)], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < kDigits && h[threadIdx.x] != 0u) atomicAdd(&b.chist[p * kDigits + threadIdx.x], h[threadIdx.x]);
+}
+
+// T = the k-th largest count, r = how many ids with count == T are kept (the lowest ids)
+__device__ __forceinline__ void sel_threshold(const unsigned *hs, int V, int k, unsigned long long &T, int &r) {
+    const SelState s = sel_state(hs, V, k, -1);
+    T = s.prefix;
+    r = s.krem;
+}
+
+__global__ void __launch_bounds__(kSelectThreads) sel_count_kernel(const long long *__restrict__ counts, int V, int k,
+                                                                   SelBufs b) {
+    __shared__ int s_gt[kSelWaves], s_eq[kSelWaves];
+    __shared__ unsigned hs[2 * kBytes * kDigits];
+    stage_tables(b, hs);
+    unsigned long long T;
+    int r;
+    sel_threshold(hs, V, k, T, r);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int j = blockIdx.x * kSelectThreads + tid;
+    const unsigned long long c = j < V ? (unsigned long long)counts[j] : 0ull;
+    const int ngt = __popcll(__ballot(j < V && c > T)), neq = __popcll(__ballot(j < V && c == T));
     if (lane == 0) {
-        s_gt[w + 1] = ngt;
-        s_eq[w + 1] = neq;
+        s_gt[w] = ngt;
+        s_eq[w] = neq;
     }
     __syncthreads();
     if (tid == 0) {
-        s_gt[0] = 0;
-        s_eq[0] = 0;
+        int g = 0, e = 0;
+        for (int q = 0; q < kSelWaves; ++q) {
+            g += s_gt[q];
+            e += s_eq[q];
+        }
+        b.tab[2 * blockIdx.x] = (unsigned)g;
+        b.tab[2 * blockIdx.x + 1] = (unsigned)e;
+    }
+}
+
+__global__ void __launch_bounds__(kSelectThreads) sel_write_kernel(const long long *__restrict__ counts, int V, int k,
+                                                                   SelBufs b, int *__restrict__ map) {
+    __shared__ int s_gt[kSelWaves + 1], s_eq[kSelWaves + 1];
+    __shared__ int s_red[2 * kSelWaves];
+    __shared__ unsigned hs[2 * kBytes * kDigits];
+    stage_tables(b, hs);
+    unsigned long long T;
+    int r;
+    sel_threshold(hs, V, k, T, r);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    // ids above / at the threshold in the workgroups before this one
+    int gb = 0, eb = 0;
+    for (int x = tid; x < (int)blockIdx.x; x += kSelectThreads) {
+        gb += (int)b.tab[2 * x];
+        eb += (int)b.tab[2 * x + 1];
+    }
+    gb = wave_sum_i32(gb);
+    eb = wave_sum_i32(eb);
+    if (lane == 0) {
+        s_red[w] = gb;
+        s_red[kSelWaves + w] = eb;
+    }
+    const int j = blockIdx.x * kSelectThreads + tid;
+    const unsigned long long c = j < V ? (unsigned long long)counts[j] : 0ull;
+    const bool gt = j < V && c > T, eq = j < V && c == T;
+    const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+    if (lane == 0) {
+        s_gt[w + 1] = __popcll(bg);
+        s_eq[w + 1] = __popcll(be);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int g = 0, e = 0;
+        for (int q = 0; q < kSelWaves; ++q) {
+            g += s_red[q];
+            e += s_red[kSelWaves + q];
+        }
+        s_gt[0] = g;
+        s_eq[0] = e;
         for (int q = 1; q <= kSelWaves; ++q) {
             s_gt[q] += s_gt[q - 1];
             s_eq[q] += s_eq[q - 1];
         }
     }
     __syncthreads();
-    int gbase = s_gt[w], ebase = s_eq[w];
-    const unsigned long long lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    for (int v = v0 + lane; v < v0 + span; v += kWave) {
-        const bool in = v < v1;
-        const unsigned long long c = in ? (unsigned long long)counts[v] : 0ull;
-        const bool gt = in && c > T, eq = in && c == T;
-        const unsigned long long bg = __ballot(gt), be = __ballot(eq);
-        const int gt_before = gbase + __popcll(bg & lt_mask);
-        const int eq_before = ebase + __popcll(be & lt_mask);
-        if (gt || (eq && eq_before < r)) map[gt_before + min(eq_before, r)] = v;
-        gbase += __popcll(bg);
-        ebase += __popcll(be);
-    }
+    const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    const int gt_before = s_gt[w] + __popcll(bg & below);
+    const int eq_before = s_eq[w] + __popcll(be & below);
+    if (gt || (eq && eq_before < r)) map[gt_before + min(eq_before, r)] = j;
 }
 
-void launch_select_topk(const long long *counts, int V, int k, int *map, hipStream_t st) {
-    hipLaunchKernelGGL(select_topk_kernel, dim3(1), dim3(kSelectThreads), 0, st, counts, V, k, map);
+}  // namespace
+
+size_t select_scratch_bytes(int V) {
+    const size_t nblk = ((size_t)V + kSelectThreads - 1) / kSelectThreads;
+    return (2 * kBytes * kDigits + 2 * nblk) * sizeof(unsigned);
+}
+
+void launch_select_topk(const long long *counts, int V, int k, void *scratch, int *map, hipStream_t st) {
+    const int nblk = (V + kSelectThreads - 1) / kSelectThreads;
+    SelBufs b;
+    b.gtot = static_cast<unsigned *>(scratch);
+    b.chist = b.gtot + kBytes * kDigits;
+    b.tab = b.chist + kBytes * kDigits;
+    hipLaunchKernelGGL(sel_zero_kernel, dim3(4), dim3(256), 0, st, b.gtot, 2 * kBytes * kDigits);
+    hipLaunchKernelGGL(sel_init_kernel, dim3(nblk), dim3(kSelectThreads), 0, st, counts, V, b);
+    for (int p = kBytes - 2; p >= 0; --p)
+        hipLaunchKernelGGL(sel_hist_kernel, dim3(nblk), dim3(kSelectThreads), 0, st, counts, V, k, p, b);
+    hipLaunchKernelGGL(sel_count_kernel, dim3(nblk), dim3(kSelectThreads), 0, st, counts, V, k, b);
+    hipLaunchKernelGGL(sel_write_kernel, dim3(nblk), dim3(kSelectThreads), 0, st, counts, V, k, b, map);
 }
 
 // One wave copies one row at a time with 16-byte lanes; rows are independent.
