@@ -68,6 +68,14 @@ __device__ __forceinline__ int source_buffer(const unsigned *__restrict__ gtot, 
     return moved & 1;
 }
 
+// Every later kernel copies the digit totals (8 KiB) into LDS first: pass_active / source_buffer read them
+// many times over.
+template <int T>
+__device__ __forceinline__ void stage_totals(const unsigned *__restrict__ gtot, unsigned *gs) {
+    for (int i = threadIdx.x; i < kPasses * kDigits; i += T) gs[i] = gtot[i];
+    __syncthreads();
+}
+
 __global__ void __launch_bounds__(256) rsort_zero_kernel(unsigned *gtot) {
     for (int i = threadIdx.x; i < kPasses * kDigits; i += 256) gtot[i] = 0u;
 }
@@ -109,8 +117,10 @@ __global__ void __launch_bounds__(kRankSortThreads) rsort_init_kernel(const long
 
 __global__ void __launch_bounds__(kRankSortThreads) rsort_hist_kernel(int n, int p, SortBufs b) {
     __shared__ unsigned h[kDigits];
-    if (!pass_active(b.gtot, p, n)) return;
-    const int src = source_buffer(b.gtot, p, n);
+    __shared__ unsigned gs[kPasses * kDigits];
+    stage_totals<kRankSortThreads>(b.gtot, gs);
+    if (!pass_active(gs, p, n)) return;
+    const int src = source_buffer(gs, p, n);
     if (threadIdx.x < kDigits) h[threadIdx.x] = 0u;
     __syncthreads();
     const int j = blockIdx.x * kRankSortThreads + threadIdx.x;
@@ -123,8 +133,10 @@ __global__ void __launch_bounds__(kRankSortThreads) rsort_scatter_kernel(int n, 
     __shared__ unsigned wcnt[kSortWaves * kDigits];   // [wave][digit]: elements of that digit in earlier waves
     __shared__ unsigned part[4 * kDigits];            // sums over a quarter of the earlier workgroups
     __shared__ unsigned offs[kDigits];                // first output slot of this workgroup's run of each digit
-    if (!pass_active(b.gtot, p, n)) return;
-    const int src = source_buffer(b.gtot, p, n);
+    __shared__ unsigned gs[kPasses * kDigits];
+    stage_totals<kRankSortThreads>(b.gtot, gs);
+    if (!pass_active(gs, p, n)) return;
+    const int src = source_buffer(gs, p, n);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int nblk = gridDim.x, blk = blockIdx.x;
 
@@ -149,7 +161,7 @@ __global__ void __launch_bounds__(kRankSortThreads) rsort_scatter_kernel(int n, 
     }
     unsigned tot = 0, inc = 0;
     if (tid < kDigits) {
-        tot = b.gtot[p * kDigits + (255 - tid)];      // digit totals in descending-digit order
+        tot = gs[p * kDigits + (255 - tid)];          // digit totals in descending-digit order
         inc = tot;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) {         // inclusive scan inside each of the four waves
@@ -196,7 +208,9 @@ __global__ void __launch_bounds__(kRankSortThreads) rsort_scatter_kernel(int n, 
 
 __global__ void __launch_bounds__(256) rsort_out_kernel(int n, int n_ids, SortBufs b, int *__restrict__ out_ids,
                                                         long long *__restrict__ out_counts) {
-    const int src = source_buffer(b.gtot, kPasses, n);
+    __shared__ unsigned gs[kPasses * kDigits];
+    stage_totals<256>(b.gtot, gs);
+    const int src = source_buffer(gs, kPasses, n);
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j < n_ids) out_ids[j] = b.ids[src][j];
     if (out_counts != nullptr && j < n) out_counts[j] = (long long)b.keys[src][j];
