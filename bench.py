@@ -311,9 +311,21 @@ def main():
             "expand_n8_m8_K8_us": replay_us(lambda: vt.tree_expand(cum8, out_logp, out_ids, min(8, n * m), out=o3)),
             "rerank_N136_T32_us": replay_us(lambda: vt.tree_rerank(c136, 32, out=o60)),
             "rerank_N392_T60_us": replay_us(lambda: vt.tree_rerank(c392, 60, out=o60)),
+            # one tree level = draft step + expansion (same W_trim copy every time, i.e. warm): two launches,
+            # and the single fused launch of vt_draft_tree_level
             "step_plus_expand_us": replay_us(lambda: (step(0), vt.tree_expand(cum8, out_logp, out_ids, min(8, n * m),
                                                                              out=o3)), reps=30),
+            "tree_level_fused_us": replay_us(lambda: vt.draft_tree_level(h, copies[0], map_, m, cum8, min(8, n * m),
+                                                                        ws=ws, out=o3, out_ids=out_ids,
+                                                                        out_logp=out_logp), reps=30),
+            "step_alone_warm_us": replay_us(lambda: step(0), reps=30),
         }
+        # the same three, launched eagerly back to back (what a caller without a graph pays)
+        tree_sel["eager_step_plus_expand_us"] = round(time_region(
+            lambda r: (step(0), vt.tree_expand(cum8, out_logp, out_ids, min(8, n * m), out=o3)), 100), 3)
+        tree_sel["eager_tree_level_fused_us"] = round(time_region(
+            lambda r: vt.draft_tree_level(h, copies[0], map_, m, cum8, min(8, n * m), ws=ws, out=o3, out_ids=out_ids,
+                                          out_logp=out_logp), 100), 3)
         log("tree selection (HIP-graph replay):", tree_sel)
 
     sweep = None

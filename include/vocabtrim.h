@@ -228,6 +228,21 @@ int vt_tree_expand(const float *parent_cum, const float *step_logp, const int32_
 int vt_tree_rerank(const float *cum, int32_t N, int32_t T, int32_t *out_idx, void *stream);
 
 /* ------------------------------------------------------------------------
+ * vt_draft_tree_level -- one level of tree drafting in one call: the draft
+ * step for the n frontier nodes followed by vt_tree_expand on its result,
+ * with the same outputs as the two calls (bit for bit).  For n <= 8 it is ONE
+ * launch: the workgroup that merges the step's partial results also ranks
+ * the n * m candidates; larger n run the step and then the expansion kernel.
+ *   arguments as in vt_draft_head_step (no out_lse / out_logp_full) and
+ *   vt_tree_expand; out_ids / out_logp [n, m] still receive the step's result.
+ *   ws: >= vt_draft_head_step_ws_bytes(n, k, d, m), initialised as for the step.
+ * ---------------------------------------------------------------------- */
+int vt_draft_tree_level(const void *h, int h_type, int32_t n, const void *W_trim, int w_type, int32_t k,
+                        int32_t d, const int32_t *map, int32_t m, const float *parent_cum, int32_t K,
+                        int32_t *out_parent, int32_t *out_token, float *out_cum, int32_t *out_ids,
+                        float *out_logp, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
  * Measurement reference (not part of the method): reads `bytes` bytes at `p`
  * once, in the launch and load shape of the small-n draft step (*sink is
  * written only if a lane's fold of its words hits one fixed value, which keeps

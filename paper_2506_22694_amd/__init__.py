@@ -5,7 +5,7 @@ include/vocabtrim.h); this package is the thin binding plus the seeded input
 generators used by tests and the benchmark.
 """
 from .binding import (StepWorkspace, VocabTrimError, build_trimmed_head, choose_k, count_tokens, draft_head_step,
-                      load_library, tree_expand, tree_rerank)
+                      draft_tree_level, load_library, tree_expand, tree_rerank)
 
 __all__ = ["StepWorkspace", "VocabTrimError", "build_trimmed_head", "choose_k", "count_tokens", "draft_head_step",
-           "load_library", "tree_expand", "tree_rerank"]
+           "draft_tree_level", "load_library", "tree_expand", "tree_rerank"]

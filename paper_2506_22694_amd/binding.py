@@ -25,7 +25,7 @@ EXPORTS = (
     "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes", "vt_build_trimmed_head_by_rank",
     "vt_choose_k", "vt_choose_k_ws_bytes",
     "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
-    "vt_tree_expand", "vt_tree_rerank", "vt_stream_read_reference",
+    "vt_tree_expand", "vt_tree_rerank", "vt_draft_tree_level", "vt_stream_read_reference",
 )
 VT_TREE_MAX_CANDIDATES, VT_TREE_MAX_KEEP = 16384, 1024
 
@@ -71,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     L.vt_tree_expand.restype = ci
     L.vt_tree_rerank.argtypes = [vp, i32, i32, vp, vp]
     L.vt_tree_rerank.restype = ci
+    L.vt_draft_tree_level.argtypes = [vp, ci, i32, vp, ci, i32, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.vt_draft_tree_level.restype = ci
     L.vt_stream_read_reference.argtypes = [vp, sz, vp, vp]
     L.vt_stream_read_reference.restype = ci
     _lib = L
@@ -289,6 +291,39 @@ def tree_rerank(cum: torch.Tensor, T: int, out: torch.Tensor | None = None) -> t
         raise ValueError("out must be a device int32 tensor of at least T elements")
     _check(L.vt_tree_rerank(_ptr(cum), cum.numel(), T, _ptr(out), _stream(cum.device)))
     return out
+
+
+def draft_tree_level(h: torch.Tensor, W_trim: torch.Tensor, map_: torch.Tensor, m: int, parent_cum: torch.Tensor,
+                     K: int, ws: StepWorkspace | None = None, out=None, out_ids: torch.Tensor | None = None,
+                     out_logp: torch.Tensor | None = None):
+    """Draft step for the frontier rows + the tree expansion on its result, in one call.
+
+    Returns (parent int32 [K], token int32 [K], cum fp32 [K], ids int32 [n,m], logp fp32 [n,m])."""
+    L = load_library()
+    _require_cuda(h, W_trim, map_, parent_cum)
+    n, d = h.shape
+    k = W_trim.shape[0]
+    if W_trim.shape[1] != d or map_.numel() != k or map_.dtype != torch.int32:
+        raise ValueError("shape / dtype mismatch between h, W_trim and map")
+    if parent_cum.dtype != torch.float32 or parent_cum.numel() != n:
+        raise ValueError("parent_cum must be float32 [n]")
+    dev = h.device
+    if ws is None:
+        ws = StepWorkspace(n, k, d, m, dev)
+    if out_ids is None:
+        out_ids = torch.empty((n, m), dtype=torch.int32, device=dev)
+    if out_logp is None:
+        out_logp = torch.empty((n, m), dtype=torch.float32, device=dev)
+    if out is not None:
+        parent, token, cum = out
+    else:
+        parent = torch.empty(K, dtype=torch.int32, device=dev)
+        token = torch.empty(K, dtype=torch.int32, device=dev)
+        cum = torch.empty(K, dtype=torch.float32, device=dev)
+    _check(L.vt_draft_tree_level(_ptr(h), _dtype_code(h), n, _ptr(W_trim), _dtype_code(W_trim), k, d, _ptr(map_), m,
+                                 _ptr(parent_cum), K, _ptr(parent), _ptr(token), _ptr(cum), _ptr(out_ids),
+                                 _ptr(out_logp), _ptr(ws.buf), ws.nbytes, _stream(dev)))
+    return parent, token, cum, out_ids, out_logp
 
 
 # --------------------------------------------------------------------------- measurement reference

@@ -137,9 +137,17 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
 // Hidden rows handled per launch group.  A step whose n no single plan covers (more than 256 rows; more
 // than 8 rows in fp32 or with d not a multiple of 128; very long fp32 rows) runs as consecutive groups
 // of `chunk` rows, each streaming W_trim again -- slower, but every shape has an answer.
+// Tree level fused behind the step (n <= 8 path only): null members = none.
+struct TreeFuse {
+    const float *cum = nullptr;
+    int K = 0;
+    int32_t *parent = nullptr;
+    int32_t *token = nullptr;
+    float *score = nullptr;
+};
 int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, int d, const int32_t *map, int m,
                    int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws,
-                   hipStream_t st);
+                   hipStream_t st, const TreeFuse &tf);
 
 int pick_chunk(int n, int k, int d, int m, int dtype) {
     if (plan_step(n, k, d, m, dtype).ok) return n;
@@ -314,10 +322,66 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
         const int rc = run_step_group(static_cast<const char *>(h) + (size_t)i0 * row_bytes, nc, W_trim, w_type, k, d, map,
                                       m, out_ids + (size_t)i0 * m, out_logp + (size_t)i0 * m,
                                       out_lse ? out_lse + i0 : nullptr,
-                                      out_logp_full ? out_logp_full + (size_t)i0 * k : nullptr, ws, st);
+                                      out_logp_full ? out_logp_full + (size_t)i0 * k : nullptr, ws, st, TreeFuse{});
         if (rc != VT_OK) return rc;
     }
     return launch_status();
+}
+
+int vt_draft_tree_level(const void *h, int h_type, int32_t n, const void *W_trim, int w_type, int32_t k, int32_t d,
+                        const int32_t *map, int32_t m, const float *parent_cum, int32_t K, int32_t *out_parent,
+                        int32_t *out_token, float *out_cum, int32_t *out_ids, float *out_logp, void *ws,
+                        size_t ws_bytes, void *stream) {
+    if ((h_type != VT_F32 && h_type != VT_BF16) || (w_type != VT_F32 && w_type != VT_BF16)) return VT_ERR_DTYPE;
+    if (h_type != w_type) return VT_ERR_DTYPE;
+    if (n <= 0 || k <= 0 || d <= 0 || k > vt::kStepMaxK) return VT_ERR_SHAPE;
+    if (m < 1 || m > k || m > VT_MAX_TOP_M) return VT_ERR_SHAPE;
+    if ((int64_t)n * m > VT_TREE_MAX_CANDIDATES || K < 1 || (int64_t)K > (int64_t)n * m) return VT_ERR_SHAPE;
+    if (h == nullptr || W_trim == nullptr || map == nullptr || out_ids == nullptr || out_logp == nullptr ||
+        parent_cum == nullptr || out_parent == nullptr || out_token == nullptr || out_cum == nullptr)
+        return VT_ERR_NULL;
+    const size_t row_bytes = (size_t)d * elem_size(w_type);
+    if ((row_bytes & 15) != 0 || !aligned(h, 16) || !aligned(W_trim, 16) || !aligned(map, 4) ||
+        !aligned(out_ids, 4) || !aligned(out_logp, 4) || !aligned(parent_cum, 4) || !aligned(out_parent, 4) ||
+        !aligned(out_token, 4) || !aligned(out_cum, 4))
+        return VT_ERR_ALIGN;
+    const int chunk = pick_chunk(n, k, d, m, w_type);
+    if (chunk == 0) return VT_ERR_SHAPE;
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < vt_draft_head_step_ws_bytes(n, k, d, m))
+        return VT_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // one launch when the small-n kernel covers the whole step: its last workgroup also ranks the candidates
+    if (chunk == n && n <= vt::kGemvMaxN && n * m <= vt::kStepWaves * 64) {
+        TreeFuse tf;
+        tf.cum = parent_cum;
+        tf.K = K;
+        tf.parent = out_parent;
+        tf.token = out_token;
+        tf.score = out_cum;
+        const int rc = run_step_group(h, n, W_trim, w_type, k, d, map, m, out_ids, out_logp, nullptr, nullptr, ws, st, tf);
+        if (rc != VT_OK) return rc;
+        return launch_status();
+    }
+    for (int i0 = 0; i0 < n; i0 += chunk) {
+        const int nc = n - i0 < chunk ? n - i0 : chunk;
+        const int rc = run_step_group(static_cast<const char *>(h) + (size_t)i0 * row_bytes, nc, W_trim, w_type, k, d, map,
+                                      m, out_ids + (size_t)i0 * m, out_logp + (size_t)i0 * m, nullptr, nullptr, ws, st,
+                                      TreeFuse{});
+        if (rc != VT_OK) return rc;
+    }
+    vt::TreeArgs a;
+    a.parent_cum = parent_cum;
+    a.vals = out_logp;
+    a.ids = out_ids;
+    a.N = n * m;
+    a.m = m;
+    a.K = K;
+    a.index_order = 0;
+    a.out_a = out_parent;
+    a.out_token = out_token;
+    a.out_score = out_cum;
+    return device_status(vt::launch_tree_select(a, st));
 }
 
 }  // extern "C"
@@ -327,7 +391,7 @@ namespace {
 // One launch group of the draft step: n rows that a single plan covers.  Arguments are validated.
 int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, int d, const int32_t *map, int m,
                    int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws,
-                   hipStream_t st) {
+                   hipStream_t st, const TreeFuse &tf) {
     const StepPlan p = plan_step(n, k, d, m, w_type);
     if (!p.ok) return VT_ERR_SHAPE;
     char *wsb = static_cast<char *>(ws);
@@ -356,13 +420,25 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.out_lse = out_lse;
         a.out_logp_full = out_logp_full;
         a.fin_conc = p.fin_conc;
+        a.tree_cum = tf.cum;
+        a.tree_K = tf.K;
+        a.tree_parent = tf.parent;
+        a.tree_token = tf.token;
+        a.tree_score = tf.score;
+        size_t lds = p.lds;
+        if (tf.cum != nullptr) {
+            // the fused ranking needs 12 bytes per (power-of-two padded) candidate plus a few words
+            size_t N2 = 64;
+            while (N2 < (size_t)n * m) N2 <<= 1;
+            if (lds < N2 * 12 + 256) lds = N2 * 12 + 256;
+        }
         const bool bf16 = w_type == VT_BF16;
         hipError_t e = hipErrorInvalidValue;
         switch (p.NP) {
-            case 1: e = vt::launch_head_gemv_np1(bf16, p.CS, a, p.lds, st); break;
-            case 2: e = vt::launch_head_gemv_np2(bf16, p.CS, a, p.lds, st); break;
-            case 4: e = vt::launch_head_gemv_np4(bf16, p.CS, a, p.lds, st); break;
-            case 8: e = vt::launch_head_gemv_np8(bf16, p.CS, a, p.lds, st); break;
+            case 1: e = vt::launch_head_gemv_np1(bf16, p.CS, a, lds, st); break;
+            case 2: e = vt::launch_head_gemv_np2(bf16, p.CS, a, lds, st); break;
+            case 4: e = vt::launch_head_gemv_np4(bf16, p.CS, a, lds, st); break;
+            case 8: e = vt::launch_head_gemv_np8(bf16, p.CS, a, lds, st); break;
             default: break;
         }
         if (e != hipSuccess) return device_status(e);

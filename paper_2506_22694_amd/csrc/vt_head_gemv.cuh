@@ -21,6 +21,7 @@
 #include "vt_device.h"
 #include "vt_step.h"
 #include "vt_step_tail.cuh"
+#include "vt_tree_dev.cuh"
 #include <type_traits>
 
 namespace vt {
@@ -347,6 +348,30 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
     if (!arrive_and_elect(a.tickets, a.nblocks)) return;
     finalize_rows(a.pms, a.pkeys, a.nblocks, a.L, a.n, a.m, a.fin_conc, a.out_ids, a.out_logp, a.out_lse, lse_buf,
                   smem, w, lane);
+    if (a.tree_cum != nullptr) {
+        // Fused tree level: the rows' tokens and log-probs were just written by the waves of this workgroup;
+        // once those stores are acknowledged the workgroup ranks the n * m candidates cum[i] + logp[i][j]
+        // (rank by counting, keys in the LDS the merge no longer needs) and keeps the best tree_K.
+        wait_stores_done();
+        __syncthreads();
+        TreeArgs t;
+        t.parent_cum = a.tree_cum;
+        t.vals = a.out_logp;
+        t.ids = a.out_ids;
+        t.N = a.n * a.m;
+        t.m = a.m;
+        t.K = a.tree_K;
+        t.index_order = 0;
+        t.out_a = a.tree_parent;
+        t.out_token = a.tree_token;
+        t.out_score = a.tree_score;
+        int N2 = kWave;
+        while (N2 < t.N) N2 <<= 1;
+        unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);
+        unsigned *cnt = reinterpret_cast<unsigned *>(smem + (size_t)N2 * 8);
+        int *wave_tot = reinterpret_cast<int *>(smem + (size_t)N2 * 12);
+        tree_select_by_count<NW * kWave, true>(t, N2, keys, cnt, wave_tot);
+    }
 }
 
 template <bool BF16, int NP, int CS>

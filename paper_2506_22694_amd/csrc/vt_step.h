@@ -34,6 +34,13 @@ struct StepArgs {
     float *out_lse;           // [n] or null
     float *out_logp_full;     // [n, k] or null (raw logits are written first, lse subtracted later)
     int fin_conc;             // waves that run the finalize stage concurrently (LDS budget)
+    // fused tree level (all null / 0 when not asked for): after the merge the last workgroup keeps the
+    // tree_K best of the n * m candidates scored tree_cum[i] + out_logp[i][j]
+    const float *tree_cum;    // [n] or null
+    int tree_K;
+    int *tree_parent;         // [tree_K]
+    int *tree_token;          // [tree_K]
+    float *tree_score;        // [tree_K]
 };
 
 // ---- matrix-core path (n > 8) ----

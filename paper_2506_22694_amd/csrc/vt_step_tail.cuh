@@ -356,11 +356,13 @@ __device__ __forceinline__ void finalize_rows(const unsigned long long *__restri
                                            int fin_conc, int *__restrict__ out_ids, float *__restrict__ out_logp,
                                            float *__restrict__ out_lse, float *__restrict__ lse_buf,
                                            unsigned char *smem, int w, int lane) {
-    if (w >= fin_conc) return;
-    unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * B * L;
-    for (int i = w; i < n; i += fin_conc)
-        finalize_row<false>(pms + (size_t)i * B, pkeys + (size_t)i * B * L, B, L, m, stage, out_ids + (size_t)i * m,
-                     out_logp + (size_t)i * m, out_lse ? out_lse + i : nullptr, lse_buf + i, lane);
+    if (w < fin_conc) {
+        unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * B * L;
+        for (int i = w; i < n; i += fin_conc)
+            finalize_row<false>(pms + (size_t)i * B, pkeys + (size_t)i * B * L, B, L, m, stage,
+                                out_ids + (size_t)i * m, out_logp + (size_t)i * m, out_lse ? out_lse + i : nullptr,
+                                lse_buf + i, lane);
+    }
 }
 
 }  // namespace vt

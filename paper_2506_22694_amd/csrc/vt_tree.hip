@@ -13,68 +13,17 @@
 // key" is "better score, then lower index".
 #include "vt_tree.h"
 #include "vt_device.h"
+#include "vt_tree_dev.cuh"
 
 namespace vt {
 
 namespace {
 
-__device__ __forceinline__ unsigned long long tree_key(const TreeArgs &a, int c) {
-    if (c >= a.N) return kNoKey;
-    float s = a.vals[c];
-    if (a.parent_cum != nullptr) s = __fadd_rn(a.parent_cum[c / a.m], s);   // one fp32 addition
-    return make_key(s, c);
-}
-
-__device__ __forceinline__ void tree_emit(const TreeArgs &a, int slot, unsigned long long key) {
-    const int c = key_id(key);
-    a.out_a[slot] = a.parent_cum != nullptr ? c / a.m : c;
-    if (a.out_token != nullptr) a.out_token[slot] = a.ids != nullptr ? a.ids[c] : c;
-    if (a.out_score != nullptr) a.out_score[slot] = key_logit(key);
-}
-
 __global__ void __launch_bounds__(kTreeThreads) tree_count_kernel(const TreeArgs a, int N2) {
     __shared__ unsigned long long keys[kTreeCountMaxN];
     __shared__ unsigned cnt[kTreeCountMaxN];
     __shared__ int wave_tot[kTreeThreads / kWave];
-    const int tid = threadIdx.x;
-    if (tid < N2) {
-        keys[tid] = tree_key(a, tid);
-        cnt[tid] = 0u;
-    }
-    __syncthreads();
-    const int c = tid & (N2 - 1), part = tid / N2, parts = kTreeThreads / N2;
-    const int j0 = (int)((long long)a.N * part / parts), j1 = (int)((long long)a.N * (part + 1) / parts);
-    const unsigned long long mine = keys[c];
-    unsigned above = 0;
-    int j = j0;
-    for (; j + 8 <= j1; j += 8) {      // eight LDS reads in flight: the loop is latency-bound otherwise
-        unsigned long long t[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = keys[j + u];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) above += t[u] > mine ? 1u : 0u;
-    }
-    for (; j < j1; ++j) above += keys[j] > mine ? 1u : 0u;
-    if (parts > 1) {
-        if (above != 0u) atomicAdd(&cnt[c], above);
-        __syncthreads();
-        above = cnt[c];
-    }
-    // threads 0 .. N2-1 (whole waves) own one candidate each
-    const bool keep = tid < a.N && (int)above < a.K;
-    if (!a.index_order) {
-        if (keep) tree_emit(a, (int)above, mine);
-        return;
-    }
-    const unsigned long long bal = __ballot(keep);
-    const int lane = tid & 63, w = tid >> 6;
-    if (lane == 0) wave_tot[w] = __popcll(bal);
-    __syncthreads();
-    if (!keep) return;
-    int base = 0;
-    for (int q = 0; q < w; ++q) base += wave_tot[q];
-    const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    tree_emit(a, base + __popcll(bal & below), mine);
+    tree_select_by_count<kTreeThreads, false>(a, N2, keys, cnt, wave_tot);
 }
 
 // descending bitonic sort of n2 (a power of two) keys in LDS by all threads of the workgroup
@@ -99,10 +48,10 @@ __device__ void bitonic_sort_desc(unsigned long long *keys, int n2) {
 
 __global__ void __launch_bounds__(kTreeThreads) tree_sort_kernel(const TreeArgs a, int N2, int K2) {
     extern __shared__ __align__(16) unsigned long long skeys[];
-    for (int c = threadIdx.x; c < N2; c += kTreeThreads) skeys[c] = tree_key(a, c);
+    for (int c = threadIdx.x; c < N2; c += kTreeThreads) skeys[c] = tree_key<false>(a, c);
     bitonic_sort_desc(skeys, N2);
     if (!a.index_order) {
-        for (int r = threadIdx.x; r < a.K; r += kTreeThreads) tree_emit(a, r, skeys[r]);
+        for (int r = threadIdx.x; r < a.K; r += kTreeThreads) tree_emit<false>(a, r, skeys[r]);
         return;
     }
     // the K winners, re-keyed by index alone (~index descending = index ascending), sorted again
@@ -123,7 +72,7 @@ __global__ void __launch_bounds__(kTreeThreads) tree_sort_kernel(const TreeArgs 
     bitonic_sort_desc(byidx, K2);
     for (int r = threadIdx.x; r < a.K; r += kTreeThreads) {
         const unsigned long long s = byidx[r];
-        tree_emit(a, r, (s << 32) | (s >> 32));
+        tree_emit<false>(a, r, (s << 32) | (s >> 32));
     }
 }
 

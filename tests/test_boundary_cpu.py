@@ -150,6 +150,24 @@ def test_choose_k_and_ranked_build_argument_errors(lib):
     assert lib.vt_build_trimmed_head_ws_bytes(128256, 3072, 32768) >= 256 + 32768 * 28
 
 
+def test_draft_tree_level_argument_errors(lib):
+    f = lib.vt_draft_tree_level
+    big = 1 << 30
+    ok = [A, 1, 8, A, 1, 32768, 3072, A, 8, A, 8, A, A, A, A, A, A, big, None]
+    assert f(*ok[:2], 0, *ok[3:]) == 2                          # n
+    bad = list(ok); bad[10] = 0
+    assert f(*bad) == 2                                         # K < 1
+    bad = list(ok); bad[10] = 65
+    assert f(*bad) == 2                                         # K > n * m
+    for pos in (0, 3, 7, 9, 11, 12, 13, 14, 15):
+        bad = list(ok); bad[pos] = None
+        assert f(*bad) == 1, pos
+    bad = list(ok); bad[1] = 0
+    assert f(*bad) == 3                                         # h and W types differ
+    bad = list(ok); bad[17] = 16
+    assert f(*bad) == 5
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):

@@ -604,3 +604,30 @@ def test_two_task_heads_from_one_head_swapped_per_step():
         torch.cuda.synchronize()
         ref = oracle.draft_head_step(h, Wt_ref, map_.cpu().numpy(), m)
         check_step(oi, ol, ref, map_.cpu().numpy(), m)
+
+
+@pytest.mark.parametrize("k,d,n,m,K,dt", [(32768, 3072, 8, 8, 8, "bf16"), (4096, 512, 1, 1, 1, "bf16"),
+                                          (5000, 1024, 8, 64, 60, "bf16"), (1000, 256, 4, 4, 16, "f32"),
+                                          (2048, 2048, 3, 5, 7, "bf16"), (4096, 1024, 40, 8, 32, "bf16"),
+                                          (3000, 200, 12, 4, 9, "bf16")])
+def test_draft_tree_level_equals_step_then_expand(k, d, n, m, K, dt):
+    # fused in one launch for n <= 8, step + expansion kernel otherwise: same results either way, and
+    # both equal to the oracle's step followed by the oracle's expansion on the GPU's log-probs
+    W, map_ = synth.trimmed_head_direct(k, d, seed=k + n, dtype=dt)
+    h = synth.hidden_rows(n, d, seed=k + n + 1, dtype=dt)
+    cum = np.linspace(-0.25, -5.0, n).astype(np.float32)
+    dh, dW, dmap, dcum = to_dev(h), to_dev(W), to_dev(map_), to_dev(cum)
+    ws = vt.StepWorkspace(n, k, d, m, dev())
+    for rep in range(2):                                       # the workspace is left ready for the next call
+        parent, token, score, oi, ol = vt.draft_tree_level(dh, dW, dmap, m, dcum, K, ws=ws)
+        torch.cuda.synchronize()
+        oi2, ol2 = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
+        p2, t2, s2 = vt.tree_expand(dcum, ol2, oi2, K)
+        torch.cuda.synchronize()
+        assert torch.equal(oi, oi2) and torch.equal(ol, ol2)
+        assert torch.equal(parent, p2) and torch.equal(token, t2) and torch.equal(score, s2)
+        ref = oracle.draft_head_step(h, W, map_, m)
+        check_step(oi, ol, ref, map_, m)
+        rp, rt, rs = oracle.tree_expand(cum, ol.cpu().numpy(), oi.cpu().numpy(), K)
+        assert np.array_equal(parent.cpu().numpy(), rp) and np.array_equal(token.cpu().numpy(), rt)
+        assert np.array_equal(score.cpu().numpy(), rs)
