@@ -140,7 +140,7 @@ int vt_build_trimmed_head_by_rank(const int64_t *counts, int32_t V, const void *
  *                   the k largest counts, p * S_V one fp64 product; 0 <= p <= 1
  *   VT_K_MIN_COUNT  k = number of ids with count >= min_count (may be 0)
  *
- *   counts  [V] int64, device (values >= 0)
+ *   counts  [V] int64, device (values >= 0, their sum below 2^63)
  *   out     [3] int64, device, out: k, S_k (tokens covered), S_V (all tokens);
  *           S_k / S_V is the coverage of the calibration set.  The caller reads
  *           k back (one small copy) before sizing W_trim for the build.

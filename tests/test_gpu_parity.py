@@ -631,3 +631,54 @@ def test_draft_tree_level_equals_step_then_expand(k, d, n, m, K, dt):
         rp, rt, rs = oracle.tree_expand(cum, ol.cpu().numpy(), oi.cpu().numpy(), K)
         assert np.array_equal(parent.cpu().numpy(), rp) and np.array_equal(token.cpu().numpy(), rt)
         assert np.array_equal(score.cpu().numpy(), rs)
+
+
+def test_random_shapes_sweep_step_tree_level_and_build():
+    # seeded sweep over shapes no other test names: sizes around the tile / wave / group boundaries, both element
+    # types, planted exact ties; every case against the oracle (step, fused tree level, both build orders, choice of k)
+    rng = np.random.default_rng(20250627)
+    for it in range(70):
+        dt = "bf16" if rng.random() < 0.7 else "f32"
+        unit = 8 if dt == "bf16" else 4
+        k = int(rng.choice([1, 2, 3, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1000, 2047, 4097,
+                            int(rng.integers(1, 6000)), int(rng.integers(6000, 20000))]))
+        d = unit * int(rng.integers(1, 2048 // unit + 1))
+        if rng.random() < 0.3:
+            d = 128 * int(rng.integers(1, 17))
+        n = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 33, 64, 65, 100, 129, 256, 257]))
+        if k * d * n > 1.5e9:
+            n = max(1, int(1.5e9 // (k * d)))
+        m = int(rng.integers(1, min(k, 64) + 1))
+        if rng.random() < 0.5:
+            m = min(m, 8)
+        W, map_ = synth.trimmed_head_direct(k, d, seed=1000 + it, dtype=dt)
+        h = synth.hidden_rows(n, d, seed=2000 + it, dtype=dt)
+        if rng.random() < 0.2 and k > 4:
+            W[k // 2] = W[0]
+            W[k - 1] = W[0]
+        case = (it, k, d, n, m, dt)
+        ref = oracle.draft_head_step(h, W, map_, m)
+        oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+        check_step(oi, ol, ref, map_, m, lse)
+        K = int(rng.integers(1, n * m + 1))
+        cum = rng.normal(-3, 1, size=n).astype(np.float32)
+        p, t, sc, oi2, ol2 = vt.draft_tree_level(to_dev(h), to_dev(W), to_dev(map_), m, to_dev(cum), K)
+        torch.cuda.synchronize()
+        assert torch.equal(oi2, oi) and torch.equal(ol2, ol), case
+        rp, rt, rs = oracle.tree_expand(cum, ol.cpu().numpy(), oi.cpu().numpy(), K)
+        assert np.array_equal(p.cpu().numpy(), rp) and np.array_equal(t.cpu().numpy(), rt), case
+        assert np.array_equal(sc.cpu().numpy(), rs), case
+    for it in range(40):
+        V = int(rng.choice([1, 2, 63, 64, 65, 1023, 1024, 1025, 4097, int(rng.integers(1, 300000))]))
+        hi = int(rng.choice([1, 2, 3, 300, 70000, 2**33, 2**62]))
+        hi = max(1, min(hi, 2**62 // V))                  # the total must fit int64
+        c = rng.integers(0, hi, size=V).astype(np.int64)
+        k = int(rng.integers(1, V + 1))
+        dc = to_dev(c)
+        a, _ = vt.build_trimmed_head(dc, None, k)
+        b, _ = vt.build_trimmed_head(dc, None, k, order="rank")
+        assert np.array_equal(a.cpu().numpy(), oracle.select(c, k)), (V, hi, k)
+        assert np.array_equal(b.cpu().numpy(), oracle.rank_order(c)[:k]), (V, hi, k)
+        P, f = float(rng.random()), int(rng.integers(0, hi + 1))
+        assert vt.choose_k(dc, top_p=P) == oracle.choose_k_top_p(c, P), (V, hi, P)
+        assert vt.choose_k(dc, min_count=f) == oracle.choose_k_min_count(c, f), (V, hi, f)
