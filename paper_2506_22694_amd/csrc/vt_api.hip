@@ -35,7 +35,8 @@ struct StepPlan {
     int rpb = 0, nblocks = 0, tpitch = 0, L = 0, fin_conc = 0;
     size_t lds = 0;
     // workspace layout (byte offsets)
-    size_t off_lse = 0, off_pms = 0, off_pkeys = 0, off_hpack = 0, bytes = 0;
+    size_t off_lse = 0, off_pms = 0, off_pkeys = 0, off_hpack = 0, off_zbuf = 0, bytes = 0;
+    bool row_select = false;   // matrix-core path: logits stored, one workgroup per hidden row finishes
 };
 
 using vt::kTicketBytes;
@@ -109,8 +110,11 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         if (p.lds > (size_t)vt::kMaxDynamicLds) return p;
         const int group = p.nlists < vt::kStepMaxBlocks ? p.nlists : vt::kStepMaxBlocks;
         p.fin_stage_keys = (group + 1) * p.L;
-        int fc = (int)(vt::kFinalizeLdsBytes / ((size_t)p.fin_stage_keys * sizeof(unsigned long long)));
-        if (fc < 1) return p;
+        const int fc = (int)(vt::kFinalizeLdsBytes / ((size_t)p.fin_stage_keys * sizeof(unsigned long long)));
+        // The per-tile candidate lists cost n * L selection rounds per tile and grow to megabytes; beyond a point
+        // (measured: more than 16 tokens per row, or n * L from about 2048; always when the lists no longer fit the
+        // merge's LDS staging) the kernel stores its logits instead and a workgroup per hidden row finishes the step.
+        p.row_select = p.L > vt::kRowSelectMinL || n * p.L >= vt::kRowSelectMinWork || fc < 1;
         // one hidden row per workgroup: n <= 256 rows spread over as many CUs, and a merging wave has its
         // SIMD to itself (the selection rounds are bound by instruction issue)
         p.fin_conc = 1;
@@ -129,6 +133,8 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
     off = round_up(off + (size_t)n * p.nblocks * p.L * sizeof(unsigned long long), 256);
     p.off_hpack = off;
     if (p.mfma && p.NT >= 8) off = round_up(off + (size_t)d * p.NT * 32, 256);
+    p.off_zbuf = off;
+    if (p.row_select) off = round_up(off + (size_t)n * k * sizeof(float), 256);
     p.bytes = off;
     p.ok = true;
     return p;
@@ -459,8 +465,15 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.pkeys = pkeys;
         a.out_logp_full = out_logp_full;
         a.hpack = p.NT >= 8 ? static_cast<void *>(wsb + p.off_hpack) : nullptr;
+        a.zbuf = nullptr;
+        if (p.row_select) a.zbuf = out_logp_full != nullptr ? out_logp_full : reinterpret_cast<float *>(wsb + p.off_zbuf);
         hipError_t e = vt::launch_head_mfma(p.NT, a, p.lds, st);
         if (e != hipSuccess) return device_status(e);
+        if (p.row_select) {
+            vt::launch_row_select(a.zbuf, map, n, k, m, out_ids, out_logp, out_lse, lse_buf, st);
+            if (out_logp_full != nullptr) vt::launch_sub_lse(out_logp_full, lse_buf, n, k, st);
+            return VT_OK;
+        }
         vt::FinalizeArgs f;
         f.pms = pms;
         f.pkeys = pkeys;

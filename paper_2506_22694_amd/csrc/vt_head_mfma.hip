@@ -211,6 +211,18 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     }
     __syncthreads();
 
+    if (a.zbuf != nullptr) {
+        // store-only tail: the tile's logits go to z [n, k]; a workgroup per hidden row finishes the step
+        // (row_select_kernel).  One wave copies a hidden row's 128 logits (512 contiguous bytes) at a time.
+        for (int i = w; i < a.n; i += kStepWaves) {
+            const float *src = zt + (size_t)i * tp;
+            float *dst = a.zbuf + (size_t)i * a.k + row0;
+            if (lane < rows_b) dst[lane] = src[lane];
+            if (lane + kWave < rows_b) dst[lane + kWave] = src[lane + kWave];
+        }
+        return;
+    }
+
     if (a.L <= 16) {
         // four hidden rows per wave and pass (16 lanes each)
         for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
@@ -413,6 +425,18 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
         }
     }
     __syncthreads();
+
+    if (a.zbuf != nullptr) {
+        // store-only tail: the tile's logits go to z [n, k]; a workgroup per hidden row finishes the step
+        // (row_select_kernel).  One wave copies a hidden row's 128 logits (512 contiguous bytes) at a time.
+        for (int i = w; i < a.n; i += kStepWaves) {
+            const float *src = zt + (size_t)i * tp;
+            float *dst = a.zbuf + (size_t)i * a.k + row0;
+            if (lane < rows_b) dst[lane] = src[lane];
+            if (lane + kWave < rows_b) dst[lane + kWave] = src[lane + kWave];
+        }
+        return;
+    }
 
     if (a.L <= 16) {
         for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)

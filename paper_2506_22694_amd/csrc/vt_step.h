@@ -45,6 +45,9 @@ struct StepArgs {
 
 // ---- matrix-core path (n > 8) ----
 constexpr int kMfmaTileRows = 128;     // rows of W_trim per workgroup (16 per wave)
+constexpr int kRowSelectMinL = 16;      // matrix-core path: with more tokens per row than this, or
+constexpr int kRowSelectMinWork = 2048; // with n * min(m, 128) from this value on, the kernel stores its logits and a
+                                        // workgroup per hidden row finishes the step
 constexpr int kMfmaChunkPieces = 9;    // an h chunk is prefetched through registers: at most this many
                                        // 16-byte pieces per thread, i.e. 16 * NT * KC * 2 <= 9 * 512 * 16 bytes
 
@@ -61,6 +64,7 @@ struct MfmaArgs {
     unsigned long long *pkeys;  // [n, nlists, L]
     float *out_logp_full;     // [n, k] or null
     void *hpack;              // more than 64 hidden rows: h re-laid in operand order, d * NT * 32 bytes
+    float *zbuf;              // [n, k] or null: store the logits and leave the rest of the step to row_select_kernel
 };
 
 struct FinalizeArgs {
@@ -92,5 +96,8 @@ void launch_sub_lse(float *logp_full, const float *lse, int n, int k, hipStream_
 // zero the arrival counters
 void launch_ws_clear(unsigned *p, int nwords, hipStream_t st);
 void launch_stream_read(const void *p, size_t bytes, unsigned *sink, hipStream_t st);
+// per-row tail on stored logits z [n, k]: lse, the m best logits and their target ids (one workgroup per row)
+void launch_row_select(const float *z, const int *map, int n, int k, int m, int *out_ids, float *out_logp,
+                       float *out_lse, float *lse_buf, hipStream_t st);
 
 }  // namespace vt

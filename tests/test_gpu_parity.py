@@ -292,6 +292,16 @@ def test_step_stress_256_nodes_sampled_rows():
     assert all(len(set(r.tolist())) == m for r in ids)
 
 
+def test_step_many_rows_with_64_tokens_per_row():
+    # m = 64 with 256 tiles: the candidate lists no longer fit the merge's staging, the per-row tail takes over
+    for (k, d, n, m) in ((32768, 256, 20, 64), (32768, 256, 70, 64), (40000, 128, 12, 63)):
+        W, map_ = synth.trimmed_head_direct(k, d, seed=k + n, dtype="bf16")
+        h = synth.hidden_rows(n, d, seed=k + n, dtype="bf16")
+        ref = oracle.draft_head_step(h, W, map_, m)
+        oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+        check_step(oi, ol, ref, map_, m, lse)
+
+
 def test_step_many_rows_full_vocabulary_many_tiles():
     k, d, n, m = 128256, 2048, 24, 8     # 1002 tiles: the merge runs in several passes
     W, map_ = synth.trimmed_head_direct(k, d, seed=6000, dtype="bf16")
