@@ -70,7 +70,7 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
                 const int CS = cs_set[q];
                 if (CS >= need && CS * NP <= 24) {
                     const size_t tile = (size_t)S * NP * p.tpitch * sizeof(float);
-                    if (tile <= 96 * 1024 && p.fin_conc >= 1) {
+                    if (tile <= 96 * 1024 && (p.fin_conc >= 1 || p.L > vt::kGemvRowSelectBase - 2 * n)) {
                         p.gemv = true;
                         p.NP = NP;
                         p.CS = CS;
@@ -120,8 +120,13 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         p.fin_conc = 1;
         p.fin_lds = (size_t)p.fin_conc * p.fin_stage_keys * sizeof(unsigned long long);
     } else {
-        const size_t fin = (size_t)p.fin_conc * stage;
-        if (fin > p.lds) p.lds = fin;
+        // many tokens per row: the selection rounds of the fused tail grow with L in every workgroup and the merge
+        // stages B * L keys per row; the per-row tail on stored logits takes over (measured crossover)
+        p.row_select = p.L > vt::kGemvRowSelectBase - 2 * n;
+        if (!p.row_select) {
+            const size_t fin = (size_t)p.fin_conc * stage;
+            if (fin > p.lds) p.lds = fin;
+        }
     }
 
     size_t off = kTicketBytes;
@@ -426,6 +431,8 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.out_lse = out_lse;
         a.out_logp_full = out_logp_full;
         a.fin_conc = p.fin_conc;
+        a.zbuf = nullptr;
+        if (p.row_select) a.zbuf = out_logp_full != nullptr ? out_logp_full : reinterpret_cast<float *>(wsb + p.off_zbuf);
         a.tree_cum = tf.cum;
         a.tree_K = tf.K;
         a.tree_parent = tf.parent;
@@ -448,6 +455,25 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             default: break;
         }
         if (e != hipSuccess) return device_status(e);
+        if (p.row_select) {
+            vt::launch_row_select(a.zbuf, map, n, k, m, out_ids, out_logp, out_lse, lse_buf, st);
+            if (out_logp_full != nullptr) vt::launch_sub_lse(out_logp_full, lse_buf, n, k, st);
+            if (tf.cum != nullptr) {       // the fused tree level needs the in-kernel merge: run the expansion kernel
+                vt::TreeArgs t;
+                t.parent_cum = tf.cum;
+                t.vals = out_logp;
+                t.ids = out_ids;
+                t.N = n * m;
+                t.m = m;
+                t.K = tf.K;
+                t.index_order = 0;
+                t.out_a = tf.parent;
+                t.out_token = tf.token;
+                t.out_score = tf.score;
+                return device_status(vt::launch_tree_select(t, st));
+            }
+            return VT_OK;
+        }
     } else {
         vt::MfmaArgs a;
         a.h = h;

@@ -330,6 +330,20 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
     for (int x = 0; x < NSLOT; ++x) wait_row<0, CS>(wb[x]);
     __syncthreads();
 
+    if (a.zbuf != nullptr) {
+        // store-only tail (many tokens per row): the tile's logits, summed over the column segments, go to
+        // z [n, k]; a workgroup per hidden row finishes the step (row_select_kernel)
+        const int sstride = NP * a.tpitch;
+        for (int i = w; i < a.n; i += NW) {
+            for (int t = lane; t < rows_b; t += kWave) {
+                float v = 0.f;
+                for (int s2 = 0; s2 < S; ++s2) v += zt[(size_t)s2 * sstride + (size_t)i * a.tpitch + t];
+                a.zbuf[(size_t)i * a.k + row0 + t] = v;
+            }
+        }
+        return;
+    }
+
     {
         const int sstride = NP * a.tpitch;
         for (int i = w; i < a.n; i += NW) {

@@ -34,6 +34,7 @@ struct StepArgs {
     float *out_lse;           // [n] or null
     float *out_logp_full;     // [n, k] or null (raw logits are written first, lse subtracted later)
     int fin_conc;             // waves that run the finalize stage concurrently (LDS budget)
+    float *zbuf;              // [n, k] or null: store the logits and leave the rest of the step to row_select_kernel
     // fused tree level (all null / 0 when not asked for): after the merge the last workgroup keeps the
     // tree_K best of the n * m candidates scored tree_cum[i] + out_logp[i][j]
     const float *tree_cum;    // [n] or null
@@ -46,6 +47,8 @@ struct StepArgs {
 // ---- matrix-core path (n > 8) ----
 constexpr int kMfmaTileRows = 128;     // rows of W_trim per workgroup (16 per wave)
 constexpr int kRowSelectMinL = 16;      // matrix-core path: with more tokens per row than this, or
+// small-n path: the same switch when L > 28 - 2 n (measured crossovers: L = 12 at n = 8, about 25 at n = 1)
+constexpr int kGemvRowSelectBase = 28;
 constexpr int kRowSelectMinWork = 2048; // with n * min(m, 128) from this value on, the kernel stores its logits and a
                                         // workgroup per hidden row finishes the step
 constexpr int kMfmaChunkPieces = 9;    // an h chunk is prefetched through registers: at most this many

@@ -692,3 +692,24 @@ def test_random_shapes_sweep_step_tree_level_and_build():
         P, f = float(rng.random()), int(rng.integers(0, hi + 1))
         assert vt.choose_k(dc, top_p=P) == oracle.choose_k_top_p(c, P), (V, hi, P)
         assert vt.choose_k(dc, min_count=f) == oracle.choose_k_min_count(c, f), (V, hi, f)
+
+
+@pytest.mark.parametrize("n,m", [(1, 27), (1, 64), (4, 21), (8, 13), (8, 64), (5, 40)])
+def test_step_few_rows_many_tokens_per_row(n, m):
+    # above the measured crossover the small-n kernel stores its logits and the per-row tail finishes the step
+    k, d = 32768, 1024
+    W, map_ = synth.trimmed_head_direct(k, d, seed=n * 100 + m, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=n * 100 + m, dtype="bf16")
+    W[100] = W[7]                                   # an exact tie inside the top region is possible
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse, full = run_step(h, W, map_, m, return_lse=True, return_full=True)
+    check_step(oi, ol, ref, map_, m, lse)
+    _, logp_ref = oracle.log_softmax(ref["z"])
+    assert np.max(np.abs(full.cpu().numpy().astype(np.float64) - logp_ref)) <= LOGP_TOL
+    # and the tree level on top of it (expansion kernel after the per-row tail)
+    cum = np.linspace(-1, -3, n).astype(np.float32)
+    p, t, sc, oi2, ol2 = vt.draft_tree_level(to_dev(h), to_dev(W), to_dev(map_), m, to_dev(cum), min(10, n * m))
+    torch.cuda.synchronize()
+    assert torch.equal(oi2, oi) and torch.equal(ol2, ol)
+    rp, rt, rs = oracle.tree_expand(cum, ol.cpu().numpy(), oi.cpu().numpy(), min(10, n * m))
+    assert np.array_equal(p.cpu().numpy(), rp) and np.array_equal(t.cpu().numpy(), rt) and np.array_equal(sc.cpu().numpy(), rs)
