@@ -122,7 +122,8 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
     } else {
         // many tokens per row: the selection rounds of the fused tail grow with L in every workgroup and the merge
         // stages B * L keys per row; the per-row tail on stored logits takes over (measured crossover)
-        p.row_select = p.L > vt::kGemvRowSelectBase - 2 * n;
+        // ... or when the merge's LDS staging cannot hold all n rows' lists at once (the rows would take turns)
+        p.row_select = p.L > vt::kGemvRowSelectBase - 2 * n || p.fin_conc < n;
         if (!p.row_select) {
             const size_t fin = (size_t)p.fin_conc * stage;
             if (fin > p.lds) p.lds = fin;

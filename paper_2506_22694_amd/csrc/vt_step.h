@@ -11,8 +11,8 @@ constexpr int kStepWaves = 8;          // waves per workgroup of the draft-step 
 constexpr int kStepMaxBlocks = 256;    // one workgroup per CU on MI355X
 constexpr int kStepMaxRowsPerBlock = 1024;
 constexpr int kStepMaxK = kStepMaxBlocks * kStepMaxRowsPerBlock;
-constexpr int kFinalizeLdsBytes = 128 * 1024;  // staging budget of the finalize stage
-constexpr int kMaxDynamicLds = 144 * 1024;     // dynamic LDS the step kernels may request
+constexpr int kFinalizeLdsBytes = 152 * 1024;  // staging budget of the finalize stage
+constexpr int kMaxDynamicLds = 159 * 1024;     // dynamic LDS the step kernels may request (160 KiB per CU less static use)
 constexpr int kTicketBytes = 2048;             // top counter + one 64-byte line per group of 16 workgroups
 constexpr int kGemvMaxN = 8;           // the VALU GEMV path covers n <= 8
 
