@@ -6,7 +6,7 @@
 // megabytes and their selection rounds dominate; it is cheaper to let the matrix-core kernel store
 // the logits (n * k * 4 bytes, written once, read back from the L2) and give every hidden row a
 // workgroup of its own:
-//   pass 1  every thread folds its share of the row into (max, sum-exp) and keeps its largest logit;
+//   pass 1  every thread (1024 per row) folds its share of the row into (max, sum-exp) and keeps its largest logit;
 //   T       a threshold that at least m logits reach, from the lanes' maxima (bit-serial selection inside each wave),
 //           so the m best logits are all >= T;
 //   pass 2  logits >= T become candidate keys in LDS (typically a few dozen), ranked by counting;
@@ -18,7 +18,7 @@ namespace vt {
 
 namespace {
 
-constexpr int kRowThreads = 512;
+constexpr int kRowThreads = 1024;
 constexpr int kRowWaves = kRowThreads / kWave;
 constexpr int kRowMaxCand = 1024;
 
@@ -58,7 +58,7 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
 
 // Values of one thread for one stretch of kRowThreads * kRowVals logits: v[u] = z[base + u * kRowThreads + tid]
 // (-inf past the end).  All loads are issued before the first use.
-constexpr int kRowVals = 64;
+constexpr int kRowVals = 32;
 constexpr int kRowSpan = kRowThreads * kRowVals;     // 32768 logits per stretch
 
 __device__ __forceinline__ void load_stretch(const float *__restrict__ zr, int base, int k, int tid,
@@ -107,9 +107,9 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
     const float S = block_sum_f32(lm == -INFINITY ? 0.f : ls * __expf(lm - M), redf, lane, w);
     const float lse = M + __logf(S);
 
-    // ---- T, a value that at least m logits reach: every wave finds the ceil(m / 8)-th largest of its lanes'
+    // ---- T, a value that at least m logits reach: every wave finds the ceil(m / 16)-th largest of its lanes'
     // maxima (bit by bit with ballots); each wave's share then holds that many logits >= its value, so the
-    // smallest of the eight values is reached by at least 8 * ceil(m / 8) >= m logits.  (Lanes without an
+    // smallest of the sixteen values is reached by at least 16 * ceil(m / 16) >= m logits.  (Lanes without an
     // element hold the lowest code.)
     const unsigned mine = lm == -INFINITY ? 0u : orderable_f32(lm);
     unsigned Tw = 0u;
