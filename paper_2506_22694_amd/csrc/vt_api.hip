@@ -70,7 +70,7 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
                 const int CS = cs_set[q];
                 if (CS >= need && CS * NP <= 24) {
                     const size_t tile = (size_t)S * NP * p.tpitch * sizeof(float);
-                    if (tile <= 96 * 1024 && (p.fin_conc >= 1 || p.L > vt::kGemvRowSelectBase - 2 * n)) {
+                    if (tile <= 96 * 1024 && (p.fin_conc >= 1 || p.L > vt::kGemvRowSelectBase - n / 2)) {
                         p.gemv = true;
                         p.NP = NP;
                         p.CS = CS;
@@ -123,7 +123,7 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         // many tokens per row: the selection rounds of the fused tail grow with L in every workgroup and the merge
         // stages B * L keys per row; the per-row tail on stored logits takes over (measured crossover)
         // ... or when the merge's LDS staging cannot hold all n rows' lists at once (the rows would take turns)
-        p.row_select = p.L > vt::kGemvRowSelectBase - 2 * n || p.fin_conc < n;
+        p.row_select = p.L > vt::kGemvRowSelectBase - n / 2 || p.fin_conc < n;
         if (!p.row_select) {
             const size_t fin = (size_t)p.fin_conc * stage;
             if (fin > p.lds) p.lds = fin;

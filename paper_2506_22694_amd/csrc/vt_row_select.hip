@@ -22,16 +22,6 @@ constexpr int kRowThreads = 1024;
 constexpr int kRowWaves = kRowThreads / kWave;
 constexpr int kRowMaxCand = 1024;
 
-__device__ __forceinline__ float block_max_f32(float v, float *red, int lane, int w) {
-    v = wave_max(v);
-    __syncthreads();
-    if (lane == 0) red[w] = v;
-    __syncthreads();
-    float r = red[0];
-#pragma unroll
-    for (int q = 1; q < kRowWaves; ++q) r = fmaxf(r, red[q]);
-    return r;
-}
 __device__ __forceinline__ float block_sum_f32(float v, float *red, int lane, int w) {
     v = wave_sum(v);
     __syncthreads();
@@ -79,7 +69,7 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
                                                                  float *__restrict__ lse_buf) {
     __shared__ float redf[kRowWaves];
     __shared__ unsigned long long red64[kRowWaves];
-    __shared__ unsigned tmax[kRowWaves];
+    __shared__ unsigned tmax[2 * kRowWaves];
     __shared__ unsigned long long cand[kRowMaxCand];
     __shared__ unsigned s_ncand;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -103,19 +93,18 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
             lm = mn;
         }
     }
-    const float M = block_max_f32(lm, redf, lane, w);
-    const float S = block_sum_f32(lm == -INFINITY ? 0.f : ls * __expf(lm - M), redf, lane, w);
-    const float lse = M + __logf(S);
-
-    // ---- T, a value that at least m logits reach: every wave finds the ceil(m / 16)-th largest of its lanes'
-    // maxima (bit by bit with ballots); each wave's share then holds that many logits >= its value, so the
-    // smallest of the sixteen values is reached by at least 16 * ceil(m / 16) >= m logits.  (Lanes without an
-    // element hold the lowest code.)
+    // ---- one exchange through LDS gives the row maximum M and the threshold T, a value that at least m logits
+    // reach: every wave finds the ceil(m / 16)-th largest of its lanes' maxima (the wave maximum itself for
+    // m <= 16, otherwise bit by bit with ballots); each wave's share then holds that many logits >= its value,
+    // so the smallest of the sixteen values is reached by at least 16 * ceil(m / 16) >= m logits.  (Lanes
+    // without an element hold the lowest code.)
     const unsigned mine = lm == -INFINITY ? 0u : orderable_f32(lm);
-    unsigned Tw = 0u;
-    {
+    const unsigned wtop = wave_max_u32(mine);
+    unsigned Tw = wtop;
+    int need = (m + kRowWaves - 1) / kRowWaves;
+    if (need > 1) {
+        Tw = 0u;
         unsigned long long alive = ~0ull;
-        int need = (m + kRowWaves - 1) / kRowWaves;
         for (int b = 31; b >= 0; --b) {
             const unsigned long long ones = __ballot((mine >> b) & 1u) & alive;
             const int c = __popcll(ones);
@@ -129,11 +118,20 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
         }
     }
     if (tid == 0) s_ncand = 0u;
-    if (lane == 0) tmax[w] = Tw;
+    if (lane == 0) {
+        tmax[w] = Tw;
+        tmax[kRowWaves + w] = wtop;
+    }
     __syncthreads();
-    unsigned T = tmax[0];
+    unsigned T = tmax[0], Mo = tmax[kRowWaves];
 #pragma unroll
-    for (int q = 1; q < kRowWaves; ++q) T = tmax[q] < T ? tmax[q] : T;
+    for (int q = 1; q < kRowWaves; ++q) {
+        T = tmax[q] < T ? tmax[q] : T;
+        Mo = tmax[kRowWaves + q] > Mo ? tmax[kRowWaves + q] : Mo;
+    }
+    const float M = from_orderable_f32(Mo);      // k >= 1: some lane holds an element
+    const float S = block_sum_f32(lm == -INFINITY ? 0.f : ls * __expf(lm - M), redf, lane, w);
+    const float lse = M + __logf(S);
     // compared as a float below (the order code is monotone; code 0 = no element maps to "everything passes")
     const float Tf = T == 0u ? -INFINITY : from_orderable_f32(T);
 
