@@ -112,7 +112,7 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         p.fin_stage_keys = (group + 1) * p.L;
         const int fc = (int)(vt::kFinalizeLdsBytes / ((size_t)p.fin_stage_keys * sizeof(unsigned long long)));
         // The per-tile candidate lists cost n * L selection rounds per tile and grow to megabytes; beyond a point
-        // (measured: more than 16 tokens per row, or n * L from about 2048; always when the lists no longer fit the
+        // (measured: 12 or more tokens per row, or n * L from about 1024; always when the lists no longer fit the
         // merge's LDS staging) the kernel stores its logits instead and a workgroup per hidden row finishes the step.
         p.row_select = p.L > vt::kRowSelectMinL || n * p.L >= vt::kRowSelectMinWork || fc < 1;
         // one hidden row per workgroup: n <= 256 rows spread over as many CUs, and a merging wave has its

@@ -210,6 +210,126 @@ __device__ __forceinline__ bool arrive_and_elect(unsigned *tickets, int nblocks)
     return s_last != 0;
 }
 
+// ------------------------------------------------------------------ direct merge of at most 2048 keys (one wave)
+// Butterfly over the wave whose first `gsteps` steps take the maximum (inside groups of 2^gsteps
+// lanes) and whose remaining steps take the minimum over those groups: the smallest group maximum.
+__device__ __forceinline__ unsigned wave_min_of_group_max_u32(unsigned v, int gsteps) {
+    unsigned t = dpp_mov<0xB1>(v);      // quad_perm [1,0,3,2]
+    v = gsteps > 0 ? (v > t ? v : t) : (v < t ? v : t);
+    t = dpp_mov<0x4E>(v);               // quad_perm [2,3,0,1]
+    v = gsteps > 1 ? (v > t ? v : t) : (v < t ? v : t);
+    t = dpp_mov<0x141>(v);              // row_half_mirror
+    v = gsteps > 2 ? (v > t ? v : t) : (v < t ? v : t);
+    t = dpp_mov<0x140>(v);              // row_mirror
+    v = gsteps > 3 ? (v > t ? v : t) : (v < t ? v : t);
+    auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = gsteps > 4 ? (r[0] > r[1] ? r[0] : r[1]) : (r[0] < r[1] ? r[0] : r[1]);
+    r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return gsteps > 5 ? (r[0] > r[1] ? r[0] : r[1]) : (r[0] < r[1] ? r[0] : r[1]);
+}
+
+constexpr int kDirectKeysPerLane = 32;      // 2048 keys stay in registers
+constexpr int kDirectMaxCand = 128;
+
+// 16 bytes per lane with the coherence of acquire_u64 (agent scope: not served from this XCD's L2).
+// Issue cost per wave is that of an 8-byte load, so two keys per load halve the request time.
+__device__ __forceinline__ void acquire_load16(u32x4 &dst, const void *p) {
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void wait_loads16(u32x4 (&r)[16]) {
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]),
+                   "+v"(r[8]), "+v"(r[9]), "+v"(r[10]), "+v"(r[11]), "+v"(r[12]), "+v"(r[13]), "+v"(r[14]),
+                   "+v"(r[15]));
+}
+
+// All `total` <= 64 U published keys of a hidden row (any order) are held in registers, U per lane
+// (U = 32: read as 16 pairs, `total` even and src 16-byte aligned; U = 4: one key per load).
+// With G = the power of two >= m, the lanes form G groups; every group's best logit is a different
+// key, so at least G >= m keys reach T = the smallest of the group maxima, and the m best keys are
+// among the keys whose logit reaches T (a few dozen).  Those are compacted into LDS and ranked by
+// counting.  Returns false, having written nothing, when more than kDirectMaxCand keys reach T
+// (massive ties): the caller then merges the sorted lists round by round.
+template <int U, bool FULL>
+__device__ __forceinline__ bool finalize_row_direct(const unsigned long long *__restrict__ src, int total, int m,
+                                                    float lse, unsigned long long *stage,
+                                                    int *__restrict__ out_ids_row, float *__restrict__ out_logp_row,
+                                                    int lane) {
+    static_assert(U == 32 || U == 4, "unsupported register budget");
+    unsigned long long kreg[U];
+    if constexpr (U == 32) {
+        u32x4 r[16];
+        const int npairs = total >> 1;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int e = u * kWave + lane;
+            if (FULL || u * kWave < npairs)       // uniform: no request for a stretch past the end
+                acquire_load16(r[u], src + 2 * (FULL ? e : min(e, npairs - 1)));
+            else
+                r[u] = u32x4{0u, 0u, 0u, 0u};
+        }
+        wait_loads16(r);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const bool valid = FULL || u * kWave + lane < npairs;
+            kreg[2 * u] = valid ? (((unsigned long long)r[u][1] << 32) | r[u][0]) : kNoKey;
+            kreg[2 * u + 1] = valid ? (((unsigned long long)r[u][3] << 32) | r[u][2]) : kNoKey;
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) kreg[u] = acquire_u64(src + min(u * kWave + lane, total - 1));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (u * kWave + lane >= total) kreg[u] = kNoKey;
+        }
+    }
+    unsigned top = 0u;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const unsigned o = (unsigned)(kreg[u] >> 32);
+        top = o > top ? o : top;
+    }
+    int gsteps = 6;                     // G = 64 >> gsteps groups, G >= m
+    while ((kWave >> gsteps) < m) --gsteps;
+    unsigned T = wave_min_of_group_max_u32(top, gsteps);
+    T = T == 0u ? 1u : T;               // an empty group: every real key is a candidate (real keys have a non-zero high word)
+    int ncand = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const bool c = (unsigned)(kreg[u] >> 32) >= T;
+        const unsigned long long mask = __ballot(c);
+        if (mask != 0ull) {
+            const int slot = ncand + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                                    __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+            if (c && slot < kDirectMaxCand) stage[slot] = kreg[u];
+            ncand += __popcll(mask);
+        }
+    }
+    if (ncand > kDirectMaxCand) return false;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int c = lane; c < ncand; c += kWave) {
+        const unsigned long long key = stage[c];
+        int above = 0;
+        int x = 0;
+        for (; x + 8 <= ncand; x += 8) {
+            unsigned long long t[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) t[q] = stage[x + q];      // every lane reads the same key: a broadcast
+#pragma unroll
+            for (int q = 0; q < 8; ++q) above += t[q] > key ? 1 : 0;
+        }
+        for (; x < ncand; ++x) above += stage[x] > key ? 1 : 0;
+        if (above < m) {
+            out_ids_row[above] = key_id(key);
+            out_logp_row[above] = key_logit(key) - lse;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    return true;
+}
+
 // ------------------------------------------------------------------ final merge of one hidden row (one wave)
 // pms_row: [B] (max | sumexp << 32); pkeys_row: [B][L] keys, each list sorted
 // descending.  stage: wave-private LDS for (min(B, 256) + 1) * L keys.
@@ -245,6 +365,25 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
     }
     const float M = wave_max(lm);
     const float lse = M + __logf(wave_sum(ls * __expf(lm - M)));
+
+    // few enough keys to hold in registers: no rounds over the list heads
+    const int total_keys = B * L;
+    if (m <= kWave && (total_keys <= 4 * kWave || (total_keys <= kDirectKeysPerLane * kWave && (total_keys & 1) == 0))) {
+        bool done;
+        if (total_keys == 32 * kWave)
+            done = finalize_row_direct<32, true>(pkeys_row, total_keys, m, lse, stage, out_ids_row, out_logp_row, lane);
+        else if (total_keys > 4 * kWave)
+            done = finalize_row_direct<32, false>(pkeys_row, total_keys, m, lse, stage, out_ids_row, out_logp_row, lane);
+        else
+            done = finalize_row_direct<4, false>(pkeys_row, total_keys, m, lse, stage, out_ids_row, out_logp_row, lane);
+        if (done) {
+            if (lane == 0) {
+                *lse_buf_i = lse;
+                if (out_lse_i) *out_lse_i = lse;
+            }
+            return;
+        }
+    }
 
     unsigned res_ord = 0u;
     unsigned res_id = 0u;
