@@ -51,17 +51,37 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
 constexpr int kRowVals = 32;
 constexpr int kRowSpan = kRowThreads * kRowVals;     // 32768 logits per stretch
 
+// VEC: four consecutive logits per load (k a multiple of 4, row 16-byte aligned): thread t's value u is logit
+// base + 4 * ((u / 4) * kRowThreads + t) + u % 4; otherwise logit base + u * kRowThreads + t.
+template <bool VEC>
+__device__ __forceinline__ int stretch_index(int base, int u, int tid) {
+    return VEC ? base + 4 * ((u >> 2) * kRowThreads + tid) + (u & 3) : base + u * kRowThreads + tid;
+}
+template <bool VEC>
 __device__ __forceinline__ void load_stretch(const float *__restrict__ zr, int base, int k, int tid,
                                              float (&v)[kRowVals]) {
+    if constexpr (VEC) {
 #pragma unroll
-    for (int u = 0; u < kRowVals; ++u) {
-        const int j = base + u * kRowThreads + tid;
-        v[u] = j < k ? zr[j] : -INFINITY;
+        for (int q = 0; q < kRowVals / 4; ++q) {
+            const int j = base + 4 * (q * kRowThreads + tid);
+            float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (j < k) t = *reinterpret_cast<const float4 *>(zr + j);
+            v[4 * q] = t.x;
+            v[4 * q + 1] = t.y;
+            v[4 * q + 2] = t.z;
+            v[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kRowVals; ++u) {
+            const int j = base + u * kRowThreads + tid;
+            v[u] = j < k ? zr[j] : -INFINITY;
+        }
     }
 }
 
 // KEEP: the row fits one stretch (k <= 32768), so its logits stay in registers for the second pass.
-template <bool KEEP>
+template <bool KEEP, bool VEC>
 __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__restrict__ z, const int *__restrict__ map,
                                                                  int k, int m, int *__restrict__ out_ids,
                                                                  float *__restrict__ out_logp,
@@ -80,7 +100,7 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
     // ---- pass 1: (max, sum-exp) and the thread's largest logit
     float lm = -INFINITY, ls = 0.f;
     for (int base = 0; base < k; base += kRowSpan) {
-        load_stretch(zr, base, k, tid, v);
+        load_stretch<VEC>(zr, base, k, tid, v);
         float cm = v[0];
 #pragma unroll
         for (int u = 1; u < kRowVals; ++u) cm = fmaxf(cm, v[u]);
@@ -137,10 +157,10 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
 
     // ---- pass 2: every logit >= T is a candidate
     for (int base = 0; base < k; base += kRowSpan) {
-        if (!KEEP) load_stretch(zr, base, k, tid, v);
+        if (!KEEP) load_stretch<VEC>(zr, base, k, tid, v);
 #pragma unroll
         for (int u = 0; u < kRowVals; ++u) {
-            const int j = base + u * kRowThreads + tid;
+            const int j = stretch_index<VEC>(base, u, tid);
             if (j < k && v[u] >= Tf) {
                 const unsigned slot = atomicAdd(&s_ncand, 1u);
                 if (slot < (unsigned)kRowMaxCand) cand[slot] = make_key(v[u], map[j]);
@@ -174,10 +194,10 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
         for (int r = 0; r < m; ++r) {
             unsigned long long best = kNoKey;
             for (int base = 0; base < k; base += kRowSpan) {
-                if (!KEEP) load_stretch(zr, base, k, tid, v);
+                if (!KEEP) load_stretch<VEC>(zr, base, k, tid, v);
 #pragma unroll
                 for (int u = 0; u < kRowVals; ++u) {
-                    const int j = base + u * kRowThreads + tid;
+                    const int j = stretch_index<VEC>(base, u, tid);
                     if (j < k && v[u] >= Tf) {
                         const unsigned long long key = make_key(v[u], map[j]);
                         if (key < prev && key > best) best = key;
@@ -200,12 +220,11 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
 
 void launch_row_select(const float *z, const int *map, int n, int k, int m, int *out_ids, float *out_logp,
                        float *out_lse, float *lse_buf, hipStream_t st) {
-    if (k <= kRowSpan)
-        hipLaunchKernelGGL(row_select_kernel<true>, dim3(n), dim3(kRowThreads), 0, st, z, map, k, m, out_ids, out_logp,
-                           out_lse, lse_buf);
-    else
-        hipLaunchKernelGGL(row_select_kernel<false>, dim3(n), dim3(kRowThreads), 0, st, z, map, k, m, out_ids, out_logp,
-                           out_lse, lse_buf);
+    const bool vec = (k & 3) == 0 && (reinterpret_cast<uintptr_t>(z) & 15) == 0;
+    const bool keep = k <= kRowSpan;
+    auto kern = keep ? (vec ? row_select_kernel<true, true> : row_select_kernel<true, false>)
+                     : (vec ? row_select_kernel<false, true> : row_select_kernel<false, false>);
+    hipLaunchKernelGGL(kern, dim3(n), dim3(kRowThreads), 0, st, z, map, k, m, out_ids, out_logp, out_lse, lse_buf);
 }
 
 }  // namespace vt
