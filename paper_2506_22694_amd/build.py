@@ -33,13 +33,44 @@ def _stale(target: str, deps) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+# The draft-step kernels issue their loads from inline assembly and wait for them by hand; the compiler
+# does not know that such a register is still in flight, so a spill of one would save a value that
+# has not arrived yet.  Their sources must therefore compile without any scratch memory.
+NO_SCRATCH = ("vt_head_", "vt_row_select")
+
+
+def _scratch_users(remarks: str):
+    """(kernel, bytes per lane) for every kernel the resource-usage remarks report with scratch memory."""
+    out, name = [], None
+    for line in remarks.splitlines():
+        if "remark: Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in line and name is not None:
+            n = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+            if n != 0:
+                out.append((name, n))
+    return out
+
+
 def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+    base = os.path.basename(src)
+    obj = os.path.join(OBJ, base[:-4] + ".o")
     headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.cuh")) + \
         glob.glob(os.path.join(ROOT, "include", "*.h"))
     if force or _stale(obj, [src] + headers):
-        r = subprocess.run([HIPCC] + FLAGS + ["-c", src, "-o", obj], capture_output=True, text=True)
-        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        check = base.startswith(NO_SCRATCH)
+        extra = ["-Rpass-analysis=kernel-resource-usage"] if check else []
+        r = subprocess.run([HIPCC] + FLAGS + extra + ["-c", src, "-o", obj], capture_output=True, text=True)
+        if check:
+            bad = _scratch_users(r.stderr)
+            if bad:
+                if os.path.exists(obj):
+                    os.remove(obj)
+                raise RuntimeError(f"{base}: kernels with hand-issued loads must not spill: {bad}")
+        lines = r.stderr.splitlines()
+        if check and r.returncode == 0:
+            lines = []      # the remarks (and their source excerpts) are not diagnostics
+        err = "\n".join(l for l in lines if "packed-fp32-ops" not in l)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{err}")
         if err.strip():

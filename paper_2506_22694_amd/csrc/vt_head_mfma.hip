@@ -81,8 +81,11 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     // stripe of W at the same time (rows are d * 2 bytes apart) the requests would crowd a subset of the
     // HBM channels (measured: 5.7 instead of 6.7 TB/s).  So the contraction is cut into four column ranges
     // and workgroup b starts with range (b / 8) % 4 -- b % 8 is the XCD -- and wraps around.  Each range
-    // is accumulated from zero in ascending order and the four partial sums are added in range order at
-    // the end, so a logit's rounding does not depend on where its workgroup started.
+    // R0..R3 is accumulated from zero in ascending order and the logit is (R0 + R1) + (R2 + R3); float
+    // addition commutes, so that value does not depend on where the workgroup started (equal rows of W
+    // give equal logits in whichever tile they lie).  Two sets of registers hold the finished ranges:
+    // ranges finish in the order rot, rot + 1, .. and the k-th to finish is added to set
+    // {0, 0, 1, 1}[k] for an even start, {0, 1, 1, 0}[k] for an odd one, which pairs R0 with R1 and R2 with R3.
     // (Rows a multiple of 4 KiB apart are the ones that crowd; at d = 3072 the plain march is 0.6 us faster.)
     const bool rotate = nunits >= 8 && a.d % 2048 == 0;
     const int rot = rotate ? ((int)blockIdx.x >> 3) & 3 : 0;
@@ -101,19 +104,20 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     u32x4 areg[kPrefetchUnits][4];
 
     f32x4 acc[NT];
-    f32x4 part0[NT], part1[NT], part2[NT], part3[NT];     // finished ranges, most recent first
+    f32x4 pair0[NT], pair1[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        part0[t] = part1[t] = part2[t] = part3[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-#define VT_CLOSE_RANGE()                          \
-    _Pragma("unroll") for (int t = 0; t < NT; ++t) { \
-        part3[t] = part2[t];                      \
-        part2[t] = part1[t];                      \
-        part1[t] = part0[t];                      \
-        part0[t] = acc[t];                        \
-        acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};       \
+    for (int t = 0; t < NT; ++t) acc[t] = pair0[t] = pair1[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int closed = 0;        // ranges finished so far
+#define VT_CLOSE_RANGE()                                                              \
+    {                                                                                 \
+        const bool to1 = (rot & 1) ? (closed == 1 || closed == 2) : closed >= 2;      \
+        _Pragma("unroll") for (int t = 0; t < NT; ++t) {                              \
+            const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};                             \
+            pair0[t] += to1 ? zero : acc[t];      /* adding zero changes nothing */   \
+            pair1[t] += to1 ? acc[t] : zero;                                          \
+            acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};                                       \
+        }                                                                             \
+        ++closed;                                                                     \
     }
 
     unsigned char *my_stage = stage + (size_t)w * 2 * kStageUnitBytes;
@@ -234,19 +238,10 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     for (int x = 0; x < kPrefetchUnits; ++x) wait_unit<0>(areg[x]);
 
     if (rotate) {
-        // range q was the (q - rot) mod 4-th to finish: it sits in part[(rot + 3 - q) mod 4]
         VT_CLOSE_RANGE()
 #undef VT_CLOSE_RANGE
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            f32x4 r[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int j = (rot + 3 - q) & 3;
-                r[q] = j == 0 ? part0[t] : j == 1 ? part1[t] : j == 2 ? part2[t] : part3[t];
-            }
-            acc[t] = ((r[0] + r[1]) + r[2]) + r[3];
-        }
+        for (int t = 0; t < NT; ++t) acc[t] = pair0[t] + pair1[t];
     }
 
     // ---- logits of this tile -> LDS tile zt[i][t] (aliases staging and h)
@@ -355,10 +350,22 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
     }
     const unsigned voff_dummy = (unsigned)lane * 16;
     const char *Wt = static_cast<const char *>(a.W) + (size_t)row0 * rs;
+    // Rotated start of the column march, as in head_mfma_kernel (same ranges, same pairing of the partial
+    // sums), for up to 128 hidden rows.  With more, the accumulators leave no registers for the pairs, and
+    // the workgroups' B-operands would come from four regions of h at once, which the L2 serves more slowly
+    // than the crowding costs (measured).
+    const bool rotate = NTW == 1 && nunits >= 8 && a.d % 2048 == 0;
+    const int rot = rotate ? ((int)blockIdx.x >> 3) & 3 : 0;
+    const int rb1 = nunits / 4, rb2 = nunits / 2, rb3 = (3 * nunits) / 4;
+    const int ustart = rot == 0 ? 0 : rot == 1 ? rb1 : rot == 2 ? rb2 : rb3;
+    auto unit_of = [&](int s) {       // unit processed at step s < nunits
+        const int u = ustart + s;
+        return u >= nunits ? u - nunits : u;
+    };
     // past the last unit the pipeline keeps its shape by reading the start of h (L2, in bounds)
     auto load_unit = [&](int u, u32x4(&dst)[4]) {
         const bool real = u < nunits;
-        const char *p = real ? Wt + (size_t)u * (kUnitCols * 2) : static_cast<const char *>(a.h);
+        const char *p = real ? Wt + (size_t)unit_of(u) * (kUnitCols * 2) : static_cast<const char *>(a.h);
 #pragma unroll
         for (int j = 0; j < 4; ++j) stream_load16(dst[j], real ? voff[j] : voff_dummy, p);
     };
@@ -366,7 +373,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
     // from the re-laid copy: 1 KiB per (unit, k-step, 16-row group)
     const char *hpk = static_cast<const char *>(a.hpack) + (size_t)(NTW * w) * 1024;
     auto load_b = [&](int u, u32x4(&dst)[NB]) {
-        const char *p = hpk + (size_t)min(u, nunits - 1) * (4 * 8 * NTW * 1024);
+        const char *p = hpk + (size_t)unit_of(min(u, nunits - 1)) * (4 * 8 * NTW * 1024);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
@@ -377,11 +384,40 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
     u32x4 areg[PU][4];
     u32x4 breg[2][NB];
     f32x4 acc[8][NTW];
+    constexpr int NPAIR = NTW == 1 ? 8 : 1;      // pair accumulators exist only where the start rotates
+    f32x4 pair0[NPAIR], pair1[NPAIR];
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
 #pragma unroll
         for (int t = 0; t < NTW; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+#pragma unroll
+    for (int mt = 0; mt < NPAIR; ++mt) pair0[mt] = pair1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int closed = 0;        // ranges finished so far
+    auto close_range = [&]() {
+        if constexpr (NTW == 1) {
+            // always into pair0; the two sets trade places when the next range belongs to the other pair
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                pair0[mt] += acc[mt][0];
+                acc[mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            const bool trade = (rot & 1) ? (closed == 0 || closed == 2) : closed == 1;
+            if (trade) {
+#pragma unroll
+                for (int mt = 0; mt < 8; ++mt) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {      // in place: no temporaries
+                        float x = pair0[mt][c], y = pair1[mt][c];
+                        asm volatile("v_swap_b32 %0, %1" : "+v"(x), "+v"(y));
+                        pair0[mt][c] = x;
+                        pair1[mt][c] = y;
+                    }
+                }
+            }
+            ++closed;
+        }
+    };
     const int wr_off = (16 * w + lgrp) * kStagePitch + lrow * 16;   // + 4 j rows
     const int rd_off = lrow * kStagePitch + lgrp * 16;              // + 16 mt rows, + ks * 64
 
@@ -395,11 +431,17 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
         *reinterpret_cast<u32x4 *>(smem + 4 * j * kStagePitch + wr_off) = areg[0][j];
     load_unit(PU, areg[0]);
     __syncthreads();
-    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
-    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
+    // target ids of the tile rows this lane ranks in the epilogue (two layouts).  With two hidden-row
+    // groups per wave they are requested after the contraction, which has no registers to spare for them.
+    int id0 = 0, id1 = 0;
     int idq[8];
+    auto load_ids = [&]() {
+        id0 = a.map[row0 + min(lane, rows_b - 1)];
+        id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) idq[q] = a.map[row0 + min(lrow + 16 * q, rows_b - 1)];
+        for (int q = 0; q < 8; ++q) idq[q] = a.map[row0 + min(lrow + 16 * q, rows_b - 1)];
+    };
+    if constexpr (NTW == 1) load_ids();
 
     // ---- steady state.  Per iteration the wave issues NB B-loads, then 4 W-loads, always in this order,
     // so the age of every outstanding load is known:
@@ -420,6 +462,12 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
         load_unit(u + 1 + PU, areg[SLOT]);
         if constexpr (NB == 4) wait_regs<kWaitB, 4>(breg[PAR]);
         else wait_regs<kWaitB, 8>(breg[PAR]);
+        if (rotate && u > 0) {
+            const int ua = unit_of(u);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ua == 0 || ua == rb1 || ua == rb2 || ua == rb3) close_range();
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
@@ -451,6 +499,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
     if (u + 2 < nunits) iteration(u + 2, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     if (u + 3 < nunits) iteration(u + 3, std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
     if (u + 4 < nunits) iteration(u + 4, std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
+    if constexpr (NTW != 1) load_ids();
     // loads past the end are still in flight: let them land before their registers die
 #pragma unroll
     for (int x = 0; x < PU; ++x) wait_regs<0, 4>(areg[x]);
@@ -460,6 +509,14 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
     } else {
         wait_regs<0, 8>(breg[0]);
         wait_regs<0, 8>(breg[1]);
+    }
+
+    if constexpr (NTW == 1) {
+        if (rotate) {
+            close_range();
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) acc[mt][0] = pair0[mt] + pair1[mt];
+        }
     }
 
     // ---- logits -> LDS tile zt[i][t] (the last barrier above freed the unit buffers)

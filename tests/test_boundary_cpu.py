@@ -172,3 +172,18 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
         binding.count_tokens(torch.zeros(4, dtype=torch.int32), 10)
+
+
+def test_build_rejects_kernels_that_use_scratch_memory():
+    # the draft-step kernels wait by hand for loads the compiler does not track, so a spilled register
+    # could be saved before its value arrives: the build parses the compiler's resource remarks
+    from paper_2506_22694_amd import build
+    remarks = "\n".join([
+        "a.hip:1:1: remark: Function Name: kernel_a [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     VGPRs: 256 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     ScratchSize [bytes/lane]: 24 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark: Function Name: kernel_b [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]",
+    ])
+    assert build._scratch_users(remarks) == [("kernel_a", 24)]
+    assert any("vt_head_mfma.hip".startswith(p) for p in build.NO_SCRATCH)
