@@ -327,6 +327,27 @@ def test_step_many_rows_exact_ties_and_full_logp():
     assert np.max(np.abs(full.cpu().numpy().astype(np.float64) - logp_ref)) <= LOGP_TOL
 
 
+@pytest.mark.parametrize("n", [20, 64, 100])
+def test_step_many_rows_exact_ties_across_tiles_with_different_starts(n):
+    # d a multiple of 2048: workgroups start the contraction at different quarters (by tile index / 8);
+    # equal rows of W must still give bit-identical logits in whichever tile they lie
+    k, d, m = 4200, 2048, 6
+    W, map_ = synth.trimmed_head_direct(k, d, seed=7100 + n, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=7100 + n, dtype="bf16")
+    z = oracle.logits(h, W)
+    i = n - 1
+    j = int(np.argmax(z[i]))
+    for off in (1100, 2200, 3300):              # 8.6 tiles apart each: all four starts
+        W[(j + off) % k] = W[j]
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+    ids, lp = oi.cpu().numpy(), ol.cpu().numpy()
+    assert np.array_equal(ids[i, :4], ref["ids"][i, :4])
+    assert np.all(np.diff(ids[i, :4]) > 0)
+    assert np.all(lp[i, :4] == lp[i, 0])
+    check_step(oi, ol, ref, map_, m, lse)
+
+
 def test_step_shapes_no_single_launch_covers_run_as_row_groups():
     # more than 8 rows with d not a multiple of 128, or in fp32, or more than 256 rows: the step runs as
     # consecutive groups of rows on one workspace; results (incl. lse and the full log-softmax) as for one launch
