@@ -186,6 +186,50 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
                        size_t ws_bytes, void *stream);
 size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m);
 
+/* ------------------------------------------------------------------------
+ * Several trimmed heads at once (Sec. 4.1, task-specific vocabularies: a small
+ * function-calling vocabulary beside the general one; the conclusion's note on
+ * swappable per-task heads).  A head is a (map, W_trim, k) triple; all heads
+ * come from one W and share d.
+ *
+ * vt_build_trimmed_heads -- Eq. 1 for n_heads count vectors:
+ *     counts   [n_heads, V] int64, device: one row of counters per head
+ *     k        [n_heads] int32, HOST: trimmed size of every head, 1 <= k[i] <= V
+ *     map      [n_heads] HOST array of device pointers, map[i] -> [k[i]] int32, out
+ *     W_trim   [n_heads] HOST array of device pointers, W_trim[i] -> [k[i], d], out;
+ *              NULL together with W to compute the maps only
+ *     ws       >= vt_build_trimmed_head_ws_bytes(V, d, max k) bytes
+ *   Every head is checked before the first is built; results as for
+ *   vt_build_trimmed_head head by head (ascending id order).
+ *
+ * vt_draft_head_step_multi -- one draft step in which hidden row i uses head
+ *   head_of_row[i]: out_ids[i, :], out_logp[i, :], out_lse[i] are what
+ *   vt_draft_head_step returns for row i on that head.  Every head that has
+ *   rows streams its W_trim once, whatever the order of the rows (rows of a
+ *   head that are not consecutive in h are staged through the workspace).
+ *     h            [n, d] device;  1 <= n <= VT_MULTI_MAX_ROWS
+ *     W_trim, map  [n_heads] HOST arrays of device pointers (entries of heads
+ *                  without rows are not read)
+ *     k            [n_heads] int32, HOST
+ *     head_of_row  [n] int32, HOST, values in [0, n_heads)
+ *     m            1 <= m <= min(VT_MAX_TOP_M, k of every head that has rows)
+ *     out_lse      nullable
+ *     ws           >= vt_draft_head_step_multi_ws_bytes(n, d, k, n_heads, m) bytes
+ *                  (0 = arguments out of range), prepared once by
+ *                  vt_draft_head_step_ws_init() like a single-head workspace
+ *   Only kernels are enqueued (no copies): the call may be captured in a graph.
+ * ---------------------------------------------------------------------- */
+#define VT_MAX_HEADS 16
+#define VT_MULTI_MAX_ROWS 256
+int vt_build_trimmed_heads(const int64_t *counts, int32_t V, int32_t n_heads, const void *W, int w_type,
+                           int32_t d, const int32_t *k, int32_t *const *map, void *const *W_trim, void *ws,
+                           size_t ws_bytes, void *stream);
+int vt_draft_head_step_multi(const void *h, int h_type, int32_t n, int32_t d, const void *const *W_trim,
+                             int w_type, const int32_t *k, const int32_t *const *map, int32_t n_heads,
+                             const int32_t *head_of_row, int32_t m, int32_t *out_ids, float *out_logp,
+                             float *out_lse, void *ws, size_t ws_bytes, void *stream);
+size_t vt_draft_head_step_multi_ws_bytes(int32_t n, int32_t d, const int32_t *k, int32_t n_heads, int32_t m);
+
 /* Clears the arrival counters at the head of a draft-step workspace (a small
  * fill kernel on `stream`; safe under stream capture).  Call once after
  * allocating the workspace, and again only if a step was aborted mid-flight. */

@@ -158,3 +158,20 @@ def draft_head_step(h, W_trim, map_, m):
     lse = lse_only(z)
     ids, lp, ti = top_m(z, lse, map_, m)
     return {"ids": ids, "logp": lp, "lse": lse, "z": z, "trim_idx": ti}
+
+
+def draft_head_step_multi(h, heads, head_of_row, m):
+    """A draft step in which hidden row i uses heads[head_of_row[i]] = (W_trim, map) (Sec. 4.1, task-specific
+    vocabularies next to the general one): row by row, the single-head step of that row on its head.
+
+    Returns dict(ids [n,m], logp [n,m] fp64, lse [n] fp64).
+    """
+    n = h.shape[0]
+    ids = np.zeros((n, m), dtype=np.int32)
+    lp = np.zeros((n, m), dtype=np.float64)
+    lse = np.zeros(n, dtype=np.float64)
+    for i in range(n):
+        W_trim, map_ = heads[int(head_of_row[i])]
+        r = draft_head_step(h[i:i + 1], W_trim, map_, m)
+        ids[i], lp[i], lse[i] = r["ids"][0], r["logp"][0], r["lse"][0]
+    return {"ids": ids, "logp": lp, "lse": lse}

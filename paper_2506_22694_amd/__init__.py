@@ -4,8 +4,10 @@ The arithmetic lives in libvocabtrim.so (hand-written HIP for gfx950, C ABI in
 include/vocabtrim.h); this package is the thin binding plus the seeded input
 generators used by tests and the benchmark.
 """
-from .binding import (StepWorkspace, VocabTrimError, build_trimmed_head, choose_k, count_tokens, draft_head_step,
-                      draft_tree_level, load_library, tree_expand, tree_rerank)
+from .binding import (MultiStepWorkspace, StepWorkspace, VocabTrimError, build_trimmed_head, build_trimmed_heads,
+                      choose_k, count_tokens, draft_head_step, draft_head_step_multi, draft_tree_level, load_library,
+                      tree_expand, tree_rerank)
 
-__all__ = ["StepWorkspace", "VocabTrimError", "build_trimmed_head", "choose_k", "count_tokens", "draft_head_step",
-           "draft_tree_level", "load_library", "tree_expand", "tree_rerank"]
+__all__ = ["MultiStepWorkspace", "StepWorkspace", "VocabTrimError", "build_trimmed_head", "build_trimmed_heads",
+           "choose_k", "count_tokens", "draft_head_step", "draft_head_step_multi", "draft_tree_level", "load_library",
+           "tree_expand", "tree_rerank"]

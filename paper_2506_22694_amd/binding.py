@@ -26,7 +26,9 @@ EXPORTS = (
     "vt_choose_k", "vt_choose_k_ws_bytes",
     "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
     "vt_tree_expand", "vt_tree_rerank", "vt_draft_tree_level", "vt_stream_read_reference",
+    "vt_build_trimmed_heads", "vt_draft_head_step_multi", "vt_draft_head_step_multi_ws_bytes",
 )
+VT_MAX_HEADS, VT_MULTI_MAX_ROWS = 16, 256
 VT_TREE_MAX_CANDIDATES, VT_TREE_MAX_KEEP = 16384, 1024
 
 _lib = None
@@ -75,6 +77,12 @@ def load_library() -> ctypes.CDLL:
     L.vt_draft_tree_level.restype = ci
     L.vt_stream_read_reference.argtypes = [vp, sz, vp, vp]
     L.vt_stream_read_reference.restype = ci
+    L.vt_build_trimmed_heads.argtypes = [vp, i32, i32, vp, ci, i32, vp, vp, vp, vp, sz, vp]
+    L.vt_build_trimmed_heads.restype = ci
+    L.vt_draft_head_step_multi.argtypes = [vp, ci, i32, i32, vp, ci, vp, vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.vt_draft_head_step_multi.restype = ci
+    L.vt_draft_head_step_multi_ws_bytes.argtypes = [i32, i32, vp, i32, i32]
+    L.vt_draft_head_step_multi_ws_bytes.restype = sz
     _lib = L
     return L
 
@@ -249,6 +257,90 @@ def draft_head_step(h: torch.Tensor, W_trim: torch.Tensor, map_: torch.Tensor, m
     if return_full:
         res.append(full)
     return tuple(res)
+
+
+# --------------------------------------------------------------------------- several task heads (Sec. 4.1)
+def _host_i32(values):
+    arr = (ctypes.c_int32 * len(values))(*[int(v) for v in values])
+    return arr
+
+
+def _host_ptrs(tensors):
+    arr = (ctypes.c_void_p * len(tensors))(*[_ptr(t) for t in tensors])
+    return arr
+
+
+def build_trimmed_heads(counts: torch.Tensor, W: torch.Tensor | None, ks, ws: torch.Tensor | None = None):
+    """Eq. 1 for several count vectors (counts int64 [n_heads, V]) over one W: [(map_i, W_trim_i or None)]."""
+    L = load_library()
+    _require_cuda(counts, W, ws)
+    if counts.dtype != torch.int64 or counts.dim() != 2 or not counts.is_contiguous():
+        raise TypeError("counts must be a contiguous int64 [n_heads, V] tensor")
+    H, V = counts.shape
+    ks = [int(k) for k in ks]
+    if len(ks) != H:
+        raise ValueError("one k per row of counts")
+    dev = counts.device
+    maps = [torch.empty(max(k, 1), dtype=torch.int32, device=dev) for k in ks]
+    if W is not None:
+        d, wt = W.shape[1], _dtype_code(W)
+        Ws = [torch.empty((max(k, 1), d), dtype=W.dtype, device=dev) for k in ks]
+    else:
+        d, wt, Ws = 8, VT_BF16, None
+    if ws is None:
+        ws = _scratch(L.vt_build_trimmed_head_ws_bytes(V, d, max(max(ks), 1)), dev)
+    _check(L.vt_build_trimmed_heads(_ptr(counts), V, H, _ptr(W), wt, d, _host_i32(ks), _host_ptrs(maps),
+                                    _host_ptrs(Ws) if Ws is not None else None, _ptr(ws), ws.numel(), _stream(dev)))
+    return [(maps[i], Ws[i] if Ws is not None else None) for i in range(H)]
+
+
+class MultiStepWorkspace:
+    """Device scratch of a multi-head draft step of up to n rows over heads of the given sizes."""
+
+    def __init__(self, n: int, d: int, ks, m: int, device):
+        L = load_library()
+        ks = [int(k) for k in ks]
+        nbytes = L.vt_draft_head_step_multi_ws_bytes(n, d, _host_i32(ks), len(ks), m)
+        if nbytes == 0:
+            raise VocabTrimError(2)
+        self.buf = _scratch(nbytes, device)
+        _check(L.vt_draft_head_step_ws_init(_ptr(self.buf), self.buf.numel(), _stream(device)))
+
+    @property
+    def nbytes(self) -> int:
+        return self.buf.numel()
+
+
+def draft_head_step_multi(h: torch.Tensor, heads, head_of_row, m: int, ws: MultiStepWorkspace | None = None,
+                          return_lse: bool = False, out_ids: torch.Tensor | None = None,
+                          out_logp: torch.Tensor | None = None):
+    """One draft step in which hidden row i uses heads[head_of_row[i]]; heads = [(W_trim, map), ...].
+
+    head_of_row is a host sequence of ints.  Returns (ids [n,m], logp [n,m]) [+ lse [n]]."""
+    L = load_library()
+    Wts = [hd[0] for hd in heads]
+    maps = [hd[1] for hd in heads]
+    _require_cuda(h, *Wts, *maps)
+    n, d = h.shape
+    for Wt, mp in heads:
+        if Wt.shape[1] != d or mp.numel() != Wt.shape[0] or mp.dtype != torch.int32 or Wt.dtype != h.dtype:
+            raise ValueError("shape / dtype mismatch between h and a head")
+    ks = [int(Wt.shape[0]) for Wt in Wts]
+    hor = [int(x) for x in head_of_row]
+    if len(hor) != n:
+        raise ValueError("head_of_row must name a head for every row of h")
+    dev = h.device
+    if ws is None:
+        ws = MultiStepWorkspace(n, d, ks, m, dev)
+    if out_ids is None:
+        out_ids = torch.empty((n, m), dtype=torch.int32, device=dev)
+    if out_logp is None:
+        out_logp = torch.empty((n, m), dtype=torch.float32, device=dev)
+    lse = torch.empty(n, dtype=torch.float32, device=dev) if return_lse else None
+    _check(L.vt_draft_head_step_multi(_ptr(h), _dtype_code(h), n, d, _host_ptrs(Wts), _dtype_code(h), _host_i32(ks),
+                                      _host_ptrs(maps), len(heads), _host_i32(hor), m, _ptr(out_ids), _ptr(out_logp),
+                                      _ptr(lse), _ptr(ws.buf), ws.nbytes, _stream(dev)))
+    return (out_ids, out_logp, lse) if return_lse else (out_ids, out_logp)
 
 
 # --------------------------------------------------------------------------- draft-tree selection (Sec. 4.1)

@@ -161,6 +161,87 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
                    int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws,
                    hipStream_t st, const TreeFuse &tf);
 
+int pick_chunk(int n, int k, int d, int m, int dtype);
+
+// All n rows of a validated step: consecutive launch groups of `chunk` rows on one workspace.
+int run_step_rows(const void *h, int n, const void *W_trim, int w_type, int k, int d, const int32_t *map, int m,
+                  int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws, hipStream_t st) {
+    const int chunk = pick_chunk(n, k, d, m, w_type);
+    if (chunk == 0) return VT_ERR_SHAPE;
+    const size_t row_bytes = (size_t)d * elem_size(w_type);
+    for (int i0 = 0; i0 < n; i0 += chunk) {
+        const int nc = n - i0 < chunk ? n - i0 : chunk;
+        const int rc = run_step_group(static_cast<const char *>(h) + (size_t)i0 * row_bytes, nc, W_trim, w_type, k, d, map,
+                                      m, out_ids + (size_t)i0 * m, out_logp + (size_t)i0 * m,
+                                      out_lse ? out_lse + i0 : nullptr,
+                                      out_logp_full ? out_logp_full + (size_t)i0 * k : nullptr, ws, st, TreeFuse{});
+        if (rc != VT_OK) return rc;
+    }
+    return VT_OK;
+}
+
+// Workspace a step of up to n rows on a head of k rows may need, whatever the element type
+size_t step_ws_bytes(int n, int k, int d, int m) {
+    size_t b = 0;
+    for (int dtype : {VT_BF16, VT_F32}) {
+        const int c = pick_chunk(n, k, d, m, dtype);
+        if (c == 0) continue;
+        const StepPlan p = plan_step(c, k, d, m, dtype);
+        if (p.bytes > b) b = p.bytes;
+        if (n % c != 0) {
+            const StepPlan r = plan_step(n % c, k, d, m, dtype);
+            if (r.ok && r.bytes > b) b = r.bytes;
+        }
+    }
+    return b;
+}
+
+// Layout of a multi-head workspace: the step workspace first (so that vt_draft_head_step_ws_init prepares
+// it), then the staged hidden rows and the staged results of one head's rows.
+struct MultiLayout {
+    size_t off_h = 0, off_ids = 0, off_logp = 0, off_lse = 0, bytes = 0;
+};
+MultiLayout multi_layout(int n, int d, const int32_t *k, int n_heads, int m) {
+    // consecutive steps repeat their shapes: the last answer is kept per host thread
+    struct Key {
+        int n = 0, d = 0, m = 0, n_heads = 0;
+        int32_t k[VT_MAX_HEADS] = {};
+        MultiLayout L;
+    };
+    static thread_local Key last;
+    if (last.n == n && last.d == d && last.m == m && last.n_heads == n_heads) {
+        bool same = true;
+        for (int hd = 0; hd < n_heads; ++hd) same = same && last.k[hd] == k[hd];
+        if (same) return last.L;
+    }
+    MultiLayout L;
+    size_t step = 0;
+    for (int hd = 0; hd < n_heads; ++hd) {
+        // a head may receive any number of the n rows, and the plan (hence its workspace) changes with it
+        for (int nn = 1; nn <= n; ++nn) {
+            const size_t b = step_ws_bytes(nn, k[hd], d, m);
+            if (b > step) step = b;
+        }
+    }
+    size_t off = round_up(step, 256);
+    L.off_h = off;
+    off = round_up(off + (size_t)n * d * sizeof(float), 256);      // sized for the wider element type
+    L.off_ids = off;
+    off = round_up(off + (size_t)n * m * sizeof(int32_t), 256);
+    L.off_logp = off;
+    off = round_up(off + (size_t)n * m * sizeof(float), 256);
+    L.off_lse = off;
+    off = round_up(off + (size_t)n * sizeof(float), 256);
+    L.bytes = off;
+    last.n = n;
+    last.d = d;
+    last.m = m;
+    last.n_heads = n_heads;
+    for (int hd = 0; hd < n_heads; ++hd) last.k[hd] = k[hd];
+    last.L = L;
+    return L;
+}
+
 int pick_chunk(int n, int k, int d, int m, int dtype) {
     if (plan_step(n, k, d, m, dtype).ok) return n;
     for (int c : {256, 8, 4, 2, 1}) {
@@ -286,19 +367,7 @@ int vt_choose_k(const int64_t *counts, int32_t V, int mode, double p, int64_t mi
 
 // ------------------------------------------------------------------ Algorithm 2, drafting lines
 size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m) {
-    // sized for either element type
-    size_t b = 0;
-    for (int dtype : {VT_BF16, VT_F32}) {
-        const int c = pick_chunk(n, k, d, m, dtype);
-        if (c == 0) continue;
-        const StepPlan p = plan_step(c, k, d, m, dtype);
-        if (p.bytes > b) b = p.bytes;
-        if (n % c != 0) {
-            const StepPlan r = plan_step(n % c, k, d, m, dtype);
-            if (r.ok && r.bytes > b) b = r.bytes;
-        }
-    }
-    return b;
+    return step_ws_bytes(n, k, d, m);      // sized for either element type
 }
 
 int vt_draft_head_step_ws_init(void *ws, size_t ws_bytes, void *stream) {
@@ -323,21 +392,106 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
         !aligned(out_ids, 4) || !aligned(out_logp, 4) || (out_lse && !aligned(out_lse, 4)) ||
         (out_logp_full && !aligned(out_logp_full, 4)))
         return VT_ERR_ALIGN;
-    const int chunk = pick_chunk(n, k, d, m, w_type);
-    if (chunk == 0) return VT_ERR_SHAPE;
+    if (pick_chunk(n, k, d, m, w_type) == 0) return VT_ERR_SHAPE;
     if (ws == nullptr || !aligned(ws, 256) || ws_bytes < vt_draft_head_step_ws_bytes(n, k, d, m))
         return VT_ERR_WORKSPACE;
     (void)hipGetLastError();
+    const int rc = run_step_rows(h, n, W_trim, w_type, k, d, map, m, out_ids, out_logp, out_lse, out_logp_full, ws,
+                                 static_cast<hipStream_t>(stream));
+    if (rc != VT_OK) return rc;
+    return launch_status();
+}
+
+// ------------------------------------------------------------------ several heads in one step
+size_t vt_draft_head_step_multi_ws_bytes(int32_t n, int32_t d, const int32_t *k, int32_t n_heads, int32_t m) {
+    if (n < 1 || n > VT_MULTI_MAX_ROWS || d < 1 || k == nullptr || n_heads < 1 || n_heads > VT_MAX_HEADS || m < 1)
+        return 0;
+    for (int hd = 0; hd < n_heads; ++hd) {
+        if (k[hd] < 1 || k[hd] > vt::kStepMaxK) return 0;
+    }
+    return multi_layout(n, d, k, n_heads, m).bytes;
+}
+
+int vt_draft_head_step_multi(const void *h, int h_type, int32_t n, int32_t d, const void *const *W_trim, int w_type,
+                             const int32_t *k, const int32_t *const *map, int32_t n_heads,
+                             const int32_t *head_of_row, int32_t m, int32_t *out_ids, float *out_logp,
+                             float *out_lse, void *ws, size_t ws_bytes, void *stream) {
+    if ((h_type != VT_F32 && h_type != VT_BF16) || (w_type != VT_F32 && w_type != VT_BF16)) return VT_ERR_DTYPE;
+    if (h_type != w_type) return VT_ERR_DTYPE;
+    if (n < 1 || n > VT_MULTI_MAX_ROWS || d < 1 || n_heads < 1 || n_heads > VT_MAX_HEADS) return VT_ERR_SHAPE;
+    if (h == nullptr || W_trim == nullptr || k == nullptr || map == nullptr || head_of_row == nullptr ||
+        out_ids == nullptr || out_logp == nullptr)
+        return VT_ERR_NULL;
+    const size_t row_bytes = (size_t)d * elem_size(w_type);
+    if ((row_bytes & 15) != 0 || !aligned(h, 16) || !aligned(out_ids, 4) || !aligned(out_logp, 4) ||
+        (out_lse && !aligned(out_lse, 4)))
+        return VT_ERR_ALIGN;
+    // rows of every head, in ascending row order
+    vt::RowList rows[VT_MAX_HEADS];
+    for (int hd = 0; hd < n_heads; ++hd) rows[hd].n = 0;
+    for (int i = 0; i < n; ++i) {
+        const int hd = head_of_row[i];
+        if (hd < 0 || hd >= n_heads) return VT_ERR_SHAPE;
+        rows[hd].idx[rows[hd].n++] = (short)i;
+    }
+    for (int hd = 0; hd < n_heads; ++hd) {
+        if (k[hd] < 1 || k[hd] > vt::kStepMaxK) return VT_ERR_SHAPE;
+        if (rows[hd].n == 0) continue;           // an unused head needs no valid pointers
+        if (m < 1 || m > k[hd] || m > VT_MAX_TOP_M) return VT_ERR_SHAPE;
+        if (W_trim[hd] == nullptr || map[hd] == nullptr) return VT_ERR_NULL;
+        if (!aligned(W_trim[hd], 16) || !aligned(map[hd], 4)) return VT_ERR_ALIGN;
+        if (pick_chunk(rows[hd].n, k[hd], d, m, w_type) == 0) return VT_ERR_SHAPE;
+    }
+    const MultiLayout L = multi_layout(n, d, k, n_heads, m);
+    if (ws == nullptr || !aligned(ws, 256) || ws_bytes < L.bytes) return VT_ERR_WORKSPACE;
+    (void)hipGetLastError();
     hipStream_t st = static_cast<hipStream_t>(stream);
-    for (int i0 = 0; i0 < n; i0 += chunk) {
-        const int nc = n - i0 < chunk ? n - i0 : chunk;
-        const int rc = run_step_group(static_cast<const char *>(h) + (size_t)i0 * row_bytes, nc, W_trim, w_type, k, d, map,
-                                      m, out_ids + (size_t)i0 * m, out_logp + (size_t)i0 * m,
-                                      out_lse ? out_lse + i0 : nullptr,
-                                      out_logp_full ? out_logp_full + (size_t)i0 * k : nullptr, ws, st, TreeFuse{});
+    char *wsb = static_cast<char *>(ws);
+    for (int hd = 0; hd < n_heads; ++hd) {
+        const vt::RowList &R = rows[hd];
+        if (R.n == 0) continue;
+        const int first = R.idx[0];
+        const bool consecutive = R.idx[R.n - 1] - first == R.n - 1;
+        if (consecutive) {
+            // the head's rows lie next to each other in h: the step reads and writes them in place
+            const int rc = run_step_rows(static_cast<const char *>(h) + (size_t)first * row_bytes, R.n, W_trim[hd], w_type,
+                                         k[hd], d, map[hd], m, out_ids + (size_t)first * m, out_logp + (size_t)first * m,
+                                         out_lse ? out_lse + first : nullptr, nullptr, ws, st);
+            if (rc != VT_OK) return rc;
+            continue;
+        }
+        int32_t *ids_s = reinterpret_cast<int32_t *>(wsb + L.off_ids);
+        float *logp_s = reinterpret_cast<float *>(wsb + L.off_logp);
+        float *lse_s = reinterpret_cast<float *>(wsb + L.off_lse);
+        vt::launch_gather_h_rows(h, wsb + L.off_h, row_bytes, R, st);
+        const int rc = run_step_rows(wsb + L.off_h, R.n, W_trim[hd], w_type, k[hd], d, map[hd], m, ids_s, logp_s, lse_s,
+                                     nullptr, ws, st);
         if (rc != VT_OK) return rc;
+        vt::launch_scatter_rows(ids_s, logp_s, lse_s, m, out_ids, out_logp, out_lse, R, st);
     }
     return launch_status();
+}
+
+// ------------------------------------------------------------------ several heads built from one W
+int vt_build_trimmed_heads(const int64_t *counts, int32_t V, int32_t n_heads, const void *W, int w_type, int32_t d,
+                           const int32_t *k, int32_t *const *map, void *const *W_trim, void *ws, size_t ws_bytes,
+                           void *stream) {
+    if (n_heads < 1 || n_heads > VT_MAX_HEADS) return VT_ERR_SHAPE;
+    if (counts == nullptr || k == nullptr || map == nullptr) return VT_ERR_NULL;
+    if ((W == nullptr) != (W_trim == nullptr)) return VT_ERR_NULL;
+    if (V <= 0) return VT_ERR_SHAPE;
+    // every head is checked before the first one is built
+    for (int hd = 0; hd < n_heads; ++hd) {
+        if (k[hd] < 1 || k[hd] > V) return VT_ERR_SHAPE;
+        if (map[hd] == nullptr || (W != nullptr && W_trim[hd] == nullptr)) return VT_ERR_NULL;
+        if (ws_bytes < vt_build_trimmed_head_ws_bytes(V, d, k[hd])) return VT_ERR_WORKSPACE;
+    }
+    for (int hd = 0; hd < n_heads; ++hd) {
+        const int rc = vt_build_trimmed_head(counts + (size_t)hd * V, V, W, w_type, d, k[hd], map[hd],
+                                             W != nullptr ? W_trim[hd] : nullptr, ws, ws_bytes, stream);
+        if (rc != VT_OK) return rc;
+    }
+    return VT_OK;
 }
 
 int vt_draft_tree_level(const void *h, int h_type, int32_t n, const void *W_trim, int w_type, int32_t k, int32_t d,

@@ -99,6 +99,16 @@ void launch_sub_lse(float *logp_full, const float *lse, int n, int k, hipStream_
 // zero the arrival counters
 void launch_ws_clear(unsigned *p, int nwords, hipStream_t st);
 void launch_stream_read(const void *p, size_t bytes, unsigned *sink, hipStream_t st);
+
+// Hidden rows of one head inside a multi-head step: passed to the kernels by value.
+constexpr int kMultiMaxRows = 256;
+struct RowList {
+    int n;
+    short idx[kMultiMaxRows];
+};
+void launch_gather_h_rows(const void *h, void *staging, size_t row_bytes, const RowList &rows, hipStream_t st);
+void launch_scatter_rows(const int *ids_s, const float *logp_s, const float *lse_s, int m, int *out_ids,
+                         float *out_logp, float *out_lse, const RowList &rows, hipStream_t st);
 // per-row tail on stored logits z [n, k]: lse, the m best logits and their target ids (one workgroup per row)
 void launch_row_select(const float *z, const int *map, int n, int k, int m, int *out_ids, float *out_logp,
                        float *out_lse, float *lse_buf, hipStream_t st);

@@ -59,4 +59,37 @@ void launch_stream_read(const void *p, size_t bytes, unsigned *sink, hipStream_t
                        sink);
 }
 
+// ---- row gather / scatter around a step over a subset of the hidden rows (several heads per call)
+// staging[b, :] = h[rows.idx[b], :]   (row_vecs 16-byte vectors per row)
+__global__ void __launch_bounds__(256) gather_h_rows_kernel(const u32x4 *__restrict__ h, u32x4 *__restrict__ staging,
+                                                            int row_vecs, const RowList rows) {
+    const int b = blockIdx.x;
+    const u32x4 *src = h + (size_t)rows.idx[b] * row_vecs;
+    u32x4 *dst = staging + (size_t)b * row_vecs;
+    for (int v = threadIdx.x; v < row_vecs; v += 256) dst[v] = src[v];
+}
+// out_*[rows.idx[b], :] = staged results of row b
+__global__ void __launch_bounds__(64) scatter_rows_kernel(const int *__restrict__ ids_s, const float *__restrict__ logp_s,
+                                                          const float *__restrict__ lse_s, int m,
+                                                          int *__restrict__ out_ids, float *__restrict__ out_logp,
+                                                          float *__restrict__ out_lse, const RowList rows) {
+    const int b = blockIdx.x;
+    const size_t dst = (size_t)rows.idx[b] * m, src = (size_t)b * m;
+    for (int r = threadIdx.x; r < m; r += 64) {
+        out_ids[dst + r] = ids_s[src + r];
+        out_logp[dst + r] = logp_s[src + r];
+    }
+    if (out_lse != nullptr && threadIdx.x == 0) out_lse[rows.idx[b]] = lse_s[b];
+}
+
+void launch_gather_h_rows(const void *h, void *staging, size_t row_bytes, const RowList &rows, hipStream_t st) {
+    hipLaunchKernelGGL(gather_h_rows_kernel, dim3(rows.n), dim3(256), 0, st, static_cast<const u32x4 *>(h),
+                       static_cast<u32x4 *>(staging), (int)(row_bytes / 16), rows);
+}
+void launch_scatter_rows(const int *ids_s, const float *logp_s, const float *lse_s, int m, int *out_ids,
+                         float *out_logp, float *out_lse, const RowList &rows, hipStream_t st) {
+    hipLaunchKernelGGL(scatter_rows_kernel, dim3(rows.n), dim3(64), 0, st, ids_s, logp_s, lse_s, m, out_ids, out_logp,
+                       out_lse, rows);
+}
+
 }  // namespace vt

@@ -187,3 +187,51 @@ def test_build_rejects_kernels_that_use_scratch_memory():
     ])
     assert build._scratch_users(remarks) == [("kernel_a", 24)]
     assert any("vt_head_mfma.hip".startswith(p) for p in build.NO_SCRATCH)
+
+
+def test_multi_head_argument_errors(lib):
+    # validation happens on the host before any device call
+    i32p = ctypes.c_int32 * 2
+    ks = i32p(1000, 500)
+    hor = (ctypes.c_int32 * 4)(0, 1, 0, 1)
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    lib.vt_draft_head_step_multi.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int32, ctypes.c_int32,
+                                             ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                             ctypes.c_void_p]
+    lib.vt_draft_head_step_multi_ws_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+                                                      ctypes.c_int32]
+    lib.vt_draft_head_step_multi_ws_bytes.restype = ctypes.c_size_t
+    call = lambda **kw: lib.vt_draft_head_step_multi(
+        kw.get("h", 0x1000), kw.get("ht", 1), kw.get("n", 4), kw.get("d", 256), kw.get("W", ptrs), kw.get("wt", 1),
+        kw.get("k", ks), kw.get("map", ptrs), kw.get("H", 2), kw.get("hor", hor), kw.get("m", 4), 0x3000, 0x4000, None,
+        kw.get("ws", 0x10000), kw.get("wsb", 1 << 30), None)
+    assert call(h=None) == 1                      # VT_ERR_NULL
+    assert call(hor=None) == 1
+    assert call(n=0) == 2 and call(n=257) == 2    # VT_ERR_SHAPE
+    assert call(H=0) == 2 and call(H=17) == 2
+    assert call(hor=(ctypes.c_int32 * 4)(0, 2, 0, 1)) == 2      # head index out of range
+    assert call(m=501) == 2                       # m beyond the smaller head that has rows
+    assert call(m=65) == 2
+    assert call(ht=0) == 3                        # VT_ERR_DTYPE: h and W differ
+    assert call(h=0x1004) == 4                    # VT_ERR_ALIGN
+    assert call(ws=None) == 5 and call(wsb=16) == 5
+    need = lib.vt_draft_head_step_multi_ws_bytes(4, 256, ks, 2, 4)
+    assert need > 0 and need % 256 == 0
+    assert lib.vt_draft_head_step_multi_ws_bytes(0, 256, ks, 2, 4) == 0
+    assert lib.vt_draft_head_step_multi_ws_bytes(4, 256, ks, 17, 4) == 0
+    # an unused head's pointers are not looked at
+    assert call(W=(ctypes.c_void_p * 2)(0x1000, None), hor=(ctypes.c_int32 * 4)(0, 0, 0, 0), wsb=16) == 5
+
+    lib.vt_build_trimmed_heads.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int,
+                                           ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    build = lambda **kw: lib.vt_build_trimmed_heads(kw.get("c", 0x1000), kw.get("V", 2000), kw.get("H", 2), None, 1, 256,
+                                                    kw.get("k", ks), kw.get("map", ptrs), None, kw.get("ws", 0x10000),
+                                                    kw.get("wsb", 1 << 30), None)
+    assert build(c=None) == 1 and build(k=None) == 1 and build(map=None) == 1
+    assert build(H=0) == 2 and build(H=17) == 2 and build(V=0) == 2
+    assert build(V=900) == 2                      # k[0] = 1000 > V
+    assert build(map=(ctypes.c_void_p * 2)(0x1000, None)) == 1
+    assert build(wsb=16) == 5

@@ -637,6 +637,103 @@ def test_two_task_heads_from_one_head_swapped_per_step():
         check_step(oi, ol, ref, map_.cpu().numpy(), m)
 
 
+def _multi_case(ks, d, head_of_row, m, seed, dt="bf16"):
+    heads_np = [synth.trimmed_head_direct(k, d, seed=seed + 7 * j, dtype=dt) for j, k in enumerate(ks)]
+    n = len(head_of_row)
+    h = synth.hidden_rows(n, d, seed=seed, dtype=dt)
+    heads_dev = [(to_dev(W), to_dev(mp)) for (W, mp) in heads_np]
+    return heads_np, heads_dev, h
+
+
+def _check_multi(oi, ol, lse, heads_np, h, head_of_row, m):
+    hor = np.asarray(head_of_row)
+    for j, (W, mp) in enumerate(heads_np):
+        rows = np.nonzero(hor == j)[0]
+        if rows.size == 0:
+            continue
+        ref = oracle.draft_head_step(h[rows], W, mp, m)
+        idx = torch.from_numpy(rows).to(oi.device)
+        check_step(oi[idx], ol[idx], ref, mp, m, lse[idx])
+
+
+@pytest.mark.parametrize("ks,d,head_of_row,m,dt", [
+    ((3000, 1500, 700), 1024, [0, 1, 2, 0, 1, 2, 0, 1, 2, 0, 1, 2], 5, "bf16"),      # interleaved: staged rows
+    ((3000, 1500, 700), 1024, [0, 0, 0, 0, 0, 1, 1, 1, 2, 2, 2, 2], 5, "bf16"),      # consecutive: in place
+    ((4099, 600), 1024, [0, 1] * 20, 8, "bf16"),                                      # 20 rows per head: matrix cores
+    ((2000, 900, 64), 200, [2, 0, 0, 2, 1, 0, 2], 3, "f32"),                          # fp32, ragged d
+    ((5000, 32768), 3072, [1, 1, 1, 1, 0, 0, 0, 0], 8, "bf16"),                       # task head beside the general one
+    ((1000, 1200, 1300), 512, [1, 1, 1, 1], 4, "bf16"),                               # heads without rows
+])
+def test_step_multi_heads_rows_pick_their_head(ks, d, head_of_row, m, dt):
+    heads_np, heads_dev, h = _multi_case(ks, d, head_of_row, m, seed=9100 + len(head_of_row) + d, dt=dt)
+    oi, ol, lse = vt.draft_head_step_multi(to_dev(h), heads_dev, head_of_row, m, return_lse=True)
+    torch.cuda.synchronize()
+    _check_multi(oi, ol, lse, heads_np, h, head_of_row, m)
+    # the same rows through the single-head call give the same bits
+    hor = np.asarray(head_of_row)
+    for j, (Wd, md) in enumerate(heads_dev):
+        rows = np.nonzero(hor == j)[0]
+        if rows.size == 0:
+            continue
+        a, b = vt.draft_head_step(to_dev(h[rows]), Wd, md, m)
+        idx = torch.from_numpy(rows).to(oi.device)
+        assert torch.equal(a, oi[idx]) and torch.equal(b, ol[idx])
+
+
+def test_step_multi_heads_consecutive_calls_on_one_workspace_and_graph_replay():
+    ks, d, m = (3000, 1500), 1024, 4
+    pats = ([0, 1, 0, 1, 1, 0], [1, 1, 1, 0, 0, 0])
+    heads_np, heads_dev, _ = _multi_case(ks, d, pats[0], m, seed=77)
+    ws = vt.MultiStepWorkspace(6, d, ks, m, dev())
+    hs = [synth.hidden_rows(6, d, seed=300 + j, dtype="bf16") for j in range(3)]
+    for step in range(6):
+        pat = pats[step % 2]
+        h = hs[step % 3]
+        oi, ol, lse = vt.draft_head_step_multi(to_dev(h), heads_dev, pat, m, ws=ws, return_lse=True)
+        torch.cuda.synchronize()
+        _check_multi(oi, ol, lse, heads_np, h, pat, m)
+    # captured once (kernels only), replayed with new hidden rows, eager calls on the same workspace in between
+    h_in = to_dev(hs[0]).clone()
+    oi = torch.empty((6, m), dtype=torch.int32, device=dev())
+    ol = torch.empty((6, m), dtype=torch.float32, device=dev())
+    want = [tuple(t.clone() for t in vt.draft_head_step_multi(to_dev(hs[j]), heads_dev, pats[0], m)) for j in range(3)]
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream(dev())
+    side.wait_stream(torch.cuda.current_stream(dev()))
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            vt.draft_head_step_multi(h_in, heads_dev, pats[0], m, ws=ws, out_ids=oi, out_logp=ol)
+    torch.cuda.synchronize()
+    for rep in range(6):
+        j = rep % 3
+        h_in.copy_(to_dev(hs[j]))
+        oi.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(oi, want[j][0]) and torch.equal(ol, want[j][1]), rep
+        a, b = vt.draft_head_step_multi(to_dev(hs[(j + 1) % 3]), heads_dev, pats[1], m, ws=ws)
+        torch.cuda.synchronize()
+
+
+def test_build_trimmed_heads_equals_head_by_head():
+    V, d = 50000, 256
+    W = synth.head_weights(V, d, seed=808, dtype="bf16")
+    streams = [synth.zipf_ids(300_000, V, 1.1, seed=61, permute=True), synth.zipf_ids(80_000, V, 1.4, seed=62, permute=True),
+               synth.zipf_ids(5_000, V, 1.0, seed=63, permute=False)]
+    ks = [8192, 1000, 37]
+    counts = torch.stack([vt.count_tokens(to_dev(ids), V) for ids in streams]).contiguous()
+    heads = vt.build_trimmed_heads(counts, to_dev(W), ks)
+    maps_only = vt.build_trimmed_heads(counts, None, ks)
+    torch.cuda.synchronize()
+    for j, ids in enumerate(streams):
+        c_ref, _ = oracle.count(ids, V)
+        want = oracle.select(c_ref, ks[j])
+        assert np.array_equal(heads[j][0].cpu().numpy(), want)
+        assert np.array_equal(maps_only[j][0].cpu().numpy(), want) and maps_only[j][1] is None
+        got = heads[j][1].view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, oracle.gather(W, want))
+
+
 @pytest.mark.parametrize("k,d,n,m,K,dt", [(32768, 3072, 8, 8, 8, "bf16"), (4096, 512, 1, 1, 1, "bf16"),
                                           (5000, 1024, 8, 64, 60, "bf16"), (1000, 256, 4, 4, 16, "f32"),
                                           (2048, 2048, 3, 5, 7, "bf16"), (4096, 1024, 40, 8, 32, "bf16"),

@@ -445,3 +445,31 @@ def test_choose_k_against_library_cumsum_and_the_stated_zipf_coverage():
     # finite Zipf(1.1) over 128256 ids: the 32768 most frequent carry about 94 % of the mass
     cov32k = cs[32767] / cs[-1]
     assert 0.93 < cov32k < 0.95
+
+
+def test_multi_head_step_is_the_single_head_step_row_by_row():
+    # Sec. 4.1 (task-specific vocabularies): a row's result depends on its own head only
+    rng = np.random.default_rng(5)
+    d, m = 24, 3
+    heads = []
+    for k in (40, 17):
+        W = rng.normal(0, 1, size=(k, d)).astype(np.float32)
+        mp = np.sort(rng.choice(1000, size=k, replace=False)).astype(np.int32)
+        heads.append((W, mp))
+    h = rng.normal(0, 1, size=(5, d)).astype(np.float32)
+    hor = [1, 0, 0, 1, 0]
+    out = oracle.draft_head_step_multi(h, heads, hor, m)
+    for i, j in enumerate(hor):
+        one = oracle.draft_head_step(h[i:i + 1], heads[j][0], heads[j][1], m)
+        assert np.array_equal(out["ids"][i], one["ids"][0])
+        assert np.array_equal(out["logp"][i], one["logp"][0]) and out["lse"][i] == one["lse"][0]
+        # every emitted id belongs to the row's own head, never to the other one's map alone
+        assert set(out["ids"][i].tolist()) <= set(heads[j][1].tolist())
+    # one head for all rows: the plain step
+    same = oracle.draft_head_step_multi(h, heads, [0] * 5, m)
+    plain = oracle.draft_head_step(h, heads[0][0], heads[0][1], m)
+    assert np.array_equal(same["ids"], plain["ids"]) and np.array_equal(same["logp"], plain["logp"])
+    # permuting the rows permutes the results
+    perm = np.array([3, 0, 4, 1, 2])
+    outp = oracle.draft_head_step_multi(h[perm], heads, [hor[p] for p in perm], m)
+    assert np.array_equal(outp["ids"], out["ids"][perm]) and np.array_equal(outp["logp"], out["logp"][perm])
