@@ -271,6 +271,35 @@ def main():
         log("tree run:", tree)
         del cps, hs
 
+    # ------------------------------------------------------------------ two heads in one call (task head beside the general one)
+    multi = None
+    if not args.no_full_vocab:
+        kt = 5000
+        Wt_np, mapt_np = synth.trimmed_head_direct(kt, d, wl.seed + 5, "bf16")
+        task_copies = [to_dev_bf16(Wt_np)]
+        task_copies += [task_copies[0].clone() for _ in range(len(copies) - 1)]
+        mapt = torch.from_numpy(mapt_np).to(dev)
+        hor_split = [0] * (n - n // 2) + [1] * (n // 2)          # consecutive rows per head: in place
+        hor_mixed = [i % 2 for i in range(n)]                    # alternating: staged through the workspace
+        wsm = vt.MultiStepWorkspace(n, d, [k, kt], m, dev)
+        om_i = torch.empty((n, m), dtype=torch.int32, device=dev)
+        om_l = torch.empty((n, m), dtype=torch.float32, device=dev)
+
+        def mstep(r, hor):
+            c = r % len(copies)
+            vt.draft_head_step_multi(h, [(copies[c], map_), (task_copies[c], mapt)], hor, m, ws=wsm,
+                                     out_ids=om_i, out_logp=om_l)
+        for r in range(30):
+            mstep(r, hor_mixed)
+        us_split = time_region(lambda r: mstep(r, hor_split), 200)
+        us_mixed = time_region(lambda r: mstep(r, hor_mixed), 200)
+        multi = {"heads": [k, kt], "rows_per_head": [n - n // 2, n // 2],
+                 "consecutive_rows_us": round(us_split, 2), "alternating_rows_us": round(us_mixed, 2),
+                 "bytes": (k + kt) * d * 2,
+                 "gbps_consecutive": round((k + kt) * d * 2 / us_split / 1e3, 1)}
+        log("multi-head step:", multi)
+        del task_copies
+
     # ------------------------------------------------------------------ draft-tree selection behind the step
     # (the paper's tree: 8 frontier nodes x top-8 -> keep 8 per level; rerank 8 + 64 + 64 nodes -> 32; the
     # depth-7 ablation reranks 392 -> 60).  Replayed from a HIP graph: these kernels run a few microseconds,
@@ -439,6 +468,7 @@ def main():
         "hip_graph_us_per_step": graph_us,
         "full_vocab_control": full,
         "tree_selection": tree_sel,
+        "multi_head_step": multi,
     }
     if tree is not None:
         out["tree_run"] = tree

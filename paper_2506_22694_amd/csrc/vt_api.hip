@@ -156,6 +156,10 @@ struct TreeFuse {
     int32_t *parent = nullptr;
     int32_t *token = nullptr;
     float *score = nullptr;
+    // rows picked out of a larger batch (small-n kernel without the per-row tail only): hidden row i of the
+    // group is row (row_pack >> 8 i) & 255 of h and of the outputs
+    unsigned long long row_pack = 0;
+    int indexed = 0;
 };
 int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, int d, const int32_t *map, int m,
                    int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws,
@@ -460,6 +464,17 @@ int vt_draft_head_step_multi(const void *h, int h_type, int32_t n, int32_t d, co
             if (rc != VT_OK) return rc;
             continue;
         }
+        const StepPlan plan = plan_step(R.n, k[hd], d, m, w_type);
+        if (R.n <= vt::kGemvMaxN && plan.ok && plan.gemv && !plan.row_select) {
+            // few rows: the small-n kernel picks its hidden rows out of h and writes their output rows itself
+            TreeFuse pick;
+            pick.indexed = 1;
+            for (int i = 0; i < R.n; ++i) pick.row_pack |= (unsigned long long)(R.idx[i] & 0xFF) << (8 * i);
+            const int rc = run_step_group(h, R.n, W_trim[hd], w_type, k[hd], d, map[hd], m, out_ids, out_logp, out_lse,
+                                          nullptr, ws, st, pick);
+            if (rc != VT_OK) return rc;
+            continue;
+        }
         int32_t *ids_s = reinterpret_cast<int32_t *>(wsb + L.off_ids);
         float *logp_s = reinterpret_cast<float *>(wsb + L.off_logp);
         float *lse_s = reinterpret_cast<float *>(wsb + L.off_lse);
@@ -588,6 +603,8 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.fin_conc = p.fin_conc;
         a.zbuf = nullptr;
         if (p.row_select) a.zbuf = out_logp_full != nullptr ? out_logp_full : reinterpret_cast<float *>(wsb + p.off_zbuf);
+        if (tf.indexed && (p.row_select || out_logp_full != nullptr)) return VT_ERR_SHAPE;
+        a.row_pack = tf.indexed ? tf.row_pack : 0x0706050403020100ull;
         a.tree_cum = tf.cum;
         a.tree_K = tf.K;
         a.tree_parent = tf.parent;
@@ -630,6 +647,7 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             return VT_OK;
         }
     } else {
+        if (tf.indexed) return VT_ERR_SHAPE;      // row picking exists in the small-n kernel only
         vt::MfmaArgs a;
         a.h = h;
         a.W = W_trim;

@@ -248,7 +248,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
     for (int c = 0; c < CS; ++c) {
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int ii = min(i, a.n - 1);
+            const int ii = (int)((a.row_pack >> (8 * min(i, a.n - 1))) & 0xFFull);
             hreg[c][i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.h) + (size_t)ii * rs + coff[c]);
         }
     }
@@ -361,7 +361,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
     float *lse_buf = reinterpret_cast<float *>(reinterpret_cast<char *>(a.tickets) + kTicketBytes);
     if (!arrive_and_elect(a.tickets, a.nblocks)) return;
     finalize_rows(a.pms, a.pkeys, a.nblocks, a.L, a.n, a.m, a.fin_conc, a.out_ids, a.out_logp, a.out_lse, lse_buf,
-                  smem, w, lane);
+                  smem, w, lane, a.row_pack);
     if (a.tree_cum != nullptr) {
         // Fused tree level: the rows' tokens and log-probs were just written by the waves of this workgroup;
         // once those stores are acknowledged the workgroup ranks the n * m candidates cum[i] + logp[i][j]

@@ -35,6 +35,9 @@ struct StepArgs {
     float *out_logp_full;     // [n, k] or null (raw logits are written first, lse subtracted later)
     int fin_conc;             // waves that run the finalize stage concurrently (LDS budget)
     float *zbuf;              // [n, k] or null: store the logits and leave the rest of the step to row_select_kernel
+    // hidden row i is row (row_pack >> 8 i) & 255 of h and of the outputs: 0x0706050403020100 for rows 0 .. n-1,
+    // other values when the rows are picked out of a larger batch (several heads per call)
+    unsigned long long row_pack;
     // fused tree level (all null / 0 when not asked for): after the merge the last workgroup keeps the
     // tree_K best of the n * m candidates scored tree_cum[i] + out_logp[i][j]
     const float *tree_cum;    // [n] or null

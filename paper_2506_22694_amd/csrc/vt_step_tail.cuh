@@ -489,18 +489,22 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
 }
 
 // Last workgroup: waves split the hidden rows; `fin_conc` waves work at a time
-// (LDS staging budget).
+// (LDS staging budget).  Hidden row i (< 8) writes output row (row_pack >> 8 i) & 255.
+constexpr unsigned long long kRowsInOrder = 0x0706050403020100ull;
 __device__ __forceinline__ void finalize_rows(const unsigned long long *__restrict__ pms,
                                            const unsigned long long *__restrict__ pkeys, int B, int L, int n, int m,
                                            int fin_conc, int *__restrict__ out_ids, float *__restrict__ out_logp,
                                            float *__restrict__ out_lse, float *__restrict__ lse_buf,
-                                           unsigned char *smem, int w, int lane) {
+                                           unsigned char *smem, int w, int lane,
+                                           unsigned long long row_pack = kRowsInOrder) {
     if (w < fin_conc) {
         unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * B * L;
-        for (int i = w; i < n; i += fin_conc)
+        for (int i = w; i < n; i += fin_conc) {
+            const int o = (int)((row_pack >> (8 * i)) & 0xFFull);
             finalize_row<false>(pms + (size_t)i * B, pkeys + (size_t)i * B * L, B, L, m, stage,
-                                out_ids + (size_t)i * m, out_logp + (size_t)i * m, out_lse ? out_lse + i : nullptr,
+                                out_ids + (size_t)o * m, out_logp + (size_t)o * m, out_lse ? out_lse + o : nullptr,
                                 lse_buf + i, lane);
+        }
     }
 }
 
