@@ -812,6 +812,33 @@ def test_random_shapes_sweep_step_tree_level_and_build():
         assert vt.choose_k(dc, min_count=f) == oracle.choose_k_min_count(c, f), (V, hi, f)
 
 
+def test_random_multi_head_steps():
+    # seeded sweep: 1-5 heads of unrelated sizes, random row-to-head assignments (consecutive runs, scattered rows,
+    # heads without rows, more than 8 rows on a head), both element types, one workspace per case reused twice
+    rng = np.random.default_rng(2506226940)
+    for it in range(40):
+        dt = "bf16" if rng.random() < 0.7 else "f32"
+        unit = 8 if dt == "bf16" else 4
+        d = 128 * int(rng.integers(1, 9)) if rng.random() < 0.5 else unit * int(rng.integers(1, 1024 // unit + 1))
+        H = int(rng.integers(1, 6))
+        ks = [int(rng.choice([1, 7, 64, 129, 1000, 2049, int(rng.integers(1, 5000))])) for _ in range(H)]
+        n = int(rng.choice([1, 2, 5, 8, 9, 13, 24, 40]))
+        if rng.random() < 0.4:
+            hor = sorted(int(x) for x in rng.integers(0, H, size=n))          # consecutive runs per head
+        else:
+            hor = [int(x) for x in rng.integers(0, H, size=n)]
+        used = sorted(set(hor))
+        m = int(rng.integers(1, min(min(ks[j] for j in used), 16) + 1))
+        heads_np = [synth.trimmed_head_direct(k, d, seed=5000 + 10 * it + j, dtype=dt) for j, k in enumerate(ks)]
+        heads_dev = [(to_dev(W), to_dev(mp)) for (W, mp) in heads_np]
+        ws = vt.MultiStepWorkspace(n, d, ks, m, dev())
+        for rep in range(2):
+            h = synth.hidden_rows(n, d, seed=6000 + 2 * it + rep, dtype=dt)
+            oi, ol, lse = vt.draft_head_step_multi(to_dev(h), heads_dev, hor, m, ws=ws, return_lse=True)
+            torch.cuda.synchronize()
+            _check_multi(oi, ol, lse, heads_np, h, hor, m)
+
+
 @pytest.mark.parametrize("n,m", [(1, 13), (1, 64), (4, 11), (8, 9), (8, 16), (8, 17), (8, 64), (5, 40)])
 def test_step_few_rows_many_tokens_per_row(n, m):
     # above the measured crossover the small-n kernel stores its logits and the per-row tail finishes the step
