@@ -75,7 +75,8 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
                         p.NP = NP;
                         p.CS = CS;
                         p.S = S;
-                        p.lds = tile;
+                        // + 1 KiB per wave behind the tile: candidate keys of the epilogue's threshold selection
+                        p.lds = ((tile + 15) & ~(size_t)15) + (size_t)vt::kStepWaves * 2 * 64 * sizeof(unsigned long long);
                     }
                     break;
                 }

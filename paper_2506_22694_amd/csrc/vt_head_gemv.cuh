@@ -352,7 +352,10 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
             unsigned long long *pms_slot = a.pms + (size_t)i * a.nblocks + blockIdx.x;
             unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nblocks + blockIdx.x) * a.L;
             if (rows_b <= 2 * kWave)
-                block_epilogue_small(zrow, S, sstride, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane);
+                block_epilogue_small(zrow, S, sstride, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane,
+                                     reinterpret_cast<unsigned long long *>(
+                                         smem + (((size_t)S * sstride * sizeof(float) + 15) & ~(size_t)15)) +
+                                         (size_t)w * 2 * kWave);
             else
                 block_epilogue_large(zrow, S, sstride, rows_b, a.L, a.map + row0, full, pms_slot, pk_slot, lane);
         }

@@ -51,6 +51,59 @@ __device__ __forceinline__ unsigned long long wave_select_top(unsigned (&ord)[Q]
     return res_ord == 0u ? kNoKey : (((unsigned long long)res_ord << 32) | (unsigned)(~res_id));
 }
 
+__device__ __forceinline__ unsigned wave_min_of_group_max_u32(unsigned v, int gsteps);
+
+// ------------------------------------------------------------------ top-L of a wave's candidates, by threshold
+// Two candidates per lane (ord = 0: none).  With G = the power of two >= L the lanes form G groups; every
+// group's best logit is a different candidate, so at least L candidates reach T = the smallest group maximum
+// and the L best are among those that do (about 2 L of 128).  They are compacted into `cand` (wave-private
+// LDS, 128 keys) and each finds its rank by counting: no L dependent selection rounds.  Rank r < L is
+// published at slot r; slots past the number of candidates get the "no key" value.
+__device__ __forceinline__ void wave_publish_top_by_threshold(const unsigned (&ord)[2], const int (&id)[2], int L,
+                                                              unsigned long long *cand,
+                                                              unsigned long long *__restrict__ pkeys_slot, int lane) {
+    const unsigned top = ord[0] > ord[1] ? ord[0] : ord[1];
+    int gsteps = 6;
+    while ((kWave >> gsteps) < L) --gsteps;
+    unsigned T = wave_min_of_group_max_u32(top, gsteps);
+    T = T == 0u ? 1u : T;               // a group without candidates: every real candidate passes
+    const bool c0 = ord[0] >= T, c1 = ord[1] >= T;
+    const unsigned long long m0 = __ballot(c0), m1 = __ballot(c1);
+    const int n0 = __popcll(m0);
+    const int ncand = n0 + __popcll(m1);
+    const unsigned long long k0 = ((unsigned long long)ord[0] << 32) | (unsigned)(~(unsigned)id[0]);
+    const unsigned long long k1 = ((unsigned long long)ord[1] << 32) | (unsigned)(~(unsigned)id[1]);
+    if (c0) cand[__builtin_amdgcn_mbcnt_hi((unsigned)(m0 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m0, 0u))] = k0;
+    if (c1)
+        cand[n0 + __builtin_amdgcn_mbcnt_hi((unsigned)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m1, 0u))] = k1;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (c0 || c1) {
+        int a0 = 0, a1 = 0;
+        int x = 0;
+        for (; x + 4 <= ncand; x += 4) {
+            unsigned long long t[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) t[q] = cand[x + q];       // every lane reads the same key: a broadcast
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                a0 += t[q] > k0 ? 1 : 0;
+                a1 += t[q] > k1 ? 1 : 0;
+            }
+        }
+        for (; x < ncand; ++x) {
+            const unsigned long long t = cand[x];
+            a0 += t > k0 ? 1 : 0;
+            a1 += t > k1 ? 1 : 0;
+        }
+        if (c0 && a0 < L) publish_u64(pkeys_slot + a0, k0);
+        if (c1 && a1 < L) publish_u64(pkeys_slot + a1, k1);
+    }
+    if (lane < L && lane >= ncand) publish_u64(pkeys_slot + lane, kNoKey);
+    __builtin_amdgcn_wave_barrier();     // the next row of this wave reuses cand
+}
+
 // ------------------------------------------------------------------ workgroup epilogue of one hidden row
 // zrow: the row's logit tile in LDS (S partial sums per logit, `sstride` floats
 // apart).  Publishes (max, sum-exp) and the L best keys of this workgroup.
@@ -59,7 +112,8 @@ template <int QMAX>
 __device__ __forceinline__ void block_epilogue_core(const float *zrow, int S, int sstride, int rows_b, int L,
                                                     const int (&idq)[QMAX], float *__restrict__ logp_full_row,
                                                     unsigned long long *__restrict__ pms_slot,
-                                                    unsigned long long *__restrict__ pkeys_slot, int lane) {
+                                                    unsigned long long *__restrict__ pkeys_slot, int lane,
+                                                    unsigned long long *cand = nullptr) {
     unsigned ord[QMAX];
     int id[QMAX];
     float zq[QMAX];
@@ -84,8 +138,17 @@ __device__ __forceinline__ void block_epilogue_core(const float *zrow, int S, in
 #pragma unroll
     for (int q = 0; q < QMAX; ++q) ls += __expf(zq[q] - M);   // exp(-inf) = 0 for absent rows
     const float Ssum = wave_sum(ls);
-    const unsigned long long key = wave_select_top<QMAX>(ord, id, L, lane);
-    if (lane < L) publish_u64(pkeys_slot + lane, key);
+    bool published = false;
+    if constexpr (QMAX == 2) {
+        if (cand != nullptr && L >= 5) {       // up to four rounds are no slower than the threshold (measured)
+            wave_publish_top_by_threshold(ord, id, L, cand, pkeys_slot, lane);
+            published = true;
+        }
+    }
+    if (!published) {
+        const unsigned long long key = wave_select_top<QMAX>(ord, id, L, lane);
+        if (lane < L) publish_u64(pkeys_slot + lane, key);
+    }
     if (lane == 0)
         publish_u64(pms_slot, ((unsigned long long)__float_as_uint(Ssum) << 32) | __float_as_uint(M));
 }
@@ -94,9 +157,10 @@ __device__ __forceinline__ void block_epilogue_core(const float *zrow, int S, in
 __device__ __forceinline__ void block_epilogue_small(const float *zrow, int S, int sstride, int rows_b, int L, int id0,
                                                   int id1, float *__restrict__ logp_full_row,
                                                   unsigned long long *__restrict__ pms_slot,
-                                                  unsigned long long *__restrict__ pkeys_slot, int lane) {
+                                                  unsigned long long *__restrict__ pkeys_slot, int lane,
+                                                  unsigned long long *cand = nullptr) {
     const int idq[2] = {id0, id1};
-    block_epilogue_core<2>(zrow, S, sstride, rows_b, L, idq, logp_full_row, pms_slot, pkeys_slot, lane);
+    block_epilogue_core<2>(zrow, S, sstride, rows_b, L, idq, logp_full_row, pms_slot, pkeys_slot, lane, cand);
 }
 
 // large tiles (<= 1024 rows): ids are read here
