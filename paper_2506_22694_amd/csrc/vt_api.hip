@@ -41,7 +41,14 @@ struct StepPlan {
 
 using vt::kTicketBytes;
 
-StepPlan plan_step(int n, int k, int d, int m, int dtype) {
+StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv);
+// force_gemv: the caller needs what only the small-n kernel offers (row picking, the fused tree level)
+StepPlan plan_step(int n, int k, int d, int m, int dtype, bool force_gemv = false) {
+    StepPlan p = plan_step_impl(n, k, d, m, dtype, force_gemv);
+    if (!p.ok && !force_gemv && n <= vt::kGemvMaxN) p = plan_step_impl(n, k, d, m, dtype, true);
+    return p;
+}
+StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) {
     StepPlan p;
     if (n <= 0 || k <= 0 || d <= 0 || m <= 0 || k > vt::kStepMaxK) return p;
     int rpb = (k + vt::kStepMaxBlocks - 1) / vt::kStepMaxBlocks;
@@ -56,7 +63,11 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         p.fin_conc = conc < vt::kStepWaves ? conc : vt::kStepWaves;
     }
 
-    if (n <= vt::kGemvMaxN) {
+    const int tiles128 = (k + vt::kMfmaTileRows - 1) / vt::kMfmaTileRows;
+    const bool prefer_mfma = !force_gemv && dtype == VT_BF16 && (d % 128) == 0 && d <= vt::kMfmaSmallMaxD &&
+                             n >= vt::kMfmaSmallMinN &&
+                             tiles128 >= vt::kMfmaSmallMinTiles && tiles128 <= vt::kStepMaxBlocks;
+    if (n <= vt::kGemvMaxN && !prefer_mfma) {
         const int NP = n <= 1 ? 1 : (n <= 2 ? 2 : (n <= 4 ? 4 : 8));
         const int epc = dtype == VT_BF16 ? 8 : 4;
         const int CT = (d + 64 * epc - 1) / (64 * epc);
@@ -120,6 +131,8 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype) {
         // SIMD to itself (the selection rounds are bound by instruction issue)
         p.fin_conc = 1;
         p.fin_lds = (size_t)p.fin_conc * p.fin_stage_keys * sizeof(unsigned long long);
+        // (Merging in the main kernel's last workgroup, as the small-n kernel does, was measured for n <= 8:
+        // 41.1 against 39.9 us -- eight merge workgroups on eight CUs beat eight waves on one.)
     } else {
         // many tokens per row: the selection rounds of the fused tail grow with L in every workgroup and the merge
         // stages B * L keys per row; the per-row tail on stored logits takes over (measured crossover)
@@ -191,11 +204,13 @@ size_t step_ws_bytes(int n, int k, int d, int m) {
     for (int dtype : {VT_BF16, VT_F32}) {
         const int c = pick_chunk(n, k, d, m, dtype);
         if (c == 0) continue;
-        const StepPlan p = plan_step(c, k, d, m, dtype);
-        if (p.bytes > b) b = p.bytes;
-        if (n % c != 0) {
-            const StepPlan r = plan_step(n % c, k, d, m, dtype);
-            if (r.ok && r.bytes > b) b = r.bytes;
+        for (bool force_gemv : {false, true}) {      // either kernel may serve a group of up to 8 rows
+            const StepPlan p = plan_step(c, k, d, m, dtype, force_gemv);
+            if (p.ok && p.bytes > b) b = p.bytes;
+            if (n % c != 0) {
+                const StepPlan r = plan_step(n % c, k, d, m, dtype, force_gemv);
+                if (r.ok && r.bytes > b) b = r.bytes;
+            }
         }
     }
     return b;
@@ -466,8 +481,8 @@ int vt_draft_head_step_multi(const void *h, int h_type, int32_t n, int32_t d, co
             continue;
         }
         const StepPlan plan = plan_step(R.n, k[hd], d, m, w_type);
-        if (R.n <= vt::kGemvMaxN && plan.ok && plan.gemv && !plan.row_select) {
-            // few rows: the small-n kernel picks its hidden rows out of h and writes their output rows itself
+        if (R.n <= vt::kGemvMaxN && plan.ok && !plan.row_select) {
+            // few rows: the kernel picks its hidden rows out of h and writes their output rows itself
             TreeFuse pick;
             pick.indexed = 1;
             for (int i = 0; i < R.n; ++i) pick.row_pack |= (unsigned long long)(R.idx[i] & 0xFF) << (8 * i);
@@ -534,7 +549,9 @@ int vt_draft_tree_level(const void *h, int h_type, int32_t n, const void *W_trim
     (void)hipGetLastError();
     hipStream_t st = static_cast<hipStream_t>(stream);
     // one launch when the small-n kernel covers the whole step: its last workgroup also ranks the candidates
-    if (chunk == n && n <= vt::kGemvMaxN && n * m <= vt::kStepWaves * 64) {
+    // (the same kernel as vt_draft_head_step would use for this shape, so both calls return the same bits)
+    const StepPlan small = plan_step(n, k, d, m, w_type);
+    if (small.ok && small.gemv && n * m <= vt::kStepWaves * 64) {
         TreeFuse tf;
         tf.cum = parent_cum;
         tf.K = K;
@@ -648,7 +665,9 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             return VT_OK;
         }
     } else {
-        if (tf.indexed) return VT_ERR_SHAPE;      // row picking exists in the small-n kernel only
+        // the fused tree level exists in the small-n kernel only; row picking needs the fused merge (n <= 8)
+        if (tf.cum != nullptr || (tf.indexed && (n > vt::kGemvMaxN || p.row_select || out_logp_full != nullptr)))
+            return VT_ERR_SHAPE;
         vt::MfmaArgs a;
         a.h = h;
         a.W = W_trim;
@@ -667,6 +686,8 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.hpack = p.NT >= 8 ? static_cast<void *>(wsb + p.off_hpack) : nullptr;
         a.zbuf = nullptr;
         if (p.row_select) a.zbuf = out_logp_full != nullptr ? out_logp_full : reinterpret_cast<float *>(wsb + p.off_zbuf);
+        a.row_pack = tf.row_pack;
+        a.indexed = tf.indexed;
         hipError_t e = vt::launch_head_mfma(p.NT, a, p.lds, st);
         if (e != hipSuccess) return device_status(e);
         if (p.row_select) {
@@ -675,6 +696,8 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             return VT_OK;
         }
         vt::FinalizeArgs f;
+        f.row_pack = tf.row_pack;
+        f.indexed = tf.indexed;
         f.pms = pms;
         f.pkeys = pkeys;
         f.nlists = p.nlists;

@@ -148,8 +148,10 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
             // 16 pieces per unit: piece pc belongs to step s0 + pc / 16
             int ua = ustart + s0 + (pc >> 4);
             ua = ua >= nunits ? ua - nunits : ua;
+            // few hidden rows may be picked out of a larger batch (their indices are packed in row_pack)
+            const int hr = a.indexed ? (int)((a.row_pack >> (8 * (r & 7))) & 0xFFull) : r;
             if (r < a.n)
-                cached_load16(hp[q], (unsigned)((size_t)r * rs + (size_t)ua * (kUnitCols * 2) + (size_t)(pc & 15) * 16),
+                cached_load16(hp[q], (unsigned)((size_t)hr * rs + (size_t)ua * (kUnitCols * 2) + (size_t)(pc & 15) * 16),
                               hbase);
             r += step_r;
             pc += step_p;
@@ -573,8 +575,9 @@ __global__ void __launch_bounds__(kStepWaves *kWave) step_finalize_kernel(const 
     const int i = blockIdx.x * f.conc + w;
     if (i >= f.n) return;
     unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * f.stage_keys;
+    const int o = f.indexed ? (int)((f.row_pack >> (8 * (i & 7))) & 0xFFull) : i;      // output row
     finalize_row<true>(f.pms + (size_t)i * f.nlists, f.pkeys + (size_t)i * f.nlists * f.L, f.nlists, f.L, f.m, stage,
-                 f.out_ids + (size_t)i * f.m, f.out_logp + (size_t)i * f.m, f.out_lse ? f.out_lse + i : nullptr,
+                 f.out_ids + (size_t)o * f.m, f.out_logp + (size_t)o * f.m, f.out_lse ? f.out_lse + o : nullptr,
                  f.lse_buf + i, lane);
 }
 

@@ -15,6 +15,13 @@ constexpr int kFinalizeLdsBytes = 152 * 1024;  // staging budget of the finalize
 constexpr int kMaxDynamicLds = 159 * 1024;     // dynamic LDS the step kernels may request (160 KiB per CU less static use)
 constexpr int kTicketBytes = 2048;             // top counter + one 64-byte line per group of 16 workgroups
 constexpr int kGemvMaxN = 8;           // the VALU GEMV path covers n <= 8
+// ... but from 4 hidden rows on the matrix-core kernel is faster when its 128-row tiles fill the 256 CUs in
+// one round (measured at d = 3072, n = 8: k = 28672: 36.9 against 37.4 us, 30720: 38.7 / 40.8, 32768: 39.9 / 41.8;
+// k = 24576: a tie; k = 16384: 29.8 / 27.4, k = 65536: 78.0 / 75.1)
+// (d = 8192, n = 8: 97.8 against 88.0 us: only up to d = 4096, where 2048, 3072 and 4096 all gain)
+constexpr int kMfmaSmallMaxD = 4096;
+constexpr int kMfmaSmallMinN = 4;
+constexpr int kMfmaSmallMinTiles = 216;
 
 struct StepArgs {
     const void *h;            // [n, d]
@@ -71,6 +78,10 @@ struct MfmaArgs {
     float *out_logp_full;     // [n, k] or null
     void *hpack;              // more than 64 hidden rows: h re-laid in operand order, d * NT * 32 bytes
     float *zbuf;              // [n, k] or null: store the logits and leave the rest of the step to row_select_kernel
+    // indexed != 0 (n <= 8 only): hidden row i is row (row_pack >> 8 i) & 255 of h -- rows picked out of a
+    // larger batch (several heads per call); the merge kernel maps the output rows the same way
+    unsigned long long row_pack;
+    int indexed;
 };
 
 struct FinalizeArgs {
@@ -83,6 +94,8 @@ struct FinalizeArgs {
     float *out_logp;
     float *out_lse;           // or null
     float *lse_buf;
+    unsigned long long row_pack;   // indexed != 0 (n <= 8): hidden row i writes output row (row_pack >> 8 i) & 255
+    int indexed;
 };
 
 size_t mfma_stage_bytes();
