@@ -274,18 +274,22 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         return;
     }
 
-    if (a.L <= 16) {
+    if (a.L <= 16 && a.n > kStepWaves) {
         // four hidden rows per wave and pass (16 lanes each)
         for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
             block_epilogue_rows4(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
                                  a.pkeys, a.nlists, (int)blockIdx.x, lane);
     } else {
+        // a wave per hidden row (all of them at once for n <= 8); candidate keys of the threshold selection
+        // sit behind the logit tile, 1 KiB per wave
+        unsigned long long *cand =
+            a.n <= kStepWaves ? reinterpret_cast<unsigned long long *>(smem + 8192) + (size_t)w * 2 * kWave : nullptr;
         for (int i = w; i < a.n; i += kStepWaves) {
             const float *zrow = zt + (size_t)i * tp;
             float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
             unsigned long long *pms_slot = a.pms + (size_t)i * a.nlists + blockIdx.x;
             unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nlists + blockIdx.x) * a.L;
-            block_epilogue_small(zrow, 1, 0, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane);
+            block_epilogue_small(zrow, 1, 0, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane, cand);
         }
     }
 }
