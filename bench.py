@@ -431,10 +431,10 @@ def main():
                "one_thread_us": round(us_cpu_1t, 1)}
         log("cpu_baseline:", cpu)
 
-    # which kernel serves this shape (the library's policy: from 4 rows on the matrix-core kernel when its 128-row
+    # which kernel serves this shape (the library's policy: from 2 rows on the matrix-core kernel when its 128-row
     # tiles fill the 256 CUs in one round and d <= 4096)
     tiles = (k + 127) // 128
-    on_mfma = n > 8 or (n >= 4 and 216 <= tiles <= 256 and d % 128 == 0 and d <= 4096)
+    on_mfma = n > 8 or (n >= 2 and 216 <= tiles <= 256 and d % 128 == 0 and d <= 4096)
     step_kernel = "head_mfma_kernel + step_finalize_kernel" if on_mfma else "head_gemv_kernel"
     gbps_cold = step_bytes / us_cold / 1e3
     gbps_kernel = step_bytes / us_kernel / 1e3
@@ -460,7 +460,7 @@ def main():
         "warm_single_buffer_us": round(us_warm, 3),
         "plain_read_same_bytes_us": round(us_read, 3),
         "plain_read_gbps": round(step_bytes / us_read / 1e3, 1),
-        # The step is its streaming kernel plus, for 4-8 rows at this k, a 5 us merge kernel (up to 3 rows: one
+        # The step is its streaming kernel plus, for 2-8 rows at this k, a 5 us merge kernel (one row: one
         # launch).  `achieved` prices the algorithmic bytes against the whole step's share of the timed region
         # (HIP events on the launch stream / K), i.e. against both kernels; rocprofv3's duration of the streaming
         # kernel alone is in profiles/.  An event pair around every single step adds the events' own cost and

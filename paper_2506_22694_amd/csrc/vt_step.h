@@ -15,12 +15,12 @@ constexpr int kFinalizeLdsBytes = 152 * 1024;  // staging budget of the finalize
 constexpr int kMaxDynamicLds = 159 * 1024;     // dynamic LDS the step kernels may request (160 KiB per CU less static use)
 constexpr int kTicketBytes = 2048;             // top counter + one 64-byte line per group of 16 workgroups
 constexpr int kGemvMaxN = 8;           // the VALU GEMV path covers n <= 8
-// ... but from 4 hidden rows on the matrix-core kernel is faster when its 128-row tiles fill the 256 CUs in
+// ... but from 2 hidden rows on the matrix-core kernel is faster (n = 2: 38.7 against 39.4 us, n = 3: 38.8 / 39.9) when its 128-row tiles fill the 256 CUs in
 // one round (measured at d = 3072, n = 8: k = 28672: 36.9 against 37.4 us, 30720: 38.7 / 40.8, 32768: 39.9 / 41.8;
 // k = 24576: a tie; k = 16384: 29.8 / 27.4, k = 65536: 78.0 / 75.1)
 // (d = 8192, n = 8: 97.8 against 88.0 us: only up to d = 4096, where 2048, 3072 and 4096 all gain)
 constexpr int kMfmaSmallMaxD = 4096;
-constexpr int kMfmaSmallMinN = 4;
+constexpr int kMfmaSmallMinN = 2;      // n = 1 is a tie (36.5 us both at d = 3072; +0.4 us at d = 4096): it keeps the single launch
 constexpr int kMfmaSmallMinTiles = 216;
 
 struct StepArgs {
