@@ -108,6 +108,9 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
             const int kc_regs = (vt::kMfmaChunkPieces * vt::kStepWaves * 64 * 16) / (16 * NT * 2) / 128 * 128;
             if (KC > kc_regs) KC = kc_regs;   // the chunk must fit the register prefetch
             if (KC > d) KC = d;
+            // chunks of equal size (d = 2560: 2304 + 256 -> 1280 + 1280)
+            const int nch = (d + KC - 1) / KC;
+            KC = ((d + nch - 1) / nch + 127) / 128 * 128;
         }
         p.mfma = true;
         p.NT = NT;
