@@ -295,7 +295,7 @@ const char *vt_last_device_error(void) { return hipGetErrorString(g_last_hip_err
 // ------------------------------------------------------------------ Algorithm 1
 size_t vt_count_tokens_ws_bytes(int32_t V, int64_t n_ids) {
     if (V <= 0 || n_ids < 0) return 0;
-    return round_up((size_t)vt::hist_num_chunks(n_ids) * (size_t)V * sizeof(unsigned), 256);
+    return round_up((size_t)vt::hist_num_chunks(n_ids, V) * (size_t)((V + 1) & ~1) * sizeof(unsigned short), 256);
 }
 
 int vt_count_tokens(const void *ids, int id_type, int64_t n_ids, int32_t V, int64_t *counts,

@@ -7,14 +7,14 @@
 namespace vt {
 
 // ---- Algorithm 1 ----
-constexpr int kHistBinsPerBlock = 32768;   // uint32 bins privatised in LDS per workgroup (128 KiB)
-constexpr int kHistMaxChunks = 64;         // id-stream chunks (partial histograms) per launch
+constexpr int kHistBinsPerBlock = 65536;   // 16-bit bins privatised in LDS per workgroup (128 KiB, two per word)
+constexpr int kHistBlocks = 256;           // workgroups per launch: id-stream chunks x bin ranges
 constexpr int kHistThreads = 1024;
 constexpr int kHistUnroll = 4;            // 16-byte id vectors in flight per thread
 
 int hist_num_ranges(int V);
-int hist_num_chunks(int64_t n_ids);
-// partial: [chunks, V] uint32 scratch
+int hist_num_chunks(int64_t n_ids, int V);
+// partial: [chunks, V rounded up to even] 16-bit scratch
 hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V, long long *counts,
                          unsigned long long *n_invalid, unsigned *partial, hipStream_t st);
 

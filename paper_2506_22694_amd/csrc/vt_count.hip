@@ -1,12 +1,18 @@
 // Algorithm 1 (Count Token Frequencies): c[t] += 1 for every token id of the stream.
 //
-// The V counters do not fit one CU's LDS (V = 128256 -> 513 KB as uint32), so
-// the vocabulary is cut into ranges of 32768 bins (128 KiB of LDS) and the id
-// stream into chunks.  Workgroup (chunk, range) reads its chunk with 16-byte
-// loads, counts the ids that fall into its range with LDS atomics (no global
-// atomic ever sees the Zipf-hot ids), and writes its private histogram to
-// scratch.  A second kernel sums the chunk histograms into the caller's int64
-// counters.  Ids outside [0, V) are skipped and tallied.
+// The V counters do not fit one CU's LDS as 32-bit words (V = 128256 -> 513 KB), so the bins
+// are 16 bits wide, two per LDS word, the vocabulary is cut into ranges of 65536 bins (128 KiB of
+// LDS; two ranges for V = 128256) and the id stream into chunks.  Workgroup (chunk, range) reads
+// its chunk with 16-byte loads, counts the ids that fall into its range with LDS atomics (no
+// global atomic sees the Zipf-hot ids more than once per 32768 occurrences), and writes its
+// private histogram to scratch.  A second kernel sums the chunk histograms into the caller's
+// int64 counters.  Ids outside [0, V) are skipped and tallied.
+//
+// A 16-bit bin never holds more than 15 bits for long: the increment that sets bit 15 (it sees the
+// old value 0x7FFF) takes 32768 back out of the bin and adds them to the result counter directly.
+// Between that increment and its subtraction the bin can only grow by the increments in flight in
+// the workgroup (a few thousand at most), far from 65536, so a bin never carries into its
+// neighbour in the same word, whatever the id distribution.
 #include "vt_build.h"
 #include "vt_device.h"
 
@@ -14,11 +20,14 @@ namespace vt {
 
 int hist_num_ranges(int V) { return (V + kHistBinsPerBlock - 1) / kHistBinsPerBlock; }
 
-int hist_num_chunks(int64_t n_ids) {
-    // at least 128K ids per chunk so that zeroing and flushing 128 KiB of LDS pays off
-    int64_t c = (n_ids + (1 << 17) - 1) >> 17;
+int hist_num_chunks(int64_t n_ids, int V) {
+    // at least 64K ids per chunk so that zeroing and flushing 128 KiB of LDS pays off; chunks x ranges = one
+    // round of workgroups over the 256 CUs
+    int cap = kHistBlocks / hist_num_ranges(V);
+    if (cap < 1) cap = 1;
+    int64_t c = (n_ids + (1 << 16) - 1) >> 16;
     if (c < 1) c = 1;
-    if (c > kHistMaxChunks) c = kHistMaxChunks;
+    if (c > cap) c = cap;
     return (int)c;
 }
 
@@ -27,12 +36,14 @@ template <bool IDS64>
 __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *__restrict__ ids_v, long long n_ids,
                                                                     int head, int V, int nchunks,
                                                                     unsigned *__restrict__ partial,
+                                                                    unsigned long long *__restrict__ counts,
                                                                     unsigned long long *__restrict__ n_invalid) {
-    extern __shared__ __align__(16) unsigned bins[];
+    extern __shared__ __align__(16) unsigned words[];     // two 16-bit bins per word
     const int chunk = blockIdx.x, range = blockIdx.y;
     const int lo = range * kHistBinsPerBlock;
     const int nb = min(kHistBinsPerBlock, V - lo);
-    for (int b = threadIdx.x; b < nb; b += kHistThreads) bins[b] = 0u;
+    const int nw = (nb + 1) >> 1;
+    for (int b = threadIdx.x; b < nw; b += kHistThreads) words[b] = 0u;
     __syncthreads();
 
     // chunk boundaries in units of 16-byte vectors (4 int32 or 2 int64), tail handled by the last chunk
@@ -46,7 +57,15 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
             invalid += 1u;
         } else {
             const unsigned b = (unsigned)((int)t - lo);
-            if (b < (unsigned)nb) atomicAdd(&bins[b], 1u);
+            if (b < (unsigned)nb) {
+                const unsigned sh = (b & 1u) << 4;
+                const unsigned old = atomicAdd(&words[b >> 1], 1u << sh);
+                if (((old >> sh) & 0xFFFFu) == 0x7FFFu) {
+                    // this increment set bit 15: 32768 occurrences move from the bin to the result counter
+                    atomicSub(&words[b >> 1], 0x8000u << sh);
+                    atomicAdd(&counts[t], 32768ull);
+                }
+            }
         }
     };
     const u32x4 *vp = reinterpret_cast<const u32x4 *>(static_cast<const char *>(ids_v) + (size_t)head * IDB);
@@ -87,8 +106,9 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
         }
     }
     __syncthreads();
-    unsigned *dst = partial + (size_t)chunk * V + lo;
-    for (int b = threadIdx.x; b < nb; b += kHistThreads) dst[b] = bins[b];
+    // rows of the scratch are (V rounded up to even) 16-bit bins long: every range starts on a word
+    unsigned *dst = partial + (((size_t)chunk * (size_t)((V + 1) & ~1) + lo) >> 1);
+    for (int b = threadIdx.x; b < nw; b += kHistThreads) dst[b] = words[b];
     // every range-workgroup of a chunk sees the same invalid ids: only range 0 reports them
     if (n_invalid != nullptr && range == 0) {
         const int tot = wave_sum_i32((int)invalid);
@@ -96,28 +116,38 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
     }
 }
 
+// One thread sums a word (two neighbouring bins) over the chunks.
 __global__ void __launch_bounds__(256) hist_reduce_kernel(const unsigned *__restrict__ partial, int nchunks, int V,
                                                           long long *__restrict__ counts) {
-    const int v = blockIdx.x * 256 + threadIdx.x;
-    if (v >= V) return;
-    long long s = 0;
+    const int wi = blockIdx.x * 256 + threadIdx.x;
+    const int Vw = (V + 1) >> 1;                   // words per scratch row
+    if (wi >= Vw) return;
+    long long s0 = 0, s1 = 0;
     int c = 0;
     for (; c + 8 <= nchunks; c += 8) {
         unsigned t[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = partial[(size_t)(c + u) * V + v];
+        for (int u = 0; u < 8; ++u) t[u] = partial[(size_t)(c + u) * Vw + wi];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += (long long)t[u];
+        for (int u = 0; u < 8; ++u) {
+            s0 += (long long)(t[u] & 0xFFFFu);
+            s1 += (long long)(t[u] >> 16);
+        }
     }
-    for (; c < nchunks; ++c) s += (long long)partial[(size_t)c * V + v];
-    counts[v] += s;
+    for (; c < nchunks; ++c) {
+        const unsigned t = partial[(size_t)c * Vw + wi];
+        s0 += (long long)(t & 0xFFFFu);
+        s1 += (long long)(t >> 16);
+    }
+    counts[2 * wi] += s0;
+    if (2 * wi + 1 < V) counts[2 * wi + 1] += s1;
 }
 
 hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V, long long *counts,
                          unsigned long long *n_invalid, unsigned *partial, hipStream_t st) {
-    const int nchunks = hist_num_chunks(n_ids);
+    const int nchunks = hist_num_chunks(n_ids, V);
     const int nranges = hist_num_ranges(V);
-    const size_t lds = (size_t)kHistBinsPerBlock * sizeof(unsigned);
+    const size_t lds = (size_t)kHistBinsPerBlock * sizeof(unsigned short);
     static bool attr_set[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -140,11 +170,12 @@ hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V
     if (head > n_ids) head = n_ids;
     if (ids64)
         hipLaunchKernelGGL(hist_partial_kernel<true>, grid, dim3(kHistThreads), lds, st, ids, (long long)n_ids,
-                           (int)head, V, nchunks, partial, n_invalid);
+                           (int)head, V, nchunks, partial, reinterpret_cast<unsigned long long *>(counts), n_invalid);
     else
         hipLaunchKernelGGL(hist_partial_kernel<false>, grid, dim3(kHistThreads), lds, st, ids, (long long)n_ids,
-                           (int)head, V, nchunks, partial, n_invalid);
-    hipLaunchKernelGGL(hist_reduce_kernel, dim3((V + 255) / 256), dim3(256), 0, st, partial, nchunks, V, counts);
+                           (int)head, V, nchunks, partial, reinterpret_cast<unsigned long long *>(counts), n_invalid);
+    hipLaunchKernelGGL(hist_reduce_kernel, dim3(((V + 1) / 2 + 255) / 256), dim3(256), 0, st, partial, nchunks, V,
+                       counts);
     return hipGetLastError();
 }
 

@@ -140,6 +140,29 @@ def test_count_all_tokens_identical_and_small_vocab():
     assert np.array_equal(vt.count_tokens(to_dev(ids), 3).cpu().numpy(), oracle.count(ids, 3)[0])
 
 
+def test_count_hot_neighbouring_bins_odd_vocabulary_and_accumulation():
+    # the LDS bins are 16 bits wide, two per word, and spill 32768 at a time into the result: long runs of
+    # one id, of two ids that share a word, of the last id of an odd-sized vocabulary, an id just across
+    # the 65536-bin range boundary, and a second call that accumulates on top of the first
+    for V in (70_001, 65_537, 12):
+        rng = np.random.default_rng(V)
+        last = V - 1
+        parts = [np.full(250_000, 10, np.int32), np.full(180_000, 11, np.int32), np.full(140_000, last, np.int32),
+                 np.full(70_000, min(65_536, last), np.int32), np.full(33_000, min(65_535, last), np.int32),
+                 rng.integers(0, V, size=200_000).astype(np.int32)]
+        ids = np.concatenate(parts)
+        rng.shuffle(ids)
+        ref, _ = oracle.count(ids, V)
+        counts = vt.count_tokens(to_dev(ids), V)
+        assert np.array_equal(counts.cpu().numpy(), ref), V
+        vt.count_tokens(to_dev(ids[:300_001]), V, counts=counts)
+        ref2, _ = oracle.count(ids[:300_001], V)
+        assert np.array_equal(counts.cpu().numpy(), ref + ref2), V
+    # unshuffled: every wave sees one id only
+    ids = np.concatenate([np.full(100_000, 4, np.int32), np.full(100_000, 5, np.int32)])
+    assert np.array_equal(vt.count_tokens(to_dev(ids), 64).cpu().numpy(), oracle.count(ids, 64)[0])
+
+
 # ----------------------------------------------------------------------------- Eq. 1
 def test_build_tiny_exact():
     wl = synth.WORKLOADS["tiny"]
