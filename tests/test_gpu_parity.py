@@ -426,6 +426,27 @@ def test_step_exact_ties_from_duplicate_rows():
     check_step(oi, ol, ref, map_, m)
 
 
+@pytest.mark.parametrize("n,d", [(8, 2048), (3, 3072), (8, 4096)])
+def test_step_few_rows_on_matrix_cores_exact_ties_across_tiles(n, d):
+    # k = 32768: 256 tiles of 128 rows, one per CU -- the shape where 2 <= n <= 8 runs on the matrix-core kernel
+    # (rotated contraction start for d a multiple of 2048, one wave per hidden row with the threshold selection,
+    # merge kernel).  Equal rows of W in far-apart tiles must tie exactly and come out in ascending id order.
+    k, m = 32768, 8
+    W, map_ = synth.trimmed_head_direct(k, d, seed=31 + n, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=31 + n, dtype="bf16")
+    z = oracle.logits(h, W)
+    i = n - 1
+    j = int(np.argmax(z[i]))
+    for off in (1, 129, 1100, 9000, 20000):           # same tile, next tile, tiles with other starts
+        W[(j + off) % k] = W[j]
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+    ids, lp = oi.cpu().numpy(), ol.cpu().numpy()
+    assert np.array_equal(ids[i, :6], ref["ids"][i, :6])
+    assert np.all(np.diff(ids[i, :6]) > 0) and np.all(lp[i, :6] == lp[i, 0])
+    check_step(oi, ol, ref, map_, m, lse)
+
+
 def test_step_non_ascending_map_ties_follow_target_id():
     k, d = 512, 512
     W, map_ = synth.trimmed_head_direct(k, d, seed=11, dtype="bf16")
