@@ -86,8 +86,8 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
                         p.NP = NP;
                         p.CS = CS;
                         p.S = S;
-                        // + 1 KiB per wave behind the tile: candidate keys of the epilogue's threshold selection
-                        p.lds = ((tile + 15) & ~(size_t)15) + (size_t)vt::kStepWaves * 2 * 64 * sizeof(unsigned long long);
+                        // + 2 KiB per wave behind the tile: candidate keys of the epilogue's threshold selection
+                        p.lds = ((tile + 15) & ~(size_t)15) + (size_t)vt::kStepWaves * 256 * sizeof(unsigned long long);
                     }
                     break;
                 }

@@ -351,13 +351,14 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
             float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
             unsigned long long *pms_slot = a.pms + (size_t)i * a.nblocks + blockIdx.x;
             unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nblocks + blockIdx.x) * a.L;
+            // candidate keys of the threshold selection sit behind the tile: kLargeTileCandCap per wave
+            unsigned long long *cand = reinterpret_cast<unsigned long long *>(
+                                           smem + (((size_t)S * sstride * sizeof(float) + 15) & ~(size_t)15)) +
+                                       (size_t)w * kLargeTileCandCap;
             if (rows_b <= 2 * kWave)
-                block_epilogue_small(zrow, S, sstride, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane,
-                                     reinterpret_cast<unsigned long long *>(
-                                         smem + (((size_t)S * sstride * sizeof(float) + 15) & ~(size_t)15)) +
-                                         (size_t)w * 2 * kWave);
+                block_epilogue_small(zrow, S, sstride, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane, cand);
             else
-                block_epilogue_large(zrow, S, sstride, rows_b, a.L, a.map + row0, full, pms_slot, pk_slot, lane);
+                block_epilogue_large(zrow, S, sstride, rows_b, a.L, a.map + row0, full, pms_slot, pk_slot, lane, cand);
         }
     }
 

@@ -104,6 +104,56 @@ __device__ __forceinline__ void wave_publish_top_by_threshold(const unsigned (&o
     __builtin_amdgcn_wave_barrier();     // the next row of this wave reuses cand
 }
 
+// The same for Q candidates per lane (tiles of more than 128 rows); `cap` keys fit `cand`.  Returns false,
+// having published nothing, when more than `cap` candidates reach the threshold.
+constexpr int kLargeTileCandCap = 256;
+template <int Q>
+__device__ __forceinline__ bool wave_publish_top_by_threshold_q(const unsigned (&ord)[Q], const int (&id)[Q], int L,
+                                                                unsigned long long *cand, int cap,
+                                                                unsigned long long *__restrict__ pkeys_slot,
+                                                                int lane) {
+    unsigned top = ord[0];
+#pragma unroll
+    for (int q = 1; q < Q; ++q) top = ord[q] > top ? ord[q] : top;
+    int gsteps = 6;
+    while ((kWave >> gsteps) < L) --gsteps;
+    unsigned T = wave_min_of_group_max_u32(top, gsteps);
+    T = T == 0u ? 1u : T;
+    int ncand = 0;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const bool c = ord[q] >= T;
+        const unsigned long long mask = __ballot(c);
+        if (mask != 0ull) {
+            const int slot = ncand + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                                    __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+            if (c && slot < cap) cand[slot] = ((unsigned long long)ord[q] << 32) | (unsigned)(~(unsigned)id[q]);
+            ncand += __popcll(mask);
+        }
+    }
+    if (ncand > cap) return false;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int c = lane; c < ncand; c += kWave) {
+        const unsigned long long key = cand[c];
+        int above = 0;
+        int x = 0;
+        for (; x + 8 <= ncand; x += 8) {
+            unsigned long long t[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) t[q] = cand[x + q];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) above += t[q] > key ? 1 : 0;
+        }
+        for (; x < ncand; ++x) above += cand[x] > key ? 1 : 0;
+        if (above < L) publish_u64(pkeys_slot + above, key);
+    }
+    if (lane < L && lane >= ncand) publish_u64(pkeys_slot + lane, kNoKey);
+    __builtin_amdgcn_wave_barrier();     // the next row of this wave reuses cand
+    return true;
+}
+
 // ------------------------------------------------------------------ workgroup epilogue of one hidden row
 // zrow: the row's logit tile in LDS (S partial sums per logit, `sstride` floats
 // apart).  Publishes (max, sum-exp) and the L best keys of this workgroup.
@@ -144,6 +194,9 @@ __device__ __forceinline__ void block_epilogue_core(const float *zrow, int S, in
             wave_publish_top_by_threshold(ord, id, L, cand, pkeys_slot, lane);
             published = true;
         }
+    } else {
+        if (cand != nullptr && L >= 3 && L <= kWave)
+            published = wave_publish_top_by_threshold_q<QMAX>(ord, id, L, cand, kLargeTileCandCap, pkeys_slot, lane);
     }
     if (!published) {
         const unsigned long long key = wave_select_top<QMAX>(ord, id, L, lane);
@@ -163,17 +216,32 @@ __device__ __forceinline__ void block_epilogue_small(const float *zrow, int S, i
     block_epilogue_core<2>(zrow, S, sstride, rows_b, L, idq, logp_full_row, pms_slot, pkeys_slot, lane, cand);
 }
 
-// large tiles (<= 1024 rows): ids are read here
+// large tiles (<= 1024 rows): ids are read here; QMAX logits per lane, sized to the tile (4, 8 or 16)
+template <int QMAX>
+__device__ __forceinline__ void block_epilogue_large_q(const float *zrow, int S, int sstride, int rows_b, int L,
+                                                       const int *__restrict__ map_tile,
+                                                       float *__restrict__ logp_full_row,
+                                                       unsigned long long *__restrict__ pms_slot,
+                                                       unsigned long long *__restrict__ pkeys_slot, int lane,
+                                                       unsigned long long *cand) {
+    int idq[QMAX];
+#pragma unroll
+    for (int q = 0; q < QMAX; ++q) idq[q] = map_tile[min(lane + q * kWave, rows_b - 1)];
+    block_epilogue_core<QMAX>(zrow, S, sstride, rows_b, L, idq, logp_full_row, pms_slot, pkeys_slot, lane, cand);
+}
 __device__ __forceinline__ void block_epilogue_large(const float *zrow, int S, int sstride, int rows_b, int L,
                                                   const int *__restrict__ map_tile,
                                                   float *__restrict__ logp_full_row,
                                                   unsigned long long *__restrict__ pms_slot,
-                                                  unsigned long long *__restrict__ pkeys_slot, int lane) {
-    constexpr int QMAX = kStepMaxRowsPerBlock / kWave;
-    int idq[QMAX];
-#pragma unroll
-    for (int q = 0; q < QMAX; ++q) idq[q] = map_tile[min(lane + q * kWave, rows_b - 1)];
-    block_epilogue_core<QMAX>(zrow, S, sstride, rows_b, L, idq, logp_full_row, pms_slot, pkeys_slot, lane);
+                                                  unsigned long long *__restrict__ pkeys_slot, int lane,
+                                                  unsigned long long *cand = nullptr) {
+    if (rows_b <= 4 * kWave)
+        block_epilogue_large_q<4>(zrow, S, sstride, rows_b, L, map_tile, logp_full_row, pms_slot, pkeys_slot, lane, cand);
+    else if (rows_b <= 8 * kWave)
+        block_epilogue_large_q<8>(zrow, S, sstride, rows_b, L, map_tile, logp_full_row, pms_slot, pkeys_slot, lane, cand);
+    else
+        block_epilogue_large_q<kStepMaxRowsPerBlock / kWave>(zrow, S, sstride, rows_b, L, map_tile, logp_full_row,
+                                                             pms_slot, pkeys_slot, lane, cand);
 }
 
 // ------------------------------------------------------------------ four hidden rows per pass
