@@ -116,31 +116,47 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
     }
 }
 
-// One thread sums a word (two neighbouring bins) over the chunks.
+// A workgroup sums 64 words (128 neighbouring bins) over the chunks: wave g takes the chunks g, g + 4, ..
+// (a load instruction reads 256 consecutive bytes of one chunk's row), the four partial sums meet in LDS.
 __global__ void __launch_bounds__(256) hist_reduce_kernel(const unsigned *__restrict__ partial, int nchunks, int V,
                                                           long long *__restrict__ counts) {
-    const int wi = blockIdx.x * 256 + threadIdx.x;
+    __shared__ long long part[3][2][kWave];
+    const int lane = (int)threadIdx.x & 63, g = (int)threadIdx.x >> 6;
+    const int wi = blockIdx.x * kWave + lane;
     const int Vw = (V + 1) >> 1;                   // words per scratch row
-    if (wi >= Vw) return;
     long long s0 = 0, s1 = 0;
-    int c = 0;
-    for (; c + 8 <= nchunks; c += 8) {
-        unsigned t[8];
+    if (wi < Vw) {
+        int c = g;
+        for (; c + 12 < nchunks; c += 16) {
+            unsigned t[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = partial[(size_t)(c + u) * Vw + wi];
+            for (int u = 0; u < 4; ++u) t[u] = partial[(size_t)(c + 4 * u) * Vw + wi];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            s0 += (long long)(t[u] & 0xFFFFu);
-            s1 += (long long)(t[u] >> 16);
+            for (int u = 0; u < 4; ++u) {
+                s0 += (long long)(t[u] & 0xFFFFu);
+                s1 += (long long)(t[u] >> 16);
+            }
+        }
+        for (; c < nchunks; c += 4) {
+            const unsigned t = partial[(size_t)c * Vw + wi];
+            s0 += (long long)(t & 0xFFFFu);
+            s1 += (long long)(t >> 16);
         }
     }
-    for (; c < nchunks; ++c) {
-        const unsigned t = partial[(size_t)c * Vw + wi];
-        s0 += (long long)(t & 0xFFFFu);
-        s1 += (long long)(t >> 16);
+    if (g > 0) {
+        part[g - 1][0][lane] = s0;
+        part[g - 1][1][lane] = s1;
     }
-    counts[2 * wi] += s0;
-    if (2 * wi + 1 < V) counts[2 * wi + 1] += s1;
+    __syncthreads();
+    if (g == 0 && wi < Vw) {
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            s0 += part[q][0][lane];
+            s1 += part[q][1][lane];
+        }
+        counts[2 * wi] += s0;
+        if (2 * wi + 1 < V) counts[2 * wi + 1] += s1;
+    }
 }
 
 hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V, long long *counts,
@@ -174,7 +190,7 @@ hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V
     else
         hipLaunchKernelGGL(hist_partial_kernel<false>, grid, dim3(kHistThreads), lds, st, ids, (long long)n_ids,
                            (int)head, V, nchunks, partial, reinterpret_cast<unsigned long long *>(counts), n_invalid);
-    hipLaunchKernelGGL(hist_reduce_kernel, dim3(((V + 1) / 2 + 255) / 256), dim3(256), 0, st, partial, nchunks, V,
+    hipLaunchKernelGGL(hist_reduce_kernel, dim3(((V + 1) / 2 + kWave - 1) / kWave), dim3(256), 0, st, partial, nchunks, V,
                        counts);
     return hipGetLastError();
 }
