@@ -626,6 +626,8 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         if (p.row_select) a.zbuf = out_logp_full != nullptr ? out_logp_full : reinterpret_cast<float *>(wsb + p.off_zbuf);
         if (tf.indexed && (p.row_select || out_logp_full != nullptr)) return VT_ERR_SHAPE;
         a.row_pack = tf.indexed ? tf.row_pack : 0x0706050403020100ull;
+        const bool split = !p.row_select && tf.cum == nullptr && n >= vt::kGemvSplitMinN;
+        a.split_tail = split ? 1 : 0;
         a.tree_cum = tf.cum;
         a.tree_K = tf.K;
         a.tree_parent = tf.parent;
@@ -648,6 +650,25 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             default: break;
         }
         if (e != hipSuccess) return device_status(e);
+        if (split) {
+            vt::FinalizeArgs f;
+            f.pms = pms;
+            f.pkeys = pkeys;
+            f.nlists = p.nblocks;
+            f.L = p.L;
+            f.n = n;
+            f.m = m;
+            f.conc = 1;
+            f.stage_keys = (p.nblocks + 1) * p.L;
+            f.out_ids = out_ids;
+            f.out_logp = out_logp;
+            f.out_lse = out_lse;
+            f.lse_buf = lse_buf;
+            f.row_pack = tf.row_pack;
+            f.indexed = tf.indexed;
+            e = vt::launch_step_finalize(f, (size_t)f.stage_keys * sizeof(unsigned long long), st);
+            if (e != hipSuccess) return device_status(e);
+        }
         if (p.row_select) {
             vt::launch_row_select(a.zbuf, map, n, k, m, out_ids, out_logp, out_lse, lse_buf, st);
             if (out_logp_full != nullptr) vt::launch_sub_lse(out_logp_full, lse_buf, n, k, st);

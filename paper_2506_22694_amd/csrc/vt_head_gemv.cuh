@@ -362,6 +362,10 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
         }
     }
 
+    if (a.split_tail) {
+        wait_stores_done();
+        return;
+    }
     float *lse_buf = reinterpret_cast<float *>(reinterpret_cast<char *>(a.tickets) + kTicketBytes);
     if (!arrive_and_elect(a.tickets, a.nblocks)) return;
     finalize_rows(a.pms, a.pkeys, a.nblocks, a.L, a.n, a.m, a.fin_conc, a.out_ids, a.out_logp, a.out_lse, lse_buf,

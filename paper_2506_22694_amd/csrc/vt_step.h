@@ -15,6 +15,8 @@ constexpr int kFinalizeLdsBytes = 152 * 1024;  // staging budget of the finalize
 constexpr int kMaxDynamicLds = 159 * 1024;     // dynamic LDS the step kernels may request (160 KiB per CU less static use)
 constexpr int kTicketBytes = 2048;             // top counter + one 64-byte line per group of 16 workgroups
 constexpr int kGemvMaxN = 8;           // the VALU GEMV path covers n <= 8
+constexpr int kGemvSplitMinN = 4;      // from this many hidden rows a separate merge kernel (a workgroup per row)
+                                       // beats the merge by the last workgroup's eight waves
 // ... but from 2 hidden rows on the matrix-core kernel is faster (n = 2: 38.7 against 39.4 us, n = 3: 38.8 / 39.9) when its 128-row tiles fill the 256 CUs in
 // one round (measured at d = 3072, n = 8: k = 28672: 36.9 against 37.4 us, 30720: 38.7 / 40.8, 32768: 39.9 / 41.8;
 // k = 24576: a tie; k = 16384: 29.8 / 27.4, k = 65536: 78.0 / 75.1)
@@ -42,6 +44,7 @@ struct StepArgs {
     float *out_logp_full;     // [n, k] or null (raw logits are written first, lse subtracted later)
     int fin_conc;             // waves that run the finalize stage concurrently (LDS budget)
     float *zbuf;              // [n, k] or null: store the logits and leave the rest of the step to row_select_kernel
+    int split_tail;           // != 0: the kernel ends after publishing its lists; step_finalize_kernel merges them
     // hidden row i is row (row_pack >> 8 i) & 255 of h and of the outputs: 0x0706050403020100 for rows 0 .. n-1,
     // other values when the rows are picked out of a larger batch (several heads per call)
     unsigned long long row_pack;

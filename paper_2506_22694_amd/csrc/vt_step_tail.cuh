@@ -392,13 +392,14 @@ __device__ __forceinline__ bool finalize_row_direct(const unsigned long long *__
     if constexpr (U == 32) {
         u32x4 r[16];
         const int npairs = total >> 1;
+        // Straight-line code from the first request to the wait: the compiler does not know that these
+        // registers are still in flight, and a branch in between (say, around the requests past the end)
+        // makes it copy them at the join -- before their values have arrived.  Requests past the end
+        // re-read the last pair instead.
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             const int e = u * kWave + lane;
-            if (FULL || u * kWave < npairs)       // uniform: no request for a stretch past the end
-                acquire_load16(r[u], src + 2 * (FULL ? e : min(e, npairs - 1)));
-            else
-                r[u] = u32x4{0u, 0u, 0u, 0u};
+            acquire_load16(r[u], src + 2 * (FULL ? e : min(e, npairs - 1)));
         }
         wait_loads16(r);
 #pragma unroll
