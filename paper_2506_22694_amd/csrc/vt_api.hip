@@ -120,14 +120,16 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.L = m < vt::kMfmaTileRows ? m : vt::kMfmaTileRows;
         p.nblocks = p.nlists;
         p.lds = NT >= 8 ? stage : stage + (size_t)16 * NT * p.hpitch;
-        const size_t tile = (size_t)n * (vt::kMfmaTileRows + 1) * sizeof(float);
+        // logit tile of the epilogue + 4 x 16 candidate keys per wave behind it
+        const size_t tile = (((size_t)n * (vt::kMfmaTileRows + 1) * sizeof(float) + 15) & ~(size_t)15) +
+                            (size_t)vt::kStepWaves * 4 * 16 * sizeof(unsigned long long);
         if (tile > p.lds) p.lds = tile;
         if (p.lds > (size_t)vt::kMaxDynamicLds) return p;
         const int group = p.nlists < vt::kStepMaxBlocks ? p.nlists : vt::kStepMaxBlocks;
         p.fin_stage_keys = (group + 1) * p.L;
         const int fc = (int)(vt::kFinalizeLdsBytes / ((size_t)p.fin_stage_keys * sizeof(unsigned long long)));
         // The per-tile candidate lists cost n * L selection rounds per tile and grow to megabytes; beyond a point
-        // (measured: 12 or more tokens per row, or n * L from about 1024; always when the lists no longer fit the
+        // (measured: 12 or more tokens per row, or n * L from about 1280; always when the lists no longer fit the
         // merge's LDS staging) the kernel stores its logits instead and a workgroup per hidden row finishes the step.
         p.row_select = p.L > vt::kRowSelectMinL || n * p.L >= vt::kRowSelectMinWork || fc < 1;
         // one hidden row per workgroup: n <= 256 rows spread over as many CUs, and a merging wave has its

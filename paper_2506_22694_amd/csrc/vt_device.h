@@ -63,6 +63,20 @@ __device__ __forceinline__ unsigned row16_allreduce_u32(unsigned v, Op op) {
     v = op(v, dpp_mov<0x141>(v));   // row_half_mirror
     return op(v, dpp_mov<0x140>(v));   // row_mirror
 }
+// Lane i of a 16-lane row receives v of lane (i - S) mod 16 of the same row (row_ror:S), 1 <= S <= 15.
+template <int S>
+__device__ __forceinline__ unsigned row16_rotate_by(unsigned v) {
+    return __builtin_amdgcn_update_dpp(0u, v, 0x120 + S, 0xF, 0xF, false);
+}
+// Number of the other 15 lanes of the row whose v is strictly greater than this lane's.
+template <int S = 15>
+__device__ __forceinline__ int row16_count_greater(unsigned v) {
+    if constexpr (S == 0) {
+        return 0;
+    } else {
+        return (row16_rotate_by<S>(v) > v ? 1 : 0) + row16_count_greater<S - 1>(v);
+    }
+}
 struct OpMaxU32 {
     __device__ __forceinline__ unsigned operator()(unsigned a, unsigned b) const { return a > b ? a : b; }
 };

@@ -276,9 +276,13 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
 
     if (a.L <= 16 && a.n > kStepWaves) {
         // four hidden rows per wave and pass (16 lanes each)
+        // candidate keys of the threshold selection: 4 rows x 16 keys per wave, behind the logit tile
+        unsigned long long *cand4 =
+            reinterpret_cast<unsigned long long *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15)) +
+            (size_t)w * 4 * 16;
         for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
             block_epilogue_rows4(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
-                                 a.pkeys, a.nlists, (int)blockIdx.x, lane);
+                                 a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
     } else {
         // a wave per hidden row (all of them at once for n <= 8); candidate keys of the threshold selection
         // sit behind the logit tile, 1 KiB per wave
@@ -556,9 +560,13 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
     }
 
     if (a.L <= 16) {
+        // candidate keys of the threshold selection: 4 rows x 16 keys per wave, behind the logit tile
+        unsigned long long *cand4 =
+            reinterpret_cast<unsigned long long *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15)) +
+            (size_t)w * 4 * 16;
         for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
             block_epilogue_rows4(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
-                                 a.pkeys, a.nlists, (int)blockIdx.x, lane);
+                                 a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
     } else {
         for (int i = w; i < a.n; i += kStepWaves) {
             const float *zrow = zt + (size_t)i * tp;

@@ -62,7 +62,7 @@ constexpr int kMfmaTileRows = 128;     // rows of W_trim per workgroup (16 per w
 constexpr int kRowSelectMinL = 11;      // matrix-core path: with more tokens per row than this, or
 // small-n path: the same switch when L > 12 - n / 2 (measured crossovers: L = 8 at n = 8, 10 at n = 4, 11-12 at n = 1)
 constexpr int kGemvRowSelectBase = 12;
-constexpr int kRowSelectMinWork = 1024; // with n * min(m, 128) from this value on, the kernel stores its logits and a
+constexpr int kRowSelectMinWork = 1280; // with n * min(m, 128) from this value on, the kernel stores its logits and a
                                         // workgroup per hidden row finishes the step
 constexpr int kMfmaChunkPieces = 9;    // an h chunk is prefetched through registers: at most this many
                                        // 16-byte pieces per thread, i.e. 16 * NT * KC * 2 <= 9 * 512 * 16 bytes

@@ -252,7 +252,7 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
                                                      const int (&idq)[8], float *__restrict__ logp_full, size_t k,
                                                      int row0, unsigned long long *__restrict__ pms,
                                                      unsigned long long *__restrict__ pkeys, int nlists, int blk,
-                                                     int lane) {
+                                                     int lane, unsigned long long *cand) {
     const int g = lane >> 4, gl = lane & 15;
     const int i = i0 + g;
     const bool active = i < n;
@@ -280,6 +280,54 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
 #pragma unroll
     for (int q = 0; q < 8; ++q) ls += __expf(zq[q] - M);
     const float Ssum = __uint_as_float(row16_allreduce_u32(__float_as_uint(ls), OpAddF32{}));
+    if (active && gl == 0)
+        publish_u64(pms + (size_t)i * nlists + blk,
+                    ((unsigned long long)__float_as_uint(Ssum) << 32) | __float_as_uint(M));
+    if (L <= 8) {
+        // Selection by threshold: T = the L-th largest of the 16 lanes' best logits, so at least L logits reach
+        // it and the L best of the row are among those that do -- about L + 2 of the 128.  They are compacted
+        // into 16 keys of LDS per row and each finds its rank by counting: no L dependent rounds.  More than 16
+        // candidates in any row of the wave (many equal logits; 3 in 1000 rows otherwise): the rounds below.
+        unsigned bo = ord[0];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) bo = ord[q] > bo ? ord[q] : bo;
+        const int above = row16_count_greater(bo);      // lanes of the row with a strictly better best logit
+        // the smallest best logit that fewer than L others beat is the L-th largest
+        unsigned T = row16_allreduce_u32(above < L ? bo : 0xFFFFFFFFu, OpMinU32{});
+        T = T == 0u ? 1u : T;   // fewer than L lanes have logits at all: every logit is a candidate
+        int cnt = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) cnt += ord[q] >= T ? 1 : 0;
+        unsigned incl = (unsigned)cnt;
+        incl += dpp_mov<0x111>(incl);       // row_shr:1 (lanes without a source read 0)
+        incl += dpp_mov<0x112>(incl);       // row_shr:2
+        incl += dpp_mov<0x114>(incl);       // row_shr:4
+        incl += dpp_mov<0x118>(incl);       // row_shr:8
+        const int total = (int)row16_allreduce_u32(incl, OpMaxU32{});
+        if (__ballot(total > 16) == 0ull) {
+            unsigned long long *crow = cand + 16 * g;
+            crow[gl] = kNoKey;              // below every candidate: unused slots count for nothing
+            int pos = (int)incl - cnt;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (ord[q] >= T) crow[pos++] = ((unsigned long long)ord[q] << 32) | (unsigned)(~(unsigned)id[q]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const unsigned long long mine = crow[gl];
+            int rank = 0;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) rank += crow[x] > mine ? 1 : 0;
+            if (active) {
+                unsigned long long *slot = pkeys + ((size_t)i * nlists + blk) * L;
+                if (gl < total && rank < L) publish_u64(slot + rank, mine);
+                if (gl < L && gl >= total) publish_u64(slot + gl, kNoKey);
+            }
+            __builtin_amdgcn_wave_barrier();     // the wave's next rows reuse cand
+            return;
+        }
+    }
     unsigned res_ord = 0u, res_id = 0u;
     for (int r = 0; r < L; ++r) {
         unsigned bo = ord[0];
@@ -305,9 +353,6 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
         const unsigned long long key =
             res_ord == 0u ? kNoKey : (((unsigned long long)res_ord << 32) | (unsigned)(~res_id));
         if (gl < L) publish_u64(pkeys + ((size_t)i * nlists + blk) * L + gl, key);
-        if (gl == 0)
-            publish_u64(pms + (size_t)i * nlists + blk,
-                        ((unsigned long long)__float_as_uint(Ssum) << 32) | __float_as_uint(M));
     }
 }
 

@@ -350,6 +350,30 @@ def test_step_many_rows_exact_ties_and_full_logp():
     assert np.max(np.abs(full.cpu().numpy().astype(np.float64) - logp_ref)) <= LOGP_TOL
 
 
+@pytest.mark.parametrize("n,m", [(20, 8), (40, 5), (70, 3)])
+def test_step_many_rows_many_equal_logits_in_one_tile(n, m):
+    # 40 copies of one row of W inside one 128-row tile: for the hidden row whose best logit they hold, more
+    # candidates tie at the top than a per-row threshold selection keeps, and the ids decide; one hidden row
+    # is zero, so all its logits are equal in every tile
+    k, d = 1500, 512
+    W, map_ = synth.trimmed_head_direct(k, d, seed=7300 + n, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=7300 + n, dtype="bf16")
+    h[n - 2] = 0
+    z = oracle.logits(h, W)
+    i = 5
+    j = int(np.argmax(z[i]))
+    base = 128 * 3 + 17
+    for t in range(40):
+        W[base + 2 * t] = W[j]
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
+    ids, lp = oi.cpu().numpy(), ol.cpu().numpy()
+    assert np.array_equal(ids[i], ref["ids"][i]) and np.all(lp[i] == lp[i, 0])
+    assert np.array_equal(ids[n - 2], np.sort(map_)[:m])
+    assert np.max(np.abs(lp[n - 2] - (-math.log(k)))) <= 1e-5
+    check_step(oi, ol, ref, map_, m, lse)
+
+
 @pytest.mark.parametrize("n", [20, 64, 100])
 def test_step_many_rows_exact_ties_across_tiles_with_different_starts(n):
     # d a multiple of 2048: workgroups start the contraction at different quarters (by tile index / 8);
