@@ -37,6 +37,9 @@ def _stale(target: str, deps) -> bool:
 # does not know that such a register is still in flight, so a spill of one would save a value that
 # has not arrived yet.  Their sources must therefore compile without any scratch memory.
 NO_SCRATCH = ("vt_head_", "vt_row_select")
+# For the same reason nothing may touch such a register between its load and the wait that covers it (a
+# copy at the join of a branch, a split live range): the device assembly of these sources is checked
+# path by path, see inflight_lint.py.
 
 
 def _scratch_users(remarks: str):
@@ -50,6 +53,22 @@ def _scratch_users(remarks: str):
             if n != 0:
                 out.append((name, n))
     return out
+
+
+def _inflight_violations(src: str):
+    """Compiles src to gfx950 assembly (same flags as the object) and runs the in-flight register check."""
+    try:
+        from . import inflight_lint
+    except ImportError:      # run as a script
+        import inflight_lint
+    asm = os.path.join(OBJ, os.path.basename(src)[:-4] + ".s")
+    r = subprocess.run([HIPCC] + FLAGS + ["--cuda-device-only", "-S", src, "-o", asm], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc -S failed on {src}:\n{r.stderr}")
+    with open(asm) as f:
+        bad, _ = inflight_lint.check_asm(f.read())
+    os.remove(asm)
+    return bad
 
 
 def _compile(src: str, force: bool) -> str:
@@ -67,6 +86,13 @@ def _compile(src: str, force: bool) -> str:
                 if os.path.exists(obj):
                     os.remove(obj)
                 raise RuntimeError(f"{base}: kernels with hand-issued loads must not spill: {bad}")
+            if r.returncode == 0:
+                touched = _inflight_violations(src)
+                if touched:
+                    os.remove(obj)
+                    raise RuntimeError(f"{base}: registers of hand-issued loads are touched before their wait "
+                                       f"(kernel, line of the load, line and text of the instruction in the "
+                                       f"device assembly): {touched[:5]}")
         lines = r.stderr.splitlines()
         if check and r.returncode == 0:
             lines = []      # the remarks (and their source excerpts) are not diagnostics

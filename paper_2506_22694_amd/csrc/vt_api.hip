@@ -102,15 +102,24 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         const size_t stage = NT >= 8 ? vt::mfma_wide_lds_bytes() : vt::mfma_stage_bytes();
         int KC = 128;   // NT >= 8: h is not staged at all (B-operands come from L2)
         if (NT < 8) {
-            const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage) / (16 * (size_t)NT);
+            // up to 8 hidden rows occupy 8 rows of LDS (the other half of the 16-row operand repeats them)
+            const size_t hrows = n <= 8 ? 8 : 16 * (size_t)NT;
+            const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage) / hrows;
             if (hmax < 272) return p;
             KC = (int)(((hmax - 16) / 2) / 128) * 128;
-            const int kc_regs = (vt::kMfmaChunkPieces * vt::kStepWaves * 64 * 16) / (16 * NT * 2) / 128 * 128;
+            const int kc_regs = (int)((vt::kMfmaChunkPieces * vt::kStepWaves * 64 * 16) / (hrows * 2) / 128 * 128);
             if (KC > kc_regs) KC = kc_regs;   // the chunk must fit the register prefetch
-            if (KC > d) KC = d;
-            // chunks of equal size (d = 2560: 2304 + 256 -> 1280 + 1280)
-            const int nch = (d + KC - 1) / KC;
-            KC = ((d + nch - 1) / nch + 127) / 128 * 128;
+            if (KC >= d) {
+                KC = d;
+            } else {
+                // several chunks: near-equal sizes (d = 2560: 2304 + 256 -> 1536 + 1024), every chunk but the
+                // last a multiple of the kernel's prefetch depth in 128-column units
+                const int U = d / 128, P = vt::kMfmaPrefetchUnits;
+                const int umax = KC / 128 / P * P;
+                if (umax < P) return p;
+                const int nch = (U + umax - 1) / umax;
+                KC = (((U + nch - 1) / nch + P - 1) / P * P) * 128;
+            }
         }
         p.mfma = true;
         p.NT = NT;
@@ -119,7 +128,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.nlists = (k + vt::kMfmaTileRows - 1) / vt::kMfmaTileRows;
         p.L = m < vt::kMfmaTileRows ? m : vt::kMfmaTileRows;
         p.nblocks = p.nlists;
-        p.lds = NT >= 8 ? stage : stage + (size_t)16 * NT * p.hpitch;
+        p.lds = NT >= 8 ? stage : stage + (n <= 8 ? 8 : 16 * (size_t)NT) * p.hpitch;
         // logit tile of the epilogue + 4 x 16 candidate keys per wave behind it
         const size_t tile = (((size_t)n * (vt::kMfmaTileRows + 1) * sizeof(float) + 15) & ~(size_t)15) +
                             (size_t)vt::kStepWaves * 4 * 16 * sizeof(unsigned long long);

@@ -31,7 +31,7 @@ constexpr int kUnitCols = 128;                       // columns per staged unit 
 constexpr int kStagePitch = 272;                     // bytes per staged row: 256 + 16 (bank spread)
 constexpr int kStageUnitBytes = 16 * kStagePitch;    // one unit of one wave
 constexpr int kStageBytes = kStepWaves * 2 * kStageUnitBytes;   // double-buffered, all waves
-constexpr int kPrefetchUnits = 3;                    // units of W in flight per wave (12 KiB)
+constexpr int kPrefetchUnits = kMfmaPrefetchUnits;   // units of W in flight per wave (12 KiB)
 
 __device__ __forceinline__ void stream_load16(u32x4 &dst, unsigned voff, const void *sbase) {
     asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(voff), "s"(sbase) : "memory");
@@ -57,7 +57,7 @@ template <int NT>
 __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const MfmaArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *stage = smem;                       // [waves][2][16][272]
-    unsigned char *hbuf = smem + kStageBytes;          // [16 * NT][hpitch]
+    unsigned char *hbuf = smem + kStageBytes;          // [16 * NT or 8][hpitch]
     float *zt = reinterpret_cast<float *>(smem);       // logit tile, aliases both after the contraction
 
     const int lane = lane_id();
@@ -125,7 +125,10 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     // operand reads : lane (row lrow, k-group lgrp) of k-step ks -> bytes ks*64 + lgrp*16
     const int wr_off = lgrp * kStagePitch + lrow * 16;
     const int rd_off = lrow * kStagePitch + lgrp * 16;
-    const int hrow_off = lrow * a.hpitch + lgrp * 16;
+    // up to 8 hidden rows: LDS holds 8 rows of h and lanes 8..15 of the operand repeat them (their products
+    // are never read)
+    const int hrows = a.n <= 8 ? 8 : 16 * NT;
+    const int hrow_off = (lrow & (hrows - 1)) * a.hpitch + lgrp * 16;
 
     // ---- h chunks: the columns of KC / 128 consecutive steps, of every hidden row (zero rows up to 16 * NT), live in LDS.  The next
     // chunk is fetched into registers while the current one is consumed, so its L2 latency is hidden;
@@ -167,7 +170,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         int r = (int)threadIdx.x / ppr, pc = (int)threadIdx.x % ppr;
 #pragma unroll
         for (int q = 0; q < kMaxPieces; ++q) {
-            if (r < 16 * NT) *reinterpret_cast<u32x4 *>(hbuf + (size_t)r * a.hpitch + pc * 16) = hp[q];
+            if (r < hrows) *reinterpret_cast<u32x4 *>(hbuf + (size_t)r * a.hpitch + pc * 16) = hp[q];
             r += step_r;
             pc += step_p;
             if (pc >= ppr) {
@@ -190,49 +193,73 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     for (int q = 0; q < 8; ++q) idq[q] = a.map[row0 + min(lrow + 16 * q, rows_b - 1)];
 
 
-    // Units are consumed in order; unit u sits in register slot u % kPrefetchUnits.
-    for (int u = 0; u < nunits;) {
+    // Units are consumed in order; unit u sits in register slot u % kPrefetchUnits.  Between a hand-issued
+    // load and its wait the compiler believes the registers already hold their data, so the order of loads
+    // and waits must be the same on every path through the code, not only on those that the values of
+    // u and c allow: the loop is written so that its shape alone guarantees it (a build step follows every
+    // path of the compiled kernel and checks this).
+    int u = 0;
+    auto run_unit = [&](u32x4(&ar)[4], int uc) {
+        // unit u's four loads are the oldest outstanding of the W stream
+        wait_unit<4 * (kPrefetchUnits - 1)>(ar);
+        unsigned char *sb = my_stage + (u & 1) * kStageUnitBytes;
 #pragma unroll
-        for (int x = 0; x < kPrefetchUnits; ++x) {
-            if (u < nunits) {   // uniform
-                const int uc = u % units_per_chunk;
-                const int c = u / units_per_chunk;
-                if (uc == 0 && c + 1 < nchunks) fetch_chunk(c + 1);
-                // unit u's four loads are the oldest outstanding of the W stream
-                wait_unit<4 * (kPrefetchUnits - 1)>(areg[x]);
-                unsigned char *sb = my_stage + (u & 1) * kStageUnitBytes;
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(sb + 4 * j * kStagePitch + wr_off) = ar[j];
+        load_unit(u + kPrefetchUnits, ar);
+        const unsigned char *hb = hbuf + hrow_off + (size_t)uc * (kUnitCols * 2);
+        if (rotate && u > 0) {
+            const int ua = unit_of(u);
+            if (ua == 0 || ua == rb1 || ua == rb2 || ua == rb3) VT_CLOSE_RANGE()
+        }
+        // operands of two k-steps are read before their MFMAs are issued, so that the LDS latency is paid
+        // once per pair and not once per MFMA
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    *reinterpret_cast<u32x4 *>(sb + 4 * j * kStagePitch + wr_off) = areg[x][j];
-                load_unit(u + kPrefetchUnits, areg[x]);
-                const unsigned char *hb = hbuf + hrow_off + (size_t)uc * (kUnitCols * 2);
-                if (rotate && u > 0) {
-                    const int ua = unit_of(u);
-                    if (ua == 0 || ua == rb1 || ua == rb2 || ua == rb3) VT_CLOSE_RANGE()
-                }
+        for (int kp = 0; kp < 4; kp += 2) {
+            u32x4 av[2], bv[2][NT];
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const u32x4 av = *reinterpret_cast<const u32x4 *>(sb + rd_off + ks * 64);
+            for (int ks = 0; ks < 2; ++ks) {
+                av[ks] = *reinterpret_cast<const u32x4 *>(sb + rd_off + (kp + ks) * 64);
 #pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        const u32x4 bv = *reinterpret_cast<const u32x4 *>(hb + (size_t)t * 16 * a.hpitch + ks * 64);
-                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
-                                                                         __builtin_bit_cast(bf16x8, bv), acc[t], 0,
-                                                                         0, 0);
-                    }
-                }
-                ++u;
-                if ((uc == units_per_chunk - 1 || u == nunits) && c + 1 < nchunks) {
-                    // The next chunk's pieces were requested units_per_chunk units ago: only W loads
-                    // issued after them may still be outstanding (one unit per consumed unit).
-                    if (units_per_chunk >= kPrefetchUnits) wait_pieces<4 * kPrefetchUnits>(hp);
-                    else if (units_per_chunk == 2) wait_pieces<8>(hp);
-                    else wait_pieces<4>(hp);
-                    __syncthreads();       // every wave is done with the current chunk
-                    store_chunk(c + 1);
-                    __syncthreads();
-                }
+                for (int t = 0; t < NT; ++t)
+                    bv[ks][t] = *reinterpret_cast<const u32x4 *>(hb + (size_t)t * 16 * a.hpitch + (kp + ks) * 64);
             }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[ks]),
+                                                                     __builtin_bit_cast(bf16x8, bv[ks][t]), acc[t],
+                                                                     0, 0, 0);
+            }
+        }
+        ++u;
+    };
+    // Chunks that have a successor hold a multiple of kPrefetchUnits units (the host plans them so): the
+    // next chunk is requested, whole rounds of units run without any test in between, and by then every
+    // piece of the next chunk has 4 * kPrefetchUnits younger loads behind it.
+    for (int c = 0; c + 1 < nchunks; ++c) {
+        fetch_chunk(c + 1);
+        int uc = 0;
+        do {
+#pragma unroll
+            for (int x = 0; x < kPrefetchUnits; ++x) run_unit(areg[x], uc++);
+        } while (uc < units_per_chunk);
+        wait_pieces<4 * kPrefetchUnits>(hp);
+        __syncthreads();       // every wave is done with the current chunk
+        store_chunk(c + 1);
+        __syncthreads();
+    }
+    // the last chunk: any number of units -- whole rounds, then the one or two that remain
+    {
+        int uc = 0;
+        for (int rounds = (nunits - u) / kPrefetchUnits; rounds > 0; --rounds) {
+#pragma unroll
+            for (int x = 0; x < kPrefetchUnits; ++x) run_unit(areg[x], uc++);
+        }
+        static_assert(kPrefetchUnits == 3, "the remainder below is written for rounds of three");
+        if (u < nunits) {
+            run_unit(areg[0], uc++);
+            if (u < nunits) run_unit(areg[1], uc++);
         }
     }
     // prefetches past the last unit are still in flight: let them land before their registers die
@@ -504,11 +531,18 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
         iteration(u + 4, std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
         iteration(u + 5, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
     }
-    if (u + 0 < nunits) iteration(u + 0, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
-    if (u + 1 < nunits) iteration(u + 1, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{});
-    if (u + 2 < nunits) iteration(u + 2, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-    if (u + 3 < nunits) iteration(u + 3, std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
-    if (u + 4 < nunits) iteration(u + 4, std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
+    do {      // the remaining 0..5 units: one exit, so that no path skips an iteration and runs a later one
+        if (u + 0 >= nunits) break;
+        iteration(u + 0, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+        if (u + 1 >= nunits) break;
+        iteration(u + 1, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{});
+        if (u + 2 >= nunits) break;
+        iteration(u + 2, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        if (u + 3 >= nunits) break;
+        iteration(u + 3, std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+        if (u + 4 >= nunits) break;
+        iteration(u + 4, std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
+    } while (false);
     if constexpr (NTW != 1) load_ids();
     // loads past the end are still in flight: let them land before their registers die
 #pragma unroll
@@ -643,6 +677,10 @@ size_t mfma_stage_bytes() { return kStageBytes; }
 size_t mfma_wide_lds_bytes() { return 2 * (size_t)kMfmaTileRows * kStagePitch; }
 
 hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t st) {
+    // the kernels for up to 64 hidden rows run a chunk that has a successor in whole rounds of units
+    if (NT <= 4 && (a.KC <= 0 || a.KC % kUnitCols != 0 ||
+                    (a.KC < a.d && (a.KC / kUnitCols) % kPrefetchUnits != 0)))
+        return hipErrorInvalidValue;
     switch (NT) {
         case 1: return launch_mfma_inst<1>(a, lds, st);
         case 2: return launch_mfma_inst<2>(a, lds, st);

@@ -64,6 +64,8 @@ constexpr int kRowSelectMinL = 11;      // matrix-core path: with more tokens pe
 constexpr int kGemvRowSelectBase = 12;
 constexpr int kRowSelectMinWork = 1280; // with n * min(m, 128) from this value on, the kernel stores its logits and a
                                         // workgroup per hidden row finishes the step
+constexpr int kMfmaPrefetchUnits = 3;  // 128-column units of W_trim in flight per wave; an h chunk that has a successor
+                                       // is a multiple of this many units
 constexpr int kMfmaChunkPieces = 9;    // an h chunk is prefetched through registers: at most this many
                                        // 16-byte pieces per thread, i.e. 16 * NT * KC * 2 <= 9 * 512 * 16 bytes
 

@@ -189,6 +189,59 @@ def test_build_rejects_kernels_that_use_scratch_memory():
     assert any("vt_head_mfma.hip".startswith(p) for p in build.NO_SCRATCH)
 
 
+_ASM_HEAD = """
+\t.text
+\t.globl\tkern
+\t.type\tkern,@function
+kern:
+"""
+
+
+def _lint(body):
+    from paper_2506_22694_amd import inflight_lint
+    bad, loads = inflight_lint.check_asm(_ASM_HEAD + body + "\ts_endpgm\n")
+    return [(b[3]) for b in bad], loads
+
+
+def test_inflight_lint_flags_touches_between_a_hand_issued_load_and_its_wait():
+    load = "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[4:7], v1, s[2:3] nt\n\t;;#ASMEND\n"
+    load2 = "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[8:11], v1, s[2:3] nt\n\t;;#ASMEND\n"
+    wait = lambda n: f"\t;;#ASMSTART\n\ts_waitcnt vmcnt({n})\n\t;;#ASMEND\n"
+    use = "\tds_write_b128 v20, v[4:7]\n"
+    # clean: wait, then use; an unrelated instruction in between is fine
+    assert _lint(load + "\tv_add_u32_e32 v30, v31, v32\n" + wait(0) + use) == ([], 1)
+    # a copy before the wait reads a register that is still in flight
+    assert _lint(load + "\tv_mov_b32_e32 v40, v5\n" + wait(0) + use)[0] == ["v_mov_b32_e32 v40, v5"]
+    # vmcnt(1) with one younger load behind covers the first load, not the second
+    assert _lint(load + load2 + wait(1) + use)[0] == []
+    assert _lint(load + load2 + wait(1) + "\tds_write_b128 v20, v[8:11]\n")[0] == ["ds_write_b128 v20, v[8:11]"]
+    # vmcnt(1) with nothing behind does not cover the load
+    assert _lint(load + wait(1) + use)[0] == ["ds_write_b128 v20, v[4:7]"]
+    # loads the compiler issued itself (outside the markers) are not followed but count as younger loads
+    assert _lint("\tglobal_load_dword v9, v[2:3], off\n\tv_mov_b32_e32 v1, v9\n") == ([], 0)
+    assert _lint(load + "\tglobal_load_dword v50, v[2:3], off\n" + wait(1) + use)[0] == []
+
+
+def test_inflight_lint_follows_every_path():
+    load = "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[4:7], v1, s[2:3] nt\n\t;;#ASMEND\n"
+    wait0 = "\t;;#ASMSTART\n\ts_waitcnt vmcnt(0)\n\t;;#ASMEND\n"
+    # a branch around the wait: the path that skips it reaches the use with the load in flight
+    body = load + "\ts_cbranch_scc1 .LBB0_2\n" + wait0 + ".LBB0_2:\n\tds_write_b128 v20, v[4:7]\n"
+    assert _lint(body)[0] == ["ds_write_b128 v20, v[4:7]"]
+    # a copy at the join of a branch that sits between the load and its wait
+    body = (load + "\ts_cbranch_scc1 .LBB0_2\n\tv_mov_b32_e32 v30, 0\n.LBB0_2:\n\tv_mov_b32_e32 v40, v4\n" + wait0 +
+            "\tds_write_b128 v20, v[40:43]\n")
+    assert _lint(body)[0] == ["v_mov_b32_e32 v40, v4"]
+    # a loop: the refill of the slot at the end of the body is waited for at the top of the next iteration
+    loop = (".LBB0_1:\n" + wait0 + "\tds_write_b128 v20, v[4:7]\n" + load + "\ts_add_i32 s4, s4, 1\n\ts_cmp_lt_i32 s4, s5\n"
+            "\ts_cbranch_scc1 .LBB0_1\n" + wait0)
+    assert _lint(load + loop)[0] == []
+    # the same loop with the staging write ahead of the wait
+    loop_bad = (".LBB0_1:\n\tds_write_b128 v20, v[4:7]\n" + wait0 + load + "\ts_cmp_lt_i32 s4, s5\n"
+                "\ts_cbranch_scc1 .LBB0_1\n" + wait0)
+    assert _lint(load + loop_bad)[0] != []
+
+
 def test_multi_head_argument_errors(lib):
     # validation happens on the host before any device call
     i32p = ctypes.c_int32 * 2
