@@ -434,7 +434,7 @@ def main():
     # which kernel serves this shape (the library's policy: from 2 rows on the matrix-core kernel when its 128-row
     # tiles fill the 256 CUs in one round and d <= 4096)
     tiles = (k + 127) // 128
-    on_mfma = n > 8 or (n >= 2 and 216 <= tiles <= 256 and d % 128 == 0 and d <= 4096)
+    on_mfma = n > 8 or (216 <= tiles <= 256 and d % 128 == 0 and d <= (4096 if n >= 2 else 3072))
     step_kernel = "head_mfma_kernel + step_finalize_kernel" if on_mfma else "head_gemv_kernel"
     gbps_cold = step_bytes / us_cold / 1e3
     gbps_kernel = step_bytes / us_kernel / 1e3

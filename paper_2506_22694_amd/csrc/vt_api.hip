@@ -65,7 +65,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
 
     const int tiles128 = (k + vt::kMfmaTileRows - 1) / vt::kMfmaTileRows;
     const bool prefer_mfma = !force_gemv && dtype == VT_BF16 && (d % 128) == 0 && d <= vt::kMfmaSmallMaxD &&
-                             n >= vt::kMfmaSmallMinN &&
+                             (n >= 2 || d <= vt::kMfmaSmallMaxDOneRow) &&
                              tiles128 >= vt::kMfmaSmallMinTiles && tiles128 <= vt::kStepMaxBlocks;
     if (n <= vt::kGemvMaxN && !prefer_mfma) {
         const int NP = n <= 1 ? 1 : (n <= 2 ? 2 : (n <= 4 ? 4 : 8));

@@ -22,7 +22,9 @@ constexpr int kGemvSplitMinN = 4;      // from this many hidden rows a separate 
 // k = 24576: a tie; k = 16384: 29.8 / 27.4, k = 65536: 78.0 / 75.1)
 // (d = 8192, n = 8: 97.8 against 88.0 us: only up to d = 4096, where 2048, 3072 and 4096 all gain)
 constexpr int kMfmaSmallMaxD = 4096;
-constexpr int kMfmaSmallMinN = 2;      // n = 1 is a tie (36.5 us both at d = 3072; +0.4 us at d = 4096): it keeps the single launch
+// a single hidden row gains up to d = 3072 (d = 2048: 27.9 against 28.6 us, d = 3072: 36.0 / 36.4) and loses at
+// d = 4096 (45.6 / 45.1)
+constexpr int kMfmaSmallMaxDOneRow = 3072;
 constexpr int kMfmaSmallMinTiles = 216;
 
 struct StepArgs {
