@@ -46,8 +46,9 @@ def log(*a):
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=300)
-    p.add_argument("--warmup", type=int, default=30)
+    p.add_argument("--steps", type=int, default=2000)
+    p.add_argument("--warmup", type=int, default=3000,
+                   help="untimed steps first; the device needs ~0.1 s of work to reach its full clocks")
     p.add_argument("--n", type=int, default=8, help="hidden rows per draft step")
     p.add_argument("--m", type=int, default=8, help="tokens kept per row")
     p.add_argument("--k", type=int, default=32768)
@@ -112,6 +113,17 @@ def main():
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps      # us per rep
+
+    def wake(fn, min_calls=100, seconds=0.15):
+        # untimed: after the device has idled (inputs are generated on the host) it takes tens of milliseconds
+        # of work to return to its full clocks; the matrix-core shapes show it most (n = 64: 61 -> 57 us)
+        t_w = time.time()
+        r = 0
+        while r < min_calls or time.time() - t_w < seconds:
+            fn(r)
+            r += 1
+            if r % 50 == 0:
+                torch.cuda.synchronize()
 
     # ------------------------------------------------------------------ inputs + calibration rows
     calib = None
@@ -257,8 +269,7 @@ def main():
         lp_all = torch.empty((16, nn, mm), dtype=torch.float32, device=dev)
         ft = lambda r: vt.draft_head_step(hs[r % 16], cps[r % 4], mapk, mm, ws=wsk, out_ids=ids_all[r % 16],
                                           out_logp=lp_all[r % 16])
-        for r in range(300):       # the device idled while the inputs were generated: let the clocks settle
-            ft(r)
+        wake(ft, 300)
         us_tree = time_region(ft, nsteps)
         # reproducibility: the 16 distinct results, folded into one number
         wgt = torch.arange(1, 16 * nn * mm + 1, device=dev, dtype=torch.int64)
@@ -361,6 +372,7 @@ def main():
     if args.sweep:
         sweep = []
         for kk in (8192, 16384, 32768, 65536, 128256):
+            torch.cuda.empty_cache()
             Wk_np, mapk_np = synth.trimmed_head_direct(kk, d, wl.seed, "bf16")
             Wk = to_dev_bf16(Wk_np)
             mapk = torch.from_numpy(mapk_np).to(dev)
@@ -371,8 +383,7 @@ def main():
                     hh = to_dev_bf16(synth.hidden_rows(nn, d, wl.seed + nn, "bf16"))
                     wsk = vt.StepWorkspace(nn, kk, d, mm, dev)
                     f = lambda r: vt.draft_head_step(hh, cps[r % ncop], mapk, mm, ws=wsk)
-                    for r in range(10):
-                        f(r)
+                    wake(f, 10, 0.15 if (nn, mm) == (1, 1) else 0.0)      # the inputs of this k were just generated
                     us = time_region(f, 100)
                     row = {"k": kk, "n": nn, "m": mm, "us": round(us, 2), "gbps": round(kk * d * 2 / us / 1e3, 1),
                            "frac": round(kk * d * 2 / us / 1e3 / HBM_PEAK_GBPS, 4)}
@@ -388,6 +399,7 @@ def main():
                  ("llama3b full-vocab control", 3072, 128256, 8, 8),
                  ("llama8b tree", 4096, 32768, 64, 8), ("stress", 8192, 32768, 256, 16)]
         for name, dd, kk, nn, mm in cases:
+            torch.cuda.empty_cache()       # fresh allocations, not pieces of the previous case's blocks
             Wk_np, mapk_np = synth.trimmed_head_direct(kk, dd, 77, "bf16")
             Wk = to_dev_bf16(Wk_np)
             mapk = torch.from_numpy(mapk_np).to(dev)
@@ -396,9 +408,8 @@ def main():
             hs = [to_dev_bf16(synth.hidden_rows(nn, dd, 77 + j, "bf16")) for j in range(4)]
             wsk = vt.StepWorkspace(nn, kk, dd, mm, dev)
             f = lambda r: vt.draft_head_step(hs[r % 4], cps[r % ncop], mapk, mm, ws=wsk)
-            for r in range(100):       # untimed: the device idled while the inputs were generated
-                f(r)
-            us = sorted(time_region(f, 100) for _ in range(3))[1]
+            wake(f)
+            us = sorted(time_region(f, 100) for _ in range(5))[2]
             row = {"workload": name, "d": dd, "k": kk, "n": nn, "m": mm, "us": round(us, 2),
                    "gbps": round(kk * dd * 2 / us / 1e3, 1), "frac_hbm": round(kk * dd * 2 / us / 1e3 / HBM_PEAK_GBPS, 4),
                    "tflops": round(2.0 * nn * kk * dd / us / 1e6, 1)}
