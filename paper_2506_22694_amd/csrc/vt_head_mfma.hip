@@ -40,6 +40,16 @@ __device__ __forceinline__ void stream_load16(u32x4 &dst, unsigned voff, const v
 __device__ __forceinline__ void cached_load16(u32x4 &dst, unsigned voff, const void *sbase) {
     asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(sbase) : "memory");
 }
+__device__ __forceinline__ void request_dword(int &dst, const int *p) {
+    asm volatile("global_load_dword %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_ids(int (&b)[10]) {
+    asm volatile("s_waitcnt vmcnt(%10)"
+                 : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7]),
+                   "+v"(b[8]), "+v"(b[9])
+                 : "n"(N));
+}
 constexpr int kMaxPieces = kMfmaChunkPieces;   // 16-byte pieces of an h chunk per thread
 template <int N>
 __device__ __forceinline__ void wait_pieces(u32x4 (&b)[kMaxPieces]) {
@@ -179,18 +189,25 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
             }
         }
     };
-    fetch_chunk(0);                       // first: everything waits for it
+    // Target ids of the tile rows this lane ranks in the epilogue (two layouts, see below).  They are requested
+    // by hand like everything else here and first of all: a load the compiler knows of would get a wait from
+    // it wherever it sees fit, and since loads return in order any such wait also waits for the W prefetch.
+    int ids[10];
+    request_dword(ids[0], a.map + row0 + min(lane, rows_b - 1));
+    request_dword(ids[1], a.map + row0 + min(lane + kWave, rows_b - 1));
+#pragma unroll
+    for (int q = 0; q < 8; ++q) request_dword(ids[2 + q], a.map + row0 + min(lrow + 16 * q, rows_b - 1));
+    fetch_chunk(0);                       // everything waits for it
 #pragma unroll
     for (int x = 0; x < kPrefetchUnits; ++x) load_unit(x, areg[x]);
     wait_pieces<4 * kPrefetchUnits>(hp);  // the W prefetch stays in flight
+    wait_ids<4 * kPrefetchUnits>(ids);    // older than the chunk: they have landed too
     store_chunk(0);
     __syncthreads();
-    // target ids of the tile rows this lane ranks in the epilogue (two layouts, see below)
-    const int id0 = a.map[row0 + min(lane, rows_b - 1)];
-    const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
+    const int id0 = ids[0], id1 = ids[1];
     int idq[8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) idq[q] = a.map[row0 + min(lrow + 16 * q, rows_b - 1)];
+    for (int q = 0; q < 8; ++q) idq[q] = ids[2 + q];
 
 
     // Units are consumed in order; unit u sits in register slot u % kPrefetchUnits.  Between a hand-issued
