@@ -33,9 +33,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the step kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE),
 # scaled by the same counters on a plain copy of known size; see profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # (workload, k, n, m): both kernels of the step: FETCH_SIZE (100613.9 + 139.4) x 1.99975 KiB +
+    # (workload, k, n, m): both kernels of the step: FETCH_SIZE (100525.4 + 139.4) x 1.99975 KiB +
     # WRITE_SIZE (304.9 + 0.8) KiB per step (profiles/head_mfma_kernel_1_llama3b_k32768_n8_m8.txt)
-    ("llama3b", 32768, 8, 8): 206_630_000,
+    ("llama3b", 32768, 8, 8): 206_449_000,
 }
 
 
