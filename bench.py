@@ -444,8 +444,12 @@ def main():
 
     # which kernel serves this shape (the library's policy: up to 8 rows go to the matrix-core kernel when its
     # 128-row tiles fill the 256 CUs in one round and d <= 4096; a single row only up to d = 3072)
-    tiles = (k + 127) // 128
-    on_mfma = n > 8 or (216 <= tiles <= 256 and d % 128 == 0 and d <= (4096 if n >= 2 else 3072))
+    def tiles_fit(rows, least):
+        return least <= (k + rows - 1) // rows <= 256
+    units = d // 128
+    on_mfma = n > 8 or (d % 128 == 0 and d <= (4096 if n >= 2 else 3072) and
+                        (tiles_fit(128, 160) or (m <= 11 and ((units % 2 == 0 and tiles_fit(64, 160)) or
+                                                              (units % 4 == 0 and tiles_fit(32, 96))))))
     step_kernel = "head_mfma_kernel + step_finalize_kernel" if on_mfma else "head_gemv_kernel"
     gbps_cold = step_bytes / us_cold / 1e3
     gbps_kernel = step_bytes / us_kernel / 1e3

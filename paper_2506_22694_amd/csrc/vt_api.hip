@@ -30,7 +30,7 @@ struct StepPlan {
     bool gemv = false;     // small-n VALU path
     bool mfma = false;     // matrix-core path
     int NP = 0, CS = 0, S = 0;
-    int NT = 0, nlists = 0, KC = 0, hpitch = 0, fin_stage_keys = 0;
+    int NT = 0, nlists = 0, KC = 0, hpitch = 0, fin_stage_keys = 0, ksplit = 1;
     size_t fin_lds = 0;
     int rpb = 0, nblocks = 0, tpitch = 0, L = 0, fin_conc = 0;
     size_t lds = 0;
@@ -63,10 +63,21 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.fin_conc = conc < vt::kStepWaves ? conc : vt::kStepWaves;
     }
 
-    const int tiles128 = (k + vt::kMfmaTileRows - 1) / vt::kMfmaTileRows;
-    const bool prefer_mfma = !force_gemv && dtype == VT_BF16 && (d % 128) == 0 && d <= vt::kMfmaSmallMaxD &&
-                             (n >= 2 || d <= vt::kMfmaSmallMaxDOneRow) &&
-                             tiles128 >= vt::kMfmaSmallMinTiles && tiles128 <= vt::kStepMaxBlocks;
+    // Up to 8 rows on the matrix-core kernel: its tiles (128 rows, or 64 / 32 with the columns of a row group
+    // split over 2 / 4 waves) must fill most of the 256 CUs in exactly one round.  The split needs the kernel's
+    // own epilogue (few tokens per row) and whole 128-column units per wave.
+    int ksplit = 0;
+    if (!force_gemv && dtype == VT_BF16 && (d % 128) == 0 && d <= vt::kMfmaSmallMaxD &&
+        (n >= 2 || d <= vt::kMfmaSmallMaxDOneRow) && n <= vt::kGemvMaxN) {
+        for (int KS = 1; KS <= 4 && ksplit == 0; KS *= 2) {
+            const int tr = vt::kMfmaTileRows / KS;
+            const int tiles = (k + tr - 1) / tr;
+            if (tiles < (KS == 4 ? vt::kMfmaSmallMinTiles32 : vt::kMfmaSmallMinTiles) || tiles > vt::kStepMaxBlocks) continue;
+            if (KS > 1 && ((d / 128) % KS != 0 || m > vt::kRowSelectMinL)) continue;
+            ksplit = KS;
+        }
+    }
+    const bool prefer_mfma = ksplit != 0;
     if (n <= vt::kGemvMaxN && !prefer_mfma) {
         const int NP = n <= 1 ? 1 : (n <= 2 ? 2 : (n <= 4 ? 4 : 8));
         const int epc = dtype == VT_BF16 ? 8 : 4;
@@ -125,13 +136,19 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.NT = NT;
         p.KC = KC;
         p.hpitch = KC * 2 + 16;
-        p.nlists = (k + vt::kMfmaTileRows - 1) / vt::kMfmaTileRows;
-        p.L = m < vt::kMfmaTileRows ? m : vt::kMfmaTileRows;
+        p.ksplit = (prefer_mfma && KC == d) ? ksplit : 1;
+        const int tile_rows = vt::kMfmaTileRows / p.ksplit;
+        p.nlists = (k + tile_rows - 1) / tile_rows;
+        p.L = m < tile_rows ? m : tile_rows;
         p.nblocks = p.nlists;
         p.lds = NT >= 8 ? stage : stage + (n <= 8 ? 8 : 16 * (size_t)NT) * p.hpitch;
         // logit tile of the epilogue + 4 x 16 candidate keys per wave behind it
-        const size_t tile = (((size_t)n * (vt::kMfmaTileRows + 1) * sizeof(float) + 15) & ~(size_t)15) +
-                            (size_t)vt::kStepWaves * 4 * 16 * sizeof(unsigned long long);
+        size_t tile = (((size_t)p.ksplit * n * (vt::kMfmaTileRows + 1) * sizeof(float) + 15) & ~(size_t)15) +
+                      (size_t)vt::kStepWaves * 4 * 16 * sizeof(unsigned long long);
+        if (n <= vt::kStepWaves) {      // a wave per row: 128 candidate keys per wave, not below 8 KiB
+            const size_t zt = ((size_t)p.ksplit * n * (vt::kMfmaTileRows + 1) * sizeof(float) + 15) & ~(size_t)15;
+            tile = (zt > 8192 ? zt : 8192) + (size_t)vt::kStepWaves * 2 * 64 * sizeof(unsigned long long);
+        }
         if (tile > p.lds) p.lds = tile;
         if (p.lds > (size_t)vt::kMaxDynamicLds) return p;
         const int group = p.nlists < vt::kStepMaxBlocks ? p.nlists : vt::kStepMaxBlocks;
@@ -723,6 +740,7 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         if (p.row_select) a.zbuf = out_logp_full != nullptr ? out_logp_full : reinterpret_cast<float *>(wsb + p.off_zbuf);
         a.row_pack = tf.row_pack;
         a.indexed = tf.indexed;
+        a.ksplit = p.ksplit;
         hipError_t e = vt::launch_head_mfma(p.NT, a, p.lds, st);
         if (e != hipSuccess) return device_status(e);
         if (p.row_select) {

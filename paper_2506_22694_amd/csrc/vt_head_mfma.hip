@@ -72,8 +72,14 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
 
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int row0 = blockIdx.x * kMfmaTileRows;
-    const int rows_b = min(kMfmaTileRows, a.k - row0);
+    // Small heads (up to 8 hidden rows only): with fewer than ~160 tiles of 128 rows the tiles shrink to
+    // 128 / KS rows and KS waves share a group of 16 rows, each taking 1 / KS of the columns; their partial
+    // logits meet in the LDS tile of the epilogue, summed in wave order.
+    const int KS = NT == 1 ? a.ksplit : 1;
+    const int tile_rows = kMfmaTileRows / KS;
+    const int rg = w / KS, ksi = w % KS;               // row group of the wave, its share of the columns
+    const int row0 = blockIdx.x * tile_rows;
+    const int rows_b = min(tile_rows, a.k - row0);
     const size_t rs = (size_t)a.d * 2;
     const int lrow = lane & 15, lgrp = lane >> 4;
 
@@ -82,11 +88,12 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     unsigned voff[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int r = min(16 * w + 4 * j + lgrp, rows_b - 1);
+        const int r = min(16 * rg + 4 * j + lgrp, rows_b - 1);
         voff[j] = (unsigned)((size_t)r * rs + (size_t)lrow * 16);
     }
     const char *Wt = static_cast<const char *>(a.W) + (size_t)row0 * rs;
     const int nunits = a.d / kUnitCols;
+    const int nun = nunits / KS;                       // units of this wave
     // Every workgroup marches over the columns of its 128 rows; if all of them sat in the same column
     // stripe of W at the same time (rows are d * 2 bytes apart) the requests would crowd a subset of the
     // HBM channels (measured: 5.7 instead of 6.7 TB/s).  So the contraction is cut into four column ranges
@@ -97,17 +104,18 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     // ranges finish in the order rot, rot + 1, .. and the k-th to finish is added to set
     // {0, 0, 1, 1}[k] for an even start, {0, 1, 1, 0}[k] for an odd one, which pairs R0 with R1 and R2 with R3.
     // (Rows a multiple of 4 KiB apart are the ones that crowd; at d = 3072 the plain march is 0.6 us faster.)
-    const bool rotate = nunits >= 8 && a.d % 2048 == 0;
+    const bool rotate = KS == 1 && nunits >= 8 && a.d % 2048 == 0;
     const int rot = rotate ? ((int)blockIdx.x >> 3) & 3 : 0;
     const int rb1 = nunits / 4, rb2 = nunits / 2, rb3 = (3 * nunits) / 4;      // first units of ranges 1..3
-    const int ustart = rot == 0 ? 0 : rot == 1 ? rb1 : rot == 2 ? rb2 : rb3;
-    // unit processed at step s (0 <= s < nunits)
+    const int ustart = KS > 1 ? ksi * nun : rot == 0 ? 0 : rot == 1 ? rb1 : rot == 2 ? rb2 : rb3;
+    const int hstart = KS > 1 ? 0 : ustart;            // first unit of h's layout in LDS (the same for all waves)
+    // unit processed at step s (0 <= s < nun)
     auto unit_of = [&](int s) {
         const int u = ustart + s;
         return u >= nunits ? u - nunits : u;
     };
     auto load_unit = [&](int u, u32x4(&dst)[4]) {
-        const char *p = Wt + (size_t)unit_of(min(u, nunits - 1)) * (kUnitCols * 2);
+        const char *p = Wt + (size_t)unit_of(min(u, nun - 1)) * (kUnitCols * 2);
 #pragma unroll
         for (int j = 0; j < 4; ++j) stream_load16(dst[j], voff[j], p);
     };
@@ -159,7 +167,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         for (int q = 0; q < kMaxPieces; ++q) {
             hp[q] = u32x4{0u, 0u, 0u, 0u};
             // 16 pieces per unit: piece pc belongs to step s0 + pc / 16
-            int ua = ustart + s0 + (pc >> 4);
+            int ua = hstart + s0 + (pc >> 4);
             ua = ua >= nunits ? ua - nunits : ua;
             // few hidden rows may be picked out of a larger batch (their indices are packed in row_pack)
             const int hr = a.indexed ? (int)((a.row_pack >> (8 * (r & 7))) & 0xFFull) : r;
@@ -268,15 +276,15 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     }
     // the last chunk: any number of units -- whole rounds, then the one or two that remain
     {
-        int uc = 0;
-        for (int rounds = (nunits - u) / kPrefetchUnits; rounds > 0; --rounds) {
+        int uc = KS > 1 ? ustart : 0;      // position of the wave's first unit in h's LDS layout
+        for (int rounds = (nun - u) / kPrefetchUnits; rounds > 0; --rounds) {
 #pragma unroll
             for (int x = 0; x < kPrefetchUnits; ++x) run_unit(areg[x], uc++);
         }
         static_assert(kPrefetchUnits == 3, "the remainder below is written for rounds of three");
-        if (u < nunits) {
+        if (u < nun) {
             run_unit(areg[0], uc++);
-            if (u < nunits) run_unit(areg[1], uc++);
+            if (u < nun) run_unit(areg[1], uc++);
         }
     }
     // prefetches past the last unit are still in flight: let them land before their registers die
@@ -297,7 +305,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     for (int t = 0; t < NT; ++t) {
         const int i = 16 * t + lrow;       // hidden row of this lane
         if (i < a.n) {
-            float *dst = zt + (size_t)i * tp + 16 * w + 4 * lgrp;
+            float *dst = zt + ((size_t)ksi * a.n + i) * tp + 16 * rg + 4 * lgrp;      // partial ksi of row i
             dst[0] = acc[t].x;
             dst[1] = acc[t].y;
             dst[2] = acc[t].z;
@@ -330,14 +338,18 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     } else {
         // a wave per hidden row (all of them at once for n <= 8); candidate keys of the threshold selection
         // sit behind the logit tile, 1 KiB per wave
+        const size_t ztile = ((size_t)KS * a.n * tp * sizeof(float) + 15) & ~(size_t)15;
         unsigned long long *cand =
-            a.n <= kStepWaves ? reinterpret_cast<unsigned long long *>(smem + 8192) + (size_t)w * 2 * kWave : nullptr;
+            a.n <= kStepWaves
+                ? reinterpret_cast<unsigned long long *>(smem + (ztile > 8192 ? ztile : 8192)) + (size_t)w * 2 * kWave
+                : nullptr;
         for (int i = w; i < a.n; i += kStepWaves) {
             const float *zrow = zt + (size_t)i * tp;
             float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
             unsigned long long *pms_slot = a.pms + (size_t)i * a.nlists + blockIdx.x;
             unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nlists + blockIdx.x) * a.L;
-            block_epilogue_small(zrow, 1, 0, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane, cand);
+            // the logit is the sum of the KS partial tiles, in wave order
+            block_epilogue_small(zrow, KS, a.n * tp, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane, cand);
         }
     }
 }
@@ -698,6 +710,12 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
     if (NT <= 4 && (a.KC <= 0 || a.KC % kUnitCols != 0 ||
                     (a.KC < a.d && (a.KC / kUnitCols) % kPrefetchUnits != 0)))
         return hipErrorInvalidValue;
+    // the column split needs one chunk, up to 8 hidden rows, whole units per wave and the fused epilogue
+    if (a.ksplit != 1 &&
+        ((a.ksplit != 2 && a.ksplit != 4) || NT != 1 || a.n > 8 || a.KC < a.d || (a.d / kUnitCols) % a.ksplit != 0 ||
+         a.zbuf != nullptr))
+        return hipErrorInvalidValue;
+    if (a.nlists != (a.k + kMfmaTileRows / a.ksplit - 1) / (kMfmaTileRows / a.ksplit)) return hipErrorInvalidValue;
     switch (NT) {
         case 1: return launch_mfma_inst<1>(a, lds, st);
         case 2: return launch_mfma_inst<2>(a, lds, st);

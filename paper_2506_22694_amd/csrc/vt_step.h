@@ -25,7 +25,14 @@ constexpr int kMfmaSmallMaxD = 4096;
 // a single hidden row gains up to d = 3072 (d = 2048: 27.9 against 28.6 us, d = 3072: 36.0 / 36.4) and loses at
 // d = 4096 (45.6 / 45.1)
 constexpr int kMfmaSmallMaxDOneRow = 3072;
-constexpr int kMfmaSmallMinTiles = 216;
+// (re-measured with all of h in LDS, n = 8, small-n / matrix-core kernel: k = 26624: 37.1 / 33.7 us, 24576: 33.6 / 32.1,
+// 22528: 32.3 / 30.7, 20480: 29.8 / 29.6, 16384: 26.5 / 27.9)
+constexpr int kMfmaSmallMinTiles = 160;
+// Smaller heads: tiles of 64 or 32 rows, the columns of a 16-row group split over 2 or 4 waves (n = 8, small-n /
+// matrix-core kernel: k = 16384: 26.1 / 24.7 us, 12288: 22.9 / 21.8, 8192: 19.0 / 18.0; n = 1: k = 8192: 17.2 / 14.8;
+// n = 4: 20.8 / 17.8).  Tiles of 32 rows pay from about 96 of them (k = 5000, 157 tiles: n = 8 18.1 / 16.1,
+// n = 1 14.6 / 12.7; k = 3072: a tie).
+constexpr int kMfmaSmallMinTiles32 = 96;
 
 struct StepArgs {
     const void *h;            // [n, d]
@@ -89,6 +96,9 @@ struct MfmaArgs {
     // larger batch (several heads per call); the merge kernel maps the output rows the same way
     unsigned long long row_pack;
     int indexed;
+    // 1, 2 or 4 (n <= 8, all of h in LDS, no zbuf): tiles of 128 / ksplit rows, ksplit waves share 16 rows and the
+    // columns; nlists counts those tiles
+    int ksplit;
 };
 
 struct FinalizeArgs {

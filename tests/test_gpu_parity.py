@@ -471,6 +471,30 @@ def test_step_few_rows_on_matrix_cores_exact_ties_across_tiles(n, d):
     check_step(oi, ol, ref, map_, m, lse)
 
 
+@pytest.mark.parametrize("k,d,n,m", [(5000, 3072, 8, 8), (16384, 2048, 3, 11), (8192, 4096, 1, 1),
+                                     (12288, 1024, 5, 4), (3100, 512, 8, 2), (16384, 2048, 2, 12)])
+def test_step_few_rows_small_heads_split_columns(k, d, n, m):
+    # heads too small for 128-row tiles run on tiles of 64 or 32 rows whose 16-row groups split their columns
+    # over 2 or 4 waves (m = 12 keeps whole columns): ragged last tiles, duplicates of the best row in other
+    # tiles, every logit (out_logp_full) and the log-sum-exp
+    W, map_ = synth.trimmed_head_direct(k, d, seed=7400 + n, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=7400 + n, dtype="bf16")
+    z = oracle.logits(h, W)
+    i = n - 1
+    j = int(np.argmax(z[i]))
+    for off in (33, 1000, k // 2 + 5):
+        W[(j + off) % k] = W[j]
+    ref = oracle.draft_head_step(h, W, map_, m)
+    oi, ol, lse, full = run_step(h, W, map_, m, return_lse=True, return_full=True)
+    ids, lp = oi.cpu().numpy(), ol.cpu().numpy()
+    t = min(m, 4)
+    assert np.array_equal(ids[i, :t], ref["ids"][i, :t])
+    assert np.all(lp[i, :t] == lp[i, 0])
+    check_step(oi, ol, ref, map_, m, lse)
+    _, logp_ref = oracle.log_softmax(ref["z"])
+    assert np.max(np.abs(full.cpu().numpy().astype(np.float64) - logp_ref)) <= LOGP_TOL
+
+
 def test_step_non_ascending_map_ties_follow_target_id():
     k, d = 512, 512
     W, map_ = synth.trimmed_head_direct(k, d, seed=11, dtype="bf16")
