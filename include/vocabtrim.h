@@ -274,9 +274,11 @@ int vt_tree_rerank(const float *cum, int32_t N, int32_t T, int32_t *out_idx, voi
 /* ------------------------------------------------------------------------
  * vt_draft_tree_level -- one level of tree drafting in one call: the draft
  * step for the n frontier nodes followed by vt_tree_expand on its result,
- * with the same outputs as the two calls (bit for bit).  For n <= 8 it is ONE
- * launch: the workgroup that merges the step's partial results also ranks
- * the n * m candidates; larger n run the step and then the expansion kernel.
+ * with the same outputs as the two calls (bit for bit).  Where one kernel of
+ * the step sees every row's result (always for n <= 8; up to 64 rows and
+ * n * m <= 512 on the bf16 matrix-core path) no launch is added: the
+ * workgroup that finishes the step last also ranks the n * m candidates;
+ * other shapes run the step and then the expansion kernel.
  *   arguments as in vt_draft_head_step (no out_lse / out_logp_full) and
  *   vt_tree_expand; out_ids / out_logp [n, m] still receive the step's result.
  *   ws: >= vt_draft_head_step_ws_bytes(n, k, d, m), initialised as for the step.

@@ -581,8 +581,12 @@ int vt_draft_tree_level(const void *h, int h_type, int32_t n, const void *W_trim
     hipStream_t st = static_cast<hipStream_t>(stream);
     // one launch when the small-n kernel covers the whole step: its last workgroup also ranks the candidates
     // (the same kernel as vt_draft_head_step would use for this shape, so both calls return the same bits)
+    // ... or, on the matrix-core path, when its merge kernel (one workgroup per hidden row) covers all rows: the
+    // workgroup that finishes last ranks the candidates
     const StepPlan small = plan_step(n, k, d, m, w_type);
-    if (small.ok && small.gemv && n * m <= vt::kStepWaves * 64) {
+    const bool fuse_gemv = small.ok && small.gemv && n * m <= vt::kStepWaves * 64;
+    const bool fuse_mfma = small.ok && small.mfma && !small.row_select && chunk >= n && n * m <= vt::kFinalizeTreeMaxN;
+    if (fuse_gemv || fuse_mfma) {
         TreeFuse tf;
         tf.cum = parent_cum;
         tf.K = K;
@@ -679,7 +683,7 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         }
         if (e != hipSuccess) return device_status(e);
         if (split) {
-            vt::FinalizeArgs f;
+            vt::FinalizeArgs f{};
             f.pms = pms;
             f.pkeys = pkeys;
             f.nlists = p.nblocks;
@@ -717,8 +721,10 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             return VT_OK;
         }
     } else {
-        // the fused tree level exists in the small-n kernel only; row picking needs the fused merge (n <= 8)
-        if (tf.cum != nullptr || (tf.indexed && (n > vt::kGemvMaxN || p.row_select || out_logp_full != nullptr)))
+        // a fused tree level needs the merge kernel (no per-row tail) and at most kFinalizeTreeMaxN candidates; row
+        // picking needs up to 8 rows and the merge kernel too
+        if ((tf.cum != nullptr && (p.row_select || tf.indexed || n * m > vt::kFinalizeTreeMaxN)) ||
+            (tf.indexed && (n > vt::kGemvMaxN || p.row_select || out_logp_full != nullptr)))
             return VT_ERR_SHAPE;
         vt::MfmaArgs a;
         a.h = h;
@@ -748,7 +754,7 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             if (out_logp_full != nullptr) vt::launch_sub_lse(out_logp_full, lse_buf, n, k, st);
             return VT_OK;
         }
-        vt::FinalizeArgs f;
+        vt::FinalizeArgs f{};
         f.row_pack = tf.row_pack;
         f.indexed = tf.indexed;
         f.pms = pms;
@@ -763,6 +769,13 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         f.out_logp = out_logp;
         f.out_lse = out_lse;
         f.lse_buf = lse_buf;
+        f.tree_cum = tf.cum;
+        f.tree_K = tf.K;
+        f.tree_parent = tf.parent;
+        f.tree_token = tf.token;
+        f.tree_score = tf.score;
+        f.ticket = reinterpret_cast<unsigned *>(wsb);
+        if (tf.cum != nullptr && (n * m > vt::kFinalizeTreeMaxN || tf.indexed)) return VT_ERR_SHAPE;
         e = vt::launch_step_finalize(f, p.fin_lds, st);
         if (e != hipSuccess) return device_status(e);
     }

@@ -18,6 +18,7 @@
 #include "vt_device.h"
 #include "vt_step.h"
 #include "vt_step_tail.cuh"
+#include "vt_tree_dev.cuh"
 #include <type_traits>
 
 namespace vt {
@@ -641,6 +642,52 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
     }
 }
 
+// The merge of one hidden row per workgroup with a tree level behind it: wave 0 merges the row (its results are
+// written through to memory) and takes a ticket; the workgroup that draws the last ticket ranks all n * m
+// candidates, reading the other rows' results with loads that bypass its caches.
+// T threads: 64 when n * m <= 64, else 512 (the waves beyond the first only help with the ranking; with more
+// threads the merging wave would not have the registers it needs).
+template <int T>
+__global__ void __launch_bounds__(T) step_finalize_tree_kernel(const FinalizeArgs f) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int s_last;
+    const int lane = lane_id();
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int i = blockIdx.x;
+    if (w == 0) {
+        unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem);
+        finalize_row<true>(f.pms + (size_t)i * f.nlists, f.pkeys + (size_t)i * f.nlists * f.L, f.nlists, f.L, f.m, stage,
+                           f.out_ids + (size_t)i * f.m, f.out_logp + (size_t)i * f.m, f.out_lse ? f.out_lse + i : nullptr,
+                           f.lse_buf + i, lane);
+        wait_stores_done();       // the row's results are written through: visible to whoever draws the last ticket
+        if (lane == 0) {
+            const unsigned v = __hip_atomic_fetch_add(f.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int last = v == (unsigned)(f.n - 1);
+            if (last) __hip_atomic_store(f.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = last;
+        }
+    }
+    __syncthreads();
+    if (!s_last) return;
+    TreeArgs t;
+    t.parent_cum = f.tree_cum;
+    t.vals = f.out_logp;
+    t.ids = f.out_ids;
+    t.N = f.n * f.m;
+    t.m = f.m;
+    t.K = f.tree_K;
+    t.index_order = 0;
+    t.out_a = f.tree_parent;
+    t.out_token = f.tree_token;
+    t.out_score = f.tree_score;
+    int N2 = kWave;
+    while (N2 < t.N) N2 <<= 1;
+    unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);
+    unsigned *cnt = reinterpret_cast<unsigned *>(smem + (size_t)N2 * 8);
+    int *wave_tot = reinterpret_cast<int *>(smem + (size_t)N2 * 12);
+    tree_select_by_count<T, true>(t, N2, keys, cnt, wave_tot);
+}
+
 // Merges the per-tile partials: one wave per hidden row.
 __global__ void __launch_bounds__(kStepWaves *kWave) step_finalize_kernel(const FinalizeArgs f) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -742,6 +789,30 @@ hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t s
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
         if (e != hipSuccess) return e;
         attr_set[dev] = true;
+    }
+    if (f.tree_cum != nullptr) {
+        // one hidden row per workgroup; LDS: the merge's staging, then the ranking's keys and counters
+        const int N = f.n * f.m;
+        if (f.conc != 1 || f.indexed || N > kFinalizeTreeMaxN || f.ticket == nullptr) return hipErrorInvalidValue;
+        int N2 = kWave;
+        while (N2 < N) N2 <<= 1;
+        const size_t need = (size_t)N2 * 12 + 256;
+        const size_t bytes = lds > need ? lds : need;
+        static bool tree_attr_set[64] = {};
+        if (!tree_attr_set[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_finalize_tree_kernel<64>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_finalize_tree_kernel<512>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
+            if (e != hipSuccess) return e;
+            tree_attr_set[dev] = true;
+        }
+        if (N <= kWave)
+            hipLaunchKernelGGL(step_finalize_tree_kernel<64>, dim3(f.n), dim3(64), bytes, st, f);
+        else
+            hipLaunchKernelGGL(step_finalize_tree_kernel<512>, dim3(f.n), dim3(512), bytes, st, f);
+        return hipGetLastError();
     }
     const int grid = (f.n + f.conc - 1) / f.conc;
     hipLaunchKernelGGL(step_finalize_kernel, dim3(grid), dim3(f.conc * kWave), lds, st, f);

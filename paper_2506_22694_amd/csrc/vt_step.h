@@ -113,7 +113,17 @@ struct FinalizeArgs {
     float *lse_buf;
     unsigned long long row_pack;   // indexed != 0 (n <= 8): hidden row i writes output row (row_pack >> 8 i) & 255
     int indexed;
+    // Tree level fused behind the merge (tree_cum != null; rows in order, n * m <= kFinalizeTreeMaxN): every
+    // workgroup takes a ticket after its row; the last one ranks the n * m candidates tree_cum[i] + logp[i][j]
+    // and keeps the tree_K best.
+    const float *tree_cum;
+    int tree_K;
+    int *tree_parent;
+    int *tree_token;
+    float *tree_score;
+    unsigned *ticket;          // one zero-initialised word; returns to zero
 };
+constexpr int kFinalizeTreeMaxN = 512;
 
 size_t mfma_stage_bytes();
 size_t mfma_wide_lds_bytes();   // NT >= 8: two shared unit buffers

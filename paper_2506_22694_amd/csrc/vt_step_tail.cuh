@@ -387,6 +387,16 @@ __device__ __forceinline__ bool arrive_and_elect(unsigned *tickets, int nblocks)
     return s_last != 0;
 }
 
+// A row's results are written through to memory (relaxed agent-scope stores, like the partials): a tree level
+// fused behind the merge reads them from another workgroup, possibly on another XCD, whose L2 would not see a
+// line that is still dirty in this one's.
+__device__ __forceinline__ void store_result(int *__restrict__ ids_row, float *__restrict__ logp_row, int slot, int id,
+                                             float logp) {
+    __hip_atomic_store(ids_row + slot, id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(reinterpret_cast<unsigned *>(logp_row) + slot, __float_as_uint(logp), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ------------------------------------------------------------------ direct merge of at most 2048 keys (one wave)
 // Butterfly over the wave whose first `gsteps` steps take the maximum (inside groups of 2^gsteps
 // lanes) and whose remaining steps take the minimum over those groups: the smallest group maximum.
@@ -500,8 +510,7 @@ __device__ __forceinline__ bool finalize_row_direct(const unsigned long long *__
         }
         for (; x < ncand; ++x) above += stage[x] > key ? 1 : 0;
         if (above < m) {
-            out_ids_row[above] = key_id(key);
-            out_logp_row[above] = key_logit(key) - lse;
+            store_result(out_ids_row, out_logp_row, (int)above, key_id(key), key_logit(key) - lse);
         }
     }
     __builtin_amdgcn_wave_barrier();
@@ -657,8 +666,7 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
         __builtin_amdgcn_wave_barrier();
     }
     if (lane < m) {
-        out_ids_row[lane] = (int)res_id;
-        out_logp_row[lane] = from_orderable_f32(res_ord) - lse;
+        store_result(out_ids_row, out_logp_row, lane, (int)res_id, from_orderable_f32(res_ord) - lse);
     }
     if (lane == 0) {
         *lse_buf_i = lse;

@@ -51,7 +51,8 @@ __global__ void __launch_bounds__(kTreeThreads) tree_sort_kernel(const TreeArgs 
     for (int c = threadIdx.x; c < N2; c += kTreeThreads) skeys[c] = tree_key<false>(a, c);
     bitonic_sort_desc(skeys, N2);
     if (!a.index_order) {
-        for (int r = threadIdx.x; r < a.K; r += kTreeThreads) tree_emit<false>(a, r, skeys[r]);
+        for (int r = threadIdx.x; r < a.K; r += kTreeThreads)
+            tree_emit(a, r, skeys[r], tree_token<false>(a, key_id(skeys[r])));
         return;
     }
     // the K winners, re-keyed by index alone (~index descending = index ascending), sorted again
@@ -72,7 +73,8 @@ __global__ void __launch_bounds__(kTreeThreads) tree_sort_kernel(const TreeArgs 
     bitonic_sort_desc(byidx, K2);
     for (int r = threadIdx.x; r < a.K; r += kTreeThreads) {
         const unsigned long long s = byidx[r];
-        tree_emit<false>(a, r, (s << 32) | (s >> 32));
+        const unsigned long long key = (s << 32) | (s >> 32);
+        tree_emit(a, r, key, tree_token<false>(a, key_id(key)));
     }
 }
 

@@ -24,20 +24,21 @@ __device__ __forceinline__ unsigned long long tree_key(const TreeArgs &a, int c)
     return make_key(s, c);
 }
 
+// The token of candidate c (c itself without an id table); requested together with the candidate's score so
+// that the two round trips overlap.
 template <bool COHERENT>
-__device__ __forceinline__ void tree_emit(const TreeArgs &a, int slot, unsigned long long key) {
+__device__ __forceinline__ int tree_token(const TreeArgs &a, int c) {
+    if (c >= a.N || a.ids == nullptr || a.out_token == nullptr) return c;
+    if constexpr (COHERENT)
+        return __hip_atomic_load(a.ids + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        return a.ids[c];
+}
+
+__device__ __forceinline__ void tree_emit(const TreeArgs &a, int slot, unsigned long long key, int tok) {
     const int c = key_id(key);
     a.out_a[slot] = a.parent_cum != nullptr ? c / a.m : c;
-    if (a.out_token != nullptr) {
-        int tok = c;
-        if (a.ids != nullptr) {
-            if constexpr (COHERENT)
-                tok = __hip_atomic_load(a.ids + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else
-                tok = a.ids[c];
-        }
-        a.out_token[slot] = tok;
-    }
+    if (a.out_token != nullptr) a.out_token[slot] = tok;
     if (a.out_score != nullptr) a.out_score[slot] = key_logit(key);
 }
 
@@ -47,7 +48,9 @@ template <int T, bool COHERENT>
 __device__ __forceinline__ void tree_select_by_count(const TreeArgs &a, int N2, unsigned long long *keys,
                                                      unsigned *cnt, int *wave_tot) {
     const int tid = threadIdx.x;
+    int tok = 0;           // threads 0 .. N2-1 own candidate tid
     if (tid < N2) {
+        tok = tree_token<COHERENT>(a, tid);
         keys[tid] = tree_key<COHERENT>(a, tid);
         cnt[tid] = 0u;
     }
@@ -73,7 +76,7 @@ __device__ __forceinline__ void tree_select_by_count(const TreeArgs &a, int N2, 
     // threads 0 .. N2-1 (whole waves) own one candidate each
     const bool keep = tid < a.N && (int)above < a.K;
     if (!a.index_order) {
-        if (keep) tree_emit<COHERENT>(a, (int)above, mine);
+        if (keep) tree_emit(a, (int)above, mine, tok);
         return;
     }
     const unsigned long long bal = __ballot(keep);
@@ -84,7 +87,7 @@ __device__ __forceinline__ void tree_select_by_count(const TreeArgs &a, int N2, 
     int base = 0;
     for (int q = 0; q < w; ++q) base += wave_tot[q];
     const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    tree_emit<COHERENT>(a, base + __popcll(bal & below), mine);
+    tree_emit(a, base + __popcll(bal & below), mine, tok);
 }
 
 }  // namespace vt

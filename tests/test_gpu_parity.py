@@ -829,10 +829,15 @@ def test_build_trimmed_heads_equals_head_by_head():
 @pytest.mark.parametrize("k,d,n,m,K,dt", [(32768, 3072, 8, 8, 8, "bf16"), (4096, 512, 1, 1, 1, "bf16"),
                                           (5000, 1024, 8, 64, 60, "bf16"), (1000, 256, 4, 4, 16, "f32"),
                                           (2048, 2048, 3, 5, 7, "bf16"), (4096, 1024, 40, 8, 32, "bf16"),
-                                          (3000, 200, 12, 4, 9, "bf16")])
+                                          (3000, 200, 12, 4, 9, "bf16"), (32768, 4096, 64, 8, 8, "bf16"),
+                                          (5000, 3072, 8, 8, 8, "bf16"), (32768, 2048, 1, 1, 1, "bf16"),
+                                          (4200, 1024, 16, 8, 100, "bf16"), (4200, 1024, 64, 8, 512, "bf16"),
+                                          (4200, 1024, 65, 8, 8, "bf16"), (16384, 2048, 5, 11, 55, "bf16")])
 def test_draft_tree_level_equals_step_then_expand(k, d, n, m, K, dt):
-    # fused in one launch for n <= 8, step + expansion kernel otherwise: same results either way, and
-    # both equal to the oracle's step followed by the oracle's expansion on the GPU's log-probs
+    # fused behind the step where one kernel sees all rows' results (the small-n kernel's last workgroup; the
+    # last workgroup of the matrix-core path's merge kernel for up to 512 candidates), step + expansion kernel
+    # otherwise: same results either way, and both equal to the oracle's step followed by the oracle's
+    # expansion on the GPU's log-probs
     W, map_ = synth.trimmed_head_direct(k, d, seed=k + n, dtype=dt)
     h = synth.hidden_rows(n, d, seed=k + n + 1, dtype=dt)
     cum = np.linspace(-0.25, -5.0, n).astype(np.float32)
