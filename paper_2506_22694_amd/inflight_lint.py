@@ -92,8 +92,12 @@ def _successors(ins, labels, i):
     return [i + 1]
 
 
-def check_function(name, ins, labels):
-    """Violations of one function: (function, line of the load, line of the instruction, its text)."""
+def check_function(name, ins, labels, drains=None):
+    """Violations of one function: (function, line of the load, line of the instruction, its text).
+
+    drains (a set, optional) collects (function, line, text) of waits the COMPILER inserted that are the first
+    to cover a hand-issued load: legal, but such a wait also holds up every older hand-issued load, so inside a
+    prefetch pipeline it is worth a look (a performance remark, not an error)."""
     bad = []
     for i, x in enumerate(ins):
         if not (x.by_hand and x.text.startswith(_LOADS)):
@@ -111,6 +115,8 @@ def check_function(name, ins, labels):
             if op == "s_waitcnt":
                 m = _VMCNT.search(y.text)
                 if m and behind >= int(m.group(1)):
+                    if drains is not None and not y.by_hand:
+                        drains.add((name, y.line, y.text))
                     continue                      # the load has landed on this path
             elif y.regs & dest:
                 bad.append((name, x.line, y.line, y.text))
@@ -121,21 +127,25 @@ def check_function(name, ins, labels):
     return bad
 
 
-def check_asm(asm: str):
+def check_asm(asm: str, drains=None):
     """All violations in an assembly file, and the number of hand-issued loads that were followed."""
     bad, loads = [], 0
     for name, ins, labels in _functions(asm):
         loads += sum(1 for x in ins if x.by_hand and x.text.startswith(_LOADS))
-        bad.extend(check_function(name, ins, labels))
+        bad.extend(check_function(name, ins, labels, drains))
     return bad, loads
 
 
 if __name__ == "__main__":
     status = 0
     for path in sys.argv[1:]:
-        violations, n = check_asm(open(path).read())
-        print(f"{path}: {n} hand-issued loads, {len(violations)} violations")
+        compiler_waits = set()
+        violations, n = check_asm(open(path).read(), compiler_waits)
+        print(f"{path}: {n} hand-issued loads, {len(violations)} violations, "
+              f"{len(compiler_waits)} compiler-inserted waits that cover hand-issued loads")
         for v in violations[:20]:
             print("  ", v)
+        for v in sorted(compiler_waits)[:20]:
+            print("   remark:", v)
         status |= bool(violations)
     sys.exit(status)

@@ -222,6 +222,15 @@ def test_inflight_lint_flags_touches_between_a_hand_issued_load_and_its_wait():
     assert _lint(load + "\tglobal_load_dword v50, v[2:3], off\n" + wait(1) + use)[0] == []
 
 
+def test_inflight_lint_reports_compiler_waits_that_drain_hand_issued_loads():
+    from paper_2506_22694_amd import inflight_lint
+    load = "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[4:7], v1, s[2:3] nt\n\t;;#ASMEND\n"
+    body = load + "\tglobal_load_dword v9, v[2:3], off\n\ts_waitcnt vmcnt(0)\n\tv_mov_b32_e32 v1, v9\n"
+    drains = set()
+    bad, _ = inflight_lint.check_asm(_ASM_HEAD + body + "\ts_endpgm\n", drains)
+    assert bad == [] and [d[2] for d in drains] == ["s_waitcnt vmcnt(0)"]
+
+
 def test_inflight_lint_follows_every_path():
     load = "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[4:7], v1, s[2:3] nt\n\t;;#ASMEND\n"
     wait0 = "\t;;#ASMSTART\n\ts_waitcnt vmcnt(0)\n\t;;#ASMEND\n"
