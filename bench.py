@@ -447,7 +447,7 @@ def main():
     def tiles_fit(rows, least):
         return least <= (k + rows - 1) // rows <= 256
     units = d // 128
-    on_mfma = n > 8 or (d % 128 == 0 and d <= (4096 if n >= 2 else 3072) and
+    on_mfma = n > 8 or (d % 128 == 0 and d <= (7168 if n >= 5 else 4096 if n >= 2 else 3072) and
                         (tiles_fit(128, 160) or (m <= 11 and ((units % 2 == 0 and tiles_fit(64, 160)) or
                                                               (units % 4 == 0 and tiles_fit(32, 96))))))
     step_kernel = "head_mfma_kernel + step_finalize_kernel" if on_mfma else "head_gemv_kernel"

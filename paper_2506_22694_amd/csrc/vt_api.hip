@@ -67,13 +67,15 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
     // split over 2 / 4 waves) must fill most of the 256 CUs in exactly one round.  The split needs the kernel's
     // own epilogue (few tokens per row) and whole 128-column units per wave.
     int ksplit = 0;
-    if (!force_gemv && dtype == VT_BF16 && (d % 128) == 0 && d <= vt::kMfmaSmallMaxD &&
+    if (!force_gemv && dtype == VT_BF16 && (d % 128) == 0 &&
+        (d <= vt::kMfmaSmallMaxD || (n >= vt::kMfmaSmallManyRows && d <= vt::kMfmaSmallMaxDManyRows)) &&
         (n >= 2 || d <= vt::kMfmaSmallMaxDOneRow) && n <= vt::kGemvMaxN) {
         for (int KS = 1; KS <= 4 && ksplit == 0; KS *= 2) {
             const int tr = vt::kMfmaTileRows / KS;
             const int tiles = (k + tr - 1) / tr;
             if (tiles < (KS == 4 ? vt::kMfmaSmallMinTiles32 : vt::kMfmaSmallMinTiles) || tiles > vt::kStepMaxBlocks) continue;
-            if (KS > 1 && ((d / 128) % KS != 0 || m > vt::kRowSelectMinL)) continue;
+            // (the split also needs all of h in LDS at once: d <= 4096)
+            if (KS > 1 && ((d / 128) % KS != 0 || m > vt::kRowSelectMinL || d > vt::kMfmaSmallMaxD)) continue;
             ksplit = KS;
         }
     }

@@ -107,7 +107,11 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     // (Rows a multiple of 4 KiB apart are the ones that crowd; at d = 3072 the plain march is 0.6 us faster.)
     const bool rotate = KS == 1 && nunits >= 8 && a.d % 2048 == 0;
     const int rot = rotate ? ((int)blockIdx.x >> 3) & 3 : 0;
-    const int rb1 = nunits / 4, rb2 = nunits / 2, rb3 = (3 * nunits) / 4;      // first units of ranges 1..3
+    // first units of ranges 1..3.  When a quarter of a row is itself a multiple of 4 KiB (d = 8192) quarter starts
+    // would crowd the same channels again: the boundaries are skewed by 1, 2 and 3 KiB (any fixed partition of the
+    // columns keeps the rounding independent of the start)
+    const int skew = ((nunits / 4) * kUnitCols * 2) % 4096 == 0 ? 4 : 0;
+    const int rb1 = nunits / 4 + skew, rb2 = nunits / 2 + 2 * skew, rb3 = (3 * nunits) / 4 + 3 * skew;
     const int ustart = KS > 1 ? ksi * nun : rot == 0 ? 0 : rot == 1 ? rb1 : rot == 2 ? rb2 : rb3;
     const int hstart = KS > 1 ? 0 : ustart;            // first unit of h's layout in LDS (the same for all waves)
     // unit processed at step s (0 <= s < nun)
@@ -423,7 +427,8 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
     // than the crowding costs (measured).
     const bool rotate = NTW == 1 && nunits >= 8 && a.d % 2048 == 0;
     const int rot = rotate ? ((int)blockIdx.x >> 3) & 3 : 0;
-    const int rb1 = nunits / 4, rb2 = nunits / 2, rb3 = (3 * nunits) / 4;
+    const int skew = ((nunits / 4) * kUnitCols * 2) % 4096 == 0 ? 4 : 0;      // as in head_mfma_kernel
+    const int rb1 = nunits / 4 + skew, rb2 = nunits / 2 + 2 * skew, rb3 = (3 * nunits) / 4 + 3 * skew;
     const int ustart = rot == 0 ? 0 : rot == 1 ? rb1 : rot == 2 ? rb2 : rb3;
     auto unit_of = [&](int s) {       // unit processed at step s < nunits
         const int u = ustart + s;

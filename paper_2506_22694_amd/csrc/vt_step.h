@@ -22,6 +22,10 @@ constexpr int kGemvSplitMinN = 4;      // from this many hidden rows a separate 
 // k = 24576: a tie; k = 16384: 29.8 / 27.4, k = 65536: 78.0 / 75.1)
 // (d = 8192, n = 8: 97.8 against 88.0 us: only up to d = 4096, where 2048, 3072 and 4096 all gain)
 constexpr int kMfmaSmallMaxD = 4096;
+// wider heads gain from five rows on (n = 8: d = 5120: 61.1 / 58.0 us, 7168: 81.3 / 78.0; n = 2..4: a tie), d = 8192
+// does not (87.4 / 92.8)
+constexpr int kMfmaSmallMaxDManyRows = 7168;
+constexpr int kMfmaSmallManyRows = 5;
 // a single hidden row gains up to d = 3072 (d = 2048: 27.9 against 28.6 us, d = 3072: 36.0 / 36.4) and loses at
 // d = 4096 (45.6 / 45.1)
 constexpr int kMfmaSmallMaxDOneRow = 3072;

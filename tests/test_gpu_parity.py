@@ -374,17 +374,18 @@ def test_step_many_rows_many_equal_logits_in_one_tile(n, m):
     check_step(oi, ol, ref, map_, m, lse)
 
 
-@pytest.mark.parametrize("n", [20, 64, 100])
-def test_step_many_rows_exact_ties_across_tiles_with_different_starts(n):
-    # d a multiple of 2048: workgroups start the contraction at different quarters (by tile index / 8);
-    # equal rows of W must still give bit-identical logits in whichever tile they lie
-    k, d, m = 4200, 2048, 6
+@pytest.mark.parametrize("n,d", [(20, 2048), (64, 2048), (100, 2048), (20, 8192), (100, 8192), (8, 6144), (6, 5120)])
+def test_step_many_rows_exact_ties_across_tiles_with_different_starts(n, d):
+    # d a multiple of 2048: workgroups start the contraction at different quarters (by tile index / 8; at
+    # d = 8192 the quarters are skewed); equal rows of W must still give bit-identical logits in whichever tile
+    # they lie.  The last two shapes are few rows on a wide head: several h chunks on the matrix-core kernel.
+    k, m = 4200 if n > 8 else 21000, 6
     W, map_ = synth.trimmed_head_direct(k, d, seed=7100 + n, dtype="bf16")
     h = synth.hidden_rows(n, d, seed=7100 + n, dtype="bf16")
     z = oracle.logits(h, W)
     i = n - 1
     j = int(np.argmax(z[i]))
-    for off in (1100, 2200, 3300):              # 8.6 tiles apart each: all four starts
+    for off in ((1100, 2200, 3300) if n > 8 else (5500, 11000, 16500)):     # tiles of all four starts
         W[(j + off) % k] = W[j]
     ref = oracle.draft_head_step(h, W, map_, m)
     oi, ol, lse = run_step(h, W, map_, m, return_lse=True)
