@@ -187,6 +187,30 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
 size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m);
 
 /* ------------------------------------------------------------------------
+ * vt_draft_head_step_static -- the same draft step for callers that cannot
+ * allocate device memory or hand in a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments,
+ * results (bit for bit) and errors as for vt_draft_head_step, without ws /
+ * ws_bytes: the partial results of the step live in an array of
+ * VT_STATIC_WS_BYTES bytes that the library itself holds on every GPU it runs
+ * on, from the first use of the library on that GPU until the process ends.
+ * The call allocates and frees nothing (its first call on a device asks the
+ * runtime for the array's address; make that call outside stream capture).
+ *   - A shape whose vt_draft_head_step_ws_bytes(n, k, d, m) exceeds
+ *     VT_STATIC_WS_BYTES returns VT_ERR_WORKSPACE and enqueues nothing (for
+ *     example n = 256 rows with 16 tokens per row at k = 32768, whose per-row
+ *     tail stores 32 MiB of logits); the paper's shapes (up to 64 tree nodes x
+ *     top-8 at k = 32768) need at most 1.2 MiB.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in
+ *     time (different streams, different host threads) race; order them on one
+ *     stream or use vt_draft_head_step with workspaces of your own.
+ * ---------------------------------------------------------------------- */
+#define VT_STATIC_WS_BYTES (4u << 20)
+int vt_draft_head_step_static(const void *h, int h_type, int32_t n, const void *W_trim, int w_type,
+                              int32_t k, int32_t d, const int32_t *map, int32_t m, int32_t *out_ids,
+                              float *out_logp, float *out_lse, float *out_logp_full, void *stream);
+
+/* ------------------------------------------------------------------------
  * Several trimmed heads at once (Sec. 4.1, task-specific vocabularies: a small
  * function-calling vocabulary beside the general one; the conclusion's note on
  * swappable per-task heads).  A head is a (map, W_trim, k) triple; all heads

@@ -25,6 +25,7 @@ EXPORTS = (
     "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes", "vt_build_trimmed_head_by_rank",
     "vt_choose_k", "vt_choose_k_ws_bytes",
     "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
+    "vt_draft_head_step_static",
     "vt_tree_expand", "vt_tree_rerank", "vt_draft_tree_level", "vt_stream_read_reference",
     "vt_build_trimmed_heads", "vt_draft_head_step_multi", "vt_draft_head_step_multi_ws_bytes",
 )
@@ -65,6 +66,8 @@ def load_library() -> ctypes.CDLL:
     L.vt_choose_k_ws_bytes.restype = sz
     L.vt_draft_head_step.argtypes = [vp, ci, i32, vp, ci, i32, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     L.vt_draft_head_step.restype = ci
+    L.vt_draft_head_step_static.argtypes = [vp, ci, i32, vp, ci, i32, i32, vp, i32, vp, vp, vp, vp, vp]
+    L.vt_draft_head_step_static.restype = ci
     L.vt_draft_head_step_ws_bytes.argtypes = [i32, i32, i32, i32]
     L.vt_draft_head_step_ws_bytes.restype = sz
     L.vt_draft_head_step_ws_init.argtypes = [vp, sz, vp]
@@ -257,6 +260,33 @@ def draft_head_step(h: torch.Tensor, W_trim: torch.Tensor, map_: torch.Tensor, m
     if return_full:
         res.append(full)
     return tuple(res)
+
+
+VT_STATIC_WS_BYTES = 4 << 20
+
+
+def draft_head_step_static(h: torch.Tensor, W_trim: torch.Tensor, map_: torch.Tensor, m: int,
+                           out_ids: torch.Tensor, out_logp: torch.Tensor, out_lse: torch.Tensor | None = None,
+                           out_logp_full: torch.Tensor | None = None):
+    """The draft step on the library's own per-GPU scratch array: no workspace, nothing allocated here either
+    (the caller supplies every result tensor).  Returns (out_ids, out_logp)."""
+    L = load_library()
+    _require_cuda(h, W_trim, map_, out_ids, out_logp, out_lse, out_logp_full)
+    n, d = h.shape
+    k = W_trim.shape[0]
+    if W_trim.shape[1] != d or map_.numel() != k or map_.dtype != torch.int32:
+        raise ValueError("shape / dtype mismatch between h, W_trim and map")
+    if out_ids.dtype != torch.int32 or out_logp.dtype != torch.float32 or out_ids.numel() != n * m or \
+            out_logp.numel() != n * m:
+        raise ValueError("out_ids / out_logp must be int32 / float32 [n, m]")
+    if out_lse is not None and (out_lse.dtype != torch.float32 or out_lse.numel() != n):
+        raise ValueError("out_lse must be float32 [n]")
+    if out_logp_full is not None and (out_logp_full.dtype != torch.float32 or out_logp_full.numel() != n * k):
+        raise ValueError("out_logp_full must be float32 [n, k]")
+    _check(L.vt_draft_head_step_static(_ptr(h), _dtype_code(h), n, _ptr(W_trim), _dtype_code(W_trim), k, d,
+                                       _ptr(map_), m, _ptr(out_ids), _ptr(out_logp), _ptr(out_lse),
+                                       _ptr(out_logp_full), _stream(h.device)))
+    return out_ids, out_logp
 
 
 # --------------------------------------------------------------------------- several task heads (Sec. 4.1)

@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "vt_build.h"
 #include "vt_step.h"
 #include "vt_tree.h"
@@ -23,6 +25,31 @@ inline int device_status(hipError_t e) {
     return VT_ERR_DEVICE;
 }
 inline int launch_status() { return device_status(hipGetLastError()); }
+
+// ---------------------------------------------------------------- library-owned step workspace
+// Device memory of the draft step for callers that cannot allocate (vt_draft_head_step_static): one array per
+// GPU, alive from the moment the code object is loaded on it until the process ends.  In host code the array's
+// name is only a handle; the device address is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[VT_STATIC_WS_BYTES];
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[64] = {};      // per device ordinal; written under the mutex, never changed afterwards
+
+int static_scratch_of_current_device(void **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return device_status(e);
+    if (dev < 0 || dev >= 64) return device_status(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return device_status(e);
+        if (p == nullptr) return device_status(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return VT_OK;
+}
 
 // ---------------------------------------------------------------- draft-step plan
 struct StepPlan {
@@ -453,6 +480,25 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
                                  static_cast<hipStream_t>(stream));
     if (rc != VT_OK) return rc;
     return launch_status();
+}
+
+int vt_draft_head_step_static(const void *h, int h_type, int32_t n, const void *W_trim, int w_type, int32_t k,
+                              int32_t d, const int32_t *map, int32_t m, int32_t *out_ids, float *out_logp,
+                              float *out_lse, float *out_logp_full, void *stream) {
+    // the size check comes first and touches no device: a shape is either out of range altogether (0) or needs
+    // more than the library's own array holds
+    if (n <= 0 || k <= 0 || d <= 0 || m < 1) return VT_ERR_SHAPE;
+    const size_t need = vt_draft_head_step_ws_bytes(n, k, d, m);
+    if (need == 0) return VT_ERR_SHAPE;
+    if (need > (size_t)VT_STATIC_WS_BYTES) return VT_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const int rc = static_scratch_of_current_device(&ws);
+    if (rc != VT_OK) return rc;
+    // The arrival counters at the head of the array are zero when the code object is loaded and every step
+    // returns them to zero, so nothing has to be cleared here; everything behind them is rewritten by a step
+    // before it is read.
+    return vt_draft_head_step(h, h_type, n, W_trim, w_type, k, d, map, m, out_ids, out_logp, out_lse, out_logp_full,
+                              ws, (size_t)VT_STATIC_WS_BYTES, stream);
 }
 
 // ------------------------------------------------------------------ several heads in one step
