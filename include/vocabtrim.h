@@ -186,6 +186,14 @@ int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim,
                        size_t ws_bytes, void *stream);
 size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m);
 
+/* Which kernels vt_draft_head_step launches for a shape, and how the head is cut
+ * into workgroups (a pure host function, for logs and benchmarks: the choice
+ * is the library's and may change between versions).  Writes a
+ * NUL-terminated line of at most text_bytes bytes to the HOST buffer `text`,
+ * for example "head_mfma_kernel<1,12> workgroups=229 tile_rows=144 waves=9
+ * column_split=1 + step_finalize_kernel".  Errors as for the step's shape checks. */
+int vt_draft_head_step_plan(int32_t n, int32_t k, int32_t d, int32_t m, int w_type, char *text, size_t text_bytes);
+
 /* ------------------------------------------------------------------------
  * vt_draft_head_step_static -- the same draft step for callers that cannot
  * allocate device memory or hand in a workspace: code under HIP graph

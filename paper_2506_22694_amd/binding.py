@@ -25,7 +25,7 @@ EXPORTS = (
     "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes", "vt_build_trimmed_head_by_rank",
     "vt_choose_k", "vt_choose_k_ws_bytes",
     "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
-    "vt_draft_head_step_static",
+    "vt_draft_head_step_static", "vt_draft_head_step_plan",
     "vt_tree_expand", "vt_tree_rerank", "vt_draft_tree_level", "vt_stream_read_reference",
     "vt_build_trimmed_heads", "vt_draft_head_step_multi", "vt_draft_head_step_multi_ws_bytes",
 )
@@ -68,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     L.vt_draft_head_step.restype = ci
     L.vt_draft_head_step_static.argtypes = [vp, ci, i32, vp, ci, i32, i32, vp, i32, vp, vp, vp, vp, vp]
     L.vt_draft_head_step_static.restype = ci
+    L.vt_draft_head_step_plan.argtypes = [i32, i32, i32, i32, ci, ctypes.c_char_p, sz]
+    L.vt_draft_head_step_plan.restype = ci
     L.vt_draft_head_step_ws_bytes.argtypes = [i32, i32, i32, i32]
     L.vt_draft_head_step_ws_bytes.restype = sz
     L.vt_draft_head_step_ws_init.argtypes = [vp, sz, vp]
@@ -260,6 +262,14 @@ def draft_head_step(h: torch.Tensor, W_trim: torch.Tensor, map_: torch.Tensor, m
     if return_full:
         res.append(full)
     return tuple(res)
+
+
+def draft_head_step_plan(n: int, k: int, d: int, m: int, dtype=torch.bfloat16) -> str:
+    """The kernels the library launches for a draft step of this shape (host-only query)."""
+    L = load_library()
+    buf = ctypes.create_string_buffer(256)
+    _check(L.vt_draft_head_step_plan(n, k, d, m, VT_BF16 if dtype == torch.bfloat16 else VT_F32, buf, 256))
+    return buf.value.decode()
 
 
 VT_STATIC_WS_BYTES = 4 << 20

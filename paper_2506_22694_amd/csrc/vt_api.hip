@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <mutex>
 
 #include "vt_build.h"
@@ -57,13 +58,14 @@ struct StepPlan {
     bool gemv = false;     // small-n VALU path
     bool mfma = false;     // matrix-core path
     int NP = 0, CS = 0, S = 0;
-    int NT = 0, nlists = 0, KC = 0, hpitch = 0, fin_stage_keys = 0, ksplit = 1;
+    int NT = 0, nlists = 0, KC = 0, hpitch = 0, fin_stage_keys = 0, ksplit = 1, nwaves = vt::kStepWaves;
     size_t fin_lds = 0;
     int rpb = 0, nblocks = 0, tpitch = 0, L = 0, fin_conc = 0;
     size_t lds = 0;
     // workspace layout (byte offsets)
     size_t off_lse = 0, off_pms = 0, off_pkeys = 0, off_hpack = 0, off_zbuf = 0, bytes = 0;
     bool row_select = false;   // matrix-core path: logits stored, one workgroup per hidden row finishes
+    int extra_rows = 0;        // matrix-core path, up to 8 rows: tile rows past the 128th (shared by the eight waves)
 };
 
 using vt::kTicketBytes;
@@ -90,20 +92,65 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.fin_conc = conc < vt::kStepWaves ? conc : vt::kStepWaves;
     }
 
-    // Up to 8 rows on the matrix-core kernel: its tiles (128 rows, or 64 / 32 with the columns of a row group
-    // split over 2 / 4 waves) must fill most of the 256 CUs in exactly one round.  The split needs the kernel's
-    // own epilogue (few tokens per row) and whole 128-column units per wave.
-    int ksplit = 0;
+    // Up to 8 rows on the matrix-core kernel: its tiles must fill most of the 256 CUs in exactly one round.  A
+    // tile is 16 rows per group of KS waves (KS = 1, 2, 4 waves share a group's columns) and a workgroup has up to
+    // kMfmaMaxWaves waves, so the tile height follows from the head: ceil(k / 256) rows rounded up to whole groups
+    // (k = 32768: 8 waves x 16 rows; the paper's k ~ 33000: 9 waves, 144 rows, 229 - 244 tiles; k = 22786: 6 groups
+    // of 2 waves, 96 rows, 238 tiles).  The split needs the kernel's own epilogue (few tokens per row), whole
+    // 128-column units per wave and all of h in LDS at once.
+    int ksplit = 0, nwaves = vt::kStepWaves, extra_rows = 0;
     if (!force_gemv && dtype == VT_BF16 && (d % 128) == 0 &&
         (d <= vt::kMfmaSmallMaxD || (n >= vt::kMfmaSmallManyRows && d <= vt::kMfmaSmallMaxDManyRows)) &&
         (n >= 2 || d <= vt::kMfmaSmallMaxDOneRow) && n <= vt::kGemvMaxN) {
-        for (int KS = 1; KS <= 4 && ksplit == 0; KS *= 2) {
-            const int tr = vt::kMfmaTileRows / KS;
+        auto feasible = [&](int KS, int NW) {
+            if (NW < KS || NW % KS != 0 || NW > vt::kMfmaMaxWaves) return false;
+            const int tr = 16 * (NW / KS);
             const int tiles = (k + tr - 1) / tr;
-            if (tiles < (KS == 4 ? vt::kMfmaSmallMinTiles32 : vt::kMfmaSmallMinTiles) || tiles > vt::kStepMaxBlocks) continue;
+            if (tiles < (KS == 4 ? vt::kMfmaSmallMinTiles32 : vt::kMfmaSmallMinTiles) || tiles > vt::kStepMaxBlocks) return false;
             // (the split also needs all of h in LDS at once: d <= 4096)
-            if (KS > 1 && ((d / 128) % KS != 0 || m > vt::kRowSelectMinL || d > vt::kMfmaSmallMaxD)) continue;
-            ksplit = KS;
+            if (KS > 1 && ((d / 128) % KS != 0 || m > vt::kRowSelectMinL || d > vt::kMfmaSmallMaxD)) return false;
+            if (NW != vt::kStepWaves) {
+                // another number of waves: all of h in LDS beside their staging buffers, fetched in one go
+                if (vt::mfma_stage_bytes(NW) + 8 * ((size_t)d * 2 + 16) > (size_t)vt::kMaxDynamicLds) return false;
+                if ((size_t)d > (size_t)vt::kMfmaChunkPieces * NW * 64) return false;
+            }
+            return true;
+        };
+        const int R = (k + vt::kStepMaxBlocks - 1) / vt::kStepMaxBlocks;      // rows per tile for 256 tiles
+        const int G = (R + 15) / 16;                                          // ... in 16-row groups
+        if (R > vt::kMfmaTileRows && R <= vt::kMfmaTileRows + 16 && (d % 1024) == 0 && (d % 2048) != 0 &&
+            d <= vt::kMfmaSmallMaxD) {
+            // 129 .. 144 rows per tile -- the paper's own trimmed sizes, k = 32959 .. 35010 -- : eight waves with 16
+            // rows each and the rows past the 128th as one more group whose columns the eight waves share; the
+            // tile is exactly R rows, so all 256 CUs stream equal shares (k = 32975, d = 3072: n = 8 40.1 us against
+            // 41.4 with nine waves on 229 CUs and 41.8 on the small-n kernel, n = 1 37.0 / 37.4 / 38.9).  Rows a
+            // multiple of 2 KiB long lose on it (d = 4096: 54.0 / 51.4 / 51.7 us, d = 2048: 30.1 / 27.5 / 29.1) and
+            // take nine waves.
+            ksplit = 1;
+            nwaves = vt::kStepWaves;
+            extra_rows = R - vt::kMfmaTileRows;
+        }
+        // more or fewer waves than eight where that measured faster than the choices below (n = 8, d = 3072:
+        // k = 40000, ten waves: 46.4 against 47.5 us; 49152, twelve: 53.6 / 55.1; 20000, five groups of two: 29.1 / 29.7;
+        // seven waves and six groups of two measured slower; nine waves: see above)
+        if (ksplit == 0 && G == 9 && feasible(1, G)) {
+            ksplit = 1;
+            nwaves = G;
+        }
+        if (ksplit == 0 && G >= 10 && feasible(1, G)) {
+            ksplit = 1;
+            nwaves = G;
+        }
+        if (ksplit == 0 && G == 5 && feasible(2, 10)) {
+            ksplit = 2;
+            nwaves = 10;
+        }
+        // otherwise eight waves and the tile that fills the chip best
+        for (int KS = 1; KS <= 4 && ksplit == 0; KS *= 2) {
+            if (feasible(KS, vt::kStepWaves)) {
+                ksplit = KS;
+                nwaves = vt::kStepWaves;
+            }
         }
     }
     const bool prefer_mfma = ksplit != 0;
@@ -139,7 +186,8 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         if (dtype != VT_BF16 || (d % 128) != 0 || n > 256) return p;
         int NT = 1;
         while (16 * NT < n) NT *= 2;
-        const size_t stage = NT >= 8 ? vt::mfma_wide_lds_bytes() : vt::mfma_stage_bytes();
+        const bool var_waves = prefer_mfma && nwaves != vt::kStepWaves;
+        const size_t stage = NT >= 8 ? vt::mfma_wide_lds_bytes() : vt::mfma_stage_bytes(var_waves ? nwaves : vt::kStepWaves);
         int KC = 128;   // NT >= 8: h is not staged at all (B-operands come from L2)
         if (NT < 8) {
             // up to 8 hidden rows occupy 8 rows of LDS (the other half of the 16-row operand repeats them)
@@ -147,7 +195,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
             const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage) / hrows;
             if (hmax < 272) return p;
             KC = (int)(((hmax - 16) / 2) / 128) * 128;
-            const int kc_regs = (int)((vt::kMfmaChunkPieces * vt::kStepWaves * 64 * 16) / (hrows * 2) / 128 * 128);
+            const int kc_regs = (int)((vt::kMfmaChunkPieces * (var_waves ? nwaves : vt::kStepWaves) * 64 * 16) / (hrows * 2) / 128 * 128);
             if (KC > kc_regs) KC = kc_regs;   // the chunk must fit the register prefetch
             if (KC >= d) {
                 KC = d;
@@ -166,7 +214,9 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.KC = KC;
         p.hpitch = KC * 2 + 16;
         p.ksplit = (prefer_mfma && KC == d) ? ksplit : 1;
-        const int tile_rows = vt::kMfmaTileRows / p.ksplit;
+        p.nwaves = (prefer_mfma && KC == d) ? nwaves : vt::kStepWaves;
+        p.extra_rows = (prefer_mfma && KC == d) ? extra_rows : 0;
+        const int tile_rows = 16 * (p.nwaves / p.ksplit) + p.extra_rows;
         p.nlists = (k + tile_rows - 1) / tile_rows;
         p.L = m < tile_rows ? m : tile_rows;
         p.nblocks = p.nlists;
@@ -174,9 +224,12 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         // logit tile of the epilogue + 4 x 16 candidate keys per wave behind it
         size_t tile = (((size_t)p.ksplit * n * (vt::kMfmaTileRows + 1) * sizeof(float) + 15) & ~(size_t)15) +
                       (size_t)vt::kStepWaves * 4 * 16 * sizeof(unsigned long long);
-        if (n <= vt::kStepWaves) {      // a wave per row: 128 candidate keys per wave, not below 8 KiB
-            const size_t zt = ((size_t)p.ksplit * n * (vt::kMfmaTileRows + 1) * sizeof(float) + 15) & ~(size_t)15;
-            tile = (zt > 8192 ? zt : 8192) + (size_t)vt::kStepWaves * 2 * 64 * sizeof(unsigned long long);
+        if (n <= vt::kStepWaves) {      // a wave per row: a candidate key per tile row and wave, not below 8 KiB
+            const int tp = (p.extra_rows != 0 ? vt::kMfmaTileRows + 16 : p.nwaves == vt::kStepWaves ? vt::kMfmaTileRows : tile_rows) + 1;
+            const size_t zt = ((size_t)p.ksplit * n * tp * sizeof(float) + 15) & ~(size_t)15;
+            tile = (zt > 8192 ? zt : 8192) +
+                   (size_t)p.nwaves * ((p.nwaves == vt::kStepWaves && p.extra_rows == 0) ? 2 : 3) * 64 * sizeof(unsigned long long) +
+                   (p.extra_rows != 0 ? (size_t)8 * n * 16 * sizeof(float) : 0);      // + the shared group's partials
         }
         if (tile > p.lds) p.lds = tile;
         if (p.lds > (size_t)vt::kMaxDynamicLds) return p;
@@ -448,6 +501,34 @@ int vt_choose_k(const int64_t *counts, int32_t V, int mode, double p, int64_t mi
 // ------------------------------------------------------------------ Algorithm 2, drafting lines
 size_t vt_draft_head_step_ws_bytes(int32_t n, int32_t k, int32_t d, int32_t m) {
     return step_ws_bytes(n, k, d, m);      // sized for either element type
+}
+
+int vt_draft_head_step_plan(int32_t n, int32_t k, int32_t d, int32_t m, int w_type, char *text, size_t text_bytes) {
+    if (w_type != VT_F32 && w_type != VT_BF16) return VT_ERR_DTYPE;
+    if (n <= 0 || k <= 0 || d <= 0 || m < 1 || m > k || m > VT_MAX_TOP_M || k > vt::kStepMaxK) return VT_ERR_SHAPE;
+    if (text == nullptr || text_bytes == 0) return VT_ERR_NULL;
+    const int chunk = pick_chunk(n, k, d, m, w_type);
+    if (chunk == 0) return VT_ERR_SHAPE;
+    const StepPlan p = plan_step(chunk, k, d, m, w_type);
+    if (!p.ok) return VT_ERR_SHAPE;
+    char head[160];
+    if (p.gemv) {
+        std::snprintf(head, sizeof head, "head_gemv_kernel<%s,%d,%d> workgroups=%d rows_per_workgroup=%d column_segments=%d",
+                      w_type == VT_BF16 ? "bf16" : "f32", p.NP, p.CS, p.nblocks, p.rpb, p.S);
+    } else if (p.NT >= 8) {
+        std::snprintf(head, sizeof head, "pack_h_kernel + head_mfma_wide_kernel<%d> workgroups=%d tile_rows=%d", p.NT / 8,
+                      p.nlists, vt::kMfmaTileRows);
+    } else {
+        std::snprintf(head, sizeof head, "head_mfma_kernel<%d,%d> workgroups=%d tile_rows=%d waves=%d column_split=%d", p.NT,
+                      p.nwaves == vt::kStepWaves ? vt::kStepWaves : vt::kMfmaMaxWaves, p.nlists,
+                      16 * (p.nwaves / p.ksplit) + p.extra_rows, p.nwaves, p.ksplit);
+    }
+    const bool split = p.gemv && !p.row_select && chunk >= vt::kGemvSplitMinN;
+    const char *tail = p.row_select ? " + row_select_kernel" : (p.mfma || split) ? " + step_finalize_kernel" : "";
+    char groups[48] = "";
+    if (chunk < n) std::snprintf(groups, sizeof groups, " x %d row groups", (n + chunk - 1) / chunk);
+    std::snprintf(text, text_bytes, "%s%s%s", head, tail, groups);
+    return VT_OK;
 }
 
 int vt_draft_head_step_ws_init(void *ws, size_t ws_bytes, void *stream) {
@@ -795,6 +876,8 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.row_pack = tf.row_pack;
         a.indexed = tf.indexed;
         a.ksplit = p.ksplit;
+        a.nwaves = p.nwaves;
+        a.extra_rows = p.extra_rows;
         hipError_t e = vt::launch_head_mfma(p.NT, a, p.lds, st);
         if (e != hipSuccess) return device_status(e);
         if (p.row_select) {

@@ -19,6 +19,7 @@
 #include "vt_step.h"
 #include "vt_step_tail.cuh"
 #include "vt_tree_dev.cuh"
+#include <mutex>
 #include <type_traits>
 
 namespace vt {
@@ -31,7 +32,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kUnitCols = 128;                       // columns per staged unit (256 B per row)
 constexpr int kStagePitch = 272;                     // bytes per staged row: 256 + 16 (bank spread)
 constexpr int kStageUnitBytes = 16 * kStagePitch;    // one unit of one wave
-constexpr int kStageBytes = kStepWaves * 2 * kStageUnitBytes;   // double-buffered, all waves
+constexpr int kStageBytes = kStepWaves * 2 * kStageUnitBytes;   // double-buffered, all waves of an 8-wave workgroup
 constexpr int kPrefetchUnits = kMfmaPrefetchUnits;   // units of W in flight per wave (12 KiB)
 
 __device__ __forceinline__ void stream_load16(u32x4 &dst, unsigned voff, const void *sbase) {
@@ -64,20 +65,39 @@ __device__ __forceinline__ void wait_unit(u32x4 (&b)[4]) {
     asm volatile("s_waitcnt vmcnt(%4)" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]) : "n"(N));
 }
 
-template <int NT>
-__global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const MfmaArgs a) {
+// MAXW: most waves a workgroup of this instantiation is launched with.  Eight is the rule: a wave per 16 rows of a
+// 128-row tile.  Up to 8 hidden rows (NT = 1, all of h in LDS) the workgroup may have any number of waves up to
+// MAXW = 12: the tile is then 16 * (waves / KS) rows, so that a head of any size up to 256 * 192 rows is cut into
+// at most 256 tiles -- one round on 256 CUs -- instead of a second, nearly empty round of 128-row tiles.
+// XG (eight waves, up to 8 hidden rows, d a multiple of 1024): the tile has 128 + extra_rows rows.  The rows past
+// the 128th form one more 16-row group; wave w multiplies the w-th eighth of its columns after its own 16 rows, so
+// all waves stream equal shares whatever the tile height is -- a head of k = 32975 rows is 256 tiles of 129 rows,
+// one per CU, instead of 258 tiles of 128.  To keep a row's logit independent of the group it lies in, every logit is
+// then formed from the partial sums P0 .. P7 of the eight column parts, each accumulated from zero in ascending
+// order, as ((P0 + P1) + (P2 + P3)) + ((P4 + P5) + (P6 + P7)) -- in registers for a wave's own rows (two parts make
+// one of the ranges described below), from LDS for the shared group.  All waves march over the columns of their
+// own rows in step, as without the shared group.  (Measured alternatives at k = 32975, n = 8, d = 3072 / 4096:
+// this kernel 40.1 / 54.0 us; every wave starting at another part, the eight partial sums kept in registers:
+// 40.8 / 57.4; all rows cut into near-equal groups whose (group, part) tasks are dealt to the waves: 40.8 / 50.5;
+// nine waves of 16 rows on 229 CUs: 41.4 / 51.4; the small-n kernel: 41.8 / 51.7.  The planner uses it where rows
+// are not a multiple of 2 KiB.)
+template <int NT, int MAXW, bool XG = false>
+__global__ void __launch_bounds__(MAXW *kWave) __attribute__((amdgpu_waves_per_eu(1, (MAXW + 3) / 4)))
+head_mfma_kernel(const MfmaArgs a) {
+    static_assert(!XG || (NT == 1 && MAXW == kStepWaves), "the shared row group is built for eight waves and one group of hidden rows");
     extern __shared__ __align__(16) unsigned char smem[];
+    const int NW = MAXW == kStepWaves ? kStepWaves : a.nwaves;     // waves of this workgroup
     unsigned char *stage = smem;                       // [waves][2][16][272]
-    unsigned char *hbuf = smem + kStageBytes;          // [16 * NT or 8][hpitch]
+    unsigned char *hbuf = smem + (size_t)NW * 2 * kStageUnitBytes;   // [16 * NT or 8][hpitch]
     float *zt = reinterpret_cast<float *>(smem);       // logit tile, aliases both after the contraction
 
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     // Small heads (up to 8 hidden rows only): with fewer than ~160 tiles of 128 rows the tiles shrink to
-    // 128 / KS rows and KS waves share a group of 16 rows, each taking 1 / KS of the columns; their partial
+    // 16 * NW / KS rows and KS waves share a group of 16 rows, each taking 1 / KS of the columns; their partial
     // logits meet in the LDS tile of the epilogue, summed in wave order.
     const int KS = NT == 1 ? a.ksplit : 1;
-    const int tile_rows = kMfmaTileRows / KS;
+    const int tile_rows = 16 * (NW / KS) + (XG ? a.extra_rows : 0);
     const int rg = w / KS, ksi = w % KS;               // row group of the wave, its share of the columns
     const int row0 = blockIdx.x * tile_rows;
     const int rows_b = min(tile_rows, a.k - row0);
@@ -92,9 +112,22 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         const int r = min(16 * rg + 4 * j + lgrp, rows_b - 1);
         voff[j] = (unsigned)((size_t)r * rs + (size_t)lrow * 16);
     }
+    // the shared group: rows 128 .. of the tile (rows past its end repeat the last row)
+    // (kept as the distance from the wave's own rows: choosing between two arrays by a run-time flag would put
+    // both into scratch memory)
+    unsigned vdelta[XG ? 4 : 1];
+    if constexpr (XG) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = min(kMfmaTileRows + 4 * j + lgrp, rows_b - 1);
+            vdelta[j] = (unsigned)((size_t)r * rs + (size_t)lrow * 16) - voff[j];
+        }
+    }
     const char *Wt = static_cast<const char *>(a.W) + (size_t)row0 * rs;
     const int nunits = a.d / kUnitCols;
-    const int nun = nunits / KS;                       // units of this wave
+    const int nun = nunits / KS;                       // units of this wave's own rows
+    const int PL = nunits / 8;                         // XG: units per column part
+    const int ntot = XG ? nun + PL : nun;              // units this wave streams
     // Every workgroup marches over the columns of its 128 rows; if all of them sat in the same column
     // stripe of W at the same time (rows are d * 2 bytes apart) the requests would crowd a subset of the
     // HBM channels (measured: 5.7 instead of 6.7 TB/s).  So the contraction is cut into four column ranges
@@ -120,9 +153,18 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         return u >= nunits ? u - nunits : u;
     };
     auto load_unit = [&](int u, u32x4(&dst)[4]) {
-        const char *p = Wt + (size_t)unit_of(min(u, nun - 1)) * (kUnitCols * 2);
+        if constexpr (XG) {
+            u = min(u, ntot - 1);
+            const bool own = u < nun;
+            const char *p = Wt + (size_t)(own ? unit_of(u) : w * PL + (u - nun)) * (kUnitCols * 2);
+            const unsigned shared = own ? 0u : 0xFFFFFFFFu;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) stream_load16(dst[j], voff[j], p);
+            for (int j = 0; j < 4; ++j) stream_load16(dst[j], voff[j] + (vdelta[j] & shared), p);
+        } else {
+            const char *p = Wt + (size_t)unit_of(min(u, nun - 1)) * (kUnitCols * 2);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) stream_load16(dst[j], voff[j], p);
+        }
     };
     u32x4 areg[kPrefetchUnits][4];
 
@@ -142,6 +184,22 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         }                                                                             \
         ++closed;                                                                     \
     }
+    // XG: a range is two column parts.  The first of them waits in `stash`; when the second is complete their sum
+    // goes the way of a range above.  (Ranges start at even parts, so the parts of a range follow one another.)
+    f32x4 stash = f32x4{0.f, 0.f, 0.f, 0.f};
+    int pcount = 0;        // units of the current part done so far
+    bool second = false;   // the current part is the second of its range
+    auto close_part = [&]() {
+        if (!second) {
+            stash = acc[0];
+            acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
+        } else {
+            acc[0] = stash + acc[0];
+            VT_CLOSE_RANGE()
+        }
+        second = !second;
+        pcount = 0;
+    };
 
     unsigned char *my_stage = stage + (size_t)w * 2 * kStageUnitBytes;
     // staging writes: instruction j, lane (row 4j + lgrp, 16-byte chunk lrow)
@@ -164,7 +222,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     auto fetch_chunk = [&](int c) {
         const int c0 = c * a.KC;
         const int ppr = min(a.KC, a.d - c0) >> 3;        // pieces per row
-        const int step_r = (kStepWaves * kWave) / ppr, step_p = (kStepWaves * kWave) % ppr;
+        const int step_r = (NW * kWave) / ppr, step_p = (NW * kWave) % ppr;
         int r = (int)threadIdx.x / ppr, pc = (int)threadIdx.x % ppr;
         const int s0 = c * (a.KC / kUnitCols);           // first step of the chunk
         const char *hbase = static_cast<const char *>(a.h);
@@ -189,7 +247,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     };
     auto store_chunk = [&](int c) {
         const int ppr = min(a.KC, a.d - c * a.KC) >> 3;
-        const int step_r = (kStepWaves * kWave) / ppr, step_p = (kStepWaves * kWave) % ppr;
+        const int step_r = (NW * kWave) / ppr, step_p = (NW * kWave) % ppr;
         int r = (int)threadIdx.x / ppr, pc = (int)threadIdx.x % ppr;
 #pragma unroll
         for (int q = 0; q < kMaxPieces; ++q) {
@@ -205,11 +263,15 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     // Target ids of the tile rows this lane ranks in the epilogue (two layouts, see below).  They are requested
     // by hand like everything else here and first of all: a load the compiler knows of would get a wait from
     // it wherever it sees fit, and since loads return in order any such wait also waits for the W prefetch.
+    // (ids[2 ..]: rows lrow + 16 q for the four-rows-per-pass epilogue of more than 8 hidden rows; with up to
+    // 12 waves or a shared row group -- up to 8 hidden rows, a wave per row -- ids[2] is the row lane + 128 of a tile
+    // of up to 192 rows)
     int ids[10];
     request_dword(ids[0], a.map + row0 + min(lane, rows_b - 1));
     request_dword(ids[1], a.map + row0 + min(lane + kWave, rows_b - 1));
 #pragma unroll
-    for (int q = 0; q < 8; ++q) request_dword(ids[2 + q], a.map + row0 + min(lrow + 16 * q, rows_b - 1));
+    for (int q = 0; q < 8; ++q)
+        request_dword(ids[2 + q], a.map + row0 + min((MAXW > kStepWaves || XG) ? lane + 2 * kWave : lrow + 16 * q, rows_b - 1));
     fetch_chunk(0);                       // everything waits for it
 #pragma unroll
     for (int x = 0; x < kPrefetchUnits; ++x) load_unit(x, areg[x]);
@@ -237,7 +299,20 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(sb + 4 * j * kStagePitch + wr_off) = ar[j];
         load_unit(u + kPrefetchUnits, ar);
         const unsigned char *hb = hbuf + hrow_off + (size_t)uc * (kUnitCols * 2);
-        if (rotate && u > 0) {
+        if constexpr (XG) {
+            if (pcount == PL) close_part();      // (at u == nun this closes the last part of the wave's own rows)
+            if (u == nun) {
+                // own rows complete: their logits wait in pair0; the shared group's part starts from zero
+                pair0[0] = pair0[0] + pair1[0];
+            }
+            if (u >= nun) {
+                // the shared group's unit w PL + (u - nun): where it lies in h's (rotated) layout in LDS
+                int pos = w * PL + (u - nun) - hstart;
+                pos = pos < 0 ? pos + nunits : pos;
+                hb = hbuf + hrow_off + (size_t)pos * (kUnitCols * 2);
+            }
+            ++pcount;
+        } else if (rotate && u > 0) {
             const int ua = unit_of(u);
             if (ua == 0 || ua == rb1 || ua == rb2 || ua == rb3) VT_CLOSE_RANGE()
         }
@@ -282,39 +357,64 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     // the last chunk: any number of units -- whole rounds, then the one or two that remain
     {
         int uc = KS > 1 ? ustart : 0;      // position of the wave's first unit in h's LDS layout
-        for (int rounds = (nun - u) / kPrefetchUnits; rounds > 0; --rounds) {
+        for (int rounds = (ntot - u) / kPrefetchUnits; rounds > 0; --rounds) {
 #pragma unroll
             for (int x = 0; x < kPrefetchUnits; ++x) run_unit(areg[x], uc++);
         }
         static_assert(kPrefetchUnits == 3, "the remainder below is written for rounds of three");
-        if (u < nun) {
+        if (u < ntot) {
             run_unit(areg[0], uc++);
-            if (u < nun) run_unit(areg[1], uc++);
+            if (u < ntot) run_unit(areg[1], uc++);
         }
     }
     // prefetches past the last unit are still in flight: let them land before their registers die
 #pragma unroll
     for (int x = 0; x < kPrefetchUnits; ++x) wait_unit<0>(areg[x]);
 
-    if (rotate) {
+    if constexpr (XG) {
+        // acc[0]: the shared group's partial logits over this wave's column part; pair0[0]: the own rows' logits
+    } else if (rotate) {
         VT_CLOSE_RANGE()
-#undef VT_CLOSE_RANGE
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[t] = pair0[t] + pair1[t];
     }
+#undef VT_CLOSE_RANGE
 
     // ---- logits of this tile -> LDS tile zt[i][t] (aliases staging and h)
     __syncthreads();
-    const int tp = kMfmaTileRows + 1;
+    const int tp = (XG ? kMfmaTileRows + 16 : MAXW == kStepWaves ? kMfmaTileRows : tile_rows) + 1;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int i = 16 * t + lrow;       // hidden row of this lane
         if (i < a.n) {
             float *dst = zt + ((size_t)ksi * a.n + i) * tp + 16 * rg + 4 * lgrp;      // partial ksi of row i
-            dst[0] = acc[t].x;
-            dst[1] = acc[t].y;
-            dst[2] = acc[t].z;
-            dst[3] = acc[t].w;
+            const f32x4 v = XG ? pair0[t] : acc[t];
+            dst[0] = v.x;
+            dst[1] = v.y;
+            dst[2] = v.z;
+            dst[3] = v.w;
+        }
+    }
+    if constexpr (XG) {
+        // the shared group: the eight waves' partials xq[part][hidden row][16] behind the tile and its candidate
+        // keys, then the same tree as in the registers above
+        float *xq = reinterpret_cast<float *>(smem + 8192 + kStepWaves * 3 * kWave * sizeof(unsigned long long));
+        if (lrow < a.n) {
+            float *dst = xq + ((size_t)w * a.n + lrow) * 16 + 4 * lgrp;
+            dst[0] = acc[0].x;
+            dst[1] = acc[0].y;
+            dst[2] = acc[0].z;
+            dst[3] = acc[0].w;
+        }
+        __syncthreads();
+        const int e = (int)threadIdx.x;
+        if (e < 16 * a.n) {
+            const int i = e >> 4, r = e & 15;
+            const float *x = xq + (size_t)i * 16 + r;
+            const size_t ps = (size_t)a.n * 16;      // from one part to the next
+            const float s01 = x[0] + x[ps], s23 = x[2 * ps] + x[3 * ps];
+            const float s45 = x[4 * ps] + x[5 * ps], s67 = x[6 * ps] + x[7 * ps];
+            zt[(size_t)i * tp + kMfmaTileRows + r] = (s01 + s23) + (s45 + s67);
         }
     }
     __syncthreads();
@@ -322,11 +422,10 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
     if (a.zbuf != nullptr) {
         // store-only tail: the tile's logits go to z [n, k]; a workgroup per hidden row finishes the step
         // (row_select_kernel).  One wave copies a hidden row's 128 logits (512 contiguous bytes) at a time.
-        for (int i = w; i < a.n; i += kStepWaves) {
+        for (int i = w; i < a.n; i += NW) {
             const float *src = zt + (size_t)i * tp;
             float *dst = a.zbuf + (size_t)i * a.k + row0;
-            if (lane < rows_b) dst[lane] = src[lane];
-            if (lane + kWave < rows_b) dst[lane + kWave] = src[lane + kWave];
+            for (int t = lane; t < rows_b; t += kWave) dst[t] = src[t];
         }
         return;
     }
@@ -344,17 +443,23 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_kernel(const Mfma
         // a wave per hidden row (all of them at once for n <= 8); candidate keys of the threshold selection
         // sit behind the logit tile, 1 KiB per wave
         const size_t ztile = ((size_t)KS * a.n * tp * sizeof(float) + 15) & ~(size_t)15;
+        constexpr int kCandPerWave = (MAXW > kStepWaves || XG) ? 3 * kWave : 2 * kWave;      // one key per tile row
         unsigned long long *cand =
             a.n <= kStepWaves
-                ? reinterpret_cast<unsigned long long *>(smem + (ztile > 8192 ? ztile : 8192)) + (size_t)w * 2 * kWave
+                ? reinterpret_cast<unsigned long long *>(smem + (ztile > 8192 ? ztile : 8192)) + (size_t)w * kCandPerWave
                 : nullptr;
-        for (int i = w; i < a.n; i += kStepWaves) {
+        for (int i = w; i < a.n; i += NW) {
             const float *zrow = zt + (size_t)i * tp;
             float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
             unsigned long long *pms_slot = a.pms + (size_t)i * a.nlists + blockIdx.x;
             unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nlists + blockIdx.x) * a.L;
             // the logit is the sum of the KS partial tiles, in wave order
-            block_epilogue_small(zrow, KS, a.n * tp, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane, cand);
+            if constexpr (MAXW > kStepWaves || XG) {
+                const int idq3[3] = {id0, id1, idq[0]};
+                block_epilogue_core<3>(zrow, KS, a.n * tp, rows_b, a.L, idq3, full, pms_slot, pk_slot, lane, cand);
+            } else {
+                block_epilogue_small(zrow, KS, a.n * tp, rows_b, a.L, id0, id1, full, pms_slot, pk_slot, lane, cand);
+            }
         }
     }
 }
@@ -734,9 +839,9 @@ hipError_t launch_mfma_wide_inst(const MfmaArgs &a, size_t lds, hipStream_t st) 
     return hipGetLastError();
 }
 
-template <int NT>
+template <int NT, int MAXW, bool XG = false>
 hipError_t launch_mfma_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
-    auto kern = head_mfma_kernel<NT>;
+    auto kern = head_mfma_kernel<NT, MAXW, XG>;
     static bool attr_set[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -748,13 +853,13 @@ hipError_t launch_mfma_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set[dev] = true;
     }
-    hipLaunchKernelGGL(kern, dim3(a.nlists), dim3(kStepWaves * kWave), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(a.nlists), dim3((MAXW == kStepWaves ? kStepWaves : a.nwaves) * kWave), lds, st, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-size_t mfma_stage_bytes() { return kStageBytes; }
+size_t mfma_stage_bytes(int nwaves) { return (size_t)nwaves * 2 * kStageUnitBytes; }
 size_t mfma_wide_lds_bytes() { return 2 * (size_t)kMfmaTileRows * kStagePitch; }
 
 hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t st) {
@@ -767,11 +872,28 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
         ((a.ksplit != 2 && a.ksplit != 4) || NT != 1 || a.n > 8 || a.KC < a.d || (a.d / kUnitCols) % a.ksplit != 0 ||
          a.zbuf != nullptr))
         return hipErrorInvalidValue;
-    if (a.nlists != (a.k + kMfmaTileRows / a.ksplit - 1) / (kMfmaTileRows / a.ksplit)) return hipErrorInvalidValue;
+    // waves per workgroup: eight, or (one group of hidden rows, all of h in LDS, up to 8 hidden rows) a multiple of
+    // the column split up to kMfmaMaxWaves
+    if (a.nwaves != kStepWaves &&
+        (NT != 1 || a.n > 8 || a.KC < a.d || a.nwaves < a.ksplit || a.nwaves > kMfmaMaxWaves ||
+         a.nwaves % a.ksplit != 0 || (size_t)a.d * 16 > (size_t)kMaxPieces * a.nwaves * kWave * 16))
+        return hipErrorInvalidValue;
+    // rows past the 128th as a group shared by the eight waves: eight column parts of whole units, all of h in LDS
+    if (a.extra_rows != 0 &&
+        (a.extra_rows < 1 || a.extra_rows > 16 || NT != 1 || a.n > 8 || a.KC < a.d || a.ksplit != 1 ||
+         a.nwaves != kStepWaves || (a.d / kUnitCols) % 8 != 0))
+        return hipErrorInvalidValue;
+    {
+        const int tile_rows = 16 * (a.nwaves / a.ksplit) + a.extra_rows;
+        if (a.nlists != (a.k + tile_rows - 1) / tile_rows) return hipErrorInvalidValue;
+    }
     switch (NT) {
-        case 1: return launch_mfma_inst<1>(a, lds, st);
-        case 2: return launch_mfma_inst<2>(a, lds, st);
-        case 4: return launch_mfma_inst<4>(a, lds, st);
+        case 1:
+            if (a.extra_rows != 0) return launch_mfma_inst<1, kStepWaves, true>(a, lds, st);
+            return a.nwaves == kStepWaves ? launch_mfma_inst<1, kStepWaves>(a, lds, st)
+                                          : launch_mfma_inst<1, kMfmaMaxWaves>(a, lds, st);
+        case 2: return launch_mfma_inst<2, kStepWaves>(a, lds, st);
+        case 4: return launch_mfma_inst<4, kStepWaves>(a, lds, st);
         case 8:
         case 16: {
             if (a.hpack == nullptr) return hipErrorInvalidValue;

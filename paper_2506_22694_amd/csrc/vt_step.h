@@ -100,9 +100,16 @@ struct MfmaArgs {
     // larger batch (several heads per call); the merge kernel maps the output rows the same way
     unsigned long long row_pack;
     int indexed;
-    // 1, 2 or 4 (n <= 8, all of h in LDS, no zbuf): tiles of 128 / ksplit rows, ksplit waves share 16 rows and the
-    // columns; nlists counts those tiles
+    // 1, 2 or 4 (n <= 8, all of h in LDS, no zbuf): tiles of 16 * nwaves / ksplit rows, ksplit waves share 16 rows
+    // and the columns; nlists counts those tiles
     int ksplit;
+    // waves per workgroup: kStepWaves, or (n <= 8, all of h in LDS, no zbuf) any multiple of ksplit up to
+    // kMfmaMaxWaves, so that the tiles can be sized to cover the head in one round of at most 256 workgroups
+    int nwaves;
+    // extra_rows != 0 (n <= 8, all of h in LDS, 8 waves, no column split, d a multiple of 1024): the tile is
+    // 128 + extra_rows rows, 1 <= extra_rows <= 16; the rows past the 128th form one more 16-row group whose
+    // columns the eight waves share
+    int extra_rows;
 };
 
 struct FinalizeArgs {
@@ -129,7 +136,10 @@ struct FinalizeArgs {
 };
 constexpr int kFinalizeTreeMaxN = 512;
 
-size_t mfma_stage_bytes();
+constexpr int kMfmaMaxWaves = 12;      // three waves per SIMD: 168 registers each
+
+size_t mfma_stage_bytes(int nwaves);
+
 size_t mfma_wide_lds_bytes();   // NT >= 8: two shared unit buffers
 hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t st);
 hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t st);
