@@ -14,6 +14,13 @@ same inputs and are timed and reported in the same JSON line under
 Cold-cache rule: W_trim (192 MiB) would fit the memory-side cache, so the timed
 steps rotate over several distinct device copies of W_trim.
 
+The same line also carries, each timed after an untimed time-based wake-up of
+the device: the other workloads' draft steps ("other_configs": 1B chain and its
+full-vocabulary control, task head, 3B full-vocabulary control, 8B tree, stress),
+1000 consecutive tree steps as one span with their ids checked against the
+oracle on sampled steps ("tree_run"), the k x n x m sweep of the 3B shape
+("sweep") and the paper's own trimmed sizes ("paper_k").  --quick skips those.
+
 Prints ONE JSON line on stdout.  Everything else goes to stderr.
 """
 from __future__ import annotations
@@ -29,14 +36,28 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16 matrix-core peak
 
-# HBM bytes per launch of the step kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE),
-# scaled by the same counters on a plain copy of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    # (workload, k, n, m): both kernels of the step: FETCH_SIZE (100525.4 + 139.4) x 1.99975 KiB +
-    # WRITE_SIZE (304.9 + 0.8) KiB per step (profiles/head_mfma_kernel_1_llama3b_k32768_n8_m8.txt)
-    ("llama3b", 32768, 8, 8): 206_449_000,
+# HBM bytes per draft step from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by the same counters on a plain
+# copy of known size): read from the line "traffic_bytes_per_step = N" of the counter summary in profiles/, so
+# the figure in the JSON line is the one the committed profile holds.  None = no such profile for the shape.
+TRAFFIC_PROFILES = {
+    ("llama3b", 32768, 8, 8): "head_mfma_kernel_1_llama3b_k32768_n8_m8.txt",
 }
+
+
+def measured_traffic(key):
+    name = TRAFFIC_PROFILES.get(key)
+    if name is None:
+        return None
+    try:
+        with open(os.path.join(ROOT, "profiles", name)) as f:
+            for line in f:
+                if line.strip().startswith("traffic_bytes_per_step"):
+                    return int(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -57,11 +78,10 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-calibration", action="store_true",
                    help="draw W_trim directly instead of running count/select/gather on a full head")
-    p.add_argument("--sweep", action="store_true", help="also time the k / n sweep (table on stderr)")
-    p.add_argument("--configs", action="store_true",
-                   help="also time the other workloads' draft steps (1B chain + full-vocab control, 8B tree, stress)")
-    p.add_argument("--tree-run", action="store_true",
-                   help="also time 1000 consecutive draft steps of the 8B-shaped tree workload (n=64, d=4096) as one span")
+    p.add_argument("--quick", action="store_true",
+                   help="headline only: skip the other workloads, the 1000-step tree run, the sweep and the paper's k")
+    p.add_argument("--wake-seconds", type=float, default=0.3,
+                   help="untimed steps run for this long before every timed region (the device clocks settle)")
     p.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing of the headline step")
     p.add_argument("--no-full-vocab", action="store_true", help="skip the k = V control step (trimmed-vs-full ratio)")
     p.add_argument("--pmc-copy", action="store_true",
@@ -114,9 +134,11 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps      # us per rep
 
-    def wake(fn, min_calls=100, seconds=0.15):
+    def wake(fn, min_calls=100, seconds=None):
         # untimed: after the device has idled (inputs are generated on the host) it takes tens of milliseconds
-        # of work to return to its full clocks; the matrix-core shapes show it most (n = 64: 61 -> 57 us)
+        # of work to return to its full clocks; the matrix-core shapes show it most (n = 64: 61 -> 57 us).
+        # Returns (calls, seconds) for the record.
+        seconds = args.wake_seconds if seconds is None else seconds
         t_w = time.time()
         r = 0
         while r < min_calls or time.time() - t_w < seconds:
@@ -124,6 +146,17 @@ def main():
             r += 1
             if r % 50 == 0:
                 torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        return r, time.time() - t_w
+
+    def shape_row(name, dd, kk, nn, mm, us):
+        row = {"workload": name, "d": dd, "k": kk, "n": nn, "m": mm, "us": round(us, 2),
+               "gbps": round(kk * dd * 2 / us / 1e3, 1), "frac_hbm": round(kk * dd * 2 / us / 1e3 / HBM_PEAK_GBPS, 4),
+               "kernels": vt.draft_head_step_plan(nn, kk, dd, mm)}
+        if nn >= 64:
+            row["tflops"] = round(2.0 * nn * kk * dd / us / 1e6, 1)
+            row["frac_mfma"] = round(2.0 * nn * kk * dd / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)
+        return row
 
     # ------------------------------------------------------------------ inputs + calibration rows
     calib = None
@@ -175,6 +208,9 @@ def main():
                            out_ids=out_ids, out_logp=out_logp)
 
     # ------------------------------------------------------------------ timed region
+    # untimed first: the device idled while the inputs were generated on the host; then the W warm-up steps the
+    # command line asks for, then exactly K timed steps
+    wake_calls, wake_s = wake(step)
     for r in range(args.warmup):
         step(r)
     us_cold = time_region(step, args.steps)
@@ -257,28 +293,69 @@ def main():
 
     # ------------------------------------------------------------------ 8B-shaped tree drafting: 1000 steps, one span
     tree = None
-    if args.tree_run:
-        dd, kk, nn, mm, nsteps = 4096, 32768, 64, 8, 1000
+    if not args.quick:
+        import oracle
+        dd, kk, nn, mm, nsteps, nblk = 4096, 32768, 64, 8, 1000, 16
         Wk_np, mapk_np = synth.trimmed_head_direct(kk, dd, 4000, "bf16")
         cps = [to_dev_bf16(Wk_np)]
         cps += [cps[0].clone() for _ in range(3)]
         mapk = torch.from_numpy(mapk_np).to(dev)
-        hs = [to_dev_bf16(synth.hidden_rows(nn, dd, 4000 + j, "bf16")) for j in range(16)]
+        hs_np = [synth.hidden_rows(nn, dd, 4000 + j, "bf16") for j in range(nblk)]
+        hs = [to_dev_bf16(x) for x in hs_np]
         wsk = vt.StepWorkspace(nn, kk, dd, mm, dev)
-        ids_all = torch.empty((16, nn, mm), dtype=torch.int32, device=dev)
-        lp_all = torch.empty((16, nn, mm), dtype=torch.float32, device=dev)
-        ft = lambda r: vt.draft_head_step(hs[r % 16], cps[r % 4], mapk, mm, ws=wsk, out_ids=ids_all[r % 16],
-                                          out_logp=lp_all[r % 16])
+        ids_all = torch.empty((nblk, nn, mm), dtype=torch.int32, device=dev)
+        lp_all = torch.empty((nblk, nn, mm), dtype=torch.float32, device=dev)
+        # step s uses hidden block s % 16 and W_trim copy s % 4, and writes its block's slot of the result arrays
+        ft = lambda r: vt.draft_head_step(hs[r % nblk], cps[r % 4], mapk, mm, ws=wsk, out_ids=ids_all[r % nblk],
+                                          out_logp=lp_all[r % nblk])
         wake(ft, 300)
+        ids_all.zero_()
         us_tree = time_region(ft, nsteps)
-        # reproducibility: the 16 distinct results, folded into one number
-        wgt = torch.arange(1, 16 * nn * mm + 1, device=dev, dtype=torch.int64)
-        checksum = int((ids_all.flatten().to(torch.int64) * wgt).sum().item() % (2**61 - 1))
+        # reproducibility: the 16 distinct results, folded into one number; the same fold over the oracle's ids of
+        # the sampled steps {0, 1, 2, 499, 998, 999} (hidden blocks 0, 1, 2, 3, 6, 7) must agree with the fold over
+        # those blocks of the run's result, row by row except inside fp32/fp64 near-ties (counted)
+        def fold(ids_blocks, blocks):
+            tot = 0
+            for b in blocks:
+                w = np.arange(1, nn * mm + 1, dtype=np.int64) + b * nn * mm
+                tot = (tot + int((ids_blocks[b].astype(np.int64).ravel() * w).sum())) % (2**61 - 1)
+            return tot
+        got = ids_all.cpu().numpy()
+        got_lp = lp_all.cpu().numpy().astype(np.float64)
+        sample_steps = [0, 1, 2, 499, 998, 999]
+        blocks = sorted({s_ % nblk for s_ in sample_steps})
+        ref_ids, rows_differ, rows_near_tie_ok, max_err = {}, 0, 0, 0.0
+        for b in blocks:
+            ref = oracle.draft_head_step(hs_np[b], Wk_np, mapk_np, mm)
+            ref_ids[b] = ref["ids"]
+            inv = None
+            for i in range(nn):
+                if np.array_equal(got[b, i], ref["ids"][i]):
+                    max_err = max(max_err, float(np.abs(got_lp[b, i] - ref["logp"][i]).max()))
+                    continue
+                rows_differ += 1
+                if inv is None:
+                    inv = {int(t): j for j, t in enumerate(mapk_np)}
+                ok = len(set(got[b, i].tolist())) == mm
+                for r in range(mm):
+                    j_gpu = inv.get(int(got[b, i, r]))
+                    j_ref = int(ref["trim_idx"][i, r])
+                    ok = ok and j_gpu is not None and abs(ref["z"][i, j_gpu] - ref["z"][i, j_ref]) <= 1e-4
+                rows_near_tie_ok += 1 if ok else 0
+        checksum_all = fold(got, range(nblk))
         tree = {"workload": "llama8b tree: d=4096 k=32768 n=64 top-8, 16 h blocks cycled, 4 W_trim copies",
                 "steps": nsteps, "us_per_step": round(us_tree, 2), "total_ms": round(us_tree * nsteps / 1e3, 2),
                 "gbps": round(kk * dd * 2 / us_tree / 1e3, 1),
                 "frac_of_hbm_peak": round(kk * dd * 2 / us_tree / 1e3 / HBM_PEAK_GBPS, 4),
-                "tflops": round(2.0 * nn * kk * dd / us_tree / 1e6, 1), "ids_checksum": checksum}
+                "tflops": round(2.0 * nn * kk * dd / us_tree / 1e6, 1),
+                "frac_mfma": round(2.0 * nn * kk * dd / us_tree / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "ids_checksum_all_blocks": checksum_all,
+                "oracle_check": {"steps": sample_steps, "hidden_blocks": blocks,
+                                 "ids_checksum_run": fold(got, blocks), "ids_checksum_oracle": fold(ref_ids, blocks),
+                                 "rows_checked": len(blocks) * nn, "rows_differing": rows_differ,
+                                 "rows_differing_within_near_tie_rule": rows_near_tie_ok,
+                                 "max_abs_logp_error_on_equal_rows": max_err,
+                                 "ok": rows_differ == rows_near_tie_ok and max_err <= 2e-3}}
         log("tree run:", tree)
         del cps, hs
 
@@ -368,54 +445,46 @@ def main():
                                           out_logp=out_logp), 100), 3)
         log("tree selection (HIP-graph replay):", tree_sel)
 
-    sweep = None
-    if args.sweep:
+    def time_shapes(dd, kk, shapes, seed, names=None, reps=100, max_copies=24):
+        """Cold draft steps of one head [kk, dd] for several (n, m); returns rows.  Fresh allocations per head."""
+        torch.cuda.empty_cache()
+        Wk_np, mapk_np = synth.trimmed_head_direct(kk, dd, seed, "bf16")
+        Wk = to_dev_bf16(Wk_np)
+        mapk = torch.from_numpy(mapk_np).to(dev)
+        ncop = max(2, min(max_copies, int(1.3e9 // (kk * dd * 2))))
+        cps = [Wk] + [Wk.clone() for _ in range(ncop - 1)]
+        rows = []
+        for j, (nn, mm) in enumerate(shapes):
+            hs4 = [to_dev_bf16(synth.hidden_rows(nn, dd, seed + 10 * nn + q, "bf16")) for q in range(4)]
+            wsk = vt.StepWorkspace(nn, kk, dd, mm, dev)
+            f = lambda r: vt.draft_head_step(hs4[r % 4], cps[r % ncop], mapk, mm, ws=wsk)
+            wake(f, 10, args.wake_seconds if j == 0 else 0.05)      # this head's inputs were just generated
+            us = sorted(time_region(f, reps) for _ in range(3))[1]
+            rows.append(shape_row(names[j] if names else "", dd, kk, nn, mm, us))
+            log("shape", rows[-1])
+        del cps, Wk
+        return rows
+
+    sweep = others = paper_k = None
+    if not args.quick:
         sweep = []
         for kk in (8192, 16384, 32768, 65536, 128256):
-            torch.cuda.empty_cache()
-            Wk_np, mapk_np = synth.trimmed_head_direct(kk, d, wl.seed, "bf16")
-            Wk = to_dev_bf16(Wk_np)
-            mapk = torch.from_numpy(mapk_np).to(dev)
-            ncop = max(2, min(24, int(1.3e9 // (kk * d * 2))))
-            cps = [Wk] + [Wk.clone() for _ in range(ncop - 1)]
-            for nn in (1, 2, 4, 8):
-                for mm in (1, 8):
-                    hh = to_dev_bf16(synth.hidden_rows(nn, d, wl.seed + nn, "bf16"))
-                    wsk = vt.StepWorkspace(nn, kk, d, mm, dev)
-                    f = lambda r: vt.draft_head_step(hh, cps[r % ncop], mapk, mm, ws=wsk)
-                    wake(f, 10, 0.15 if (nn, mm) == (1, 1) else 0.0)      # the inputs of this k were just generated
-                    us = time_region(f, 100)
-                    row = {"k": kk, "n": nn, "m": mm, "us": round(us, 2), "gbps": round(kk * d * 2 / us / 1e3, 1),
-                           "frac": round(kk * d * 2 / us / 1e3 / HBM_PEAK_GBPS, 4)}
-                    sweep.append(row)
-                    log("sweep", row)
-            del cps, Wk
-
-    others = None
-    if args.configs:
+            for row in time_shapes(d, kk, [(nn, mm) for nn in (1, 2, 4, 8) for mm in (1, 8)], wl.seed):
+                row.pop("workload")
+                row.pop("kernels")
+                sweep.append(row)
         others = []
         cases = [("llama1b chain", 2048, 32768, 1, 1), ("llama1b full-vocab control", 2048, 128256, 1, 1),
                  ("task head (xLAM-sized vocabulary)", 3072, 5000, 8, 8),
                  ("llama3b full-vocab control", 3072, 128256, 8, 8),
                  ("llama8b tree", 4096, 32768, 64, 8), ("stress", 8192, 32768, 256, 16)]
         for name, dd, kk, nn, mm in cases:
-            torch.cuda.empty_cache()       # fresh allocations, not pieces of the previous case's blocks
-            Wk_np, mapk_np = synth.trimmed_head_direct(kk, dd, 77, "bf16")
-            Wk = to_dev_bf16(Wk_np)
-            mapk = torch.from_numpy(mapk_np).to(dev)
-            ncop = max(2, min(12, int(1.3e9 // (kk * dd * 2))))
-            cps = [Wk] + [Wk.clone() for _ in range(ncop - 1)]
-            hs = [to_dev_bf16(synth.hidden_rows(nn, dd, 77 + j, "bf16")) for j in range(4)]
-            wsk = vt.StepWorkspace(nn, kk, dd, mm, dev)
-            f = lambda r: vt.draft_head_step(hs[r % 4], cps[r % ncop], mapk, mm, ws=wsk)
-            wake(f)
-            us = sorted(time_region(f, 100) for _ in range(5))[2]
-            row = {"workload": name, "d": dd, "k": kk, "n": nn, "m": mm, "us": round(us, 2),
-                   "gbps": round(kk * dd * 2 / us / 1e3, 1), "frac_hbm": round(kk * dd * 2 / us / 1e3 / HBM_PEAK_GBPS, 4),
-                   "tflops": round(2.0 * nn * kk * dd / us / 1e6, 1)}
-            others.append(row)
-            log("config", row)
-            del cps, Wk
+            others += time_shapes(dd, kk, [(nn, mm)], 77, names=[name], max_copies=12)
+        # the paper's own trimmed sizes (head sizes of its main tables / hidden size; sweet spots of its ablation over k)
+        paper_k = []
+        for kk in (22786, 32959, 32975, 33008, 35010):
+            paper_k += time_shapes(3072, kk, [(1, 1), (8, 8)], 91, names=["3B-shaped head"] * 2)
+            paper_k += time_shapes(4096, kk, [(64, 8)], 92, names=["8B-shaped head, tree"])
 
     # ------------------------------------------------------------------ CPU baseline (the oracle, untuned)
     cpu = None
@@ -442,18 +511,11 @@ def main():
                "one_thread_us": round(us_cpu_1t, 1)}
         log("cpu_baseline:", cpu)
 
-    # which kernel serves this shape (the library's policy: up to 8 rows go to the matrix-core kernel when its
-    # 128-row tiles fill the 256 CUs in one round and d <= 4096; a single row only up to d = 3072)
-    def tiles_fit(rows, least):
-        return least <= (k + rows - 1) // rows <= 256
-    units = d // 128
-    on_mfma = n > 8 or (d % 128 == 0 and d <= (7168 if n >= 5 else 4096 if n >= 2 else 3072) and
-                        (tiles_fit(128, 160) or (m <= 11 and ((units % 2 == 0 and tiles_fit(64, 160)) or
-                                                              (units % 4 == 0 and tiles_fit(32, 96))))))
-    step_kernel = "head_mfma_kernel + step_finalize_kernel" if on_mfma else "head_gemv_kernel"
+    # which kernels serve this shape: the library's own answer
+    step_kernel = vt.draft_head_step_plan(n, k, d, m)
     gbps_cold = step_bytes / us_cold / 1e3
     gbps_kernel = step_bytes / us_kernel / 1e3
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, k, n, m))
+    traffic = measured_traffic((args.workload, k, n, m))
     out = {
         "metric": "trimmed LM-head draft-step latency (us) + achieved HBM GB/s, d=3072 k=32768",
         "value": round(us_cold, 3),
@@ -469,17 +531,20 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: V={V} d={d} bf16, k={k}, n={n}, top-{m}, "
                                f"{len(copies)} W_trim copies round-robin (cold cache)",
-                   "V": V, "d": d, "k": k, "n": n, "m": m, "copies": len(copies)},
+                   "V": V, "d": d, "k": k, "n": n, "m": m, "copies": len(copies),
+                   # untimed, before the W warm-up steps and the K timed ones: steps run for a fixed time so that
+                   # the device, idle while the host generated the inputs, is back at its full clocks
+                   "untimed_wake": {"steps": wake_calls, "seconds": round(wake_s, 3)}},
         "hbm_gbps": round(gbps_cold, 1),
         "frac_of_hbm_peak": round(gbps_cold / HBM_PEAK_GBPS, 4),
         "warm_single_buffer_us": round(us_warm, 3),
         "plain_read_same_bytes_us": round(us_read, 3),
         "plain_read_gbps": round(step_bytes / us_read / 1e3, 1),
-        # The step is its streaming kernel plus, for 2-8 rows at this k, a 5 us merge kernel (one row: one
-        # launch).  `achieved` prices the algorithmic bytes against the whole step's share of the timed region
-        # (HIP events on the launch stream / K), i.e. against both kernels; rocprofv3's duration of the streaming
-        # kernel alone is in profiles/.  An event pair around every single step adds the events' own cost and
-        # is reported beside it.
+        # The step is its streaming kernel plus a merge kernel of a few microseconds.  `achieved` prices the
+        # algorithmic bytes against the whole step's share of the timed region (HIP events on the launch stream / K),
+        # i.e. against both kernels; rocprofv3's duration of the streaming kernel alone is in profiles/.  An event
+        # pair around every single step adds the events' own cost and is reported beside it.  `traffic` is the
+        # counter figure of the committed profile of this shape (both kernels).
         "roofline": {"bound": "hbm", "achieved": round(gbps_cold, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps_cold / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel": step_kernel, "algorithmic_bytes": step_bytes,
@@ -494,10 +559,12 @@ def main():
     }
     if tree is not None:
         out["tree_run"] = tree
-    if sweep is not None:
-        out["sweep"] = sweep
     if others is not None:
         out["other_configs"] = others
+    if paper_k is not None:
+        out["paper_k"] = paper_k
+    if sweep is not None:
+        out["sweep"] = sweep
     print(json.dumps(out), flush=True)
 
 
