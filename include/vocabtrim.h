@@ -174,11 +174,10 @@ size_t vt_choose_k_ws_bytes(int32_t V);
  *   out_lse        [n] fp32, device, out, nullable
  *   out_logp_full  [n, k] fp32, device, out, nullable: log-softmax of every
  *                  trimmed logit (costs an extra pass; meant for checks)
- *   ws             >= vt_draft_head_step_ws_bytes(n, k, d, m) bytes, prepared
- *                  once by vt_draft_head_step_ws_init() after allocation.  The
- *                  step leaves the workspace ready for the next call, so no
- *                  further initialisation is needed between steps, whatever
- *                  their shapes (as long as the size suffices).
+ *   ws             >= vt_draft_head_step_ws_bytes(n, k, d, m) bytes.  Its contents
+ *                  need no initialisation, before the first step or between
+ *                  steps, whatever their shapes (as long as the size suffices)
+ *                  and whatever an earlier step that never completed left behind.
  * ---------------------------------------------------------------------- */
 int vt_draft_head_step(const void *h, int h_type, int32_t n, const void *W_trim, int w_type,
                        int32_t k, int32_t d, const int32_t *map, int32_t m, int32_t *out_ids,
@@ -247,8 +246,7 @@ int vt_draft_head_step_static(const void *h, int h_type, int32_t n, const void *
  *     m            1 <= m <= min(VT_MAX_TOP_M, k of every head that has rows)
  *     out_lse      nullable
  *     ws           >= vt_draft_head_step_multi_ws_bytes(n, d, k, n_heads, m) bytes
- *                  (0 = arguments out of range), prepared once by
- *                  vt_draft_head_step_ws_init() like a single-head workspace
+ *                  (0 = arguments out of range); no initialisation
  *   Only kernels are enqueued (no copies): the call may be captured in a graph.
  * ---------------------------------------------------------------------- */
 #define VT_MAX_HEADS 16
@@ -262,9 +260,9 @@ int vt_draft_head_step_multi(const void *h, int h_type, int32_t n, int32_t d, co
                              float *out_lse, void *ws, size_t ws_bytes, void *stream);
 size_t vt_draft_head_step_multi_ws_bytes(int32_t n, int32_t d, const int32_t *k, int32_t n_heads, int32_t m);
 
-/* Clears the arrival counters at the head of a draft-step workspace (a small
- * fill kernel on `stream`; safe under stream capture).  Call once after
- * allocating the workspace, and again only if a step was aborted mid-flight. */
+/* Not needed any more (a draft-step workspace needs no initialisation); kept for
+ * callers written against earlier versions.  Zeroes the first 2 KiB of the
+ * workspace with a small fill kernel on `stream`. */
 int vt_draft_head_step_ws_init(void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
@@ -313,24 +311,12 @@ int vt_tree_rerank(const float *cum, int32_t N, int32_t T, int32_t *out_idx, voi
  * other shapes run the step and then the expansion kernel.
  *   arguments as in vt_draft_head_step (no out_lse / out_logp_full) and
  *   vt_tree_expand; out_ids / out_logp [n, m] still receive the step's result.
- *   ws: >= vt_draft_head_step_ws_bytes(n, k, d, m), initialised as for the step.
+ *   ws: >= vt_draft_head_step_ws_bytes(n, k, d, m); no initialisation.
  * ---------------------------------------------------------------------- */
 int vt_draft_tree_level(const void *h, int h_type, int32_t n, const void *W_trim, int w_type, int32_t k,
                         int32_t d, const int32_t *map, int32_t m, const float *parent_cum, int32_t K,
                         int32_t *out_parent, int32_t *out_token, float *out_cum, int32_t *out_ids,
                         float *out_logp, void *ws, size_t ws_bytes, void *stream);
-
-/* ------------------------------------------------------------------------
- * Measurement reference (not part of the method): reads `bytes` bytes at `p`
- * once, in the launch and load shape of the small-n draft step (*sink is
- * written only if a lane's fold of its words hits one fixed value, which keeps
- * the loads alive at no cost).  Its duration is what the device needs to merely
- * stream the bytes a draft step has to stream; the benchmark reports it next
- * to the step.
- *   p      device, 16-byte aligned;  bytes > 0, a multiple of 16
- *   sink   [1] uint32, device
- * ---------------------------------------------------------------------- */
-int vt_stream_read_reference(const void *p, size_t bytes, uint32_t *sink, void *stream);
 
 #ifdef __cplusplus
 }

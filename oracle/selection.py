@@ -22,7 +22,7 @@ import numpy as np
 
 
 def rank_order(counts: np.ndarray) -> np.ndarray:
-    """All ids by (count desc, id asc), int32 [V]: plain insertion of (count, id) pairs into a sorted list."""
+    """All ids by (count desc, id asc), int32 [V]: a plain full sort of the (count, id) pairs."""
     pairs = [(-int(c), t) for t, c in enumerate(np.asarray(counts, dtype=np.int64).tolist())]
     pairs.sort()                                   # tuples compare by -count, then id
     return np.array([t for _, t in pairs], dtype=np.int32)

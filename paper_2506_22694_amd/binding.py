@@ -219,7 +219,7 @@ def choose_k(counts: torch.Tensor, top_p: float | None = None, min_count: int | 
 
 # --------------------------------------------------------------------------- Alg. 2, drafting lines
 class StepWorkspace:
-    """Device scratch of the draft step: allocated and initialised once, reused by every step."""
+    """Device scratch of the draft step: allocated once (no initialisation needed), reused by every step."""
 
     def __init__(self, n: int, k: int, d: int, m: int, device):
         L = load_library()
@@ -227,7 +227,6 @@ class StepWorkspace:
         if nbytes == 0:
             raise VocabTrimError(2)
         self.buf = _scratch(nbytes, device)
-        _check(L.vt_draft_head_step_ws_init(_ptr(self.buf), self.buf.numel(), _stream(device)))
 
     @property
     def nbytes(self) -> int:
@@ -344,7 +343,6 @@ class MultiStepWorkspace:
         if nbytes == 0:
             raise VocabTrimError(2)
         self.buf = _scratch(nbytes, device)
-        _check(L.vt_draft_head_step_ws_init(_ptr(self.buf), self.buf.numel(), _stream(device)))
 
     @property
     def nbytes(self) -> int:

@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <chrono>
 #include <cstdio>
 #include <mutex>
 
@@ -26,6 +28,24 @@ inline int device_status(hipError_t e) {
     return VT_ERR_DEVICE;
 }
 inline int launch_status() { return device_status(hipGetLastError()); }
+
+// Arrival counters in a step workspace are stamped with a number no earlier launch of this process has used (see
+// arrive_and_elect): 48 bits, never zero.
+// The sequence starts at a point of its 2^48 - 1 values that differs from process to process (clock, address of
+// a static), so that bytes which merely look like a small counter are not mistaken for this process's first launches.
+unsigned long long generation_seed() {
+    static int anchor;
+    unsigned long long x = (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() ^
+                           ((unsigned long long)reinterpret_cast<uintptr_t>(&anchor) << 17);
+    x ^= x >> 33;
+    x *= 0xff51afd7ed558ccdull;      // 64-bit finaliser of a well-known hash mixer
+    x ^= x >> 33;
+    return x;
+}
+std::atomic<unsigned long long> g_generation{generation_seed()};
+inline unsigned long long next_generation() {
+    return (g_generation.fetch_add(1, std::memory_order_relaxed) % ((1ull << 48) - 1)) + 1;
+}
 
 // ---------------------------------------------------------------- library-owned step workspace
 // Device memory of the draft step for callers that cannot allocate (vt_draft_head_step_static): one array per
@@ -53,6 +73,23 @@ int static_scratch_of_current_device(void **out) {
 }
 
 // ---------------------------------------------------------------- draft-step plan
+// Workgroups one round of the draft-step kernels may have: the compute units of the current device (one workgroup
+// per CU: they take most of a CU's LDS), read once per process; 256 on MI355X, which is also the most the kernels'
+// tables are sized for and the answer where no device is visible (the workspace-size functions are pure host code).
+// The measured crossovers below (so many tiles of so many rows) are scaled to it.
+int round_workgroups() {
+    static const int cus = []() {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            return vt::kStepMaxBlocks;
+        }
+        return n < vt::kStepMaxBlocks ? n : vt::kStepMaxBlocks;
+    }();
+    return cus;
+}
+
 struct StepPlan {
     bool ok = false;
     bool gemv = false;     // small-n VALU path
@@ -80,7 +117,8 @@ StepPlan plan_step(int n, int k, int d, int m, int dtype, bool force_gemv = fals
 StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) {
     StepPlan p;
     if (n <= 0 || k <= 0 || d <= 0 || m <= 0 || k > vt::kStepMaxK) return p;
-    int rpb = (k + vt::kStepMaxBlocks - 1) / vt::kStepMaxBlocks;
+    const int CUS = round_workgroups();
+    int rpb = (k + CUS - 1) / CUS;
     rpb = (rpb + 7) / 8 * 8;
     p.rpb = rpb;
     p.nblocks = (k + rpb - 1) / rpb;
@@ -106,7 +144,8 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
             if (NW < KS || NW % KS != 0 || NW > vt::kMfmaMaxWaves) return false;
             const int tr = 16 * (NW / KS);
             const int tiles = (k + tr - 1) / tr;
-            if (tiles < (KS == 4 ? vt::kMfmaSmallMinTiles32 : vt::kMfmaSmallMinTiles) || tiles > vt::kStepMaxBlocks) return false;
+            if (tiles < (KS == 4 ? vt::kMfmaSmallMinTiles32 : vt::kMfmaSmallMinTiles) * CUS / vt::kStepMaxBlocks || tiles > CUS)
+                return false;
             // (the split also needs all of h in LDS at once: d <= 4096)
             if (KS > 1 && ((d / 128) % KS != 0 || m > vt::kRowSelectMinL || d > vt::kMfmaSmallMaxD)) return false;
             if (NW != vt::kStepWaves) {
@@ -116,7 +155,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
             }
             return true;
         };
-        const int R = (k + vt::kStepMaxBlocks - 1) / vt::kStepMaxBlocks;      // rows per tile for 256 tiles
+        const int R = (k + CUS - 1) / CUS;                                    // rows per tile for one tile per CU
         const int G = (R + 15) / 16;                                          // ... in 16-row groups
         if (R > vt::kMfmaTileRows && R <= vt::kMfmaTileRows + 16 && (d % 1024) == 0 && (d % 2048) != 0 &&
             d <= vt::kMfmaSmallMaxD) {
@@ -329,8 +368,8 @@ size_t step_ws_bytes(int n, int k, int d, int m) {
     return b;
 }
 
-// Layout of a multi-head workspace: the step workspace first (so that vt_draft_head_step_ws_init prepares
-// it), then the staged hidden rows and the staged results of one head's rows.
+// Layout of a multi-head workspace: the step workspace first, then the staged hidden rows and the staged results
+// of one head's rows.
 struct MultiLayout {
     size_t off_h = 0, off_ids = 0, off_logp = 0, off_lse = 0, bytes = 0;
 };
@@ -575,9 +614,9 @@ int vt_draft_head_step_static(const void *h, int h_type, int32_t n, const void *
     void *ws = nullptr;
     const int rc = static_scratch_of_current_device(&ws);
     if (rc != VT_OK) return rc;
-    // The arrival counters at the head of the array are zero when the code object is loaded and every step
-    // returns them to zero, so nothing has to be cleared here; everything behind them is rewritten by a step
-    // before it is read.
+    // Nothing has to be cleared here: the arrival counters at the head of the array are stamped per launch and
+    // recognise whatever an earlier call left in them, and everything behind them is rewritten by a step before
+    // it is read.
     return vt_draft_head_step(h, h_type, n, W_trim, w_type, k, d, map, m, out_ids, out_logp, out_lse, out_logp_full,
                               ws, (size_t)VT_STATIC_WS_BYTES, stream);
 }
@@ -777,7 +816,8 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.nblocks = p.nblocks;
         a.pms = pms;
         a.pkeys = pkeys;
-        a.tickets = reinterpret_cast<unsigned *>(wsb);
+        a.tickets = reinterpret_cast<unsigned long long *>(wsb);
+        a.generation = next_generation();
         a.out_ids = out_ids;
         a.out_logp = out_logp;
         a.out_lse = out_lse;
@@ -878,6 +918,7 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.ksplit = p.ksplit;
         a.nwaves = p.nwaves;
         a.extra_rows = p.extra_rows;
+        a.ticket_clear = tf.cum != nullptr ? reinterpret_cast<unsigned *>(wsb) : nullptr;
         hipError_t e = vt::launch_head_mfma(p.NT, a, p.lds, st);
         if (e != hipSuccess) return device_status(e);
         if (p.row_select) {
@@ -953,15 +994,6 @@ int vt_tree_rerank(const float *cum, int32_t N, int32_t T, int32_t *out_idx, voi
     a.out_token = nullptr;
     a.out_score = nullptr;
     return device_status(vt::launch_tree_select(a, static_cast<hipStream_t>(stream)));
-}
-
-int vt_stream_read_reference(const void *p, size_t bytes, uint32_t *sink, void *stream) {
-    if (p == nullptr || sink == nullptr) return VT_ERR_NULL;
-    if (bytes == 0 || (bytes & 15) != 0) return VT_ERR_SHAPE;
-    if (!aligned(p, 16) || !aligned(sink, 4)) return VT_ERR_ALIGN;
-    (void)hipGetLastError();
-    vt::launch_stream_read(p, bytes, sink, static_cast<hipStream_t>(stream));
-    return launch_status();
 }
 
 }  // extern "C"

@@ -15,6 +15,7 @@
 // neighbour in the same word, whatever the id distribution.
 #include "vt_build.h"
 #include "vt_device.h"
+#include "vt_launch.h"
 
 namespace vt {
 
@@ -164,20 +165,10 @@ hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V
     const int nchunks = hist_num_chunks(n_ids, V);
     const int nranges = hist_num_ranges(V);
     const size_t lds = (size_t)kHistBinsPerBlock * sizeof(unsigned short);
-    static bool attr_set[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    static LdsLimitOnce lds_limit;
+    hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(hist_partial_kernel<false>),
+                                                 reinterpret_cast<const void *>(hist_partial_kernel<true>)}, (int)lds);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hist_partial_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hist_partial_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set[dev] = true;
-    }
     dim3 grid(nchunks, nranges);
     // ids before the first 16-byte boundary are counted one by one
     const int idb = ids64 ? 8 : 4;

@@ -19,9 +19,10 @@
 //     top-m, remap.  No second launch, no host round trip, no cache-wide fence.
 #pragma once
 #include "vt_device.h"
+#include "vt_launch.h"
 #include "vt_step.h"
-#include "vt_step_tail.cuh"
-#include "vt_tree_dev.cuh"
+#include "vt_step_tail.h"
+#include "vt_tree_dev.h"
 #include <type_traits>
 
 namespace vt {
@@ -367,7 +368,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
         return;
     }
     float *lse_buf = reinterpret_cast<float *>(reinterpret_cast<char *>(a.tickets) + kTicketBytes);
-    if (!arrive_and_elect(a.tickets, a.nblocks)) return;
+    if (!arrive_and_elect(a.tickets, a.nblocks, a.generation)) return;
     finalize_rows(a.pms, a.pkeys, a.nblocks, a.L, a.n, a.m, a.fin_conc, a.out_ids, a.out_logp, a.out_lse, lse_buf,
                   smem, w, lane, a.row_pack);
     if (a.tree_cum != nullptr) {
@@ -400,17 +401,9 @@ template <bool BF16, int NP, int CS>
 inline hipError_t launch_gemv_inst(const StepArgs &a, size_t lds, hipStream_t st) {
     auto kern = head_gemv_kernel<BF16, NP, CS>;
     // allow large dynamic LDS (finalize staging budget + headroom), once per device
-    static bool attr_set[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    static LdsLimitOnce lds_limit;
+    hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(kern)}, kMaxDynamicLds);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kMaxDynamicLds);
-        if (e != hipSuccess) return e;
-        attr_set[dev] = true;
-    }
     hipLaunchKernelGGL(kern, dim3(a.nblocks), dim3(kStepWaves * kWave), lds, st, a);
     return hipGetLastError();
 }

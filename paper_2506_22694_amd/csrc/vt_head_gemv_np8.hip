@@ -1,5 +1,5 @@
 // Instantiations of the small-n draft-step kernel for NP = 8 padded hidden rows.
-#include "vt_head_gemv.cuh"
+#include "vt_head_gemv_kernel.h"
 
 namespace vt {
 

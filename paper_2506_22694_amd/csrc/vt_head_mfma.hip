@@ -16,9 +16,10 @@
 //     the tile's best candidates per hidden row;
 //   * a second small kernel merges the tiles: one wave per hidden row.
 #include "vt_device.h"
+#include "vt_launch.h"
 #include "vt_step.h"
-#include "vt_step_tail.cuh"
-#include "vt_tree_dev.cuh"
+#include "vt_step_tail.h"
+#include "vt_tree_dev.h"
 #include <mutex>
 #include <type_traits>
 
@@ -93,6 +94,8 @@ head_mfma_kernel(const MfmaArgs a) {
 
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (a.ticket_clear != nullptr && blockIdx.x == 0 && threadIdx.x == 0)
+        __hip_atomic_store(a.ticket_clear, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // Small heads (up to 8 hidden rows only): with fewer than ~160 tiles of 128 rows the tiles shrink to
     // 16 * NW / KS rows and KS waves share a group of 16 rows, each taking 1 / KS of the columns; their partial
     // logits meet in the LDS tile of the epilogue, summed in wave order.
@@ -511,6 +514,8 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
 
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (a.ticket_clear != nullptr && blockIdx.x == 0 && threadIdx.x == 0)
+        __hip_atomic_store(a.ticket_clear, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int row0 = blockIdx.x * kMfmaTileRows;
     const int rows_b = min(kMfmaTileRows, a.k - row0);
     const size_t rs = (size_t)a.d * 2;
@@ -824,17 +829,9 @@ hipError_t launch_pack_h_impl(const MfmaArgs &a, int groups, hipStream_t st) {
 template <int NTW>
 hipError_t launch_mfma_wide_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
     auto kern = head_mfma_wide_kernel<NTW>;
-    static bool attr_set[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    static LdsLimitOnce lds_limit;
+    hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(kern)}, kMaxDynamicLds);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kMaxDynamicLds);
-        if (e != hipSuccess) return e;
-        attr_set[dev] = true;
-    }
     hipLaunchKernelGGL(kern, dim3(a.nlists), dim3(kStepWaves * kWave), lds, st, a);
     return hipGetLastError();
 }
@@ -842,17 +839,9 @@ hipError_t launch_mfma_wide_inst(const MfmaArgs &a, size_t lds, hipStream_t st) 
 template <int NT, int MAXW, bool XG = false>
 hipError_t launch_mfma_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
     auto kern = head_mfma_kernel<NT, MAXW, XG>;
-    static bool attr_set[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    static LdsLimitOnce lds_limit;
+    hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(kern)}, kMaxDynamicLds);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kMaxDynamicLds);
-        if (e != hipSuccess) return e;
-        attr_set[dev] = true;
-    }
     hipLaunchKernelGGL(kern, dim3(a.nlists), dim3((MAXW == kStepWaves ? kStepWaves : a.nwaves) * kWave), lds, st, a);
     return hipGetLastError();
 }
@@ -906,17 +895,9 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
 }
 
 hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t st) {
-    static bool attr_set[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    static LdsLimitOnce lds_limit;
+    hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(step_finalize_kernel)}, kMaxDynamicLds);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_finalize_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
-        if (e != hipSuccess) return e;
-        attr_set[dev] = true;
-    }
     if (f.tree_cum != nullptr) {
         // one hidden row per workgroup; LDS: the merge's staging, then the ranking's keys and counters
         const int N = f.n * f.m;
@@ -925,16 +906,11 @@ hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t s
         while (N2 < N) N2 <<= 1;
         const size_t need = (size_t)N2 * 12 + 256;
         const size_t bytes = lds > need ? lds : need;
-        static bool tree_attr_set[64] = {};
-        if (!tree_attr_set[dev]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_finalize_tree_kernel<64>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
-            if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_finalize_tree_kernel<512>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
-            if (e != hipSuccess) return e;
-            tree_attr_set[dev] = true;
-        }
+        static LdsLimitOnce tree_lds_limit;
+        e = allow_dynamic_lds(tree_lds_limit, {reinterpret_cast<const void *>(step_finalize_tree_kernel<64>),
+                                               reinterpret_cast<const void *>(step_finalize_tree_kernel<512>)},
+                              kMaxDynamicLds);
+        if (e != hipSuccess) return e;
         if (N <= kWave)
             hipLaunchKernelGGL(step_finalize_tree_kernel<64>, dim3(f.n), dim3(64), bytes, st, f);
         else

@@ -281,7 +281,10 @@ __global__ void __launch_bounds__(kRankSortThreads) choose_k_kernel(const long l
     if (blk == 0 && tid == 0) out[2] = total;
 
     if (mode == 0) {
-        const long long target = (long long)ceil(P * (double)total);     // one fp64 product, then its ceiling
+        // one fp64 product, then its ceiling; never above the total (beyond 2^53 tokens the product of P = 1
+        // can round up past it, and no prefix would reach it)
+        const long long want = (long long)ceil(P * (double)total);
+        const long long target = want > total ? total : want;
         // inclusive prefix of c inside the workgroup: wave scan, then the earlier waves' sums
         long long inc = c;
 #pragma unroll

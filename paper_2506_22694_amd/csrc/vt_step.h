@@ -50,7 +50,8 @@ struct StepArgs {
     int nblocks;
     unsigned long long *pms;    // [n, nblocks]  max | sumexp << 32
     unsigned long long *pkeys;  // [n, nblocks, L] candidate keys, sorted descending per list
-    unsigned *tickets;        // arrival counters (kTicketBytes), zero between calls
+    unsigned long long *tickets;     // arrival counters (kTicketBytes); any contents
+    unsigned long long generation;   // drawn afresh by the host for every launch, 1 <= generation < 2^48
     int *out_ids;             // [n, m]
     float *out_logp;          // [n, m]
     float *out_lse;           // [n] or null
@@ -110,6 +111,9 @@ struct MfmaArgs {
     // 128 + extra_rows rows, 1 <= extra_rows <= 16; the rows past the 128th form one more 16-row group whose
     // columns the eight waves share
     int extra_rows;
+    // or null: a word the kernel sets to zero (the merge kernel behind it counts its workgroups there when a tree
+    // level is fused; the kernel boundary orders the two)
+    unsigned *ticket_clear;
 };
 
 struct FinalizeArgs {
@@ -132,7 +136,7 @@ struct FinalizeArgs {
     int *tree_parent;
     int *tree_token;
     float *tree_score;
-    unsigned *ticket;          // one zero-initialised word; returns to zero
+    unsigned *ticket;          // one word, zeroed by the kernel that produced the lists (ticket_clear); returns to zero
 };
 constexpr int kFinalizeTreeMaxN = 512;
 

@@ -359,10 +359,33 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
 // ------------------------------------------------------------------ arrival
 // Two-level arrival counters (groups of 16 workgroups, then one counter for the
 // groups): same-address atomics are serialised at the memory side, so a single
-// counter would put ~256 of them on the critical path.  Counters return to
-// zero, so consecutive calls need no re-initialisation.
+// counter would put ~256 of them on the critical path.
+//
+// A counter is a 64-bit word, generation << 16 | arrivals.  The generation is a number the host draws afresh for
+// every launch, so whatever a counter holds when a launch begins -- the bytes of a fresh allocation, the count of
+// a launch that never finished, another shape's counters -- belongs to another generation and is recognised as
+// such: the workgroup that meets it replaces it by this launch's empty counter (compare-and-swap, repeated until
+// the word carries this generation) and arrives again.  Only the first arrivals of a launch take that detour;
+// the last one, whose answer everybody waits for, finds its generation in place.  The workspace therefore needs
+// no initialisation.  (A finished launch leaves zero behind, which no generation equals: a replayed graph,
+// whose launches repeat their generations, starts from a foreign word like any other launch.)
+__device__ __forceinline__ unsigned arrive(unsigned long long *counter, unsigned long long gen) {
+    unsigned long long old = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((old >> 16) != gen) {
+        for (;;) {
+            unsigned long long seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((seen >> 16) == gen) break;
+            if (__hip_atomic_compare_exchange_strong(counter, &seen, gen << 16, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT))
+                break;
+        }
+        // from here on the word carries this generation until the launch's last arrival: additions only
+        old = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return (unsigned)(old & 0xFFFFull);
+}
 // Returns true in exactly one workgroup: the last to arrive.
-__device__ __forceinline__ bool arrive_and_elect(unsigned *tickets, int nblocks) {
+__device__ __forceinline__ bool arrive_and_elect(unsigned long long *tickets, int nblocks, unsigned long long gen) {
     __shared__ int s_last;
     wait_stores_done();     // this wave's publications are acknowledged
     __syncthreads();        // ... and so are those of every other wave of the workgroup
@@ -370,14 +393,12 @@ __device__ __forceinline__ bool arrive_and_elect(unsigned *tickets, int nblocks)
         const int g = (int)blockIdx.x >> 4;
         const int ngroups = (nblocks + 15) >> 4;
         const int gsize = min(16, nblocks - (g << 4));
-        unsigned *gt = tickets + 16 * (1 + g);      // one 64-byte line per counter
+        unsigned long long *gt = tickets + 8 * (1 + g);      // one 64-byte line per counter
         int last = 0;
-        const unsigned v = __hip_atomic_fetch_add(gt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (v == (unsigned)(gsize - 1)) {
-            __hip_atomic_store(gt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const unsigned u = __hip_atomic_fetch_add(tickets, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (u == (unsigned)(ngroups - 1)) {
-                __hip_atomic_store(tickets, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (arrive(gt, gen) == (unsigned)(gsize - 1)) {
+            __hip_atomic_store(gt, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (arrive(tickets, gen) == (unsigned)(ngroups - 1)) {
+                __hip_atomic_store(tickets, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 last = 1;
             }
         }

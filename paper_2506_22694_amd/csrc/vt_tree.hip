@@ -13,7 +13,8 @@
 // key" is "better score, then lower index".
 #include "vt_tree.h"
 #include "vt_device.h"
-#include "vt_tree_dev.cuh"
+#include "vt_launch.h"
+#include "vt_tree_dev.h"
 
 namespace vt {
 
@@ -95,18 +96,10 @@ hipError_t launch_tree_select(const TreeArgs &a, hipStream_t st) {
     const int N2 = pow2_at_least(a.N, 2 * kTreeCountMaxN);
     const int K2 = pow2_at_least(a.K, 2);
     const size_t lds = (size_t)N2 * sizeof(unsigned long long);
-    static bool attr_set[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    static LdsLimitOnce lds_limit;
+    hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(tree_sort_kernel)},
+                                     (int)(kTreeMaxN * sizeof(unsigned long long)));
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(tree_sort_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(kTreeMaxN * sizeof(unsigned long long)));
-        if (e != hipSuccess) return e;
-        attr_set[dev] = true;
-    }
     hipLaunchKernelGGL(tree_sort_kernel, dim3(1), dim3(kTreeThreads), lds, st, a, N2, K2);
     return hipGetLastError();
 }

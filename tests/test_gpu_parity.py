@@ -643,10 +643,10 @@ def test_step_workspace_reuse_poison_and_determinism():
     first = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
     torch.cuda.synchronize()
     a_ids, a_lp = first[0].clone(), first[1].clone()
-    # poison everything behind the arrival counters (the first 2048 bytes, kept at zero by the
-    # library); the next call must not read stale partials
-    ws.buf[2048:] = 0xFF
-    for _ in range(3):
+    # poison the whole workspace, arrival counters included: the next call must neither read stale partials nor
+    # mistake the bytes for counts of its own
+    for fill in (0xFF, 0x00, 0x5A):
+        ws.buf[:] = fill
         oi, ol = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
         torch.cuda.synchronize()
         assert torch.equal(oi, a_ids) and torch.equal(ol, a_lp)
@@ -662,6 +662,105 @@ def test_step_workspace_reuse_poison_and_determinism():
     assert torch.equal(oi, a_ids) and torch.equal(ol, a_lp)
     ref = oracle.draft_head_step(h, W, map_, m)
     check_step(oi, ol, ref, map_, m)
+
+
+@pytest.mark.parametrize("k,d,n,m,tree", [(65536, 3072, 1, 1, False), (1000, 512, 2, 3, False), (4099, 264, 3, 4, True),
+                                          (32768, 3072, 8, 8, True), (32768, 2048, 40, 4, True)])
+def test_step_workspace_needs_no_initialisation(k, d, n, m, tree):
+    # shapes whose last workgroup is elected through the arrival counters at the head of the workspace (the small-n
+    # kernel's own merge; the tree level fused behind a merge kernel): whatever the workspace holds -- fresh
+    # bytes, all ones, text, the counters of other shapes -- the results are those of a zeroed workspace
+    W, map_ = synth.trimmed_head_direct(k, d, seed=15 + n, dtype="bf16")
+    h = synth.hidden_rows(n, d, seed=15 + n, dtype="bf16")
+    dW, dmap, dh = to_dev(W), to_dev(map_), to_dev(h)
+    cum = to_dev(np.linspace(-0.5, -3.0, n).astype(np.float32))
+    K = min(8, n * m)
+    ws = vt.StepWorkspace(n, k, d, m, dev())
+
+    def run():
+        if tree:
+            out = vt.draft_tree_level(dh, dW, dmap, m, cum, K, ws=ws)
+        else:
+            out = vt.draft_head_step(dh, dW, dmap, m, ws=ws)
+        torch.cuda.synchronize()
+        return [t.clone() for t in out]
+
+    ws.buf.zero_()
+    want = run()
+    ref = oracle.draft_head_step(h, W, map_, m)
+    check_step(want[-2], want[-1], ref, map_, m)
+    g = torch.Generator(device="cpu").manual_seed(99)
+    fills = [lambda b: b.fill_(0xFF), lambda b: b.fill_(0x01), lambda b: b.fill_(0x5A),
+             lambda b: b.copy_(torch.randint(0, 256, (b.numel(),), dtype=torch.uint8, generator=g)),
+             # words that look like small counts, as a counter of an unfinished launch would
+             lambda b: b.view(torch.int64)[:256].copy_(torch.arange(256, dtype=torch.int64) % 7)]
+    for fill in fills:
+        fill(ws.buf)
+        for _ in range(2):      # the second call meets what the first one left
+            got = run()
+            assert all(torch.equal(a, b) for a, b in zip(got, want))
+
+
+def test_soak_cross_workgroup_election_200k_steps_bit_identical():
+    # The cross-workgroup hand-over (partials written through to memory, arrival counters, the last workgroup
+    # reading everybody's partials past its caches) uses no cache-wide fence.  2 * 10^5 back-to-back steps on the
+    # paths that elect a last workgroup inside a kernel -- the small-n kernel's own merge (1 - 3 rows), the tree
+    # level fused into it, the tree level fused behind the matrix-core kernel's merge kernel -- with the shapes
+    # alternating on ONE workspace; every result is compared on the device, bit for bit, with the first result of
+    # its shape, and the first differing step (if any) is reported.
+    shapes = [(4099, 264, 3, 4, False), (1000, 512, 2, 3, False), (4099, 264, 3, 4, True), (9000, 1024, 1, 1, False),
+              (32768, 3072, 8, 8, True), (16384, 2048, 40, 4, True)]
+    weights = [60000, 60000, 40000, 30000, 5000, 5000]          # steps per shape: 2 * 10^5 in all
+    cases = []
+    ws_bytes = 0
+    L = vt.load_library()
+    for (k, d, n, m, tree) in shapes:
+        W, map_ = synth.trimmed_head_direct(k, d, seed=50 + n, dtype="bf16")
+        h = synth.hidden_rows(n, d, seed=50 + n, dtype="bf16")
+        cases.append((to_dev(h), to_dev(W), to_dev(map_), m, to_dev(np.linspace(-0.5, -3.0, n).astype(np.float32)),
+                      min(8, n * m), tree, h, W, map_))
+        ws_bytes = max(ws_bytes, L.vt_draft_head_step_ws_bytes(n, k, d, m))
+    ws = vt.StepWorkspace(1, 64, 64, 1, dev())
+    ws.buf = torch.empty(ws_bytes, dtype=torch.uint8, device=dev())      # one workspace for every shape
+    outs, wants = [], []
+    for (dh, dW, dmap, m, cum, K, tree, h, W, map_) in cases:
+        n = dh.shape[0]
+        o = {"ids": torch.empty((n, m), dtype=torch.int32, device=dev()),
+             "lp": torch.empty((n, m), dtype=torch.float32, device=dev()),
+             "tree": (torch.empty(K, dtype=torch.int32, device=dev()), torch.empty(K, dtype=torch.int32, device=dev()),
+                      torch.empty(K, dtype=torch.float32, device=dev()))}
+        outs.append(o)
+
+    def run(c):
+        (dh, dW, dmap, m, cum, K, tree, _, _, _) = cases[c]
+        o = outs[c]
+        if tree:
+            vt.draft_tree_level(dh, dW, dmap, m, cum, K, ws=ws, out=o["tree"], out_ids=o["ids"], out_logp=o["lp"])
+        else:
+            vt.draft_head_step(dh, dW, dmap, m, ws=ws, out_ids=o["ids"], out_logp=o["lp"])
+
+    for c in range(len(cases)):
+        run(c)
+        torch.cuda.synchronize()
+        o = outs[c]
+        wants.append([o["ids"].clone(), o["lp"].clone()] + ([t.clone() for t in o["tree"]] if cases[c][6] else []))
+        ref = oracle.draft_head_step(cases[c][7], cases[c][8], cases[c][9], cases[c][3])
+        check_step(o["ids"], o["lp"], ref, cases[c][9], cases[c][3])
+    order = np.random.Generator(np.random.PCG64(7)).permutation(np.repeat(np.arange(len(cases)), weights))
+    BIG = 1 << 40
+    first_bad = torch.full((), BIG, dtype=torch.int64, device=dev())
+    for step, c in enumerate(order.tolist()):
+        run(c)
+        o, wnt = outs[c], wants[c]
+        bad = (o["ids"] != wnt[0]).any() | (o["lp"] != wnt[1]).any()
+        if cases[c][6]:
+            bad = bad | (o["tree"][0] != wnt[2]).any() | (o["tree"][1] != wnt[3]).any() | (o["tree"][2] != wnt[4]).any()
+        first_bad = torch.minimum(first_bad, torch.where(bad, step, BIG))
+        if step % 20000 == 19999:          # stop at the first difference, within 20000 steps of it
+            fb = int(first_bad.item())
+            assert fb == BIG, f"step {fb} (shape {shapes[order[fb]]}) differs from the first result of its shape"
+    fb = int(first_bad.item())
+    assert fb == BIG, f"step {fb} (shape {shapes[order[fb]]}) differs from the first result of its shape"
 
 
 def test_error_statuses_on_device():
