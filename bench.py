@@ -381,7 +381,12 @@ def main():
             mstep(r, hor_mixed)
         us_split = time_region(lambda r: mstep(r, hor_split), 200)
         us_mixed = time_region(lambda r: mstep(r, hor_mixed), 200)
-        multi = {"heads": [k, kt], "rows_per_head": [n - n // 2, n // 2],
+        # Eq. 1 for both heads in one call (the selection is bound by its eleven launches, taken once for all heads)
+        counts2 = torch.stack([torch.randint(0, 50, (V,), device=dev, dtype=torch.int64) for _ in range(2)]).contiguous()
+        for _ in range(3):
+            vt.build_trimmed_heads(counts2, None, [k, kt])
+        us_sel2 = time_region(lambda r: vt.build_trimmed_heads(counts2, None, [k, kt]), 20)
+        multi = {"heads": [k, kt], "rows_per_head": [n - n // 2, n // 2], "select_both_heads_us": round(us_sel2, 2),
                  "consecutive_rows_us": round(us_split, 2), "alternating_rows_us": round(us_mixed, 2),
                  "bytes": (k + kt) * d * 2,
                  "gbps_consecutive": round((k + kt) * d * 2 / us_split / 1e3, 1)}

@@ -716,6 +716,28 @@ int vt_build_trimmed_heads(const int64_t *counts, int32_t V, int32_t n_heads, co
         if (map[hd] == nullptr || (W != nullptr && W_trim[hd] == nullptr)) return VT_ERR_NULL;
         if (ws_bytes < vt_build_trimmed_head_ws_bytes(V, d, k[hd])) return VT_ERR_WORKSPACE;
     }
+    // the checks of the single-head build, for every head
+    if (w_type != VT_F32 && w_type != VT_BF16) return VT_ERR_DTYPE;
+    if (d <= 0) return VT_ERR_SHAPE;
+    const size_t row_bytes = (size_t)d * elem_size(w_type);
+    if (!aligned(counts, 8)) return VT_ERR_ALIGN;
+    if (W != nullptr && ((row_bytes & 15) != 0 || !aligned(W, 16))) return VT_ERR_ALIGN;
+    for (int hd = 0; hd < n_heads; ++hd) {
+        if (!aligned(map[hd], 4) || (W != nullptr && !aligned(W_trim[hd], 16))) return VT_ERR_ALIGN;
+    }
+    if (ws == nullptr || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
+    static_assert(VT_MAX_HEADS == vt::kSelectMaxHeads, "heads per batched launch");
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (256 + (size_t)n_heads * vt::select_scratch_stride(V) <= ws_bytes) {
+        // all heads together: the selection's eleven launches and the row copy once, with the head as grid.y
+        // (the selection is bound by its launches: 60 us for one head or sixteen)
+        vt::launch_select_topk_heads(reinterpret_cast<const long long *>(counts), V, n_heads, k,
+                                     static_cast<char *>(ws) + 256, map, st);
+        if (W != nullptr)
+            vt::launch_gather_rows_heads(W, row_bytes, n_heads, k, const_cast<const int *const *>(map), W_trim, st);
+        return launch_status();
+    }
     for (int hd = 0; hd < n_heads; ++hd) {
         const int rc = vt_build_trimmed_head(counts + (size_t)hd * V, V, W, w_type, d, k[hd], map[hd],
                                              W != nullptr ? W_trim[hd] : nullptr, ws, ws_bytes, stream);

@@ -20,10 +20,17 @@ hipError_t launch_count_tokens(const void *ids, bool ids64, int64_t n_ids, int V
 
 // ---- Eq. 1 ----
 constexpr int kSelectThreads = 1024;
+constexpr int kSelectMaxHeads = 16;        // heads per batched launch (VT_MAX_HEADS)
 // scratch: select_scratch_bytes(V) of device memory, no initialisation
 size_t select_scratch_bytes(int V);
 void launch_select_topk(const long long *counts, int V, int k, void *scratch, int *map, hipStream_t st);
 void launch_gather_rows(const void *W, size_t row_bytes, const int *map, int k, void *W_trim, hipStream_t st);
+// several heads per launch sequence (grid.y = head): counts [n_heads, V]; scratch n_heads * select_scratch_stride(V)
+size_t select_scratch_stride(int V);
+void launch_select_topk_heads(const long long *counts, int V, int n_heads, const int *k, void *scratch, int *const *map,
+                              hipStream_t st);
+void launch_gather_rows_heads(const void *W, size_t row_bytes, int n_heads, const int *k, const int *const *map,
+                              void *const *W_trim, hipStream_t st);
 
 // ---- Sec. 3.2: frequency-rank order, Top-P / minimum-count choice of k ----
 constexpr int kRankSortThreads = 1024;

@@ -29,6 +29,23 @@ struct SelBufs {
     unsigned *tab;     // [nblk][2] ids above / at the threshold per workgroup
 };
 
+// Several heads per launch (grid.y = head): head y selects k[y] of the counts at counts + y V into map[y], with
+// the scratch of a single selection at scratch + y stride.
+struct SelBatch {
+    unsigned char *scratch;
+    size_t stride;
+    int nblk;
+    int k[kSelectMaxHeads];
+    int *map[kSelectMaxHeads];
+};
+__device__ __forceinline__ SelBufs head_bufs(const SelBatch &sb) {
+    SelBufs b;
+    b.gtot = reinterpret_cast<unsigned *>(sb.scratch + (size_t)blockIdx.y * sb.stride);
+    b.chist = b.gtot + kBytes * kDigits;
+    b.tab = b.chist + kBytes * kDigits;
+    return b;
+}
+
 // Every kernel first copies both histogram tables (16 KiB, contiguous in the scratch) into LDS: the walk
 // below reads them a few words at a time with each read depending on the previous choice.
 __device__ __forceinline__ void stage_tables(const SelBufs &b, unsigned *hs) {
@@ -101,12 +118,15 @@ __device__ __forceinline__ SelState sel_state(const unsigned *hs, int V, int k, 
     return s;
 }
 
-__global__ void __launch_bounds__(256) sel_zero_kernel(unsigned *p, int nwords) {
+__global__ void __launch_bounds__(256) sel_zero_kernel(SelBatch sb, int nwords) {
+    unsigned *p = head_bufs(sb).gtot;
     for (int i = blockIdx.x * 256 + threadIdx.x; i < nwords; i += gridDim.x * 256) p[i] = 0u;
 }
 
-__global__ void __launch_bounds__(kSelectThreads) sel_init_kernel(const long long *__restrict__ counts, int V,
-                                                                  SelBufs b) {
+__global__ void __launch_bounds__(kSelectThreads) sel_init_kernel(const long long *__restrict__ counts_all, int V,
+                                                                  SelBatch sb) {
+    const SelBufs b = head_bufs(sb);
+    const long long *__restrict__ counts = counts_all + (size_t)blockIdx.y * V;
     __shared__ unsigned h[kBytes * kDigits];
     for (int i = threadIdx.x; i < kBytes * kDigits; i += kSelectThreads) h[i] = 0u;
     __syncthreads();
@@ -133,8 +153,11 @@ __global__ void __launch_bounds__(kSelectThreads) sel_init_kernel(const long lon
     }
 }
 
-__global__ void __launch_bounds__(kSelectThreads) sel_hist_kernel(const long long *__restrict__ counts, int V, int k,
-                                                                  int p, SelBufs b) {
+__global__ void __launch_bounds__(kSelectThreads) sel_hist_kernel(const long long *__restrict__ counts_all, int V,
+                                                                  int p, SelBatch sb) {
+    const SelBufs b = head_bufs(sb);
+    const long long *__restrict__ counts = counts_all + (size_t)blockIdx.y * V;
+    const int k = sb.k[blockIdx.y];
     __shared__ unsigned h[kDigits];
     __shared__ unsigned hs[2 * kBytes * kDigits];
     stage_tables(b, hs);
@@ -159,8 +182,11 @@ __device__ __forceinline__ void sel_threshold(const unsigned *hs, int V, int k, 
     r = s.krem;
 }
 
-__global__ void __launch_bounds__(kSelectThreads) sel_count_kernel(const long long *__restrict__ counts, int V, int k,
-                                                                   SelBufs b) {
+__global__ void __launch_bounds__(kSelectThreads) sel_count_kernel(const long long *__restrict__ counts_all, int V,
+                                                                   SelBatch sb) {
+    const SelBufs b = head_bufs(sb);
+    const long long *__restrict__ counts = counts_all + (size_t)blockIdx.y * V;
+    const int k = sb.k[blockIdx.y];
     __shared__ int s_gt[kSelWaves], s_eq[kSelWaves];
     __shared__ unsigned hs[2 * kBytes * kDigits];
     stage_tables(b, hs);
@@ -187,8 +213,12 @@ __global__ void __launch_bounds__(kSelectThreads) sel_count_kernel(const long lo
     }
 }
 
-__global__ void __launch_bounds__(kSelectThreads) sel_write_kernel(const long long *__restrict__ counts, int V, int k,
-                                                                   SelBufs b, int *__restrict__ map) {
+__global__ void __launch_bounds__(kSelectThreads) sel_write_kernel(const long long *__restrict__ counts_all, int V,
+                                                                   SelBatch sb) {
+    const SelBufs b = head_bufs(sb);
+    const long long *__restrict__ counts = counts_all + (size_t)blockIdx.y * V;
+    const int k = sb.k[blockIdx.y];
+    int *__restrict__ map = sb.map[blockIdx.y];
     __shared__ int s_gt[kSelWaves + 1], s_eq[kSelWaves + 1];
     __shared__ int s_red[2 * kSelWaves];
     __shared__ unsigned hs[2 * kBytes * kDigits];
@@ -245,21 +275,48 @@ size_t select_scratch_bytes(int V) {
     return (2 * kBytes * kDigits + 2 * nblk) * sizeof(unsigned);
 }
 
-void launch_select_topk(const long long *counts, int V, int k, void *scratch, int *map, hipStream_t st) {
-    const int nblk = (V + kSelectThreads - 1) / kSelectThreads;
-    SelBufs b;
-    b.gtot = static_cast<unsigned *>(scratch);
-    b.chist = b.gtot + kBytes * kDigits;
-    b.tab = b.chist + kBytes * kDigits;
-    hipLaunchKernelGGL(sel_zero_kernel, dim3(4), dim3(256), 0, st, b.gtot, 2 * kBytes * kDigits);
-    hipLaunchKernelGGL(sel_init_kernel, dim3(nblk), dim3(kSelectThreads), 0, st, counts, V, b);
+size_t select_scratch_stride(int V) { return (select_scratch_bytes(V) + 255) / 256 * 256; }
+
+// counts: [n_heads, V]; scratch: n_heads * select_scratch_stride(V) bytes
+void launch_select_topk_heads(const long long *counts, int V, int n_heads, const int *k, void *scratch, int *const *map,
+                              hipStream_t st) {
+    SelBatch sb;
+    sb.scratch = static_cast<unsigned char *>(scratch);
+    sb.stride = select_scratch_stride(V);
+    sb.nblk = (V + kSelectThreads - 1) / kSelectThreads;
+    for (int hd = 0; hd < kSelectMaxHeads; ++hd) {
+        sb.k[hd] = hd < n_heads ? k[hd] : 1;
+        sb.map[hd] = hd < n_heads ? map[hd] : nullptr;
+    }
+    const dim3 grid(sb.nblk, n_heads);
+    hipLaunchKernelGGL(sel_zero_kernel, dim3(4, n_heads), dim3(256), 0, st, sb, 2 * kBytes * kDigits);
+    hipLaunchKernelGGL(sel_init_kernel, grid, dim3(kSelectThreads), 0, st, counts, V, sb);
     for (int p = kBytes - 2; p >= 0; --p)
-        hipLaunchKernelGGL(sel_hist_kernel, dim3(nblk), dim3(kSelectThreads), 0, st, counts, V, k, p, b);
-    hipLaunchKernelGGL(sel_count_kernel, dim3(nblk), dim3(kSelectThreads), 0, st, counts, V, k, b);
-    hipLaunchKernelGGL(sel_write_kernel, dim3(nblk), dim3(kSelectThreads), 0, st, counts, V, k, b, map);
+        hipLaunchKernelGGL(sel_hist_kernel, grid, dim3(kSelectThreads), 0, st, counts, V, p, sb);
+    hipLaunchKernelGGL(sel_count_kernel, grid, dim3(kSelectThreads), 0, st, counts, V, sb);
+    hipLaunchKernelGGL(sel_write_kernel, grid, dim3(kSelectThreads), 0, st, counts, V, sb);
 }
 
-// One wave copies one row at a time with 16-byte lanes; rows are independent.
+void launch_select_topk(const long long *counts, int V, int k, void *scratch, int *map, hipStream_t st) {
+    launch_select_topk_heads(counts, V, 1, &k, scratch, &map, st);
+}
+
+// One wave copies one row at a time with 16-byte lanes, four loads in flight; rows are independent.
+__device__ __forceinline__ void copy_row(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t nvec, int lane) {
+    size_t c = lane;
+    for (; c + 3 * kWave < nvec; c += 4 * kWave) {
+        const u32x4 a0 = __builtin_nontemporal_load(src + c);
+        const u32x4 a1 = __builtin_nontemporal_load(src + c + kWave);
+        const u32x4 a2 = __builtin_nontemporal_load(src + c + 2 * kWave);
+        const u32x4 a3 = __builtin_nontemporal_load(src + c + 3 * kWave);
+        __builtin_nontemporal_store(a0, dst + c);
+        __builtin_nontemporal_store(a1, dst + c + kWave);
+        __builtin_nontemporal_store(a2, dst + c + 2 * kWave);
+        __builtin_nontemporal_store(a3, dst + c + 3 * kWave);
+    }
+    for (; c < nvec; c += kWave) __builtin_nontemporal_store(__builtin_nontemporal_load(src + c), dst + c);
+}
+
 __global__ void __launch_bounds__(256) gather_rows_kernel(const char *__restrict__ W, size_t row_bytes,
                                                           const int *__restrict__ map, int k,
                                                           char *__restrict__ W_trim) {
@@ -268,21 +325,46 @@ __global__ void __launch_bounds__(256) gather_rows_kernel(const char *__restrict
     const int nwaves = (int)((gridDim.x * blockDim.x) >> 6);
     const size_t nvec = row_bytes >> 4;
     for (int j = wave; j < k; j += nwaves) {
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(W + (size_t)map[j] * row_bytes);
-        u32x4 *dst = reinterpret_cast<u32x4 *>(W_trim + (size_t)j * row_bytes);
-        size_t c = lane;
-        for (; c + 3 * kWave < nvec; c += 4 * kWave) {
-            const u32x4 a0 = __builtin_nontemporal_load(src + c);
-            const u32x4 a1 = __builtin_nontemporal_load(src + c + kWave);
-            const u32x4 a2 = __builtin_nontemporal_load(src + c + 2 * kWave);
-            const u32x4 a3 = __builtin_nontemporal_load(src + c + 3 * kWave);
-            __builtin_nontemporal_store(a0, dst + c);
-            __builtin_nontemporal_store(a1, dst + c + kWave);
-            __builtin_nontemporal_store(a2, dst + c + 2 * kWave);
-            __builtin_nontemporal_store(a3, dst + c + 3 * kWave);
-        }
-        for (; c < nvec; c += kWave) __builtin_nontemporal_store(__builtin_nontemporal_load(src + c), dst + c);
+        copy_row(reinterpret_cast<const u32x4 *>(W + (size_t)map[j] * row_bytes),
+                 reinterpret_cast<u32x4 *>(W_trim + (size_t)j * row_bytes), nvec, lane);
     }
+}
+
+// The same for several heads in one launch (grid.y = head).
+struct GatherBatch {
+    int k[kSelectMaxHeads];
+    const int *map[kSelectMaxHeads];
+    char *W_trim[kSelectMaxHeads];
+};
+__global__ void __launch_bounds__(256) gather_rows_heads_kernel(const char *__restrict__ W, size_t row_bytes,
+                                                                GatherBatch gb) {
+    const int lane = lane_id();
+    const int wave = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    const int nwaves = (int)((gridDim.x * blockDim.x) >> 6);
+    const size_t nvec = row_bytes >> 4;
+    const int k = gb.k[blockIdx.y];
+    const int *__restrict__ map = gb.map[blockIdx.y];
+    char *__restrict__ W_trim = gb.W_trim[blockIdx.y];
+    for (int j = wave; j < k; j += nwaves) {
+        copy_row(reinterpret_cast<const u32x4 *>(W + (size_t)map[j] * row_bytes),
+                 reinterpret_cast<u32x4 *>(W_trim + (size_t)j * row_bytes), nvec, lane);
+    }
+}
+
+void launch_gather_rows_heads(const void *W, size_t row_bytes, int n_heads, const int *k, const int *const *map,
+                              void *const *W_trim, hipStream_t st) {
+    GatherBatch gb;
+    int kmax = 1;
+    for (int hd = 0; hd < kSelectMaxHeads; ++hd) {
+        gb.k[hd] = hd < n_heads ? k[hd] : 0;
+        gb.map[hd] = hd < n_heads ? map[hd] : nullptr;
+        gb.W_trim[hd] = hd < n_heads ? static_cast<char *>(W_trim[hd]) : nullptr;
+        if (hd < n_heads && k[hd] > kmax) kmax = k[hd];
+    }
+    int blocks = (kmax + 3) / 4;          // 4 waves per workgroup
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(gather_rows_heads_kernel, dim3(blocks, n_heads), dim3(256), 0, st, static_cast<const char *>(W),
+                       row_bytes, gb);
 }
 
 void launch_gather_rows(const void *W, size_t row_bytes, const int *map, int k, void *W_trim, hipStream_t st) {

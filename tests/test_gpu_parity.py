@@ -1053,6 +1053,21 @@ def test_build_trimmed_heads_equals_head_by_head():
         assert np.array_equal(got, oracle.gather(W, want))
 
 
+def test_build_sixteen_heads_in_one_batch_llama_vocabulary():
+    # the most heads one call takes, over Llama-3's vocabulary: every k from 1 to V, counts with heavy ties
+    V, d, H = 128256, 64, 16
+    g = np.random.Generator(np.random.PCG64(64))
+    counts_np = np.stack([g.integers(0, 3 + 40 * j, size=V).astype(np.int64) * (1 + 1000 * (j % 3)) for j in range(H)])
+    ks = [1, 2, 37, 1000, 5000, 8192, 16384, 22786, 32768, 32975, 35010, 65536, 100000, 128255, 128256, 4099]
+    W = synth.head_weights(V, d, seed=809, dtype="bf16")
+    heads = vt.build_trimmed_heads(to_dev(counts_np), to_dev(W), ks)
+    torch.cuda.synchronize()
+    for j in range(H):
+        want = oracle.select(counts_np[j], ks[j])
+        assert np.array_equal(heads[j][0].cpu().numpy(), want), j
+        assert np.array_equal(from_bf16(heads[j][1]), oracle.gather(W, want)), j
+
+
 @pytest.mark.parametrize("k,d,n,m,K,dt", [(32768, 3072, 8, 8, 8, "bf16"), (4096, 512, 1, 1, 1, "bf16"),
                                           (5000, 1024, 8, 64, 60, "bf16"), (1000, 256, 4, 4, 16, "f32"),
                                           (2048, 2048, 3, 5, 7, "bf16"), (4096, 1024, 40, 8, 32, "bf16"),
