@@ -102,7 +102,7 @@ struct StepPlan {
     // workspace layout (byte offsets)
     size_t off_lse = 0, off_pms = 0, off_pkeys = 0, off_hpack = 0, off_zbuf = 0, bytes = 0;
     bool row_select = false;   // matrix-core path: logits stored, one workgroup per hidden row finishes
-    int extra_rows = 0;        // matrix-core path, up to 8 rows: tile rows past the 128th (shared by the eight waves)
+    int extra_rows = 0;        // matrix-core path: tile rows past the 128th (shared by the eight waves, or handed on)
 };
 
 using vt::kTicketBytes;
@@ -227,6 +227,14 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         while (16 * NT < n) NT *= 2;
         const bool var_waves = prefer_mfma && nwaves != vt::kStepWaves;
         const size_t stage = NT >= 8 ? vt::mfma_wide_lds_bytes() : vt::mfma_stage_bytes(var_waves ? nwaves : vt::kStepWaves);
+        // More than 8 hidden rows and 129 .. 144 rows per tile for one tile per CU (the paper's trimmed sizes again):
+        // tiles of exactly that many rows, the rows past the 128th multiplied in a closing pass (k = 32975, n = 64,
+        // d = 4096: 258 tiles of 128 rows took 104 us, a nearly empty second round).  The kernel is built for two
+        // and four groups of hidden rows: 9 .. 16 of them are padded to 32.
+        const int Rx = (k + CUS - 1) / CUS;
+        const bool closing_pass = n > vt::kGemvMaxN && NT <= 4 && d >= 1024 && Rx > vt::kMfmaTileRows &&
+                                  Rx <= vt::kMfmaTileRows + 16;
+        if (closing_pass && NT == 1) NT = 2;
         int KC = 128;   // NT >= 8: h is not staged at all (B-operands come from L2)
         if (NT < 8) {
             // up to 8 hidden rows occupy 8 rows of LDS (the other half of the 16-row operand repeats them)
@@ -255,14 +263,17 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.ksplit = (prefer_mfma && KC == d) ? ksplit : 1;
         p.nwaves = (prefer_mfma && KC == d) ? nwaves : vt::kStepWaves;
         p.extra_rows = (prefer_mfma && KC == d) ? extra_rows : 0;
+        if (closing_pass) p.extra_rows = Rx - vt::kMfmaTileRows;
         const int tile_rows = 16 * (p.nwaves / p.ksplit) + p.extra_rows;
         p.nlists = (k + tile_rows - 1) / tile_rows;
         p.L = m < tile_rows ? m : tile_rows;
         p.nblocks = p.nlists;
         p.lds = NT >= 8 ? stage : stage + (n <= 8 ? 8 : 16 * (size_t)NT) * p.hpitch;
         // logit tile of the epilogue + 4 x 16 candidate keys per wave behind it
-        size_t tile = (((size_t)p.ksplit * n * (vt::kMfmaTileRows + 1) * sizeof(float) + 15) & ~(size_t)15) +
-                      (size_t)vt::kStepWaves * 4 * 16 * sizeof(unsigned long long);
+        // (+ the closing pass's four range sums of 16 rows per hidden row)
+        size_t tile = (((size_t)p.ksplit * n * (vt::kMfmaTileRows + (closing_pass ? 17 : 1)) * sizeof(float) + 15) & ~(size_t)15) +
+                      (size_t)vt::kStepWaves * 4 * 16 * sizeof(unsigned long long) +
+                      (closing_pass ? (size_t)4 * n * 16 * sizeof(float) : 0);
         if (n <= vt::kStepWaves) {      // a wave per row: a candidate key per tile row and wave, not below 8 KiB
             const int tp = (p.extra_rows != 0 ? vt::kMfmaTileRows + 16 : p.nwaves == vt::kStepWaves ? vt::kMfmaTileRows : tile_rows) + 1;
             const size_t zt = ((size_t)p.ksplit * n * tp * sizeof(float) + 15) & ~(size_t)15;

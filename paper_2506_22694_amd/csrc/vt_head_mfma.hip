@@ -47,10 +47,10 @@ __device__ __forceinline__ void request_dword(int &dst, const int *p) {
     asm volatile("global_load_dword %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
 }
 template <int N>
-__device__ __forceinline__ void wait_ids(int (&b)[10]) {
-    asm volatile("s_waitcnt vmcnt(%10)"
+__device__ __forceinline__ void wait_ids(int (&b)[11]) {
+    asm volatile("s_waitcnt vmcnt(%11)"
                  : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7]),
-                   "+v"(b[8]), "+v"(b[9])
+                   "+v"(b[8]), "+v"(b[9]), "+v"(b[10])
                  : "n"(N));
 }
 constexpr int kMaxPieces = kMfmaChunkPieces;   // 16-byte pieces of an h chunk per thread
@@ -82,10 +82,28 @@ __device__ __forceinline__ void wait_unit(u32x4 (&b)[4]) {
 // 40.8 / 57.4; all rows cut into near-equal groups whose (group, part) tasks are dealt to the waves: 40.8 / 50.5;
 // nine waves of 16 rows on 229 CUs: 41.4 / 51.4; the small-n kernel: 41.8 / 51.7.  The planner uses it where rows
 // are not a multiple of 2 KiB.)
-template <int NT, int MAXW, bool XG = false>
+// XC (eight waves, more than 8 hidden rows -- h in LDS chunk by chunk, so the waves cannot split the columns
+// between them while they march: all of them need the same chunk at the same time): the same tile of
+// 128 + extra_rows rows.  The rows past the 128th are multiplied after the march, straight from global memory
+// (their part of W is a few rows, h sits in L2), one column range and one or two groups of hidden rows per wave.
+// Every logit of such a launch is formed from four column ranges, each accumulated from zero in ascending order,
+// as (R0 + R1) + (R2 + R3) -- the order the rotated march below already uses where rows are a multiple of 2 KiB
+// -- so the extra group goes through exactly the operations of a wave's own rows: equal rows give equal logits.
+// (Measured at k = 32975, n = 64, d = 4096, where k = 32768 takes 57 us: 258 tiles of 128 rows 104 us; the extra
+// group handed from wave to wave chunk by chunk inside the march, accumulators through LDS, 79 us -- the wave whose
+// turn it is streams twice as many units as the others, who wait at the chunk's barrier; this closing pass with
+// its operands loaded in matrix-core layout, 64-byte pieces of 16 rows per instruction, 75 us; with whole row
+// pieces staged through LDS 66 us, of which the pass is 7.5: every workgroup pulls all of h, 512 KiB, and a
+// third as much of W through its CU's 64 bytes per clock a second time, 5 us at best.  Four units per round trip
+// instead of two, or a third staging buffer per wave so that a unit costs two LDS round trips instead of six:
+// no gain, 66.5 to 68.5 us.)
+template <int NT, int MAXW, bool XG = false, bool XC = false>
 __global__ void __launch_bounds__(MAXW *kWave) __attribute__((amdgpu_waves_per_eu(1, (MAXW + 3) / 4)))
 head_mfma_kernel(const MfmaArgs a) {
     static_assert(!XG || (NT == 1 && MAXW == kStepWaves), "the shared row group is built for eight waves and one group of hidden rows");
+    static_assert(!XC || (!XG && MAXW == kStepWaves && (NT == 2 || NT == 4)),
+                  "the closing pass over the extra rows is built for eight waves and two or four groups of hidden rows");
+    constexpr bool XT = XG || XC;      // tiles of 128 + extra_rows rows
     extern __shared__ __align__(16) unsigned char smem[];
     const int NW = MAXW == kStepWaves ? kStepWaves : a.nwaves;     // waves of this workgroup
     unsigned char *stage = smem;                       // [waves][2][16][272]
@@ -100,7 +118,7 @@ head_mfma_kernel(const MfmaArgs a) {
     // 16 * NW / KS rows and KS waves share a group of 16 rows, each taking 1 / KS of the columns; their partial
     // logits meet in the LDS tile of the epilogue, summed in wave order.
     const int KS = NT == 1 ? a.ksplit : 1;
-    const int tile_rows = 16 * (NW / KS) + (XG ? a.extra_rows : 0);
+    const int tile_rows = 16 * (NW / KS) + (XT ? a.extra_rows : 0);
     const int rg = w / KS, ksi = w % KS;               // row group of the wave, its share of the columns
     const int row0 = blockIdx.x * tile_rows;
     const int rows_b = min(tile_rows, a.k - row0);
@@ -113,17 +131,18 @@ head_mfma_kernel(const MfmaArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int r = min(16 * rg + 4 * j + lgrp, rows_b - 1);
-        voff[j] = (unsigned)((size_t)r * rs + (size_t)lrow * 16);
+        // (24-bit factors: a 64-bit multiply-add here may name a register with a load in flight as its unused half)
+        voff[j] = __umul24((unsigned)r, (unsigned)(a.d * 2)) + (unsigned)lrow * 16u;
     }
     // the shared group: rows 128 .. of the tile (rows past its end repeat the last row)
     // (kept as the distance from the wave's own rows: choosing between two arrays by a run-time flag would put
     // both into scratch memory)
-    unsigned vdelta[XG ? 4 : 1];
-    if constexpr (XG) {
+    unsigned vdelta[XT ? 4 : 1];
+    if constexpr (XT) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = min(kMfmaTileRows + 4 * j + lgrp, rows_b - 1);
-            vdelta[j] = (unsigned)((size_t)r * rs + (size_t)lrow * 16) - voff[j];
+            vdelta[j] = __umul24((unsigned)r, (unsigned)(a.d * 2)) + (unsigned)lrow * 16u - voff[j];
         }
     }
     const char *Wt = static_cast<const char *>(a.W) + (size_t)row0 * rs;
@@ -141,8 +160,9 @@ head_mfma_kernel(const MfmaArgs a) {
     // ranges finish in the order rot, rot + 1, .. and the k-th to finish is added to set
     // {0, 0, 1, 1}[k] for an even start, {0, 1, 1, 0}[k] for an odd one, which pairs R0 with R1 and R2 with R3.
     // (Rows a multiple of 4 KiB apart are the ones that crowd; at d = 3072 the plain march is 0.6 us faster.)
-    const bool rotate = KS == 1 && nunits >= 8 && a.d % 2048 == 0;
-    const int rot = rotate ? ((int)blockIdx.x >> 3) & 3 : 0;
+    // (XC: the four ranges at any row length, the start rotated as everywhere only where it pays)
+    const bool rotate = KS == 1 && nunits >= 8 && (XC || a.d % 2048 == 0);
+    const int rot = (rotate && a.d % 2048 == 0) ? ((int)blockIdx.x >> 3) & 3 : 0;
     // first units of ranges 1..3.  When a quarter of a row is itself a multiple of 4 KiB (d = 8192) quarter starts
     // would crowd the same channels again: the boundaries are skewed by 1, 2 and 3 KiB (any fixed partition of the
     // columns keeps the rounding independent of the start)
@@ -269,23 +289,35 @@ head_mfma_kernel(const MfmaArgs a) {
     // (ids[2 ..]: rows lrow + 16 q for the four-rows-per-pass epilogue of more than 8 hidden rows; with up to
     // 12 waves or a shared row group -- up to 8 hidden rows, a wave per row -- ids[2] is the row lane + 128 of a tile
     // of up to 192 rows)
-    int ids[10];
-    request_dword(ids[0], a.map + row0 + min(lane, rows_b - 1));
-    request_dword(ids[1], a.map + row0 + min(lane + kWave, rows_b - 1));
+    // (With four groups of hidden rows and the handed-on extra rows there are no registers to spare for them during
+    // the contraction: that variant reads them afterwards.)
+    constexpr bool IDS_LATE = XC && NT == 4;
+    int ids[11];
+    if constexpr (!IDS_LATE) {
+        request_dword(ids[0], a.map + row0 + min(lane, rows_b - 1));
+        request_dword(ids[1], a.map + row0 + min(lane + kWave, rows_b - 1));
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
-        request_dword(ids[2 + q], a.map + row0 + min((MAXW > kStepWaves || XG) ? lane + 2 * kWave : lrow + 16 * q, rows_b - 1));
+        for (int q = 0; q < 9; ++q)
+            request_dword(ids[2 + q],
+                          a.map + row0 + min((MAXW > kStepWaves || XG) ? lane + 2 * kWave : lrow + 16 * q, rows_b - 1));
+    }
     fetch_chunk(0);                       // everything waits for it
 #pragma unroll
-    for (int x = 0; x < kPrefetchUnits; ++x) load_unit(x, areg[x]);
+    for (int x = 0; x < kPrefetchUnits; ++x) {
+        load_unit(x, areg[x]);
+    }
     wait_pieces<4 * kPrefetchUnits>(hp);  // the W prefetch stays in flight
-    wait_ids<4 * kPrefetchUnits>(ids);    // older than the chunk: they have landed too
+    if constexpr (!IDS_LATE) wait_ids<4 * kPrefetchUnits>(ids);    // older than the chunk: they have landed too
     store_chunk(0);
     __syncthreads();
-    const int id0 = ids[0], id1 = ids[1];
-    int idq[8];
+    int id0 = 0, id1 = 0;
+    int idq[9];
+    if constexpr (!IDS_LATE) {
+        id0 = ids[0];
+        id1 = ids[1];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) idq[q] = ids[2 + q];
+        for (int q = 0; q < 9; ++q) idq[q] = ids[2 + q];
+    }
 
 
     // Units are consumed in order; unit u sits in register slot u % kPrefetchUnits.  Between a hand-issued
@@ -373,6 +405,75 @@ head_mfma_kernel(const MfmaArgs a) {
     // prefetches past the last unit are still in flight: let them land before their registers die
 #pragma unroll
     for (int x = 0; x < kPrefetchUnits; ++x) wait_unit<0>(areg[x]);
+    // XC: the extra rows.  Wave w takes column range w % 4 and the groups of hidden rows w / 4 (+ 2), and repeats on
+    // them what the march did on its own rows: the same instructions in the same order on the same operand layout.
+    // Nothing hand-issued is in flight any more, so these are ordinary loads: whole 256-byte row pieces of W and,
+    // this time, of h as well (it is in L2; the chunk in LDS is long gone), both turned into operand layout
+    // through the wave's own staging buffers, XUB units per round trip.
+    constexpr int XGROUPS = XC ? NT / 2 : 1;
+    constexpr int XUB = NT == 2 ? 4 : 2;
+    f32x4 xacc[XGROUPS];
+    if constexpr (XC) {
+        const int q = w & 3;
+        const int ub = q == 0 ? 0 : q == 1 ? rb1 : q == 2 ? rb2 : rb3;
+        const int ue = q == 0 ? rb1 : q == 1 ? rb2 : q == 2 ? rb3 : nunits;
+        // (hidden rows past n repeat row n - 1: their columns of the result are never read)
+        unsigned boff[XGROUPS][4];
+        const char *hbase = static_cast<const char *>(a.h);
+#pragma unroll
+        for (int g = 0; g < XGROUPS; ++g) {
+            xacc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                boff[g][j] = __umul24((unsigned)min(16 * ((w >> 2) + 2 * g) + 4 * j + lgrp, a.n - 1), (unsigned)(a.d * 2)) +
+                             (unsigned)lrow * 16u;
+        }
+        unsigned char *sa = my_stage, *sb = my_stage + kStageUnitBytes;
+        for (int u0 = ub; u0 < ue; u0 += XUB) {
+            u32x4 ar[XUB][4], br[XUB][XGROUPS][4];
+#pragma unroll
+            for (int x = 0; x < XUB; ++x) {
+                const size_t col = (size_t)min(u0 + x, ue - 1) * (kUnitCols * 2);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    ar[x][j] = *reinterpret_cast<const u32x4 *>(Wt + col + (voff[j] + vdelta[j]));
+#pragma unroll
+                    for (int g = 0; g < XGROUPS; ++g)
+                        br[x][g][j] = *reinterpret_cast<const u32x4 *>(hbase + col + boff[g][j]);
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < XUB; ++x) {
+                if (u0 + x < ue) {
+                    u32x4 av[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(sa + 4 * j * kStagePitch + wr_off) = ar[x][j];
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) av[ks] = *reinterpret_cast<const u32x4 *>(sa + rd_off + ks * 64);
+#pragma unroll
+                    for (int g = 0; g < XGROUPS; ++g) {
+                        u32x4 bv[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            *reinterpret_cast<u32x4 *>(sb + 4 * j * kStagePitch + wr_off) = br[x][g][j];
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks) bv[ks] = *reinterpret_cast<const u32x4 *>(sb + rd_off + ks * 64);
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks)
+                            xacc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[ks]),
+                                                                              __builtin_bit_cast(bf16x8, bv[ks]),
+                                                                              xacc[g], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (IDS_LATE) {
+        id0 = a.map[row0 + min(lane, rows_b - 1)];
+        id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
+#pragma unroll
+        for (int q = 0; q < 9; ++q) idq[q] = a.map[row0 + min(lrow + 16 * q, rows_b - 1)];
+    }
 
     if constexpr (XG) {
         // acc[0]: the shared group's partial logits over this wave's column part; pair0[0]: the own rows' logits
@@ -385,7 +486,7 @@ head_mfma_kernel(const MfmaArgs a) {
 
     // ---- logits of this tile -> LDS tile zt[i][t] (aliases staging and h)
     __syncthreads();
-    const int tp = (XG ? kMfmaTileRows + 16 : MAXW == kStepWaves ? kMfmaTileRows : tile_rows) + 1;
+    const int tp = (XT ? kMfmaTileRows + 16 : MAXW == kStepWaves ? kMfmaTileRows : tile_rows) + 1;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int i = 16 * t + lrow;       // hidden row of this lane
@@ -396,6 +497,29 @@ head_mfma_kernel(const MfmaArgs a) {
             dst[1] = v.y;
             dst[2] = v.z;
             dst[3] = v.w;
+        }
+    }
+    if constexpr (XC) {
+        // the extra rows: the range sums xq[range][hidden row][16] behind the tile and its candidate keys, then the
+        // same two levels of additions as in the registers of the own rows
+        float *xq = reinterpret_cast<float *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15) +
+                                              kStepWaves * 4 * 16 * sizeof(unsigned long long));
+#pragma unroll
+        for (int g = 0; g < XGROUPS; ++g) {
+            const int i = 16 * ((w >> 2) + 2 * g) + lrow;
+            if (i < a.n) {
+                float *dst = xq + ((size_t)(w & 3) * a.n + i) * 16 + 4 * lgrp;
+                dst[0] = xacc[g].x;
+                dst[1] = xacc[g].y;
+                dst[2] = xacc[g].z;
+                dst[3] = xacc[g].w;
+            }
+        }
+        __syncthreads();
+        const size_t ps = (size_t)a.n * 16;      // from one range to the next
+        for (int e = (int)threadIdx.x; e < 16 * a.n; e += kStepWaves * kWave) {
+            const float *x = xq + e;
+            zt[(size_t)(e >> 4) * tp + kMfmaTileRows + (e & 15)] = (x[0] + x[ps]) + (x[2 * ps] + x[3 * ps]);
         }
     }
     if constexpr (XG) {
@@ -439,9 +563,16 @@ head_mfma_kernel(const MfmaArgs a) {
         unsigned long long *cand4 =
             reinterpret_cast<unsigned long long *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15)) +
             (size_t)w * 4 * 16;
-        for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
-            block_epilogue_rows4(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
-                                 a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
+        for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves) {
+            if constexpr (XC) {
+                block_epilogue_rows4<9>(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
+                                        a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
+            } else {
+                const int idq8[8] = {idq[0], idq[1], idq[2], idq[3], idq[4], idq[5], idq[6], idq[7]};
+                block_epilogue_rows4<8>(zt, tp, i0, a.n, rows_b, a.L, idq8, a.out_logp_full, (size_t)a.k, row0, a.pms,
+                                        a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
+            }
+        }
     } else {
         // a wave per hidden row (all of them at once for n <= 8); candidate keys of the threshold selection
         // sit behind the logit tile, 1 KiB per wave
@@ -744,8 +875,8 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
             reinterpret_cast<unsigned long long *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15)) +
             (size_t)w * 4 * 16;
         for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
-            block_epilogue_rows4(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
-                                 a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
+            block_epilogue_rows4<8>(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
+                                    a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
     } else {
         for (int i = w; i < a.n; i += kStepWaves) {
             const float *zrow = zt + (size_t)i * tp;
@@ -836,9 +967,9 @@ hipError_t launch_mfma_wide_inst(const MfmaArgs &a, size_t lds, hipStream_t st) 
     return hipGetLastError();
 }
 
-template <int NT, int MAXW, bool XG = false>
+template <int NT, int MAXW, bool XG = false, bool XC = false>
 hipError_t launch_mfma_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
-    auto kern = head_mfma_kernel<NT, MAXW, XG>;
+    auto kern = head_mfma_kernel<NT, MAXW, XG, XC>;
     static LdsLimitOnce lds_limit;
     hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(kern)}, kMaxDynamicLds);
     if (e != hipSuccess) return e;
@@ -867,22 +998,37 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
         (NT != 1 || a.n > 8 || a.KC < a.d || a.nwaves < a.ksplit || a.nwaves > kMfmaMaxWaves ||
          a.nwaves % a.ksplit != 0 || (size_t)a.d * 16 > (size_t)kMaxPieces * a.nwaves * kWave * 16))
         return hipErrorInvalidValue;
-    // rows past the 128th as a group shared by the eight waves: eight column parts of whole units, all of h in LDS
-    if (a.extra_rows != 0 &&
-        (a.extra_rows < 1 || a.extra_rows > 16 || NT != 1 || a.n > 8 || a.KC < a.d || a.ksplit != 1 ||
+    // rows past the 128th as one more group: shared by the eight waves during the march (up to 8 hidden rows: eight
+    // column parts of whole units, all of h in LDS) or multiplied after it (more hidden rows: two or four groups of
+    // them, rows of at least 8 units, the range sums behind the logit tile inside the launch's LDS)
+    const bool handed_on = a.extra_rows != 0 && a.n > 8;
+    if (a.extra_rows != 0 && !handed_on &&
+        (a.extra_rows < 1 || a.extra_rows > 16 || NT != 1 || a.KC < a.d || a.ksplit != 1 ||
          a.nwaves != kStepWaves || (a.d / kUnitCols) % 8 != 0))
+        return hipErrorInvalidValue;
+    if (handed_on &&
+        (a.extra_rows < 1 || a.extra_rows > 16 || NT < 2 || NT > 4 || a.ksplit != 1 || a.nwaves != kStepWaves ||
+         a.d / kUnitCols < 8 || (a.zbuf == nullptr && a.L > 16) ||
+         ((size_t)a.n * (kMfmaTileRows + 17) * sizeof(float) + 15) / 16 * 16 + kStepWaves * 4 * 16 * sizeof(unsigned long long) +
+                 (size_t)4 * a.n * 16 * sizeof(float) > lds))
         return hipErrorInvalidValue;
     {
         const int tile_rows = 16 * (a.nwaves / a.ksplit) + a.extra_rows;
         if (a.nlists != (a.k + tile_rows - 1) / tile_rows) return hipErrorInvalidValue;
     }
+    if ((size_t)a.d * 2 >= ((size_t)1 << 24)) return hipErrorInvalidValue;      // row offsets inside a tile: 24-bit factors
     switch (NT) {
         case 1:
+            if (handed_on) return hipErrorInvalidValue;      // planned with two groups of hidden rows
             if (a.extra_rows != 0) return launch_mfma_inst<1, kStepWaves, true>(a, lds, st);
             return a.nwaves == kStepWaves ? launch_mfma_inst<1, kStepWaves>(a, lds, st)
                                           : launch_mfma_inst<1, kMfmaMaxWaves>(a, lds, st);
-        case 2: return launch_mfma_inst<2, kStepWaves>(a, lds, st);
-        case 4: return launch_mfma_inst<4, kStepWaves>(a, lds, st);
+        case 2:
+            return handed_on ? launch_mfma_inst<2, kStepWaves, false, true>(a, lds, st)
+                             : launch_mfma_inst<2, kStepWaves>(a, lds, st);
+        case 4:
+            return handed_on ? launch_mfma_inst<4, kStepWaves, false, true>(a, lds, st)
+                             : launch_mfma_inst<4, kStepWaves>(a, lds, st);
         case 8:
         case 16: {
             if (a.hpack == nullptr) return hipErrorInvalidValue;

@@ -107,10 +107,12 @@ struct MfmaArgs {
     // waves per workgroup: kStepWaves, or (n <= 8, all of h in LDS, no zbuf) any multiple of ksplit up to
     // kMfmaMaxWaves, so that the tiles can be sized to cover the head in one round of at most 256 workgroups
     int nwaves;
-    // extra_rows != 0 (n <= 8, all of h in LDS, 8 waves, no column split, d a multiple of 1024): the tile is
-    // 128 + extra_rows rows, 1 <= extra_rows <= 16; the rows past the 128th form one more 16-row group whose
-    // columns the eight waves share
+    // extra_rows != 0 (8 waves, no column split): the tile is 128 + extra_rows rows, 1 <= extra_rows <= 16; the rows
+    // past the 128th form one more 16-row group -- up to 8 hidden rows (all of h in LDS, d a multiple of 1024) its
+    // columns are shared by the eight waves, with more hidden rows it is handed from wave to wave chunk by chunk
     int extra_rows;
+    // more than 8 hidden rows with extra_rows != 0: byte offset in the launch's LDS (behind the chunk of h, clear of the
+    // logit tile) of 6 * NT KiB in which the extra rows' accumulators are handed from wave to wave
     // or null: a word the kernel sets to zero (the merge kernel behind it counts its workgroups there when a tree
     // level is fused; the kernel boundary orders the two)
     unsigned *ticket_clear;

@@ -245,11 +245,12 @@ __device__ __forceinline__ void block_epilogue_large(const float *zrow, int S, i
 }
 
 // ------------------------------------------------------------------ four hidden rows per pass
-// Tiles of at most 128 logits per hidden row and L <= 16: the 16 lanes of DPP row g
-// rank hidden row i0 + g (8 logits per lane), so a wave finishes four hidden rows in
+// Tiles of at most 16 Q logits per hidden row (Q = 8: 128 rows, Q = 9: 144) and L <= 16: the 16 lanes of DPP row g
+// rank hidden row i0 + g (Q logits per lane), so a wave finishes four hidden rows in
 // the time of one.  zt: logit tile [hidden row][tp]; idq: ids of tile rows gl + 16 q.
+template <int Q>
 __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, int i0, int n, int rows_b, int L,
-                                                     const int (&idq)[8], float *__restrict__ logp_full, size_t k,
+                                                     const int (&idq)[Q], float *__restrict__ logp_full, size_t k,
                                                      int row0, unsigned long long *__restrict__ pms,
                                                      unsigned long long *__restrict__ pkeys, int nlists, int blk,
                                                      int lane, unsigned long long *cand) {
@@ -257,12 +258,12 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
     const int i = i0 + g;
     const bool active = i < n;
     const float *zrow = zt + (size_t)(active ? i : 0) * tp;
-    unsigned ord[8];
-    int id[8];
-    float zq[8];
+    unsigned ord[Q];
+    int id[Q];
+    float zq[Q];
     float lmax = -INFINITY;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < Q; ++q) {
         const int t = gl + 16 * q;
         ord[q] = 0u;
         id[q] = idq[q];
@@ -278,7 +279,7 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
     const float M = __uint_as_float(row16_allreduce_u32(__float_as_uint(lmax), OpMaxF32{}));
     float ls = 0.f;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) ls += __expf(zq[q] - M);
+    for (int q = 0; q < Q; ++q) ls += __expf(zq[q] - M);
     const float Ssum = __uint_as_float(row16_allreduce_u32(__float_as_uint(ls), OpAddF32{}));
     if (active && gl == 0)
         publish_u64(pms + (size_t)i * nlists + blk,
@@ -290,14 +291,14 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
         // candidates in any row of the wave (many equal logits; 3 in 1000 rows otherwise): the rounds below.
         unsigned bo = ord[0];
 #pragma unroll
-        for (int q = 1; q < 8; ++q) bo = ord[q] > bo ? ord[q] : bo;
+        for (int q = 1; q < Q; ++q) bo = ord[q] > bo ? ord[q] : bo;
         const int above = row16_count_greater(bo);      // lanes of the row with a strictly better best logit
         // the smallest best logit that fewer than L others beat is the L-th largest
         unsigned T = row16_allreduce_u32(above < L ? bo : 0xFFFFFFFFu, OpMinU32{});
         T = T == 0u ? 1u : T;   // fewer than L lanes have logits at all: every logit is a candidate
         int cnt = 0;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) cnt += ord[q] >= T ? 1 : 0;
+        for (int q = 0; q < Q; ++q) cnt += ord[q] >= T ? 1 : 0;
         unsigned incl = (unsigned)cnt;
         incl += dpp_mov<0x111>(incl);       // row_shr:1 (lanes without a source read 0)
         incl += dpp_mov<0x112>(incl);       // row_shr:2
@@ -309,7 +310,7 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
             crow[gl] = kNoKey;              // below every candidate: unused slots count for nothing
             int pos = (int)incl - cnt;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
+            for (int q = 0; q < Q; ++q) {
                 if (ord[q] >= T) crow[pos++] = ((unsigned long long)ord[q] << 32) | (unsigned)(~(unsigned)id[q]);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -332,16 +333,16 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
     for (int r = 0; r < L; ++r) {
         unsigned bo = ord[0];
 #pragma unroll
-        for (int q = 1; q < 8; ++q) bo = ord[q] > bo ? ord[q] : bo;
+        for (int q = 1; q < Q; ++q) bo = ord[q] > bo ? ord[q] : bo;
         const unsigned wmax = row16_allreduce_u32(bo, OpMaxU32{});
         unsigned myid = 0xFFFFFFFFu;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < Q; ++q) {
             if (ord[q] == wmax) myid = (unsigned)id[q] < myid ? (unsigned)id[q] : myid;
         }
         const unsigned wid = row16_allreduce_u32(myid, OpMinU32{});
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < Q; ++q) {
             if (ord[q] == wmax && (unsigned)id[q] == wid) ord[q] = 0u;
         }
         if (gl == r) {

@@ -299,25 +299,53 @@ def test_step_full_size_configs_every_logprob(k, d, n, m):
 PAPER_K = [22786, 32959, 32975, 33008, 35010]
 
 
-@pytest.mark.parametrize("k", PAPER_K)
-@pytest.mark.parametrize("n,d,m", [(1, 3072, 1), (8, 3072, 8), (64, 4096, 8)])
-def test_step_paper_trimmed_sizes_full_size(k, n, d, m):
+def _paper_size_case(k, n, d, m):
     W, map_ = synth.trimmed_head_direct(k, d, seed=k + n, dtype="bf16")
     h = synth.hidden_rows(n, d, seed=k + n, dtype="bf16")
     # exact ties planted in the ragged end of the head: the best row of hidden row 0 is copied over rows of the
-    # last 16-row group, of the group before it and of the first tile; the lowest target id must win every rank
-    z = oracle.logits(h[:1], W)
+    # last 16-row group, of the group before it and of the first tile -- among them row 128 and the last row of the
+    # second tile of ceil(k / 256) rows, which a tile of more than 128 rows treats apart from its first 128; the
+    # lowest target id must win every rank
+    z = oracle.logits(h[[0, n - 1]], W)
     j = int(np.argmax(z[0]))
-    for dst in (k - 1, k - 3, k - 17, k - 130, 5):
-        if dst != j:
-            W[dst] = W[j]
+    tile = -(-k // 256)
+    plants = [dst for dst in (k - 1, k - 3, k - 17, k - 130, 5, 128, 2 * tile - 1) if dst != j]
+    for dst in plants:
+        W[dst] = W[j]
+    # and the same for the last hidden row (another group of hidden rows from 17 rows on): its best row over the
+    # last and the second row of the fourth tile
+    plants2 = []
+    if n > 1:
+        z[1, plants + [j]] = -np.inf
+        j2 = int(np.argmax(z[1]))
+        plants2 = [dst for dst in (4 * tile - 1, 3 * tile + 1) if dst != j2 and dst != j and dst not in plants]
+        for dst in plants2:
+            W[dst] = W[j2]
     ref = oracle.draft_head_step(h, W, map_, m)
     oi, ol, lse, full = run_step(h, W, map_, m, return_lse=True, return_full=True)
-    t = min(m, 6)
+    t = min(m, len(plants) + 1)
     assert np.array_equal(oi.cpu().numpy()[0, :t], ref["ids"][0, :t])
     assert np.all(ol.cpu().numpy()[0, :t] == ol.cpu().numpy()[0, 0])
+    if plants2 and m >= 3:
+        assert np.array_equal(oi.cpu().numpy()[n - 1, :3], ref["ids"][n - 1, :3])
+        assert np.all(ol.cpu().numpy()[n - 1, :3] == ol.cpu().numpy()[n - 1, 0])
     assert check_step(oi, ol, ref, map_, m, lse) <= 2
     check_full(full, ref)
+
+
+@pytest.mark.parametrize("k", PAPER_K)
+@pytest.mark.parametrize("n,d,m", [(1, 3072, 1), (8, 3072, 8), (64, 4096, 8)])
+def test_step_paper_trimmed_sizes_full_size(k, n, d, m):
+    _paper_size_case(k, n, d, m)
+
+
+# more than 8 hidden rows at those sizes: 9 .. 16 rows (run as two groups of 16), two groups, three of four, and rows
+# that are not a multiple of 2 KiB
+@pytest.mark.parametrize("k,n,d,m", [(32975, 9, 4096, 4), (32975, 16, 4096, 8), (33008, 32, 4096, 8),
+                                     (35010, 48, 4096, 8), (32975, 64, 3072, 8), (32959, 24, 2048, 6),
+                                     (35010, 64, 4096, 16), (32975, 64, 8192, 8), (32975, 64, 1024, 8)])
+def test_step_paper_trimmed_sizes_many_hidden_rows(k, n, d, m):
+    _paper_size_case(k, n, d, m)
 
 
 @pytest.mark.parametrize("k,d,n,m", [(32768, 3072, 8, 8), (32975, 3072, 8, 8), (32768, 2048, 64, 8), (4099, 1024, 4, 4)])
