@@ -56,6 +56,54 @@ def test_workspace_sizes_are_pure_host_functions(lib):
     assert lib.vt_build_trimmed_head_ws_bytes(128256, 3072, 32768) >= 1
 
 
+VT_F32, VT_BF16 = binding.VT_F32, binding.VT_BF16
+VT_ERR_NULL, VT_ERR_SHAPE, VT_ERR_DTYPE = 1, 2, 3      # as in include/vocabtrim.h
+
+
+def _plan(lib, n, k, d, m, w_type=VT_BF16):
+    buf = ctypes.create_string_buffer(256)
+    lib.vt_draft_head_step_plan.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
+    lib.vt_draft_head_step_plan.restype = ctypes.c_int
+    rc = lib.vt_draft_head_step_plan(n, k, d, m, w_type, buf, 256)
+    return rc, buf.value.decode()
+
+
+def test_step_plan_is_a_pure_host_function_and_follows_the_head(lib):
+    # (no device here: the planner assumes 256 CUs)
+    # the benchmark's k: one tile of 128 rows per CU, eight waves
+    assert _plan(lib, 8, 32768, 3072, 8) == (
+        0, "head_mfma_kernel<1,8> workgroups=256 tile_rows=128 waves=8 column_split=1 + step_finalize_kernel")
+    # the paper's own trimmed sizes: tiles of exactly ceil(k / 256) rows, still one per CU -- the extra rows shared
+    # by the eight waves (rows a multiple of 1 KiB but not of 2 KiB), else nine waves
+    for k, rows in ((32959, 129), (32975, 129), (33008, 129), (35010, 137)):
+        for n, m in ((1, 1), (8, 8)):
+            rc, text = _plan(lib, n, k, 3072, m)
+            assert rc == 0 and f"head_mfma_kernel<1,8> workgroups=256 tile_rows={rows} waves=8" in text, text
+        rc, text = _plan(lib, 8, k, 4096, 8)
+        assert rc == 0 and "head_mfma_kernel<1,12>" in text and "tile_rows=144 waves=9" in text, text
+        # more than 8 hidden rows: the same tiles, two or four groups of hidden rows (9 .. 16 rows run as two)
+        for n, nt in ((9, 2), (16, 2), (32, 2), (33, 4), (64, 4)):
+            rc, text = _plan(lib, n, k, 4096, 8)
+            assert rc == 0 and f"head_mfma_kernel<{nt},8> workgroups=256 tile_rows={rows} waves=8" in text, text
+    # below one tile per CU nothing changes for more than 8 rows; small heads shrink their tiles instead
+    assert "head_mfma_kernel<4,8> workgroups=179 tile_rows=128" in _plan(lib, 64, 22786, 4096, 8)[1]
+    assert "tile_rows=32 waves=8 column_split=4" in _plan(lib, 8, 5000, 3072, 8)[1]
+    # more tiles than CUs at 144 rows each: ten and twelve waves
+    assert "tile_rows=160 waves=10" in _plan(lib, 8, 40000, 3072, 8)[1]
+    assert "tile_rows=192 waves=12" in _plan(lib, 8, 49152, 3072, 8)[1]
+    # beyond 256 x 192 rows, and fp32: the small-n kernel
+    assert _plan(lib, 8, 65536, 3072, 8)[1].startswith("head_gemv_kernel<bf16,8,")
+    assert _plan(lib, 4, 4096, 256, 4, VT_F32)[1].startswith("head_gemv_kernel<f32,4,")
+    # many hidden rows, many tokens per row
+    assert _plan(lib, 256, 32768, 8192, 16)[1] == (
+        "pack_h_kernel + head_mfma_wide_kernel<2> workgroups=256 tile_rows=128 + row_select_kernel")
+    # errors: shape, dtype, no buffer
+    assert _plan(lib, 0, 32768, 3072, 8)[0] == VT_ERR_SHAPE
+    assert _plan(lib, 8, 32768, 3072, 65)[0] == VT_ERR_SHAPE
+    assert _plan(lib, 8, 32768, 3072, 8, 7)[0] == VT_ERR_DTYPE
+    assert lib.vt_draft_head_step_plan(8, 32768, 3072, 8, VT_BF16, None, 0) == VT_ERR_NULL
+
+
 A = ctypes.c_void_p(0x10000)      # a well-aligned fake device address; never dereferenced on these paths
 ODD = ctypes.c_void_p(0x10004)
 
