@@ -102,7 +102,8 @@ struct StepPlan {
     // workspace layout (byte offsets)
     size_t off_lse = 0, off_pms = 0, off_pkeys = 0, off_hpack = 0, off_zbuf = 0, bytes = 0;
     bool row_select = false;   // matrix-core path: logits stored, one workgroup per hidden row finishes
-    int extra_rows = 0;        // matrix-core path: tile rows past the 128th (shared by the eight waves, or handed on)
+    int extra_rows = 0;        // matrix-core path: tile rows past the 128th (shared by the eight waves, or in LDS beside h)
+    int xoff = 0;              // ... more than 8 hidden rows: LDS offset of their accumulators
 };
 
 using vt::kTicketBytes;
@@ -228,21 +229,35 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         const bool var_waves = prefer_mfma && nwaves != vt::kStepWaves;
         const size_t stage = NT >= 8 ? vt::mfma_wide_lds_bytes() : vt::mfma_stage_bytes(var_waves ? nwaves : vt::kStepWaves);
         // More than 8 hidden rows and 129 .. 144 rows per tile for one tile per CU (the paper's trimmed sizes again):
-        // tiles of exactly that many rows, the rows past the 128th multiplied in a closing pass (k = 32975, n = 64,
-        // d = 4096: 258 tiles of 128 rows took 104 us, a nearly empty second round).  The kernel is built for two
-        // and four groups of hidden rows: 9 .. 16 of them are padded to 32.
+        // tiles of exactly that many rows (k = 32975, n = 64, d = 4096: 258 tiles of 128 rows took 104 us, a nearly
+        // empty second round).  With two groups of hidden rows (9 .. 16 rows are padded to 32) the columns of the rows
+        // past the 128th sit in LDS beside h's chunk (16 more rows) and their accumulators behind it (3 KiB per
+        // group); with four groups they are multiplied in a pass after the march (measured crossover: the kernel's
+        // comment has the figures).
         const int Rx = (k + CUS - 1) / CUS;
-        const bool closing_pass = n > vt::kGemvMaxN && NT <= 4 && d >= 1024 && Rx > vt::kMfmaTileRows &&
-                                  Rx <= vt::kMfmaTileRows + 16;
-        if (closing_pass && NT == 1) NT = 2;
+        const bool xany = n > vt::kGemvMaxN && NT <= 4 && d >= 1024 && Rx > vt::kMfmaTileRows &&
+                          Rx <= vt::kMfmaTileRows + 16;
+        if (xany && NT == 1) NT = 2;
+        const bool xrows = xany && NT == 2;      // ... in LDS beside the chunk
+        const bool xpass = xany && NT == 4;      // ... after the march
+        const size_t xbytes = xrows ? (size_t)3 * NT * 1024 : 0;
         int KC = 128;   // NT >= 8: h is not staged at all (B-operands come from L2)
         if (NT < 8) {
             // up to 8 hidden rows occupy 8 rows of LDS (the other half of the 16-row operand repeats them)
-            const size_t hrows = n <= 8 ? 8 : 16 * (size_t)NT;
-            const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage) / hrows;
+            const size_t hrows = (n <= 8 ? 8 : 16 * (size_t)NT) + (xrows ? 16 : 0);
+            const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage - xbytes) / hrows;
             if (hmax < 272) return p;
             KC = (int)(((hmax - 16) / 2) / 128) * 128;
-            const int kc_regs = (int)((vt::kMfmaChunkPieces * (var_waves ? nwaves : vt::kStepWaves) * 64 * 16) / (hrows * 2) / 128 * 128);
+            int kc_regs = (int)((vt::kMfmaChunkPieces * (var_waves ? nwaves : vt::kStepWaves) * 64 * 16) / (hrows * 2) / 128 * 128);
+            if (xrows) {
+                // the extra rows' pieces start at a piece number of their own behind h's
+                const int T = vt::kStepWaves * 64;
+                kc_regs = (kc_regs / 128 + 1) * 128;
+                do {
+                    kc_regs -= 128;
+                } while (kc_regs > 0 && (16 * NT * (kc_regs / 8) + T - 1) / T + (16 * (kc_regs / 8) + T - 1) / T > vt::kMfmaChunkPieces);
+                if (kc_regs <= 0) return p;
+            }
             if (KC > kc_regs) KC = kc_regs;   // the chunk must fit the register prefetch
             if (KC >= d) {
                 KC = d;
@@ -263,17 +278,22 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.ksplit = (prefer_mfma && KC == d) ? ksplit : 1;
         p.nwaves = (prefer_mfma && KC == d) ? nwaves : vt::kStepWaves;
         p.extra_rows = (prefer_mfma && KC == d) ? extra_rows : 0;
-        if (closing_pass) p.extra_rows = Rx - vt::kMfmaTileRows;
+        if (xany) p.extra_rows = Rx - vt::kMfmaTileRows;
         const int tile_rows = 16 * (p.nwaves / p.ksplit) + p.extra_rows;
         p.nlists = (k + tile_rows - 1) / tile_rows;
         p.L = m < tile_rows ? m : tile_rows;
         p.nblocks = p.nlists;
-        p.lds = NT >= 8 ? stage : stage + (n <= 8 ? 8 : 16 * (size_t)NT) * p.hpitch;
+        p.lds = NT >= 8 ? stage : stage + ((n <= 8 ? 8 : 16 * (size_t)NT) + (xrows ? 16 : 0)) * p.hpitch;
+        if (xrows) {
+            p.xoff = (int)((p.lds + 15) & ~(size_t)15);
+            p.lds = (size_t)p.xoff + xbytes;
+        }
         // logit tile of the epilogue + 4 x 16 candidate keys per wave behind it
-        // (+ the closing pass's four range sums of 16 rows per hidden row)
-        size_t tile = (((size_t)p.ksplit * n * (vt::kMfmaTileRows + (closing_pass ? 17 : 1)) * sizeof(float) + 15) & ~(size_t)15) +
+        // (+ the four range sums of 16 rows per hidden row that a pass after the march leaves)
+        size_t tile = (((size_t)p.ksplit * n * (vt::kMfmaTileRows + (xany ? 17 : 1)) * sizeof(float) + 15) & ~(size_t)15) +
                       (size_t)vt::kStepWaves * 4 * 16 * sizeof(unsigned long long) +
-                      (closing_pass ? (size_t)4 * n * 16 * sizeof(float) : 0);
+                      (xpass ? (size_t)4 * n * 16 * sizeof(float) : 0);
+        if (xrows && tile > (size_t)p.xoff) return p;      // (the extra rows' logits are read from behind the chunk into the tile)
         if (n <= vt::kStepWaves) {      // a wave per row: a candidate key per tile row and wave, not below 8 KiB
             const int tp = (p.extra_rows != 0 ? vt::kMfmaTileRows + 16 : p.nwaves == vt::kStepWaves ? vt::kMfmaTileRows : tile_rows) + 1;
             const size_t zt = ((size_t)p.ksplit * n * tp * sizeof(float) + 15) & ~(size_t)15;
@@ -951,6 +971,7 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.ksplit = p.ksplit;
         a.nwaves = p.nwaves;
         a.extra_rows = p.extra_rows;
+        a.xoff = p.xoff;
         a.ticket_clear = tf.cum != nullptr ? reinterpret_cast<unsigned *>(wsb) : nullptr;
         hipError_t e = vt::launch_head_mfma(p.NT, a, p.lds, st);
         if (e != hipSuccess) return device_status(e);

@@ -82,28 +82,37 @@ __device__ __forceinline__ void wait_unit(u32x4 (&b)[4]) {
 // 40.8 / 57.4; all rows cut into near-equal groups whose (group, part) tasks are dealt to the waves: 40.8 / 50.5;
 // nine waves of 16 rows on 229 CUs: 41.4 / 51.4; the small-n kernel: 41.8 / 51.7.  The planner uses it where rows
 // are not a multiple of 2 KiB.)
-// XC (eight waves, more than 8 hidden rows -- h in LDS chunk by chunk, so the waves cannot split the columns
+// XC != 0 (eight waves, more than 8 hidden rows -- h in LDS chunk by chunk, so the waves cannot split the columns
 // between them while they march: all of them need the same chunk at the same time): the same tile of
-// 128 + extra_rows rows.  The rows past the 128th are multiplied after the march, straight from global memory
-// (their part of W is a few rows, h sits in L2), one column range and one or two groups of hidden rows per wave.
-// Every logit of such a launch is formed from four column ranges, each accumulated from zero in ascending order,
-// as (R0 + R1) + (R2 + R3) -- the order the rotated march below already uses where rows are a multiple of 2 KiB
-// -- so the extra group goes through exactly the operations of a wave's own rows: equal rows give equal logits.
-// (Measured at k = 32975, n = 64, d = 4096, where k = 32768 takes 57 us: 258 tiles of 128 rows 104 us; the extra
-// group handed from wave to wave chunk by chunk inside the march, accumulators through LDS, 79 us -- the wave whose
-// turn it is streams twice as many units as the others, who wait at the chunk's barrier; this closing pass with
-// its operands loaded in matrix-core layout, 64-byte pieces of 16 rows per instruction, 75 us; with whole row
-// pieces staged through LDS 66 us, of which the pass is 7.5: every workgroup pulls all of h, 512 KiB, and a
-// third as much of W through its CU's 64 bytes per clock a second time, 5 us at best.  Four units per round trip
-// instead of two, or a third staging buffer per wave so that a unit costs two LDS round trips instead of six:
-// no gain, 66.5 to 68.5 us.)
-template <int NT, int MAXW, bool XG = false, bool XC = false>
+// 128 + extra_rows rows.  Every logit of such a launch is formed from four column ranges, each accumulated from
+// zero in ascending order, as (R0 + R1) + (R2 + R3) -- the order the rotated march below already uses where rows
+// are a multiple of 2 KiB -- and the extra group passes the same range boundaries with the same instructions on
+// the same operand layout: equal rows give equal logits.  Two ways to multiply the rows past the 128th:
+// XC == 1 (two groups of hidden rows): the chunk of h in LDS is followed by the same columns of those rows, fetched
+//   with it a chunk ahead; both operands of the extra group's products are then in LDS, in operand layout, and
+//   multiplying them takes no place in any wave's W stream.  After its own units of chunk c wave (c + t) mod 8 does
+//   that for hidden-row group t: 4 products per unit into an accumulator that lives in LDS between chunks, handed
+//   from wave to wave at the chunk's barriers.
+// XC == 2 (four groups): after the march, straight from global memory (their part of W is a few rows, h sits in
+//   L2), one column range and two groups of hidden rows per wave, whole 256-byte row pieces turned into operand
+//   layout through the wave's staging buffers.
+// (Measured at k = 32975, d = 4096, n = 64 / n = 32, where k = 32768 takes 57 / 51.5 us and these tiles without
+// the extra group's products 58.6 us at n = 64: 258 tiles of 128 rows 104 / 80.5 us; the extra group handed from
+// wave to wave as more units of the W stream 79 / 61.9 -- the wave whose turn it is streams twice as many units
+// as the others, who wait at the chunk's barrier; after the march 66 / 59.7, whatever its load pipeline (loads in
+// matrix-core layout: 75; more units in flight, fewer operand rows loaded, a third staging buffer: 66.5 to 68.5) --
+// every workgroup pulls all of h through its CU a second time, 134 MB at once over the L2s' 17 TB/s at n = 64;
+// from LDS beside the chunk 69 / 56.5 -- with four groups of hidden rows the march is bound by its LDS traffic,
+// to which the extra group adds a sixth, with two it is not.)
+template <int NT, int MAXW, bool XG = false, int XC = 0>
 __global__ void __launch_bounds__(MAXW *kWave) __attribute__((amdgpu_waves_per_eu(1, (MAXW + 3) / 4)))
 head_mfma_kernel(const MfmaArgs a) {
     static_assert(!XG || (NT == 1 && MAXW == kStepWaves), "the shared row group is built for eight waves and one group of hidden rows");
-    static_assert(!XC || (!XG && MAXW == kStepWaves && (NT == 2 || NT == 4)),
-                  "the closing pass over the extra rows is built for eight waves and two or four groups of hidden rows");
-    constexpr bool XT = XG || XC;      // tiles of 128 + extra_rows rows
+    static_assert(XC == 0 || (!XG && MAXW == kStepWaves && ((XC == 1 && NT == 2) || (XC == 2 && NT == 4))),
+                  "the extra row group in LDS is built for eight waves and two or four groups of hidden rows");
+    constexpr bool XT = XG || XC != 0;      // tiles of 128 + extra_rows rows
+    constexpr bool XL = XC == 1;            // the extra rows' columns in LDS beside the chunk of h
+    constexpr bool XP = XC == 2;            // the extra rows in a pass after the march
     extern __shared__ __align__(16) unsigned char smem[];
     const int NW = MAXW == kStepWaves ? kStepWaves : a.nwaves;     // waves of this workgroup
     unsigned char *stage = smem;                       // [waves][2][16][272]
@@ -161,7 +170,7 @@ head_mfma_kernel(const MfmaArgs a) {
     // {0, 0, 1, 1}[k] for an even start, {0, 1, 1, 0}[k] for an odd one, which pairs R0 with R1 and R2 with R3.
     // (Rows a multiple of 4 KiB apart are the ones that crowd; at d = 3072 the plain march is 0.6 us faster.)
     // (XC: the four ranges at any row length, the start rotated as everywhere only where it pays)
-    const bool rotate = KS == 1 && nunits >= 8 && (XC || a.d % 2048 == 0);
+    const bool rotate = KS == 1 && nunits >= 8 && (XC != 0 || a.d % 2048 == 0);
     const int rot = (rotate && a.d % 2048 == 0) ? ((int)blockIdx.x >> 3) & 3 : 0;
     // first units of ranges 1..3.  When a quarter of a row is itself a multiple of 4 KiB (d = 8192) quarter starts
     // would crowd the same channels again: the boundaries are skewed by 1, 2 and 3 KiB (any fixed partition of the
@@ -242,24 +251,33 @@ head_mfma_kernel(const MfmaArgs a) {
     u32x4 hp[kMaxPieces];
     // piece e = q * 512 + tid of a chunk is (hidden row e / ppr, 16-byte piece e % ppr); one division per
     // chunk, then a carry per step
+    // XC == 1: the pieces of h are followed, from a piece number of their own on, by those of the 16 extra rows (the same
+    // columns of W; rows past the tile's end repeat its last row), which land in LDS rows 16 NT .. behind h.
     auto fetch_chunk = [&](int c) {
         const int c0 = c * a.KC;
         const int ppr = min(a.KC, a.d - c0) >> 3;        // pieces per row
         const int step_r = (NW * kWave) / ppr, step_p = (NW * kWave) % ppr;
-        int r = (int)threadIdx.x / ppr, pc = (int)threadIdx.x % ppr;
+        const int r_first = (int)threadIdx.x / ppr, pc_first = (int)threadIdx.x % ppr;
+        int r = r_first, pc = pc_first;
+        const int qx = XL ? (16 * NT * ppr + NW * kWave - 1) / (NW * kWave) : kMaxPieces;      // first piece of the extra rows
         const int s0 = c * (a.KC / kUnitCols);           // first step of the chunk
         const char *hbase = static_cast<const char *>(a.h);
 #pragma unroll
         for (int q = 0; q < kMaxPieces; ++q) {
             hp[q] = u32x4{0u, 0u, 0u, 0u};
+            const bool extra = XL && q >= qx;            // (uniform)
+            if (XL && q == qx) {
+                r = r_first;
+                pc = pc_first;
+            }
             // 16 pieces per unit: piece pc belongs to step s0 + pc / 16
             int ua = hstart + s0 + (pc >> 4);
             ua = ua >= nunits ? ua - nunits : ua;
             // few hidden rows may be picked out of a larger batch (their indices are packed in row_pack)
-            const int hr = a.indexed ? (int)((a.row_pack >> (8 * (r & 7))) & 0xFFull) : r;
-            if (r < a.n)
-                cached_load16(hp[q], (unsigned)((size_t)hr * rs + (size_t)ua * (kUnitCols * 2) + (size_t)(pc & 15) * 16),
-                              hbase);
+            const int hr = extra ? min(kMfmaTileRows + r, rows_b - 1)
+                                 : a.indexed ? (int)((a.row_pack >> (8 * (r & 7))) & 0xFFull) : r;
+            const unsigned off = __umul24((unsigned)hr, (unsigned)(a.d * 2)) + (unsigned)ua * (kUnitCols * 2) + (unsigned)(pc & 15) * 16u;
+            if (r < (extra ? 16 : a.n)) cached_load16(hp[q], off, extra ? static_cast<const void *>(Wt) : static_cast<const void *>(hbase));
             r += step_r;
             pc += step_p;
             if (pc >= ppr) {
@@ -271,10 +289,18 @@ head_mfma_kernel(const MfmaArgs a) {
     auto store_chunk = [&](int c) {
         const int ppr = min(a.KC, a.d - c * a.KC) >> 3;
         const int step_r = (NW * kWave) / ppr, step_p = (NW * kWave) % ppr;
-        int r = (int)threadIdx.x / ppr, pc = (int)threadIdx.x % ppr;
+        const int r_first = (int)threadIdx.x / ppr, pc_first = (int)threadIdx.x % ppr;
+        int r = r_first, pc = pc_first;
+        const int qx = XL ? (16 * NT * ppr + NW * kWave - 1) / (NW * kWave) : kMaxPieces;
 #pragma unroll
         for (int q = 0; q < kMaxPieces; ++q) {
-            if (r < hrows) *reinterpret_cast<u32x4 *>(hbuf + (size_t)r * a.hpitch + pc * 16) = hp[q];
+            const bool extra = XL && q >= qx;
+            if (XL && q == qx) {
+                r = r_first;
+                pc = pc_first;
+            }
+            if (r < (extra ? 16 : hrows))
+                *reinterpret_cast<u32x4 *>(hbuf + (size_t)(extra ? 16 * NT + r : r) * a.hpitch + pc * 16) = hp[q];
             r += step_r;
             pc += step_p;
             if (pc >= ppr) {
@@ -291,7 +317,7 @@ head_mfma_kernel(const MfmaArgs a) {
     // of up to 192 rows)
     // (With four groups of hidden rows and the handed-on extra rows there are no registers to spare for them during
     // the contraction: that variant reads them afterwards.)
-    constexpr bool IDS_LATE = XC && NT == 4;
+    constexpr bool IDS_LATE = XC != 0 && NT == 4;
     int ids[11];
     if constexpr (!IDS_LATE) {
         request_dword(ids[0], a.map + row0 + min(lane, rows_b - 1));
@@ -377,13 +403,68 @@ head_mfma_kernel(const MfmaArgs a) {
     // Chunks that have a successor hold a multiple of kPrefetchUnits units (the host plans them so): the
     // next chunk is requested, whole rounds of units run without any test in between, and by then every
     // piece of the next chunk has 4 * kPrefetchUnits younger loads behind it.
+    // XC == 1: the extra group's accumulators live in LDS behind the chunk, [acc, pair0, pair1][hidden-row group][lane],
+    // and start at zero (the wave that has a group in the first chunk sets them).  extra_group(t, ..) multiplies the
+    // chunk's `count` units (march positions u_first ..) of the extra rows by hidden-row group t: the same operand
+    // layout, instructions and range boundaries as a wave's own rows in run_unit; t only selects LDS addresses.
+    f32x4 *xs = reinterpret_cast<f32x4 *>(smem + a.xoff);
+    auto extra_group = [&](int t, int count, int u_first, int xclosed, bool first, bool last) {
+        f32x4 *sacc = xs + (size_t)(0 * NT + t) * kWave + lane;
+        f32x4 *spair0 = xs + (size_t)(1 * NT + t) * kWave + lane;
+        f32x4 *spair1 = xs + (size_t)(2 * NT + t) * kWave + lane;
+        if (first) *sacc = *spair0 = *spair1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        f32x4 xa = *sacc;
+        const unsigned char *arow = hbuf + (size_t)(16 * NT + lrow) * a.hpitch + lgrp * 16;
+        const unsigned char *brow = hbuf + (size_t)(16 * t + lrow) * a.hpitch + lgrp * 16;
+        auto close = [&]() {
+            const bool to1 = (rot & 1) ? (xclosed == 1 || xclosed == 2) : xclosed >= 2;
+            f32x4 *dst = to1 ? spair1 : spair0;
+            *dst = *dst + xa;
+            xa = f32x4{0.f, 0.f, 0.f, 0.f};
+            ++xclosed;
+        };
+        // (a unit's h operands are on their way from LDS while the unit before it is multiplied)
+        u32x4 bv[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) bv[ks] = *reinterpret_cast<const u32x4 *>(brow + ks * 64);
+        for (int j = 0; j < count; ++j) {
+            u32x4 av[4], bn[4];
+            const size_t jn = (size_t)min(j + 1, count - 1) * (kUnitCols * 2);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                av[ks] = *reinterpret_cast<const u32x4 *>(arow + (size_t)j * (kUnitCols * 2) + ks * 64);
+                bn[ks] = *reinterpret_cast<const u32x4 *>(brow + jn + ks * 64);
+            }
+            const int xu = u_first + j;
+            if (xu > 0) {
+                const int ua = unit_of(xu);
+                if (ua == 0 || ua == rb1 || ua == rb2 || ua == rb3) close();
+            }
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                xa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[ks]),
+                                                             __builtin_bit_cast(bf16x8, bv[ks]), xa, 0, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bv[ks] = bn[ks];
+        }
+        if (last) {
+            close();
+            xa = *spair0 + *spair1;
+        }
+        *sacc = xa;
+    };
     for (int c = 0; c + 1 < nchunks; ++c) {
         fetch_chunk(c + 1);
+        const int u_first = u, closed_first = closed;
         int uc = 0;
         do {
 #pragma unroll
             for (int x = 0; x < kPrefetchUnits; ++x) run_unit(areg[x], uc++);
         } while (uc < units_per_chunk);
+        if constexpr (XL) {
+            const int t = (w - c) & 7;
+            if (t < NT) extra_group(t, units_per_chunk, u_first, closed_first, c == 0, false);
+        }
         wait_pieces<4 * kPrefetchUnits>(hp);
         __syncthreads();       // every wave is done with the current chunk
         store_chunk(c + 1);
@@ -391,6 +472,7 @@ head_mfma_kernel(const MfmaArgs a) {
     }
     // the last chunk: any number of units -- whole rounds, then the one or two that remain
     {
+        const int u_first = u, closed_first = closed;
         int uc = KS > 1 ? ustart : 0;      // position of the wave's first unit in h's LDS layout
         for (int rounds = (ntot - u) / kPrefetchUnits; rounds > 0; --rounds) {
 #pragma unroll
@@ -401,19 +483,23 @@ head_mfma_kernel(const MfmaArgs a) {
             run_unit(areg[0], uc++);
             if (u < ntot) run_unit(areg[1], uc++);
         }
+        if constexpr (XL) {
+            const int t = (w - (nchunks - 1)) & 7;
+            if (t < NT) extra_group(t, ntot - u_first, u_first, closed_first, nchunks == 1, true);
+        }
     }
     // prefetches past the last unit are still in flight: let them land before their registers die
 #pragma unroll
     for (int x = 0; x < kPrefetchUnits; ++x) wait_unit<0>(areg[x]);
-    // XC: the extra rows.  Wave w takes column range w % 4 and the groups of hidden rows w / 4 (+ 2), and repeats on
+    // XC == 2: the extra rows.  Wave w takes column range w % 4 and the groups of hidden rows w / 4 (+ 2), and repeats on
     // them what the march did on its own rows: the same instructions in the same order on the same operand layout.
     // Nothing hand-issued is in flight any more, so these are ordinary loads: whole 256-byte row pieces of W and,
     // this time, of h as well (it is in L2; the chunk in LDS is long gone), both turned into operand layout
     // through the wave's own staging buffers, XUB units per round trip.
-    constexpr int XGROUPS = XC ? NT / 2 : 1;
+    constexpr int XGROUPS = XP ? NT / 2 : 1;
     constexpr int XUB = NT == 2 ? 4 : 2;
     f32x4 xacc[XGROUPS];
-    if constexpr (XC) {
+    if constexpr (XP) {
         const int q = w & 3;
         const int ub = q == 0 ? 0 : q == 1 ? rb1 : q == 2 ? rb2 : rb3;
         const int ue = q == 0 ? rb1 : q == 1 ? rb2 : q == 2 ? rb3 : nunits;
@@ -499,7 +585,22 @@ head_mfma_kernel(const MfmaArgs a) {
             dst[3] = v.w;
         }
     }
-    if constexpr (XC) {
+    if constexpr (XL) {
+        // the extra rows' logits wait in LDS (behind the chunk, not under the tile) in accumulator layout: wave t
+        // copies those of hidden rows 16 t ..
+        if (w < NT) {
+            const f32x4 v = xs[(size_t)w * kWave + lane];
+            const int i = 16 * w + lrow;
+            if (i < a.n) {
+                float *dst = zt + (size_t)i * tp + kMfmaTileRows + 4 * lgrp;
+                dst[0] = v.x;
+                dst[1] = v.y;
+                dst[2] = v.z;
+                dst[3] = v.w;
+            }
+        }
+    }
+    if constexpr (XP) {
         // the extra rows: the range sums xq[range][hidden row][16] behind the tile and its candidate keys, then the
         // same two levels of additions as in the registers of the own rows
         float *xq = reinterpret_cast<float *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15) +
@@ -564,7 +665,7 @@ head_mfma_kernel(const MfmaArgs a) {
             reinterpret_cast<unsigned long long *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15)) +
             (size_t)w * 4 * 16;
         for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves) {
-            if constexpr (XC) {
+            if constexpr (XC != 0) {
                 block_epilogue_rows4<9>(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
                                         a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
             } else {
@@ -967,7 +1068,7 @@ hipError_t launch_mfma_wide_inst(const MfmaArgs &a, size_t lds, hipStream_t st) 
     return hipGetLastError();
 }
 
-template <int NT, int MAXW, bool XG = false, bool XC = false>
+template <int NT, int MAXW, bool XG = false, int XC = 0>
 hipError_t launch_mfma_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
     auto kern = head_mfma_kernel<NT, MAXW, XG, XC>;
     static LdsLimitOnce lds_limit;
@@ -998,20 +1099,33 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
         (NT != 1 || a.n > 8 || a.KC < a.d || a.nwaves < a.ksplit || a.nwaves > kMfmaMaxWaves ||
          a.nwaves % a.ksplit != 0 || (size_t)a.d * 16 > (size_t)kMaxPieces * a.nwaves * kWave * 16))
         return hipErrorInvalidValue;
-    // rows past the 128th as one more group: shared by the eight waves during the march (up to 8 hidden rows: eight
-    // column parts of whole units, all of h in LDS) or multiplied after it (more hidden rows: two or four groups of
-    // them, rows of at least 8 units, the range sums behind the logit tile inside the launch's LDS)
+    // rows past the 128th as one more group: shared by the eight waves (up to 8 hidden rows: eight column parts of
+    // whole units, all of h in LDS), multiplied from LDS beside h's chunk (two groups of hidden rows) or after the
+    // march (four groups); rows of at least 8 units
     const bool handed_on = a.extra_rows != 0 && a.n > 8;
     if (a.extra_rows != 0 && !handed_on &&
         (a.extra_rows < 1 || a.extra_rows > 16 || NT != 1 || a.KC < a.d || a.ksplit != 1 ||
          a.nwaves != kStepWaves || (a.d / kUnitCols) % 8 != 0))
         return hipErrorInvalidValue;
     if (handed_on &&
-        (a.extra_rows < 1 || a.extra_rows > 16 || NT < 2 || NT > 4 || a.ksplit != 1 || a.nwaves != kStepWaves ||
-         a.d / kUnitCols < 8 || (a.zbuf == nullptr && a.L > 16) ||
-         ((size_t)a.n * (kMfmaTileRows + 17) * sizeof(float) + 15) / 16 * 16 + kStepWaves * 4 * 16 * sizeof(unsigned long long) +
-                 (size_t)4 * a.n * 16 * sizeof(float) > lds))
+        (a.extra_rows < 1 || a.extra_rows > 16 || (NT != 2 && NT != 4) || a.ksplit != 1 || a.nwaves != kStepWaves ||
+         a.d / kUnitCols < 8 || (a.zbuf == nullptr && a.L > 16)))
         return hipErrorInvalidValue;
+    const size_t xtile = ((size_t)a.n * (kMfmaTileRows + 17) * sizeof(float) + 15) / 16 * 16 +
+                         kStepWaves * 4 * 16 * sizeof(unsigned long long);      // logit tile and candidate keys of the epilogue
+    if (handed_on && NT == 2) {
+        // the chunk and the extra rows' pieces fit the register prefetch; the accumulators' LDS lies behind the chunk,
+        // inside the launch's LDS and clear of the logit tile
+        const int ppr = min(a.KC, a.d) >> 3;
+        const int qx = (16 * NT * ppr + kStepWaves * kWave - 1) / (kStepWaves * kWave);
+        const int xpieces = (16 * ppr + kStepWaves * kWave - 1) / (kStepWaves * kWave);
+        if (qx + xpieces > kMaxPieces || (a.xoff & 15) != 0 ||
+            (size_t)a.xoff < (size_t)kStageBytes + (size_t)(16 * NT + 16) * a.hpitch ||
+            (size_t)a.xoff + (size_t)3 * NT * kWave * sizeof(f32x4) > lds || xtile > (size_t)a.xoff)
+            return hipErrorInvalidValue;
+    }
+    // (four groups: the pass after the march leaves its four range sums per logit behind the tile)
+    if (handed_on && NT == 4 && xtile + (size_t)4 * a.n * 16 * sizeof(float) > lds) return hipErrorInvalidValue;
     {
         const int tile_rows = 16 * (a.nwaves / a.ksplit) + a.extra_rows;
         if (a.nlists != (a.k + tile_rows - 1) / tile_rows) return hipErrorInvalidValue;
@@ -1024,10 +1138,10 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
             return a.nwaves == kStepWaves ? launch_mfma_inst<1, kStepWaves>(a, lds, st)
                                           : launch_mfma_inst<1, kMfmaMaxWaves>(a, lds, st);
         case 2:
-            return handed_on ? launch_mfma_inst<2, kStepWaves, false, true>(a, lds, st)
+            return handed_on ? launch_mfma_inst<2, kStepWaves, false, 1>(a, lds, st)
                              : launch_mfma_inst<2, kStepWaves>(a, lds, st);
         case 4:
-            return handed_on ? launch_mfma_inst<4, kStepWaves, false, true>(a, lds, st)
+            return handed_on ? launch_mfma_inst<4, kStepWaves, false, 2>(a, lds, st)
                              : launch_mfma_inst<4, kStepWaves>(a, lds, st);
         case 8:
         case 16: {

@@ -109,10 +109,11 @@ struct MfmaArgs {
     int nwaves;
     // extra_rows != 0 (8 waves, no column split): the tile is 128 + extra_rows rows, 1 <= extra_rows <= 16; the rows
     // past the 128th form one more 16-row group -- up to 8 hidden rows (all of h in LDS, d a multiple of 1024) its
-    // columns are shared by the eight waves, with more hidden rows it is handed from wave to wave chunk by chunk
+    // columns are shared by the eight waves; with more hidden rows their columns follow h's chunk in LDS (16 more
+    // rows of hpitch bytes) and their accumulators live in 3 * NT KiB of LDS at byte offset xoff (behind the chunk,
+    // clear of the logit tile of the epilogue, inside the launch's LDS)
     int extra_rows;
-    // more than 8 hidden rows with extra_rows != 0: byte offset in the launch's LDS (behind the chunk of h, clear of the
-    // logit tile) of 6 * NT KiB in which the extra rows' accumulators are handed from wave to wave
+    int xoff;
     // or null: a word the kernel sets to zero (the merge kernel behind it counts its workgroups there when a tree
     // level is fused; the kernel boundary orders the two)
     unsigned *ticket_clear;

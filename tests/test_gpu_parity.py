@@ -402,12 +402,14 @@ def test_step_many_rows_mid_size(n, d):
     check_step(oi, ol, ref, map_, m, lse)
 
 
-def test_step_llama8b_tree_64_nodes_1000_consecutive_steps():
+@pytest.mark.parametrize("k", [32768, 32975])
+def test_step_llama8b_tree_64_nodes_1000_consecutive_steps(k):
     # 1000 consecutive steps on one workspace, hidden rows cycling over 16 blocks (step s uses block s % 16) and
     # W_trim over 4 device copies, as the benchmark does.  Steps 0, 1, 2, 499, 998 and 999 are kept and compared
     # with the oracle element by element; every other step must repeat the bits of the kept step of its block
     # (a running check on the device), and the remaining blocks are oracle-checked through their first step.
-    k, d, n, m, nsteps, nblk = 32768, 4096, 64, 8, 1000, 16
+    # (k = 32975, the 3B EAGLE drafter's trimmed size: tiles of 129 rows, the 129th in the kernel's closing pass)
+    d, n, m, nsteps, nblk = 4096, 64, 8, 1000, 16
     W, map_ = synth.trimmed_head_direct(k, d, seed=4000, dtype="bf16")
     copies = [to_dev(W)]
     copies += [copies[0].clone() for _ in range(3)]
