@@ -482,14 +482,15 @@ def main():
         cases = [("llama1b chain", 2048, 32768, 1, 1), ("llama1b full-vocab control", 2048, 128256, 1, 1),
                  ("task head (xLAM-sized vocabulary)", 3072, 5000, 8, 8),
                  ("llama3b full-vocab control", 3072, 128256, 8, 8),
-                 ("llama8b tree", 4096, 32768, 64, 8), ("stress", 8192, 32768, 256, 16)]
+                 ("llama8b tree, 32 nodes", 4096, 32768, 32, 8), ("llama8b tree", 4096, 32768, 64, 8),
+                 ("stress", 8192, 32768, 256, 16)]
         for name, dd, kk, nn, mm in cases:
             others += time_shapes(dd, kk, [(nn, mm)], 77, names=[name], max_copies=12)
         # the paper's own trimmed sizes (head sizes of its main tables / hidden size; sweet spots of its ablation over k)
         paper_k = []
         for kk in (22786, 32959, 32975, 33008, 35010):
             paper_k += time_shapes(3072, kk, [(1, 1), (8, 8)], 91, names=["3B-shaped head"] * 2)
-            paper_k += time_shapes(4096, kk, [(64, 8)], 92, names=["8B-shaped head, tree"])
+            paper_k += time_shapes(4096, kk, [(32, 8), (64, 8)], 92, names=["8B-shaped head, tree"] * 2)
 
     # ------------------------------------------------------------------ CPU baseline (the oracle, untuned)
     cpu = None
