@@ -1130,6 +1130,39 @@ def test_draft_tree_level_equals_step_then_expand(k, d, n, m, K, dt):
         assert np.array_equal(score.cpu().numpy(), rs)
 
 
+def test_random_shapes_around_one_tile_per_cu():
+    # seeded sweep over heads that are not a multiple of 256 x 128 rows: 129 .. 144 rows per tile (the paper's trimmed
+    # sizes lie here), 145 .. 192 and fewer than 128, any d that is a multiple of 128, 1 .. 64 hidden rows; exact ties
+    # planted across the row groups of a tile (own rows, the rows past the 128th, the ragged end); every logit and
+    # every token against the oracle
+    rng = np.random.default_rng(32975)
+    kernels = set()
+    for it in range(36):
+        r = rng.random()
+        k = int(rng.integers(32769, 36865)) if r < 0.5 else int(rng.integers(36865, 49153)) if r < 0.75 else \
+            int(rng.integers(12000, 32769))
+        d = 128 * int(rng.choice([8, 16, 24, 32, 12, 20, 48, int(rng.integers(1, 33))]))
+        n = int(rng.choice([1, 3, 8, 9, 12, 16, 17, 24, 32, 33, 48, 64]))
+        if k * d * n > 5e9:
+            n = max(1, int(5e9 // (k * d)))
+        m = int(rng.choice([1, 4, 8, 8, 11, 12, 16, int(rng.integers(1, 33))]))
+        W, map_ = synth.trimmed_head_direct(k, d, seed=5000 + it, dtype="bf16")
+        h = synth.hidden_rows(n, d, seed=6000 + it, dtype="bf16")
+        tile = -(-k // 256)
+        if rng.random() < 0.6:
+            j = int(np.argmax(oracle.logits(h[:1], W)[0]))
+            for dst in (5, 128, tile - 1, 3 * tile + 128, 7 * tile - 1, k - 1, k - 17, int(rng.integers(0, k))):
+                if 0 <= dst < k and dst != j:
+                    W[dst] = W[j]
+        kernels.add(vt.draft_head_step_plan(n, k, d, m).split(" workgroups")[0])
+        ref = oracle.draft_head_step(h, W, map_, m)
+        oi, ol, lse, full = run_step(h, W, map_, m, return_lse=True, return_full=True)
+        assert check_step(oi, ol, ref, map_, m, lse) <= 2, (it, k, d, n, m)
+        check_full(full, ref)
+    # the sweep reaches every kernel that serves such heads
+    assert {"head_mfma_kernel<1,8>", "head_mfma_kernel<1,12>", "head_mfma_kernel<2,8>", "head_mfma_kernel<4,8>"} <= kernels
+
+
 def test_random_shapes_sweep_step_tree_level_and_build():
     # seeded sweep over shapes no other test names: sizes around the tile / wave / group boundaries, both element
     # types, planted exact ties; every case against the oracle (step, fused tree level, both build orders, choice of k)
