@@ -172,12 +172,19 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         }
         // more or fewer waves than eight where that measured faster than the choices below (n = 8, d = 3072:
         // k = 40000, ten waves: 46.4 against 47.5 us; 49152, twelve: 53.6 / 55.1; 20000, five groups of two: 29.1 / 29.7;
-        // seven waves and six groups of two measured slower; nine waves: see above)
+        // six groups of two measured slower; nine waves: see above)
         if (ksplit == 0 && G == 9 && feasible(1, G)) {
             ksplit = 1;
             nwaves = G;
         }
         if (ksplit == 0 && G >= 10 && feasible(1, G)) {
+            ksplit = 1;
+            nwaves = G;
+        }
+        // six waves of 16 rows (k = 20481 .. 24576: 214 - 256 tiles instead of 160 - 192 of 128 rows) pay for up to 4
+        // hidden rows, seven for one (k = 22786, d = 3072: n = 1 27.4 against 28.2 us, n = 2 27.5 / 28.4, n = 4 30.8 /
+        // 31.2, n = 8 32.2 / 31.7; d = 2048, n = 1: 20.6 / 21.9; k = 26000, n = 1: 29.9 / 30.1, n = 2: a tie)
+        if (ksplit == 0 && ((G == 6 && n <= 4) || (G == 7 && n == 1)) && feasible(1, G)) {
             ksplit = 1;
             nwaves = G;
         }

@@ -339,6 +339,14 @@ def test_step_paper_trimmed_sizes_full_size(k, n, d, m):
     _paper_size_case(k, n, d, m)
 
 
+# few hidden rows on heads of 20 .. 28 thousand rows: tiles of six and seven waves
+@pytest.mark.parametrize("k,n,d,m", [(22786, 2, 3072, 8), (22786, 4, 3072, 8), (24576, 1, 2048, 1), (26000, 1, 3072, 1),
+                                     (28672, 1, 3072, 8), (20481, 3, 3072, 4)])
+def test_step_six_and_seven_wave_tiles(k, n, d, m):
+    assert "waves=6" in vt.draft_head_step_plan(n, k, d, m) or "waves=7" in vt.draft_head_step_plan(n, k, d, m)
+    _paper_size_case(k, n, d, m)
+
+
 # more than 8 hidden rows at those sizes: 9 .. 16 rows (run as two groups of 16), two groups, three of four, and rows
 # that are not a multiple of 2 KiB
 @pytest.mark.parametrize("k,n,d,m", [(32975, 9, 4096, 4), (32975, 16, 4096, 8), (33008, 32, 4096, 8),
