@@ -234,7 +234,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         int NT = 1;
         while (16 * NT < n) NT *= 2;
         const bool var_waves = prefer_mfma && nwaves != vt::kStepWaves;
-        const size_t stage = NT >= 8 ? vt::mfma_wide_lds_bytes() : vt::mfma_stage_bytes(var_waves ? nwaves : vt::kStepWaves);
+        size_t stage = NT >= 8 ? vt::mfma_wide_lds_bytes() : vt::mfma_stage_bytes(var_waves ? nwaves : vt::kStepWaves);
         // More than 8 hidden rows and 129 .. 144 rows per tile for one tile per CU (the paper's trimmed sizes again):
         // tiles of exactly that many rows (k = 32975, n = 64, d = 4096: 258 tiles of 128 rows took 104 us, a nearly
         // empty second round).  With two groups of hidden rows (9 .. 16 rows are padded to 32) the columns of the rows
@@ -245,6 +245,15 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         const bool xany = n > vt::kGemvMaxN && NT <= 4 && d >= 1024 && Rx > vt::kMfmaTileRows &&
                           Rx <= vt::kMfmaTileRows + 16;
         if (xany && NT == 1) NT = 2;
+        // ... and fewer than 112 rows per tile for one tile per CU: tiles of 5 .. 7 waves (16 rows each) instead of
+        // leaving CUs idle with 128-row tiles
+        const int Gx = (Rx + 15) / 16;
+        // (their threads must still prefetch a chunk of at least three units of h through their registers)
+        const bool few = n > vt::kGemvMaxN && NT <= 4 && !xany && Gx >= 5 && Gx <= vt::kMfmaFewWaves &&
+                         (size_t)vt::kMfmaChunkPieces * Gx * 64 * 16 >= (size_t)16 * (NT < 2 ? 2 : NT) * 2 * 128 * vt::kMfmaPrefetchUnits;
+        if (few && NT == 1) NT = 2;
+        const int NWx = few ? Gx : vt::kStepWaves;      // waves of a workgroup for more than 8 hidden rows
+        if (few) stage = vt::mfma_stage_bytes(NWx);
         const bool xrows = xany && NT == 2;      // ... in LDS beside the chunk
         const bool xpass = xany && NT == 4;      // ... after the march
         const size_t xbytes = xrows ? (size_t)3 * NT * 1024 : 0;
@@ -255,7 +264,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
             const size_t hmax = ((size_t)vt::kMaxDynamicLds - stage - xbytes) / hrows;
             if (hmax < 272) return p;
             KC = (int)(((hmax - 16) / 2) / 128) * 128;
-            int kc_regs = (int)((vt::kMfmaChunkPieces * (var_waves ? nwaves : vt::kStepWaves) * 64 * 16) / (hrows * 2) / 128 * 128);
+            int kc_regs = (int)((vt::kMfmaChunkPieces * (var_waves ? nwaves : NWx) * 64 * 16) / (hrows * 2) / 128 * 128);
             if (xrows) {
                 // the extra rows' pieces start at a piece number of their own behind h's
                 const int T = vt::kStepWaves * 64;
@@ -283,7 +292,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.KC = KC;
         p.hpitch = KC * 2 + 16;
         p.ksplit = (prefer_mfma && KC == d) ? ksplit : 1;
-        p.nwaves = (prefer_mfma && KC == d) ? nwaves : vt::kStepWaves;
+        p.nwaves = (prefer_mfma && KC == d) ? nwaves : NWx;
         p.extra_rows = (prefer_mfma && KC == d) ? extra_rows : 0;
         if (xany) p.extra_rows = Rx - vt::kMfmaTileRows;
         const int tile_rows = 16 * (p.nwaves / p.ksplit) + p.extra_rows;
@@ -597,7 +606,7 @@ int vt_draft_head_step_plan(int32_t n, int32_t k, int32_t d, int32_t m, int w_ty
                       p.nlists, vt::kMfmaTileRows);
     } else {
         std::snprintf(head, sizeof head, "head_mfma_kernel<%d,%d> workgroups=%d tile_rows=%d waves=%d column_split=%d", p.NT,
-                      p.nwaves == vt::kStepWaves ? vt::kStepWaves : vt::kMfmaMaxWaves, p.nlists,
+                      p.nwaves == vt::kStepWaves ? vt::kStepWaves : p.NT > 1 ? vt::kMfmaFewWaves : vt::kMfmaMaxWaves, p.nlists,
                       16 * (p.nwaves / p.ksplit) + p.extra_rows, p.nwaves, p.ksplit);
     }
     const bool split = p.gemv && !p.row_select && chunk >= vt::kGemvSplitMinN;

@@ -664,7 +664,7 @@ head_mfma_kernel(const MfmaArgs a) {
         unsigned long long *cand4 =
             reinterpret_cast<unsigned long long *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15)) +
             (size_t)w * 4 * 16;
-        for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves) {
+        for (int i0 = 4 * w; i0 < a.n; i0 += 4 * NW) {
             if constexpr (XC != 0) {
                 block_epilogue_rows4<9>(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
                                         a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
@@ -1095,7 +1095,13 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
         return hipErrorInvalidValue;
     // waves per workgroup: eight, or (one group of hidden rows, all of h in LDS, up to 8 hidden rows) a multiple of
     // the column split up to kMfmaMaxWaves
-    if (a.nwaves != kStepWaves &&
+    // ... or (two or four groups of hidden rows, no column split) five to seven: tiles of 80 .. 112 rows
+    const bool few = a.nwaves != kStepWaves && NT > 1;
+    if (few && ((NT != 2 && NT != 4) || a.nwaves < 5 || a.nwaves > kMfmaFewWaves || a.ksplit != 1 || a.extra_rows != 0 ||
+                (a.zbuf == nullptr && a.L > 16) ||
+                (size_t)16 * NT * min(a.KC, a.d) * 2 > (size_t)kMaxPieces * a.nwaves * kWave * 16))
+        return hipErrorInvalidValue;
+    if (a.nwaves != kStepWaves && !few &&
         (NT != 1 || a.n > 8 || a.KC < a.d || a.nwaves < a.ksplit || a.nwaves > kMfmaMaxWaves ||
          a.nwaves % a.ksplit != 0 || (size_t)a.d * 16 > (size_t)kMaxPieces * a.nwaves * kWave * 16))
         return hipErrorInvalidValue;
@@ -1138,9 +1144,11 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
             return a.nwaves == kStepWaves ? launch_mfma_inst<1, kStepWaves>(a, lds, st)
                                           : launch_mfma_inst<1, kMfmaMaxWaves>(a, lds, st);
         case 2:
+            if (few) return launch_mfma_inst<2, kMfmaFewWaves>(a, lds, st);
             return handed_on ? launch_mfma_inst<2, kStepWaves, false, 1>(a, lds, st)
                              : launch_mfma_inst<2, kStepWaves>(a, lds, st);
         case 4:
+            if (few) return launch_mfma_inst<4, kMfmaFewWaves>(a, lds, st);
             return handed_on ? launch_mfma_inst<4, kStepWaves, false, 2>(a, lds, st)
                              : launch_mfma_inst<4, kStepWaves>(a, lds, st);
         case 8:

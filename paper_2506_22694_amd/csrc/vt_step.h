@@ -144,6 +144,8 @@ struct FinalizeArgs {
 constexpr int kFinalizeTreeMaxN = 512;
 
 constexpr int kMfmaMaxWaves = 12;      // three waves per SIMD: 168 registers each
+constexpr int kMfmaFewWaves = 7;       // more than 8 hidden rows: the instantiation for 5 .. 7 waves (smaller tiles for heads that
+                                       // would leave CUs idle with 128-row tiles)
 
 size_t mfma_stage_bytes(int nwaves);
 

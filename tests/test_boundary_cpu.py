@@ -85,8 +85,11 @@ def test_step_plan_is_a_pure_host_function_and_follows_the_head(lib):
         for n, nt in ((9, 2), (16, 2), (32, 2), (33, 4), (64, 4)):
             rc, text = _plan(lib, n, k, 4096, 8)
             assert rc == 0 and f"head_mfma_kernel<{nt},8> workgroups=256 tile_rows={rows} waves=8" in text, text
-    # below one tile per CU nothing changes for more than 8 rows; small heads shrink their tiles instead
-    assert "head_mfma_kernel<4,8> workgroups=179 tile_rows=128" in _plan(lib, 64, 22786, 4096, 8)[1]
+    # below one tile per CU: five to seven waves of 16 rows for more than 8 hidden rows (where their threads can still
+    # prefetch a chunk of h), smaller tiles with shared row groups for up to 8
+    assert "head_mfma_kernel<4,7> workgroups=238 tile_rows=96 waves=6" in _plan(lib, 64, 22786, 4096, 8)[1]
+    assert "head_mfma_kernel<2,7> workgroups=225 tile_rows=80 waves=5" in _plan(lib, 32, 18000, 4096, 8)[1]
+    assert "head_mfma_kernel<4,8> workgroups=141 tile_rows=128" in _plan(lib, 64, 18000, 4096, 8)[1]
     assert "head_mfma_kernel<1,8> workgroups=179 tile_rows=128" in _plan(lib, 8, 22786, 3072, 8)[1]
     assert "head_mfma_kernel<1,12> workgroups=238 tile_rows=96 waves=6" in _plan(lib, 1, 22786, 3072, 1)[1]
     assert "tile_rows=32 waves=8 column_split=4" in _plan(lib, 8, 5000, 3072, 8)[1]

@@ -347,6 +347,16 @@ def test_step_six_and_seven_wave_tiles(k, n, d, m):
     _paper_size_case(k, n, d, m)
 
 
+# more than 8 hidden rows on such heads: tiles of five to seven waves too
+@pytest.mark.parametrize("k,n,d,m", [(22786, 32, 4096, 8), (26000, 64, 4096, 8), (18000, 32, 4096, 8),
+                                     (22786, 64, 4096, 16), (22786, 12, 3072, 8), (22786, 64, 8192, 8),
+                                     (22786, 20, 640, 8), (28672, 64, 4096, 8), (24576, 48, 2048, 4)])
+def test_step_five_to_seven_wave_tiles_many_hidden_rows(k, n, d, m):
+    plan = vt.draft_head_step_plan(n, k, d, m)
+    assert "head_mfma_kernel<2,7>" in plan or "head_mfma_kernel<4,7>" in plan, plan
+    _paper_size_case(k, n, d, m)
+
+
 # more than 8 hidden rows at those sizes: 9 .. 16 rows (run as two groups of 16), two groups, three of four, and rows
 # that are not a multiple of 2 KiB
 @pytest.mark.parametrize("k,n,d,m", [(32975, 9, 4096, 4), (32975, 16, 4096, 8), (33008, 32, 4096, 8),
