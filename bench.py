@@ -368,7 +368,7 @@ def main():
         task_copies += [task_copies[0].clone() for _ in range(len(copies) - 1)]
         mapt = torch.from_numpy(mapt_np).to(dev)
         hor_split = [0] * (n - n // 2) + [1] * (n // 2)          # consecutive rows per head: in place
-        hor_mixed = [i % 2 for i in range(n)]                    # alternating: staged through the workspace
+        hor_mixed = [i % 2 for i in range(n)]                    # alternating
         wsm = vt.MultiStepWorkspace(n, d, [k, kt], m, dev)
         om_i = torch.empty((n, m), dtype=torch.int32, device=dev)
         om_l = torch.empty((n, m), dtype=torch.float32, device=dev)
@@ -389,7 +389,9 @@ def main():
         multi = {"heads": [k, kt], "rows_per_head": [n - n // 2, n // 2], "select_both_heads_us": round(us_sel2, 2),
                  "consecutive_rows_us": round(us_split, 2), "alternating_rows_us": round(us_mixed, 2),
                  "bytes": (k + kt) * d * 2,
-                 "gbps_consecutive": round((k + kt) * d * 2 / us_split / 1e3, 1)}
+                 "gbps_consecutive": round((k + kt) * d * 2 / us_split / 1e3, 1),
+                 "frac_hbm_consecutive": round((k + kt) * d * 2 / us_split / 1e3 / HBM_PEAK_GBPS, 4),
+                 "kernels": vt.draft_head_step_multi_plan(n, d, [k, kt], hor_split, m)}
         log("multi-head step:", multi)
         del task_copies
 

@@ -235,9 +235,15 @@ int vt_draft_head_step_static(const void *h, int h_type, int32_t n, const void *
  *
  * vt_draft_head_step_multi -- one draft step in which hidden row i uses head
  *   head_of_row[i]: out_ids[i, :], out_logp[i, :], out_lse[i] are what
- *   vt_draft_head_step returns for row i on that head.  Every head that has
- *   rows streams its W_trim once, whatever the order of the rows (rows of a
- *   head that are not consecutive in h are staged through the workspace).
+ *   vt_draft_head_step returns for row i on that head -- the same tokens, and
+ *   log-probs that differ at most by the rounding of the log-sum-exp (a few
+ *   1e-7), whose partial sums follow the tiles the head is cut into.  Every
+ *   head that has rows streams its W_trim once, whatever the order of the
+ *   rows.  Up to 8 rows (bf16, d a multiple of 128 up to 4096, m <= 11) on two
+ *   or more heads run as ONE launch over all those heads' tiles, so the fixed
+ *   costs of a step are paid once, not per head; otherwise the heads run one
+ *   after another (rows of a head that are not consecutive in h are picked
+ *   out by the kernel or staged through the workspace).
  *     h            [n, d] device;  1 <= n <= VT_MULTI_MAX_ROWS
  *     W_trim, map  [n_heads] HOST arrays of device pointers (entries of heads
  *                  without rows are not read)
@@ -259,6 +265,12 @@ int vt_draft_head_step_multi(const void *h, int h_type, int32_t n, int32_t d, co
                              const int32_t *head_of_row, int32_t m, int32_t *out_ids, float *out_logp,
                              float *out_lse, void *ws, size_t ws_bytes, void *stream);
 size_t vt_draft_head_step_multi_ws_bytes(int32_t n, int32_t d, const int32_t *k, int32_t n_heads, int32_t m);
+/* Pure host function: how vt_draft_head_step_multi would run these rows, as text
+ * ("head_mfma_kernel<1,12> heads=2 workgroups=237 tile_rows=160 ..." for one
+ * launch over several heads' tiles, "head by head (N)" otherwise).  k and
+ * head_of_row are HOST arrays as above.  Returns VT_OK or an argument error. */
+int vt_draft_head_step_multi_plan(int32_t n, int32_t d, const int32_t *k, int32_t n_heads, const int32_t *head_of_row,
+                                  int32_t m, int w_type, char *text, size_t text_bytes);
 
 /* Not needed any more (a draft-step workspace needs no initialisation); kept for
  * callers written against earlier versions.  Zeroes the first 2 KiB of the

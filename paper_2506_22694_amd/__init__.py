@@ -5,9 +5,9 @@ include/vocabtrim.h); this package is the thin binding plus the seeded input
 generators used by tests and the benchmark.
 """
 from .binding import (MultiStepWorkspace, StepWorkspace, VocabTrimError, build_trimmed_head, build_trimmed_heads,
-                      choose_k, count_tokens, draft_head_step, draft_head_step_multi, draft_head_step_plan, draft_head_step_static,
+                      choose_k, count_tokens, draft_head_step, draft_head_step_multi, draft_head_step_multi_plan, draft_head_step_plan, draft_head_step_static,
                       draft_tree_level, load_library, tree_expand, tree_rerank)
 
 __all__ = ["MultiStepWorkspace", "StepWorkspace", "VocabTrimError", "build_trimmed_head", "build_trimmed_heads",
-           "choose_k", "count_tokens", "draft_head_step", "draft_head_step_multi", "draft_head_step_plan",
+           "choose_k", "count_tokens", "draft_head_step", "draft_head_step_multi", "draft_head_step_multi_plan", "draft_head_step_plan",
            "draft_head_step_static", "draft_tree_level", "load_library", "tree_expand", "tree_rerank"]

@@ -25,7 +25,7 @@ EXPORTS = (
     "vt_build_trimmed_head", "vt_build_trimmed_head_ws_bytes", "vt_build_trimmed_head_by_rank",
     "vt_choose_k", "vt_choose_k_ws_bytes",
     "vt_draft_head_step", "vt_draft_head_step_ws_bytes", "vt_draft_head_step_ws_init",
-    "vt_draft_head_step_static", "vt_draft_head_step_plan",
+    "vt_draft_head_step_static", "vt_draft_head_step_plan", "vt_draft_head_step_multi_plan",
     "vt_tree_expand", "vt_tree_rerank", "vt_draft_tree_level", "vt_stream_read_reference",
     "vt_build_trimmed_heads", "vt_draft_head_step_multi", "vt_draft_head_step_multi_ws_bytes",
 )
@@ -70,6 +70,8 @@ def load_library() -> ctypes.CDLL:
     L.vt_draft_head_step_static.restype = ci
     L.vt_draft_head_step_plan.argtypes = [i32, i32, i32, i32, ci, ctypes.c_char_p, sz]
     L.vt_draft_head_step_plan.restype = ci
+    L.vt_draft_head_step_multi_plan.argtypes = [i32, i32, vp, i32, vp, i32, ci, ctypes.c_char_p, sz]
+    L.vt_draft_head_step_multi_plan.restype = ci
     L.vt_draft_head_step_ws_bytes.argtypes = [i32, i32, i32, i32]
     L.vt_draft_head_step_ws_bytes.restype = sz
     L.vt_draft_head_step_ws_init.argtypes = [vp, sz, vp]
@@ -331,6 +333,17 @@ def build_trimmed_heads(counts: torch.Tensor, W: torch.Tensor | None, ks, ws: to
     _check(L.vt_build_trimmed_heads(_ptr(counts), V, H, _ptr(W), wt, d, _host_i32(ks), _host_ptrs(maps),
                                     _host_ptrs(Ws) if Ws is not None else None, _ptr(ws), ws.numel(), _stream(dev)))
     return [(maps[i], Ws[i] if Ws is not None else None) for i in range(H)]
+
+
+def draft_head_step_multi_plan(n: int, d: int, ks, head_of_row, m: int, dtype=torch.bfloat16) -> str:
+    """How draft_head_step_multi would run these rows (pure host): one launch over several heads' tiles, or head by head."""
+    L = load_library()
+    buf = ctypes.create_string_buffer(256)
+    ks = [int(k) for k in ks]
+    hor = [int(x) for x in head_of_row]
+    _check(L.vt_draft_head_step_multi_plan(n, d, _host_i32(ks), len(ks), _host_i32(hor), m,
+                                           VT_BF16 if dtype == torch.bfloat16 else VT_F32, buf, 256))
+    return buf.value.decode()
 
 
 class MultiStepWorkspace:

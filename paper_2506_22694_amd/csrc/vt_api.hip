@@ -108,14 +108,18 @@ struct StepPlan {
 
 using vt::kTicketBytes;
 
-StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv);
+// fixed: a tile shape the caller has chosen (several heads in one launch): waves, column split, number of tiles
+struct FixedTiles {
+    int nwaves = 0, ksplit = 1, nlists = 0;
+};
+StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv, const FixedTiles &fixed = FixedTiles{});
 // force_gemv: the caller needs what only the small-n kernel offers (row picking, the fused tree level)
 StepPlan plan_step(int n, int k, int d, int m, int dtype, bool force_gemv = false) {
     StepPlan p = plan_step_impl(n, k, d, m, dtype, force_gemv);
     if (!p.ok && !force_gemv && n <= vt::kGemvMaxN) p = plan_step_impl(n, k, d, m, dtype, true);
     return p;
 }
-StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) {
+StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv, const FixedTiles &fixed) {
     StepPlan p;
     if (n <= 0 || k <= 0 || d <= 0 || m <= 0 || k > vt::kStepMaxK) return p;
     const int CUS = round_workgroups();
@@ -198,6 +202,22 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
                 ksplit = KS;
                 nwaves = vt::kStepWaves;
             }
+        }
+    }
+    if (fixed.nwaves != 0) {
+        // (the same limits as above: whole units per wave, the kernel's own epilogue, all of h in LDS at once)
+        ksplit = 0;
+        nwaves = vt::kStepWaves;
+        extra_rows = 0;
+        if (dtype == VT_BF16 && (d % 128) == 0 && d <= vt::kMfmaSmallMaxD && n <= vt::kGemvMaxN && m <= vt::kRowSelectMinL &&
+            (d / 128) % fixed.ksplit == 0 && (fixed.ksplit == 1 || fixed.nwaves == vt::kStepWaves) &&
+            fixed.nwaves >= vt::kStepWaves && fixed.nwaves <= vt::kMfmaMaxWaves &&
+            vt::mfma_stage_bytes(fixed.nwaves) + 8 * ((size_t)d * 2 + 16) <= (size_t)vt::kMaxDynamicLds &&
+            (size_t)d <= (size_t)vt::kMfmaChunkPieces * fixed.nwaves * 64) {
+            ksplit = fixed.ksplit;
+            nwaves = fixed.nwaves;
+        } else {
+            return p;
         }
     }
     const bool prefer_mfma = ksplit != 0;
@@ -296,7 +316,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv) 
         p.extra_rows = (prefer_mfma && KC == d) ? extra_rows : 0;
         if (xany) p.extra_rows = Rx - vt::kMfmaTileRows;
         const int tile_rows = 16 * (p.nwaves / p.ksplit) + p.extra_rows;
-        p.nlists = (k + tile_rows - 1) / tile_rows;
+        p.nlists = fixed.nwaves != 0 ? fixed.nlists : (k + tile_rows - 1) / tile_rows;
         p.L = m < tile_rows ? m : tile_rows;
         p.nblocks = p.nlists;
         p.lds = NT >= 8 ? stage : stage + ((n <= 8 ? 8 : 16 * (size_t)NT) + (xrows ? 16 : 0)) * p.hpitch;
@@ -380,6 +400,13 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
 
 int pick_chunk(int n, int k, int d, int m, int dtype);
 
+// several heads' tiles in one launch (defined with the launch code below)
+constexpr int kNotFused = -1;
+StepPlan plan_heads_fused(int n, int d, const int32_t *k, const int *used, int nused, int m, int w_type);
+int run_step_heads_fused(const void *h, int n, int d, const void *const *W_trim, int w_type, const int32_t *k,
+                         const int32_t *const *map, int n_heads, const int32_t *head_of_row, const vt::RowList *rows, int m,
+                         int32_t *out_ids, float *out_logp, float *out_lse, void *ws, size_t ws_step_bytes, hipStream_t st);
+
 // All n rows of a validated step: consecutive launch groups of `chunk` rows on one workspace.
 int run_step_rows(const void *h, int n, const void *W_trim, int w_type, int k, int d, const int32_t *map, int m,
                   int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws, hipStream_t st) {
@@ -440,6 +467,19 @@ MultiLayout multi_layout(int n, int d, const int32_t *k, int n_heads, int m) {
         for (int nn = 1; nn <= n; ++nn) {
             const size_t b = step_ws_bytes(nn, k[hd], d, m);
             if (b > step) step = b;
+        }
+    }
+    // ... and several heads' tiles in one launch: at most one tile per CU, whatever their shape
+    if (n <= vt::kGemvMaxN) {
+        for (int nw = vt::kStepWaves; nw <= vt::kMfmaMaxWaves; ++nw) {
+            for (int ks = 1; ks <= (nw == vt::kStepWaves ? 4 : 1); ks *= 2) {
+                FixedTiles ft;
+                ft.nwaves = nw;
+                ft.ksplit = ks;
+                ft.nlists = vt::kStepMaxBlocks;
+                const StepPlan p = plan_step_impl(n, vt::kStepMaxBlocks * 16 * (nw / ks), d, m, VT_BF16, false, ft);
+                if (p.ok && p.bytes > step) step = p.bytes;
+            }
         }
     }
     size_t off = round_up(step, 256);
@@ -617,6 +657,35 @@ int vt_draft_head_step_plan(int32_t n, int32_t k, int32_t d, int32_t m, int w_ty
     return VT_OK;
 }
 
+int vt_draft_head_step_multi_plan(int32_t n, int32_t d, const int32_t *k, int32_t n_heads, const int32_t *head_of_row,
+                                  int32_t m, int w_type, char *text, size_t text_bytes) {
+    if (w_type != VT_F32 && w_type != VT_BF16) return VT_ERR_DTYPE;
+    if (n < 1 || n > VT_MULTI_MAX_ROWS || d < 1 || n_heads < 1 || n_heads > VT_MAX_HEADS) return VT_ERR_SHAPE;
+    if (k == nullptr || head_of_row == nullptr || text == nullptr || text_bytes == 0) return VT_ERR_NULL;
+    int rows_of[VT_MAX_HEADS] = {};
+    for (int i = 0; i < n; ++i) {
+        if (head_of_row[i] < 0 || head_of_row[i] >= n_heads) return VT_ERR_SHAPE;
+        ++rows_of[head_of_row[i]];
+    }
+    int used[VT_MAX_HEADS], nused = 0;
+    for (int hd = 0; hd < n_heads; ++hd) {
+        if (k[hd] < 1 || k[hd] > vt::kStepMaxK) return VT_ERR_SHAPE;
+        if (rows_of[hd] == 0) continue;
+        if (m < 1 || m > k[hd] || m > VT_MAX_TOP_M) return VT_ERR_SHAPE;
+        used[nused++] = hd;
+    }
+    const StepPlan p = plan_heads_fused(n, d, k, used, nused, m, w_type);
+    if (p.ok) {
+        std::snprintf(text, text_bytes,
+                      "head_mfma_kernel<1,%d> heads=%d workgroups=%d tile_rows=%d waves=%d column_split=%d + step_finalize_kernel",
+                      p.nwaves == vt::kStepWaves ? vt::kStepWaves : vt::kMfmaMaxWaves, nused, p.nlists,
+                      16 * (p.nwaves / p.ksplit), p.nwaves, p.ksplit);
+    } else {
+        std::snprintf(text, text_bytes, "head by head (%d)", nused);
+    }
+    return VT_OK;
+}
+
 int vt_draft_head_step_ws_init(void *ws, size_t ws_bytes, void *stream) {
     if (ws == nullptr || !aligned(ws, 256) || ws_bytes < kTicketBytes) return VT_ERR_WORKSPACE;
     (void)hipGetLastError();
@@ -713,6 +782,11 @@ int vt_draft_head_step_multi(const void *h, int h_type, int32_t n, int32_t d, co
     (void)hipGetLastError();
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *wsb = static_cast<char *>(ws);
+    {
+        const int rc = run_step_heads_fused(h, n, d, W_trim, w_type, k, map, n_heads, head_of_row, rows, m, out_ids, out_logp,
+                                            out_lse, ws, L.off_h, st);
+        if (rc != kNotFused) return rc == VT_OK ? launch_status() : rc;
+    }
     for (int hd = 0; hd < n_heads; ++hd) {
         const vt::RowList &R = rows[hd];
         if (R.n == 0) continue;
@@ -860,6 +934,88 @@ int vt_draft_tree_level(const void *h, int h_type, int32_t n, const void *W_trim
 namespace {
 
 // One launch group of the draft step: n rows that a single plan covers.  Arguments are validated.
+// Up to 8 hidden rows on two or more heads: one launch of the matrix-core kernel over all those heads' tiles -- every
+// head streams once and the fixed costs of a step (launches, epilogue, merge) are paid once, not per head -- then
+// the merge kernel.  All tiles have one height, the smallest for which every head, cut on its own, fits one tile
+// per CU in all: 32, 64 or 128 rows with eight waves (4, 2, 1 waves per 16-row group), 144 .. 192 rows with 9 .. 12
+// waves.  Returns kNotFused where that does not apply (the caller then runs the heads one after another).
+// The plan of that launch (ok = false where it does not apply): used = the heads that have rows.
+StepPlan plan_heads_fused(int n, int d, const int32_t *k, const int *used, int nused, int m, int w_type) {
+    StepPlan p;
+    if (n > vt::kGemvMaxN || w_type != VT_BF16 || nused < 2) return p;
+    const int CUS = round_workgroups();
+    static const int shapes[][2] = {{8, 4}, {8, 2}, {8, 1}, {9, 1}, {10, 1}, {11, 1}, {12, 1}};
+    for (const auto &sh : shapes) {
+        const int T = 16 * (sh[0] / sh[1]);
+        int tiles = 0;
+        for (int q = 0; q < nused; ++q) tiles += (k[used[q]] + T - 1) / T;
+        if (tiles > CUS) continue;
+        FixedTiles ft;
+        ft.nwaves = sh[0];
+        ft.ksplit = sh[1];
+        ft.nlists = tiles;
+        p = plan_step_impl(n, tiles * T, d, m, w_type, false, ft);
+        if (p.ok) break;
+    }
+    if (p.ok && (!p.mfma || p.row_select || p.KC != d || p.NT != 1)) p.ok = false;
+    return p;
+}
+int run_step_heads_fused(const void *h, int n, int d, const void *const *W_trim, int w_type, const int32_t *k,
+                         const int32_t *const *map, int n_heads, const int32_t *head_of_row, const vt::RowList *rows, int m,
+                         int32_t *out_ids, float *out_logp, float *out_lse, void *ws, size_t ws_step_bytes, hipStream_t st) {
+    int used[VT_MAX_HEADS], nused = 0;
+    for (int hd = 0; hd < n_heads; ++hd)
+        if (rows[hd].n != 0) used[nused++] = hd;
+    const StepPlan p = plan_heads_fused(n, d, k, used, nused, m, w_type);
+    if (!p.ok || p.bytes > ws_step_bytes) return kNotFused;
+    const int T = 16 * (p.nwaves / p.ksplit);
+    vt::MultiHeadTable t{};
+    t.n_heads = nused;
+    t.tile_first[0] = 0;
+    int slot_of_head[VT_MAX_HEADS];
+    for (int q = 0; q < nused; ++q) {
+        const int hd = used[q];
+        slot_of_head[hd] = q;
+        t.W[q] = W_trim[hd];
+        t.map[q] = map[hd];
+        t.k[q] = k[hd];
+        t.tile_first[q + 1] = t.tile_first[q] + (k[hd] + T - 1) / T;
+    }
+    for (int i = 0; i < n; ++i) t.head_of_row |= (unsigned long long)slot_of_head[head_of_row[i]] << (8 * i);
+    char *wsb = static_cast<char *>(ws);
+    vt::MfmaArgs a{};
+    a.h = h;
+    a.n = n;
+    a.d = d;
+    a.m = m;
+    a.L = p.L;
+    a.nlists = p.nlists;
+    a.KC = p.KC;
+    a.hpitch = p.hpitch;
+    a.pms = reinterpret_cast<unsigned long long *>(wsb + p.off_pms);
+    a.pkeys = reinterpret_cast<unsigned long long *>(wsb + p.off_pkeys);
+    a.ksplit = p.ksplit;
+    a.nwaves = p.nwaves;
+    hipError_t e = vt::launch_head_mfma_multi(a, t, p.lds, st);
+    if (e != hipSuccess) return device_status(e);
+    vt::FinalizeArgs f{};
+    f.pms = a.pms;
+    f.pkeys = a.pkeys;
+    f.nlists = p.nlists;
+    f.L = p.L;
+    f.n = n;
+    f.m = m;
+    f.conc = p.fin_conc;
+    f.stage_keys = p.fin_stage_keys;
+    f.out_ids = out_ids;
+    f.out_logp = out_logp;
+    f.out_lse = out_lse;
+    f.lse_buf = reinterpret_cast<float *>(wsb + p.off_lse);
+    f.ticket = reinterpret_cast<unsigned *>(wsb);
+    e = vt::launch_step_finalize(f, p.fin_lds, st);
+    return e == hipSuccess ? VT_OK : device_status(e);
+}
+
 int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, int d, const int32_t *map, int m,
                    int32_t *out_ids, float *out_logp, float *out_lse, float *out_logp_full, void *ws,
                    hipStream_t st, const TreeFuse &tf) {

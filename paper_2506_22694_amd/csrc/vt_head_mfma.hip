@@ -104,9 +104,11 @@ __device__ __forceinline__ void wait_unit(u32x4 (&b)[4]) {
 // every workgroup pulls all of h through its CU a second time, 134 MB at once over the L2s' 17 TB/s at n = 64;
 // from LDS beside the chunk 69 / 56.5 -- with four groups of hidden rows the march is bound by its LDS traffic,
 // to which the extra group adds a sixth, with two it is not.)
-template <int NT, int MAXW, bool XG = false, int XC = 0>
+// MH: the tiles of several heads in one launch (see MultiHeadTable); one group of hidden rows, all of h in LDS.
+template <int NT, int MAXW, bool XG = false, int XC = 0, bool MH = false>
 __global__ void __launch_bounds__(MAXW *kWave) __attribute__((amdgpu_waves_per_eu(1, (MAXW + 3) / 4)))
-head_mfma_kernel(const MfmaArgs a) {
+head_mfma_kernel(const MfmaArgs a, const std::conditional_t<MH, MultiHeadTable, SingleHead> mh) {
+    static_assert(!MH || (NT == 1 && !XG && XC == 0), "several heads per launch: one group of hidden rows, plain tiles");
     static_assert(!XG || (NT == 1 && MAXW == kStepWaves), "the shared row group is built for eight waves and one group of hidden rows");
     static_assert(XC == 0 || (!XG && MAXW == kStepWaves && ((XC == 1 && NT == 2) || (XC == 2 && NT == 4))),
                   "the extra row group in LDS is built for eight waves and two or four groups of hidden rows");
@@ -129,8 +131,19 @@ head_mfma_kernel(const MfmaArgs a) {
     const int KS = NT == 1 ? a.ksplit : 1;
     const int tile_rows = 16 * (NW / KS) + (XT ? a.extra_rows : 0);
     const int rg = w / KS, ksi = w % KS;               // row group of the wave, its share of the columns
-    const int row0 = blockIdx.x * tile_rows;
-    const int rows_b = min(tile_rows, a.k - row0);
+    // the head this tile belongs to, its first tile, size, rows and ids
+    int hd = 0, tile_lo = 0, head_k = a.k;
+    const void *head_W = a.W;
+    const int *head_map = a.map;
+    if constexpr (MH) {
+        for (int q = 1; q < mh.n_heads; ++q) hd = (int)blockIdx.x >= mh.tile_first[q] ? q : hd;
+        tile_lo = mh.tile_first[hd];
+        head_k = mh.k[hd];
+        head_W = mh.W[hd];
+        head_map = mh.map[hd];
+    }
+    const int row0 = ((int)blockIdx.x - tile_lo) * tile_rows;
+    const int rows_b = min(tile_rows, head_k - row0);
     const size_t rs = (size_t)a.d * 2;
     const int lrow = lane & 15, lgrp = lane >> 4;
 
@@ -154,7 +167,7 @@ head_mfma_kernel(const MfmaArgs a) {
             vdelta[j] = __umul24((unsigned)r, (unsigned)(a.d * 2)) + (unsigned)lrow * 16u - voff[j];
         }
     }
-    const char *Wt = static_cast<const char *>(a.W) + (size_t)row0 * rs;
+    const char *Wt = static_cast<const char *>(head_W) + (size_t)row0 * rs;
     const int nunits = a.d / kUnitCols;
     const int nun = nunits / KS;                       // units of this wave's own rows
     const int PL = nunits / 8;                         // XG: units per column part
@@ -320,12 +333,12 @@ head_mfma_kernel(const MfmaArgs a) {
     constexpr bool IDS_LATE = XC != 0 && NT == 4;
     int ids[11];
     if constexpr (!IDS_LATE) {
-        request_dword(ids[0], a.map + row0 + min(lane, rows_b - 1));
-        request_dword(ids[1], a.map + row0 + min(lane + kWave, rows_b - 1));
+        request_dword(ids[0], head_map + row0 + min(lane, rows_b - 1));
+        request_dword(ids[1], head_map + row0 + min(lane + kWave, rows_b - 1));
 #pragma unroll
         for (int q = 0; q < 9; ++q)
             request_dword(ids[2 + q],
-                          a.map + row0 + min((MAXW > kStepWaves || XG) ? lane + 2 * kWave : lrow + 16 * q, rows_b - 1));
+                          head_map + row0 + min((MAXW > kStepWaves || XG) ? lane + 2 * kWave : lrow + 16 * q, rows_b - 1));
     }
     fetch_chunk(0);                       // everything waits for it
 #pragma unroll
@@ -555,10 +568,10 @@ head_mfma_kernel(const MfmaArgs a) {
         }
     }
     if constexpr (IDS_LATE) {
-        id0 = a.map[row0 + min(lane, rows_b - 1)];
-        id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
+        id0 = head_map[row0 + min(lane, rows_b - 1)];
+        id1 = head_map[row0 + min(lane + kWave, rows_b - 1)];
 #pragma unroll
-        for (int q = 0; q < 9; ++q) idq[q] = a.map[row0 + min(lrow + 16 * q, rows_b - 1)];
+        for (int q = 0; q < 9; ++q) idq[q] = head_map[row0 + min(lrow + 16 * q, rows_b - 1)];
     }
 
     if constexpr (XG) {
@@ -688,6 +701,15 @@ head_mfma_kernel(const MfmaArgs a) {
             float *full = a.out_logp_full ? a.out_logp_full + (size_t)i * a.k + row0 : nullptr;
             unsigned long long *pms_slot = a.pms + (size_t)i * a.nlists + blockIdx.x;
             unsigned long long *pk_slot = a.pkeys + ((size_t)i * a.nlists + blockIdx.x) * a.L;
+            if constexpr (MH) {
+                // a hidden row of another head: nothing of this tile is its business -- an empty list, and a
+                // (max, sum-exp) pair that adds nothing to any log-sum-exp
+                if ((int)((mh.head_of_row >> (8 * i)) & 0xFFull) != hd) {
+                    if (lane == 0) publish_u64(pms_slot, (unsigned long long)__float_as_uint(-3.0e38f));
+                    if (lane < a.L) publish_u64(pk_slot + lane, kNoKey);
+                    continue;
+                }
+            }
             // the logit is the sum of the KS partial tiles, in wave order
             if constexpr (MAXW > kStepWaves || XG) {
                 const int idq3[3] = {id0, id1, idq[0]};
@@ -1070,11 +1092,21 @@ hipError_t launch_mfma_wide_inst(const MfmaArgs &a, size_t lds, hipStream_t st) 
 
 template <int NT, int MAXW, bool XG = false, int XC = 0>
 hipError_t launch_mfma_inst(const MfmaArgs &a, size_t lds, hipStream_t st) {
-    auto kern = head_mfma_kernel<NT, MAXW, XG, XC>;
+    auto kern = head_mfma_kernel<NT, MAXW, XG, XC, false>;
     static LdsLimitOnce lds_limit;
     hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(kern)}, kMaxDynamicLds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(a.nlists), dim3((MAXW == kStepWaves ? kStepWaves : a.nwaves) * kWave), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(a.nlists), dim3((MAXW == kStepWaves ? kStepWaves : a.nwaves) * kWave), lds, st, a,
+                       SingleHead{});
+    return hipGetLastError();
+}
+template <int MAXW>
+hipError_t launch_mfma_multi_inst(const MfmaArgs &a, const MultiHeadTable &t, size_t lds, hipStream_t st) {
+    auto kern = head_mfma_kernel<1, MAXW, false, 0, true>;
+    static LdsLimitOnce lds_limit;
+    hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(kern)}, kMaxDynamicLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(a.nlists), dim3((MAXW == kStepWaves ? kStepWaves : a.nwaves) * kWave), lds, st, a, t);
     return hipGetLastError();
 }
 
@@ -1160,6 +1192,28 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
         }
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_head_mfma_multi(const MfmaArgs &a, const MultiHeadTable &t, size_t lds, hipStream_t st) {
+    // up to 8 hidden rows in place, all of h in LDS, plain tiles (a column split only with eight waves), the kernel's
+    // own epilogue; every head cut into tiles of the launch's height on its own
+    if (a.n < 1 || a.n > 8 || a.KC != a.d || a.indexed != 0 || a.zbuf != nullptr || a.out_logp_full != nullptr ||
+        a.extra_rows != 0 || a.ticket_clear != nullptr || a.d % kUnitCols != 0 || a.L < 1 || a.L > 16 ||
+        a.nwaves < kStepWaves || a.nwaves > kMfmaMaxWaves || (a.ksplit != 1 && (a.nwaves != kStepWaves || (a.ksplit != 2 && a.ksplit != 4))) ||
+        (a.d / kUnitCols) % a.ksplit != 0 || (size_t)a.d * 16 > (size_t)kMaxPieces * a.nwaves * kWave * 16 ||
+        (size_t)a.d * 2 >= ((size_t)1 << 24) || t.n_heads < 1 || t.n_heads > 16 || t.tile_first[0] != 0)
+        return hipErrorInvalidValue;
+    const int tile_rows = 16 * (a.nwaves / a.ksplit);
+    for (int q = 0; q < t.n_heads; ++q) {
+        if (t.W[q] == nullptr || t.map[q] == nullptr || t.k[q] < 1 ||
+            t.tile_first[q + 1] - t.tile_first[q] != (t.k[q] + tile_rows - 1) / tile_rows)
+            return hipErrorInvalidValue;
+    }
+    for (int i = 0; i < a.n; ++i)
+        if ((int)((t.head_of_row >> (8 * i)) & 0xFFull) >= t.n_heads) return hipErrorInvalidValue;
+    if (a.nlists != t.tile_first[t.n_heads] || a.nlists > kStepMaxBlocks) return hipErrorInvalidValue;
+    return a.nwaves == kStepWaves ? launch_mfma_multi_inst<kStepWaves>(a, t, lds, st)
+                                  : launch_mfma_multi_inst<kMfmaMaxWaves>(a, t, lds, st);
 }
 
 hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t st) {

@@ -119,6 +119,20 @@ struct MfmaArgs {
     unsigned *ticket_clear;
 };
 
+// Several heads in one launch of the matrix-core kernel (up to 8 hidden rows in all): the tiles of head i are the
+// workgroups tile_first[i] .. tile_first[i + 1] - 1, each head cut into tiles of the launch's height on its own
+// (the last one ragged); hidden row r belongs to head (head_of_row >> 8 r) & 255.  Every tile multiplies all hidden
+// rows -- they share the 16-row operand anyway -- and publishes an empty list for the rows of other heads.
+struct MultiHeadTable {
+    const void *W[16];
+    const int *map[16];
+    int k[16];
+    int tile_first[17];
+    unsigned long long head_of_row;
+    int n_heads;
+};
+struct SingleHead {};      // the kernels' second argument when there is one head
+
 struct FinalizeArgs {
     const unsigned long long *pms;
     const unsigned long long *pkeys;
@@ -151,6 +165,8 @@ size_t mfma_stage_bytes(int nwaves);
 
 size_t mfma_wide_lds_bytes();   // NT >= 8: two shared unit buffers
 hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t st);
+// a.W, a.map, a.k are not read: the table names every head's; a.nlists = tile_first[n_heads]
+hipError_t launch_head_mfma_multi(const MfmaArgs &a, const MultiHeadTable &t, size_t lds_bytes, hipStream_t st);
 hipError_t launch_step_finalize(const FinalizeArgs &f, size_t lds, hipStream_t st);
 
 // Launchers, one translation unit per padded row count NP (1, 2, 4, 8).

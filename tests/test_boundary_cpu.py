@@ -6,6 +6,7 @@ import os
 import re
 
 import pytest
+import torch
 
 from paper_2506_22694_amd import binding
 
@@ -107,6 +108,25 @@ def test_step_plan_is_a_pure_host_function_and_follows_the_head(lib):
     assert _plan(lib, 8, 32768, 3072, 65)[0] == VT_ERR_SHAPE
     assert _plan(lib, 8, 32768, 3072, 8, 7)[0] == VT_ERR_DTYPE
     assert lib.vt_draft_head_step_plan(8, 32768, 3072, 8, VT_BF16, None, 0) == VT_ERR_NULL
+
+
+def test_multi_head_step_plan_one_launch_or_head_by_head():
+    plan = binding.draft_head_step_multi_plan
+    # the general head beside a task head, four rows each: ten-wave tiles of 160 rows, 205 + 32 of them
+    assert plan(8, 3072, [32768, 5000], [0, 0, 0, 0, 1, 1, 1, 1], 8) == (
+        "head_mfma_kernel<1,12> heads=2 workgroups=237 tile_rows=160 waves=10 column_split=1 + step_finalize_kernel")
+    # small heads: 32-row tiles, four waves per row group; heads without rows do not count
+    assert plan(7, 1024, [1500, 700, 3000, 99999], [2, 0, 1, 1, 0, 2, 2], 5) == (
+        "head_mfma_kernel<1,8> heads=3 workgroups=163 tile_rows=32 waves=8 column_split=4 + step_finalize_kernel")
+    # too many rows for one tile per CU even at 192 rows, more than 8 hidden rows, one head only, fp32, many tokens
+    assert plan(4, 3072, [33008, 32975], [0, 1, 1, 0], 8) == "head by head (2)"
+    assert plan(12, 1024, [3000, 1500], [0, 1] * 6, 5) == "head by head (2)"
+    assert plan(4, 512, [1000, 1200], [1, 1, 1, 1], 4) == "head by head (1)"
+    assert plan(4, 512, [1000, 1200], [0, 1, 1, 0], 4, torch.float32) == "head by head (2)"
+    assert plan(8, 4096, [16384, 16384], [0, 0, 0, 1, 1, 1, 1, 1], 12) == "head by head (2)"
+    assert "heads=2 workgroups=256 tile_rows=128" in plan(8, 4096, [16384, 16384], [0, 0, 0, 1, 1, 1, 1, 1], 11)
+    with pytest.raises(binding.VocabTrimError):
+        plan(4, 512, [1000, 1200], [0, 2, 1, 0], 4)
 
 
 A = ctypes.c_void_p(0x10000)      # a well-aligned fake device address; never dereferenced on these paths
