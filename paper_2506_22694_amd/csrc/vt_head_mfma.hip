@@ -1140,18 +1140,18 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
     // rows past the 128th as one more group: shared by the eight waves (up to 8 hidden rows: eight column parts of
     // whole units, all of h in LDS), multiplied from LDS beside h's chunk (two groups of hidden rows) or after the
     // march (four groups); rows of at least 8 units
-    const bool handed_on = a.extra_rows != 0 && a.n > 8;
-    if (a.extra_rows != 0 && !handed_on &&
+    const bool xmany = a.extra_rows != 0 && a.n > 8;      // extra rows with more than 8 hidden rows
+    if (a.extra_rows != 0 && !xmany &&
         (a.extra_rows < 1 || a.extra_rows > 16 || NT != 1 || a.KC < a.d || a.ksplit != 1 ||
          a.nwaves != kStepWaves || (a.d / kUnitCols) % 8 != 0))
         return hipErrorInvalidValue;
-    if (handed_on &&
+    if (xmany &&
         (a.extra_rows < 1 || a.extra_rows > 16 || (NT != 2 && NT != 4) || a.ksplit != 1 || a.nwaves != kStepWaves ||
          a.d / kUnitCols < 8 || (a.zbuf == nullptr && a.L > 16)))
         return hipErrorInvalidValue;
     const size_t xtile = ((size_t)a.n * (kMfmaTileRows + 17) * sizeof(float) + 15) / 16 * 16 +
                          kStepWaves * 4 * 16 * sizeof(unsigned long long);      // logit tile and candidate keys of the epilogue
-    if (handed_on && NT == 2) {
+    if (xmany && NT == 2) {
         // the chunk and the extra rows' pieces fit the register prefetch; the accumulators' LDS lies behind the chunk,
         // inside the launch's LDS and clear of the logit tile
         const int ppr = min(a.KC, a.d) >> 3;
@@ -1163,7 +1163,7 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
             return hipErrorInvalidValue;
     }
     // (four groups: the pass after the march leaves its four range sums per logit behind the tile)
-    if (handed_on && NT == 4 && xtile + (size_t)4 * a.n * 16 * sizeof(float) > lds) return hipErrorInvalidValue;
+    if (xmany && NT == 4 && xtile + (size_t)4 * a.n * 16 * sizeof(float) > lds) return hipErrorInvalidValue;
     {
         const int tile_rows = 16 * (a.nwaves / a.ksplit) + a.extra_rows;
         if (a.nlists != (a.k + tile_rows - 1) / tile_rows) return hipErrorInvalidValue;
@@ -1171,17 +1171,17 @@ hipError_t launch_head_mfma(int NT, const MfmaArgs &a, size_t lds, hipStream_t s
     if ((size_t)a.d * 2 >= ((size_t)1 << 24)) return hipErrorInvalidValue;      // row offsets inside a tile: 24-bit factors
     switch (NT) {
         case 1:
-            if (handed_on) return hipErrorInvalidValue;      // planned with two groups of hidden rows
+            if (xmany) return hipErrorInvalidValue;      // planned with two groups of hidden rows
             if (a.extra_rows != 0) return launch_mfma_inst<1, kStepWaves, true>(a, lds, st);
             return a.nwaves == kStepWaves ? launch_mfma_inst<1, kStepWaves>(a, lds, st)
                                           : launch_mfma_inst<1, kMfmaMaxWaves>(a, lds, st);
         case 2:
             if (few) return launch_mfma_inst<2, kMfmaFewWaves>(a, lds, st);
-            return handed_on ? launch_mfma_inst<2, kStepWaves, false, 1>(a, lds, st)
+            return xmany ? launch_mfma_inst<2, kStepWaves, false, 1>(a, lds, st)
                              : launch_mfma_inst<2, kStepWaves>(a, lds, st);
         case 4:
             if (few) return launch_mfma_inst<4, kMfmaFewWaves>(a, lds, st);
-            return handed_on ? launch_mfma_inst<4, kStepWaves, false, 2>(a, lds, st)
+            return xmany ? launch_mfma_inst<4, kStepWaves, false, 2>(a, lds, st)
                              : launch_mfma_inst<4, kStepWaves>(a, lds, st);
         case 8:
         case 16: {
