@@ -998,7 +998,7 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_mfma_wide_kernel(const
             reinterpret_cast<unsigned long long *>(smem + (((size_t)a.n * tp * sizeof(float) + 15) & ~(size_t)15)) +
             (size_t)w * 4 * 16;
         for (int i0 = 4 * w; i0 < a.n; i0 += 4 * kStepWaves)
-            block_epilogue_rows4<8>(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
+            block_epilogue_rows4<8, true>(zt, tp, i0, a.n, rows_b, a.L, idq, a.out_logp_full, (size_t)a.k, row0, a.pms,
                                     a.pkeys, a.nlists, (int)blockIdx.x, lane, cand4);
     } else {
         for (int i = w; i < a.n; i += kStepWaves) {

@@ -248,7 +248,7 @@ __device__ __forceinline__ void block_epilogue_large(const float *zrow, int S, i
 // Tiles of at most 16 Q logits per hidden row (Q = 8: 128 rows, Q = 9: 144) and L <= 16: the 16 lanes of DPP row g
 // rank hidden row i0 + g (Q logits per lane), so a wave finishes four hidden rows in
 // the time of one.  zt: logit tile [hidden row][tp]; idq: ids of tile rows gl + 16 q.
-template <int Q>
+template <int Q, bool GUARDED = false>
 __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, int i0, int n, int rows_b, int L,
                                                      const int (&idq)[Q], float *__restrict__ logp_full, size_t k,
                                                      int row0, unsigned long long *__restrict__ pms,
@@ -262,18 +262,41 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
     int id[Q];
     float zq[Q];
     float lmax = -INFINITY;
+    if constexpr (GUARDED) {
+        // (a branch per logit: fewer registers live at once -- the many-row kernel has none to spare)
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int t = gl + 16 * q;
-        ord[q] = 0u;
-        id[q] = idq[q];
-        zq[q] = -INFINITY;
-        if (active && t < rows_b) {
-            const float z = zrow[t];
-            if (logp_full) logp_full[(size_t)i * k + row0 + t] = z;
-            zq[q] = z;
-            ord[q] = orderable_f32(z);
-            lmax = fmaxf(lmax, z);
+        for (int q = 0; q < Q; ++q) {
+            const int t = gl + 16 * q;
+            ord[q] = 0u;
+            id[q] = idq[q];
+            zq[q] = -INFINITY;
+            if (active && t < rows_b) {
+                const float z = zrow[t];
+                if (logp_full) logp_full[(size_t)i * k + row0 + t] = z;
+                zq[q] = z;
+                ord[q] = orderable_f32(z);
+                lmax = fmaxf(lmax, z);
+            }
+        }
+    } else {
+        // every lane reads -- past the tile's end its last logit again -- and selects afterwards: no branch per logit
+        // (a third of the instructions of a pass were those branches)
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int t = gl + 16 * q;
+            const bool ok = active && t < rows_b;
+            const float z = zrow[min(t, rows_b - 1)];
+            id[q] = idq[q];
+            zq[q] = ok ? z : -INFINITY;
+            ord[q] = ok ? orderable_f32(z) : 0u;
+            lmax = fmaxf(lmax, zq[q]);
+        }
+        if (logp_full != nullptr) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int t = gl + 16 * q;
+                if (active && t < rows_b) logp_full[(size_t)i * k + row0 + t] = zq[q];
+            }
         }
     }
     const float M = __uint_as_float(row16_allreduce_u32(__float_as_uint(lmax), OpMaxF32{}));
