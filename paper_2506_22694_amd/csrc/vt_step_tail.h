@@ -482,9 +482,11 @@ __device__ __forceinline__ void wait_loads16(u32x4 (&r)[16]) {
 // among the keys whose logit reaches T (a few dozen).  Those are compacted into LDS and ranked by
 // counting.  Returns false, having written nothing, when more than kDirectMaxCand keys reach T
 // (massive ties): the caller then merges the sorted lists round by round.
-template <int U, bool FULL>
+// lse_fn() is called once, after the wait for the keys, and returns the row's log-sum-exp (what it reduces was
+// requested by the caller before this call, so those loads and the keys' travel together); lse_out receives it.
+template <int U, bool FULL, typename LseFn>
 __device__ __forceinline__ bool finalize_row_direct(const unsigned long long *__restrict__ src, int total, int m,
-                                                    float lse, unsigned long long *stage,
+                                                    LseFn &&lse_fn, float &lse_out, unsigned long long *stage,
                                                     int *__restrict__ out_ids_row, float *__restrict__ out_logp_row,
                                                     int lane) {
     static_assert(U == 32 || U == 4, "unsupported register budget");
@@ -516,6 +518,8 @@ __device__ __forceinline__ bool finalize_row_direct(const unsigned long long *__
             if (u * kWave + lane >= total) kreg[u] = kNoKey;
         }
     }
+    const float lse = lse_fn();
+    lse_out = lse;
     unsigned top = 0u;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -576,9 +580,47 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
     constexpr int GROUP = kStepMaxBlocks;        // lists merged per pass
     constexpr int BQ = GROUP / kWave + (CARRY ? 1 : 0);   // lists per lane
     constexpr int U = 32;                        // 64-lane loads in flight per batch (16 KiB)
-    // log-sum-exp over all lists: requested first, reduced while the keys are in flight
-    float lm = -INFINITY, ls = 0.f;
-    {
+    // log-sum-exp over all lists.  Up to GROUP lists the (max, sum) words are requested first and reduced only
+    // after the keys of the direct merge have been requested too: one trip to memory instead of two in a row.
+    const int total_keys = B * L;
+    const bool direct = m <= kWave && (total_keys <= 4 * kWave ||
+                                       (total_keys <= kDirectKeysPerLane * kWave && (total_keys & 1) == 0));
+    float lse;
+    if (direct && B <= GROUP) {
+        unsigned long long ms[GROUP / kWave];
+#pragma unroll
+        for (int q = 0; q < GROUP / kWave; ++q) ms[q] = acquire_u64(pms_row + min(lane + kWave * q, B - 1));
+        auto lse_fn = [&]() {
+            float lm = -INFINITY, ls = 0.f;
+#pragma unroll
+            for (int q = 0; q < GROUP / kWave; ++q) {
+                if (lane + kWave * q < B) {
+                    const float Mb = __uint_as_float((unsigned)ms[q]);
+                    const float Sb = __uint_as_float((unsigned)(ms[q] >> 32));
+                    const float Mn = fmaxf(lm, Mb);
+                    ls = ls * __expf(lm - Mn) + Sb * __expf(Mb - Mn);   // exp(-inf) = 0 on the first term
+                    lm = Mn;
+                }
+            }
+            const float M = wave_max(lm);
+            return M + __logf(wave_sum(ls * __expf(lm - M)));
+        };
+        bool done;
+        if (total_keys == 32 * kWave)
+            done = finalize_row_direct<32, true>(pkeys_row, total_keys, m, lse_fn, lse, stage, out_ids_row, out_logp_row, lane);
+        else if (total_keys > 4 * kWave)
+            done = finalize_row_direct<32, false>(pkeys_row, total_keys, m, lse_fn, lse, stage, out_ids_row, out_logp_row, lane);
+        else
+            done = finalize_row_direct<4, false>(pkeys_row, total_keys, m, lse_fn, lse, stage, out_ids_row, out_logp_row, lane);
+        if (done) {
+            if (lane == 0) {
+                *lse_buf_i = lse;
+                if (out_lse_i) *out_lse_i = lse;
+            }
+            return;
+        }
+    } else {
+        float lm = -INFINITY, ls = 0.f;
         unsigned long long ms[GROUP / kWave];
         for (int b0 = 0; b0 < B; b0 += GROUP) {
 #pragma unroll
@@ -594,27 +636,8 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
                 }
             }
         }
-    }
-    const float M = wave_max(lm);
-    const float lse = M + __logf(wave_sum(ls * __expf(lm - M)));
-
-    // few enough keys to hold in registers: no rounds over the list heads
-    const int total_keys = B * L;
-    if (m <= kWave && (total_keys <= 4 * kWave || (total_keys <= kDirectKeysPerLane * kWave && (total_keys & 1) == 0))) {
-        bool done;
-        if (total_keys == 32 * kWave)
-            done = finalize_row_direct<32, true>(pkeys_row, total_keys, m, lse, stage, out_ids_row, out_logp_row, lane);
-        else if (total_keys > 4 * kWave)
-            done = finalize_row_direct<32, false>(pkeys_row, total_keys, m, lse, stage, out_ids_row, out_logp_row, lane);
-        else
-            done = finalize_row_direct<4, false>(pkeys_row, total_keys, m, lse, stage, out_ids_row, out_logp_row, lane);
-        if (done) {
-            if (lane == 0) {
-                *lse_buf_i = lse;
-                if (out_lse_i) *out_lse_i = lse;
-            }
-            return;
-        }
+        const float M = wave_max(lm);
+        lse = M + __logf(wave_sum(ls * __expf(lm - M)));
     }
 
     unsigned res_ord = 0u;
