@@ -15,8 +15,12 @@ constexpr int kFinalizeLdsBytes = 152 * 1024;  // staging budget of the finalize
 constexpr int kMaxDynamicLds = 159 * 1024;     // dynamic LDS the step kernels may request (160 KiB per CU less static use)
 constexpr int kTicketBytes = 2048;             // top counter + one 64-byte line per group of 16 workgroups
 constexpr int kGemvMaxN = 8;           // the VALU GEMV path covers n <= 8
-constexpr int kGemvSplitMinN = 4;      // from this many hidden rows a separate merge kernel (a workgroup per row)
-                                       // beats the merge by the last workgroup's eight waves
+constexpr int kGemvSplitMinN = 1;      // from this many hidden rows a separate merge kernel (a workgroup per row)
+                                       // beats the merge by the last workgroup to arrive.  Measured again since the merge
+                                       // kernel waits for memory once: it wins at every n (k = 65536, d = 3072: n = 1 64.9
+                                       // against 66.3 us, n = 2 67.8 / 69.3; k = 128256: n = 1 119.3 / 120.8, n = 3 123.5 /
+                                       // 124.9; d = 2048: 82.9 / 84.2) -- the arrival counters cost more than the kernel
+                                       // boundary.  The last workgroup still merges when a tree level is fused behind it.
 // ... but from 2 hidden rows on the matrix-core kernel is faster (n = 2: 38.7 against 39.4 us, n = 3: 38.8 / 39.9) when its 128-row tiles fill the 256 CUs in
 // one round (measured at d = 3072, n = 8: k = 28672: 36.9 against 37.4 us, 30720: 38.7 / 40.8, 32768: 39.9 / 41.8;
 // k = 24576: a tie; k = 16384: 29.8 / 27.4, k = 65536: 78.0 / 75.1)

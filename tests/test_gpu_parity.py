@@ -752,11 +752,12 @@ def test_step_workspace_needs_no_initialisation(k, d, n, m, tree):
 def test_soak_cross_workgroup_election_200k_steps_bit_identical():
     # The cross-workgroup hand-over (partials written through to memory, arrival counters, the last workgroup
     # reading everybody's partials past its caches) uses no cache-wide fence.  2 * 10^5 back-to-back steps on the
-    # paths that elect a last workgroup inside a kernel -- the small-n kernel's own merge (1 - 3 rows), the tree
-    # level fused into it, the tree level fused behind the matrix-core kernel's merge kernel -- with the shapes
-    # alternating on ONE workspace; every result is compared on the device, bit for bit, with the first result of
-    # its shape, and the first differing step (if any) is reported.
-    shapes = [(4099, 264, 3, 4, False), (1000, 512, 2, 3, False), (4099, 264, 3, 4, True), (9000, 1024, 1, 1, False),
+    # paths that elect a last workgroup inside a kernel -- the tree level fused into the small-n kernel (its last
+    # workgroup merges the lists and ranks the candidates; 1 - 3 rows), the tree level fused behind the matrix-core
+    # kernel's merge kernel -- and a plain step between them, with the shapes alternating on ONE workspace; every
+    # result is compared on the device, bit for bit, with the first result of its shape, and the first differing
+    # step (if any) is reported.
+    shapes = [(4099, 264, 3, 4, True), (1000, 512, 2, 3, True), (4099, 264, 3, 4, False), (9000, 1024, 1, 1, True),
               (32768, 3072, 8, 8, True), (16384, 2048, 40, 4, True)]
     weights = [60000, 60000, 40000, 30000, 5000, 5000]          # steps per shape: 2 * 10^5 in all
     cases = []
