@@ -4,8 +4,6 @@
 
 #include <hip/hip_runtime.h>
 
-#include <atomic>
-#include <chrono>
 #include <cstdio>
 #include <mutex>
 
@@ -28,24 +26,6 @@ inline int device_status(hipError_t e) {
     return VT_ERR_DEVICE;
 }
 inline int launch_status() { return device_status(hipGetLastError()); }
-
-// Arrival counters in a step workspace are stamped with a number no earlier launch of this process has used (see
-// arrive_and_elect): 48 bits, never zero.
-// The sequence starts at a point of its 2^48 - 1 values that differs from process to process (clock, address of
-// a static), so that bytes which merely look like a small counter are not mistaken for this process's first launches.
-unsigned long long generation_seed() {
-    static int anchor;
-    unsigned long long x = (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() ^
-                           ((unsigned long long)reinterpret_cast<uintptr_t>(&anchor) << 17);
-    x ^= x >> 33;
-    x *= 0xff51afd7ed558ccdull;      // 64-bit finaliser of a well-known hash mixer
-    x ^= x >> 33;
-    return x;
-}
-std::atomic<unsigned long long> g_generation{generation_seed()};
-inline unsigned long long next_generation() {
-    return (g_generation.fetch_add(1, std::memory_order_relaxed) % ((1ull << 48) - 1)) + 1;
-}
 
 // ---------------------------------------------------------------- library-owned step workspace
 // Device memory of the draft step for callers that cannot allocate (vt_draft_head_step_static): one array per
@@ -129,11 +109,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv, 
     p.nblocks = (k + rpb - 1) / rpb;
     p.tpitch = rpb + 1;
     p.L = m < rpb ? m : rpb;
-    const size_t stage = (size_t)p.nblocks * p.L * sizeof(unsigned long long);
-    {
-        const int conc = (int)(vt::kFinalizeLdsBytes / stage);
-        p.fin_conc = conc < vt::kStepWaves ? conc : vt::kStepWaves;
-    }
+    p.fin_conc = 1;      // the merge kernel takes one hidden row per workgroup
 
     // Up to 8 rows on the matrix-core kernel: its tiles must fill most of the 256 CUs in exactly one round.  A
     // tile is 16 rows per group of KS waves (KS = 1, 2, 4 waves share a group's columns) and a workgroup has up to
@@ -235,7 +211,7 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv, 
                 const int CS = cs_set[q];
                 if (CS >= need && CS * NP <= 24) {
                     const size_t tile = (size_t)S * NP * p.tpitch * sizeof(float);
-                    if (tile <= 96 * 1024 && (p.fin_conc >= 1 || p.L > vt::kGemvRowSelectBase - n / 2)) {
+                    if (tile <= 96 * 1024) {
                         p.gemv = true;
                         p.NP = NP;
                         p.CS = CS;
@@ -350,17 +326,12 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv, 
         // SIMD to itself (the selection rounds are bound by instruction issue)
         p.fin_conc = 1;
         p.fin_lds = (size_t)p.fin_conc * p.fin_stage_keys * sizeof(unsigned long long);
-        // (Merging in the main kernel's last workgroup, as the small-n kernel does, was measured for n <= 8:
-        // 41.1 against 39.9 us -- eight merge workgroups on eight CUs beat eight waves on one.)
+        // (Merging in the main kernel's last workgroup to arrive was measured for n <= 8: 41.1 against 39.9 us --
+        // eight merge workgroups on eight CUs beat eight waves on one; and for n <= 3 once more: 39.6 against 35.3.)
     } else {
         // many tokens per row: the selection rounds of the fused tail grow with L in every workgroup and the merge
         // stages B * L keys per row; the per-row tail on stored logits takes over (measured crossover)
-        // ... or when the merge's LDS staging cannot hold all n rows' lists at once (the rows would take turns)
-        p.row_select = p.L > vt::kGemvRowSelectBase - n / 2 || p.fin_conc < n;
-        if (!p.row_select) {
-            const size_t fin = (size_t)p.fin_conc * stage;
-            if (fin > p.lds) p.lds = fin;
-        }
+        p.row_select = p.L > vt::kGemvRowSelectBase - n / 2;
     }
 
     size_t off = kTicketBytes;
@@ -649,8 +620,7 @@ int vt_draft_head_step_plan(int32_t n, int32_t k, int32_t d, int32_t m, int w_ty
                       p.nwaves == vt::kStepWaves ? vt::kStepWaves : p.NT > 1 ? vt::kMfmaFewWaves : vt::kMfmaMaxWaves, p.nlists,
                       16 * (p.nwaves / p.ksplit) + p.extra_rows, p.nwaves, p.ksplit);
     }
-    const bool split = p.gemv && !p.row_select && chunk >= vt::kGemvSplitMinN;
-    const char *tail = p.row_select ? " + row_select_kernel" : (p.mfma || split) ? " + step_finalize_kernel" : "";
+    const char *tail = p.row_select ? " + row_select_kernel" : " + step_finalize_kernel";
     char groups[48] = "";
     if (chunk < n) std::snprintf(groups, sizeof groups, " x %d row groups", (n + chunk - 1) / chunk);
     std::snprintf(text, text_bytes, "%s%s%s", head, tail, groups);
@@ -730,9 +700,8 @@ int vt_draft_head_step_static(const void *h, int h_type, int32_t n, const void *
     void *ws = nullptr;
     const int rc = static_scratch_of_current_device(&ws);
     if (rc != VT_OK) return rc;
-    // Nothing has to be cleared here: the arrival counters at the head of the array are stamped per launch and
-    // recognise whatever an earlier call left in them, and everything behind them is rewritten by a step before
-    // it is read.
+    // Nothing has to be cleared here: a step rewrites everything it reads in the array before it reads it (the
+    // one counted word, the ticket of a fused tree level, is zeroed by the kernel that runs before its user).
     return vt_draft_head_step(h, h_type, n, W_trim, w_type, k, d, map, m, out_ids, out_logp, out_lse, out_logp_full,
                               ws, (size_t)VT_STATIC_WS_BYTES, stream);
 }
@@ -1041,31 +1010,16 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
         a.nblocks = p.nblocks;
         a.pms = pms;
         a.pkeys = pkeys;
-        a.tickets = reinterpret_cast<unsigned long long *>(wsb);
-        a.generation = next_generation();
-        a.out_ids = out_ids;
-        a.out_logp = out_logp;
-        a.out_lse = out_lse;
         a.out_logp_full = out_logp_full;
-        a.fin_conc = p.fin_conc;
         a.zbuf = nullptr;
         if (p.row_select) a.zbuf = out_logp_full != nullptr ? out_logp_full : reinterpret_cast<float *>(wsb + p.off_zbuf);
         if (tf.indexed && (p.row_select || out_logp_full != nullptr)) return VT_ERR_SHAPE;
         a.row_pack = tf.indexed ? tf.row_pack : 0x0706050403020100ull;
-        const bool split = !p.row_select && tf.cum == nullptr && n >= vt::kGemvSplitMinN;
-        a.split_tail = split ? 1 : 0;
-        a.tree_cum = tf.cum;
-        a.tree_K = tf.K;
-        a.tree_parent = tf.parent;
-        a.tree_token = tf.token;
-        a.tree_score = tf.score;
-        size_t lds = p.lds;
-        if (tf.cum != nullptr) {
-            // the fused ranking needs 12 bytes per (power-of-two padded) candidate plus a few words
-            size_t N2 = 64;
-            while (N2 < (size_t)n * m) N2 <<= 1;
-            if (lds < N2 * 12 + 256) lds = N2 * 12 + 256;
-        }
+        // a tree level fused behind the merge kernel: rows in order, at most kFinalizeTreeMaxN candidates
+        const bool tree_behind_merge = tf.cum != nullptr && !p.row_select;
+        if (tree_behind_merge && (tf.indexed || n * m > vt::kFinalizeTreeMaxN)) return VT_ERR_SHAPE;
+        a.ticket_clear = tree_behind_merge ? reinterpret_cast<unsigned *>(wsb) : nullptr;
+        const size_t lds = p.lds;
         const bool bf16 = w_type == VT_BF16;
         hipError_t e = hipErrorInvalidValue;
         switch (p.NP) {
@@ -1076,7 +1030,7 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             default: break;
         }
         if (e != hipSuccess) return device_status(e);
-        if (split) {
+        if (!p.row_select) {
             vt::FinalizeArgs f{};
             f.pms = pms;
             f.pkeys = pkeys;
@@ -1092,13 +1046,19 @@ int run_step_group(const void *h, int n, const void *W_trim, int w_type, int k, 
             f.lse_buf = lse_buf;
             f.row_pack = tf.row_pack;
             f.indexed = tf.indexed;
+            f.tree_cum = tf.cum;
+            f.tree_K = tf.K;
+            f.tree_parent = tf.parent;
+            f.tree_token = tf.token;
+            f.tree_score = tf.score;
+            f.ticket = reinterpret_cast<unsigned *>(wsb);
             e = vt::launch_step_finalize(f, (size_t)f.stage_keys * sizeof(unsigned long long), st);
             if (e != hipSuccess) return device_status(e);
         }
         if (p.row_select) {
             vt::launch_row_select(a.zbuf, map, n, k, m, out_ids, out_logp, out_lse, lse_buf, st);
             if (out_logp_full != nullptr) vt::launch_sub_lse(out_logp_full, lse_buf, n, k, st);
-            if (tf.cum != nullptr) {       // the fused tree level needs the in-kernel merge: run the expansion kernel
+            if (tf.cum != nullptr) {       // the fused tree level needs the merge kernel: run the expansion kernel
                 vt::TreeArgs t;
                 t.parent_cum = tf.cum;
                 t.vals = out_logp;

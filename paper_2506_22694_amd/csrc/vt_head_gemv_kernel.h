@@ -15,14 +15,13 @@
 //     one finished logit per lane, which goes to an LDS tile;
 //   * the workgroup epilogue turns the tile into (max, sum-exp) and the
 //     workgroup's best m candidates per hidden row;
-//   * the last workgroup to arrive (two-level ticket) merges all partials: lse,
-//     top-m, remap.  No second launch, no host round trip, no cache-wide fence.
+//   * the kernel ends there; step_finalize_kernel (a workgroup per hidden row)
+//     merges the partials: lse, top-m, remap.
 #pragma once
 #include "vt_device.h"
 #include "vt_launch.h"
 #include "vt_step.h"
 #include "vt_step_tail.h"
-#include "vt_tree_dev.h"
 #include <type_traits>
 
 namespace vt {
@@ -253,6 +252,8 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
             hreg[c][i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.h) + (size_t)ii * rs + coff[c]);
         }
     }
+    if (a.ticket_clear != nullptr && blockIdx.x == 0 && threadIdx.x == 0)
+        __hip_atomic_store(a.ticket_clear, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // target ids of the tile rows this lane will rank in the epilogue (small tiles)
     const int id0 = a.map[row0 + min(lane, rows_b - 1)];
     const int id1 = a.map[row0 + min(lane + kWave, rows_b - 1)];
@@ -362,45 +363,12 @@ __global__ void __launch_bounds__(kStepWaves *kWave) head_gemv_kernel(const Step
                 block_epilogue_large(zrow, S, sstride, rows_b, a.L, a.map + row0, full, pms_slot, pk_slot, lane, cand);
         }
     }
-
-    if (a.split_tail) {
-        wait_stores_done();
-        return;
-    }
-    float *lse_buf = reinterpret_cast<float *>(reinterpret_cast<char *>(a.tickets) + kTicketBytes);
-    if (!arrive_and_elect(a.tickets, a.nblocks, a.generation)) return;
-    finalize_rows(a.pms, a.pkeys, a.nblocks, a.L, a.n, a.m, a.fin_conc, a.out_ids, a.out_logp, a.out_lse, lse_buf,
-                  smem, w, lane, a.row_pack);
-    if (a.tree_cum != nullptr) {
-        // Fused tree level: the rows' tokens and log-probs were just written by the waves of this workgroup;
-        // once those stores are acknowledged the workgroup ranks the n * m candidates cum[i] + logp[i][j]
-        // (rank by counting, keys in the LDS the merge no longer needs) and keeps the best tree_K.
-        wait_stores_done();
-        __syncthreads();
-        TreeArgs t;
-        t.parent_cum = a.tree_cum;
-        t.vals = a.out_logp;
-        t.ids = a.out_ids;
-        t.N = a.n * a.m;
-        t.m = a.m;
-        t.K = a.tree_K;
-        t.index_order = 0;
-        t.out_a = a.tree_parent;
-        t.out_token = a.tree_token;
-        t.out_score = a.tree_score;
-        int N2 = kWave;
-        while (N2 < t.N) N2 <<= 1;
-        unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);
-        unsigned *cnt = reinterpret_cast<unsigned *>(smem + (size_t)N2 * 8);
-        int *wave_tot = reinterpret_cast<int *>(smem + (size_t)N2 * 12);
-        tree_select_by_count<NW * kWave, true>(t, N2, keys, cnt, wave_tot);
-    }
 }
 
 template <bool BF16, int NP, int CS>
 inline hipError_t launch_gemv_inst(const StepArgs &a, size_t lds, hipStream_t st) {
     auto kern = head_gemv_kernel<BF16, NP, CS>;
-    // allow large dynamic LDS (finalize staging budget + headroom), once per device
+    // allow large dynamic LDS (the logit tile of tall row blocks), once per device
     static LdsLimitOnce lds_limit;
     hipError_t e = allow_dynamic_lds(lds_limit, {reinterpret_cast<const void *>(kern)}, kMaxDynamicLds);
     if (e != hipSuccess) return e;

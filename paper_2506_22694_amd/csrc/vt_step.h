@@ -13,14 +13,13 @@ constexpr int kStepMaxRowsPerBlock = 1024;
 constexpr int kStepMaxK = kStepMaxBlocks * kStepMaxRowsPerBlock;
 constexpr int kFinalizeLdsBytes = 152 * 1024;  // staging budget of the finalize stage
 constexpr int kMaxDynamicLds = 159 * 1024;     // dynamic LDS the step kernels may request (160 KiB per CU less static use)
-constexpr int kTicketBytes = 2048;             // top counter + one 64-byte line per group of 16 workgroups
+constexpr int kTicketBytes = 2048;             // head of a step workspace: the ticket word of a fused tree level
 constexpr int kGemvMaxN = 8;           // the VALU GEMV path covers n <= 8
-constexpr int kGemvSplitMinN = 1;      // from this many hidden rows a separate merge kernel (a workgroup per row)
-                                       // beats the merge by the last workgroup to arrive.  Measured again since the merge
-                                       // kernel waits for memory once: it wins at every n (k = 65536, d = 3072: n = 1 64.9
-                                       // against 66.3 us, n = 2 67.8 / 69.3; k = 128256: n = 1 119.3 / 120.8, n = 3 123.5 /
-                                       // 124.9; d = 2048: 82.9 / 84.2) -- the arrival counters cost more than the kernel
-                                       // boundary.  The last workgroup still merges when a tree level is fused behind it.
+// The small-n kernel ends after publishing its lists and a separate merge kernel (a workgroup per hidden row)
+// follows.  Merging in the kernel's last workgroup to arrive (arrival counters, no second launch) was the first
+// design; it lost from 4 hidden rows on at once, and at every n since the merge kernel waits for memory once
+// (k = 65536, d = 3072: n = 1 64.9 against 66.3 us, n = 2 67.8 / 69.3; k = 128256: n = 1 119.3 / 120.8, n = 3
+// 123.5 / 124.9; d = 2048: 82.9 / 84.2): the counters cost more than the kernel boundary.
 // ... but from 2 hidden rows on the matrix-core kernel is faster (n = 2: 38.7 against 39.4 us, n = 3: 38.8 / 39.9) when its 128-row tiles fill the 256 CUs in
 // one round (measured at d = 3072, n = 8: k = 28672: 36.9 against 37.4 us, 30720: 38.7 / 40.8, 32768: 39.9 / 41.8;
 // k = 24576: a tie; k = 16384: 29.8 / 27.4, k = 65536: 78.0 / 75.1)
@@ -54,25 +53,14 @@ struct StepArgs {
     int nblocks;
     unsigned long long *pms;    // [n, nblocks]  max | sumexp << 32
     unsigned long long *pkeys;  // [n, nblocks, L] candidate keys, sorted descending per list
-    unsigned long long *tickets;     // arrival counters (kTicketBytes); any contents
-    unsigned long long generation;   // drawn afresh by the host for every launch, 1 <= generation < 2^48
-    int *out_ids;             // [n, m]
-    float *out_logp;          // [n, m]
-    float *out_lse;           // [n] or null
     float *out_logp_full;     // [n, k] or null (raw logits are written first, lse subtracted later)
-    int fin_conc;             // waves that run the finalize stage concurrently (LDS budget)
     float *zbuf;              // [n, k] or null: store the logits and leave the rest of the step to row_select_kernel
-    int split_tail;           // != 0: the kernel ends after publishing its lists; step_finalize_kernel merges them
-    // hidden row i is row (row_pack >> 8 i) & 255 of h and of the outputs: 0x0706050403020100 for rows 0 .. n-1,
-    // other values when the rows are picked out of a larger batch (several heads per call)
+    // hidden row i is row (row_pack >> 8 i) & 255 of h: 0x0706050403020100 for rows 0 .. n-1, other values when
+    // the rows are picked out of a larger batch (several heads per call)
     unsigned long long row_pack;
-    // fused tree level (all null / 0 when not asked for): after the merge the last workgroup keeps the
-    // tree_K best of the n * m candidates scored tree_cum[i] + out_logp[i][j]
-    const float *tree_cum;    // [n] or null
-    int tree_K;
-    int *tree_parent;         // [tree_K]
-    int *tree_token;          // [tree_K]
-    float *tree_score;        // [tree_K]
+    // or null: a word the kernel sets to zero (the merge kernel behind it counts its workgroups there when a tree
+    // level is fused; the kernel boundary orders the two)
+    unsigned *ticket_clear;
 };
 
 // ---- matrix-core path (n > 8) ----

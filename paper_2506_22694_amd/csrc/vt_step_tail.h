@@ -380,58 +380,6 @@ __device__ __forceinline__ void block_epilogue_rows4(const float *zt, int tp, in
     }
 }
 
-// ------------------------------------------------------------------ arrival
-// Two-level arrival counters (groups of 16 workgroups, then one counter for the
-// groups): same-address atomics are serialised at the memory side, so a single
-// counter would put ~256 of them on the critical path.
-//
-// A counter is a 64-bit word, generation << 16 | arrivals.  The generation is a number the host draws afresh for
-// every launch, so whatever a counter holds when a launch begins -- the bytes of a fresh allocation, the count of
-// a launch that never finished, another shape's counters -- belongs to another generation and is recognised as
-// such: the workgroup that meets it replaces it by this launch's empty counter (compare-and-swap, repeated until
-// the word carries this generation) and arrives again.  Only the first arrivals of a launch take that detour;
-// the last one, whose answer everybody waits for, finds its generation in place.  The workspace therefore needs
-// no initialisation.  (A finished launch leaves zero behind, which no generation equals: a replayed graph,
-// whose launches repeat their generations, starts from a foreign word like any other launch.)
-__device__ __forceinline__ unsigned arrive(unsigned long long *counter, unsigned long long gen) {
-    unsigned long long old = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if ((old >> 16) != gen) {
-        for (;;) {
-            unsigned long long seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((seen >> 16) == gen) break;
-            if (__hip_atomic_compare_exchange_strong(counter, &seen, gen << 16, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT))
-                break;
-        }
-        // from here on the word carries this generation until the launch's last arrival: additions only
-        old = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    return (unsigned)(old & 0xFFFFull);
-}
-// Returns true in exactly one workgroup: the last to arrive.
-__device__ __forceinline__ bool arrive_and_elect(unsigned long long *tickets, int nblocks, unsigned long long gen) {
-    __shared__ int s_last;
-    wait_stores_done();     // this wave's publications are acknowledged
-    __syncthreads();        // ... and so are those of every other wave of the workgroup
-    if (threadIdx.x == 0) {
-        const int g = (int)blockIdx.x >> 4;
-        const int ngroups = (nblocks + 15) >> 4;
-        const int gsize = min(16, nblocks - (g << 4));
-        unsigned long long *gt = tickets + 8 * (1 + g);      // one 64-byte line per counter
-        int last = 0;
-        if (arrive(gt, gen) == (unsigned)(gsize - 1)) {
-            __hip_atomic_store(gt, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (arrive(tickets, gen) == (unsigned)(ngroups - 1)) {
-                __hip_atomic_store(tickets, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                last = 1;
-            }
-        }
-        s_last = last;
-    }
-    __syncthreads();
-    return s_last != 0;
-}
-
 // A row's results are written through to memory (relaxed agent-scope stores, like the partials): a tree level
 // fused behind the merge reads them from another workgroup, possibly on another XCD, whose L2 would not see a
 // line that is still dirty in this one's.
@@ -739,26 +687,6 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
     if (lane == 0) {
         *lse_buf_i = lse;
         if (out_lse_i) *out_lse_i = lse;
-    }
-}
-
-// Last workgroup: waves split the hidden rows; `fin_conc` waves work at a time
-// (LDS staging budget).  Hidden row i (< 8) writes output row (row_pack >> 8 i) & 255.
-constexpr unsigned long long kRowsInOrder = 0x0706050403020100ull;
-__device__ __forceinline__ void finalize_rows(const unsigned long long *__restrict__ pms,
-                                           const unsigned long long *__restrict__ pkeys, int B, int L, int n, int m,
-                                           int fin_conc, int *__restrict__ out_ids, float *__restrict__ out_logp,
-                                           float *__restrict__ out_lse, float *__restrict__ lse_buf,
-                                           unsigned char *smem, int w, int lane,
-                                           unsigned long long row_pack = kRowsInOrder) {
-    if (w < fin_conc) {
-        unsigned long long *stage = reinterpret_cast<unsigned long long *>(smem) + (size_t)w * B * L;
-        for (int i = w; i < n; i += fin_conc) {
-            const int o = (int)((row_pack >> (8 * i)) & 0xFFull);
-            finalize_row<false>(pms + (size_t)i * B, pkeys + (size_t)i * B * L, B, L, m, stage,
-                                out_ids + (size_t)o * m, out_logp + (size_t)o * m, out_lse ? out_lse + o : nullptr,
-                                lse_buf + i, lane);
-        }
     }
 }
 

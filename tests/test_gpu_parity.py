@@ -715,9 +715,9 @@ def test_step_workspace_reuse_poison_and_determinism():
 @pytest.mark.parametrize("k,d,n,m,tree", [(65536, 3072, 1, 1, False), (1000, 512, 2, 3, False), (4099, 264, 3, 4, True),
                                           (32768, 3072, 8, 8, True), (32768, 2048, 40, 4, True)])
 def test_step_workspace_needs_no_initialisation(k, d, n, m, tree):
-    # shapes whose last workgroup is elected through the arrival counters at the head of the workspace (the small-n
-    # kernel's own merge; the tree level fused behind a merge kernel): whatever the workspace holds -- fresh
-    # bytes, all ones, text, the counters of other shapes -- the results are those of a zeroed workspace
+    # plain steps on both streaming kernels, and tree levels fused behind a merge kernel (whose workgroups draw
+    # tickets from a word at the head of the workspace): whatever the workspace holds -- fresh bytes, all ones,
+    # text, what other shapes left there -- the results are those of a zeroed workspace
     W, map_ = synth.trimmed_head_direct(k, d, seed=15 + n, dtype="bf16")
     h = synth.hidden_rows(n, d, seed=15 + n, dtype="bf16")
     dW, dmap, dh = to_dev(W), to_dev(map_), to_dev(h)
@@ -1174,9 +1174,8 @@ def test_build_sixteen_heads_in_one_batch_llama_vocabulary():
                                           (4200, 1024, 16, 8, 100, "bf16"), (4200, 1024, 64, 8, 512, "bf16"),
                                           (4200, 1024, 65, 8, 8, "bf16"), (16384, 2048, 5, 11, 55, "bf16")])
 def test_draft_tree_level_equals_step_then_expand(k, d, n, m, K, dt):
-    # fused behind the step where one kernel sees all rows' results (the small-n kernel's last workgroup; the
-    # last workgroup of the matrix-core path's merge kernel for up to 512 candidates), step + expansion kernel
-    # otherwise: same results either way, and both equal to the oracle's step followed by the oracle's
+    # fused behind the step where one kernel sees all rows' results (the last workgroup of the step's merge
+    # kernel, for up to 512 candidates), step + expansion kernel otherwise: same results either way, and both equal to the oracle's step followed by the oracle's
     # expansion on the GPU's log-probs
     W, map_ = synth.trimmed_head_direct(k, d, seed=k + n, dtype=dt)
     h = synth.hidden_rows(n, d, seed=k + n + 1, dtype=dt)

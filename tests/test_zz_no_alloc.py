@@ -45,8 +45,8 @@ def _static_step(h, W, mp, n, k, m, want_lse=True, want_full=False):
 @pytest.mark.gpu
 def test_static_scratch_step_matches_workspace_step_two_calls_second_smaller():
     # first call: the headline shape (matrix-core kernel + merge kernel); second call, right behind it on the
-    # same array: a smaller head with fewer rows (small-n kernel, merge by the last workgroup: it uses the
-    # arrival counters at the head of the array); then the first shape again
+    # same array: a smaller head with fewer rows (small-n kernel + merge kernel: other offsets inside the
+    # array); then the first shape again
     cases = [(32768, 3072, 8, 8, 31, "bf16"), (1000, 512, 2, 3, 32, "bf16"), (32768, 3072, 8, 8, 31, "bf16"),
              (4096, 256, 4, 4, 33, "f32")]
     for (k, d, n, m, seed, dtype) in cases:
