@@ -53,11 +53,16 @@ __device__ __forceinline__ void stage_tables(const SelBufs &b, unsigned *hs) {
     __syncthreads();
 }
 
-// true iff every count has the same byte p (one bin holds all V).  All 64 lanes must call.
-__device__ __forceinline__ bool byte_idle(const unsigned *__restrict__ gtot, int p, int V) {
-    bool idle = false;
-    for (int d = lane_id(); d < kDigits; d += kWave) idle |= gtot[p * kDigits + d] == (unsigned)V;
-    return __ballot(idle) != 0ull;
+// true iff every count has the same byte p (one bin holds all V); *digit is then that byte.  All 64 lanes must call.
+__device__ __forceinline__ bool byte_idle(const unsigned *__restrict__ gtot, int p, int V, int *digit = nullptr) {
+    int mine = -1;
+    for (int d = lane_id(); d < kDigits; d += kWave) {
+        if (gtot[p * kDigits + d] == (unsigned)V) mine = d;
+    }
+    const unsigned long long who = __ballot(mine >= 0);
+    if (who == 0ull) return false;
+    if (digit != nullptr) *digit = __builtin_amdgcn_readlane(mine, __ffsll((long long)who) - 1);
+    return true;
 }
 
 // Walks the byte positions from 7 down to `stop + 1`, choosing at each the digit in which the k-th
@@ -78,9 +83,14 @@ __device__ __forceinline__ SelState sel_state(const unsigned *hs, int V, int k, 
     s.krem = k;
     s.top = -1;
     for (int q = kBytes - 1; q > stop; --q) {
-        const bool idle = byte_idle(gtot, q, V);
-        if (!idle && s.top < 0) s.top = q;
-        const unsigned *H = (idle || q == s.top) ? gtot + q * kDigits : chist + q * kDigits;
+        int same = 0;
+        const bool idle = byte_idle(gtot, q, V, &same);
+        if (idle) {      // nothing to choose at this position, and nobody to leave behind
+            s.prefix = (s.prefix << 8) | (unsigned long long)same;
+            continue;
+        }
+        if (s.top < 0) s.top = q;
+        const unsigned *H = q == s.top ? gtot + q * kDigits : chist + q * kDigits;
         // lane l holds digits 255 - 4 l .. 252 - 4 l (descending); inclusive scan over lanes
         unsigned v[4], sum = 0;
 #pragma unroll
@@ -160,15 +170,17 @@ __global__ void __launch_bounds__(kSelectThreads) sel_hist_kernel(const long lon
     const int k = sb.k[blockIdx.y];
     __shared__ unsigned h[kDigits];
     __shared__ unsigned hs[2 * kBytes * kDigits];
+    // this thread's count is requested first: it depends on nothing, and its trip to memory passes while the
+    // tables are staged and walked (these kernels are chains of latencies, not of work)
+    const int j = blockIdx.x * kSelectThreads + threadIdx.x;
+    const unsigned long long c = j < V ? (unsigned long long)counts[j] : 0ull;
     stage_tables(b, hs);
     if (byte_idle(hs, p, V)) return;
     const SelState s = sel_state(hs, V, k, p);
     if (s.top < 0 || p >= s.top) return;          // the highest varying byte uses the totals themselves
     if (threadIdx.x < kDigits) h[threadIdx.x] = 0u;
     __syncthreads();
-    const int j = blockIdx.x * kSelectThreads + threadIdx.x;
     if (j < V) {
-        const unsigned long long c = (unsigned long long)counts[j];
         if ((c >> (8 * (p + 1))) == s.prefix) atomicAdd(&h[(int)((c >> (8 * p)) & 255ull)], 1u);
     }
     __syncthreads();
@@ -189,13 +201,13 @@ __global__ void __launch_bounds__(kSelectThreads) sel_count_kernel(const long lo
     const int k = sb.k[blockIdx.y];
     __shared__ int s_gt[kSelWaves], s_eq[kSelWaves];
     __shared__ unsigned hs[2 * kBytes * kDigits];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int j = blockIdx.x * kSelectThreads + tid;
+    const unsigned long long c = j < V ? (unsigned long long)counts[j] : 0ull;      // requested before the walk
     stage_tables(b, hs);
     unsigned long long T;
     int r;
     sel_threshold(hs, V, k, T, r);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int j = blockIdx.x * kSelectThreads + tid;
-    const unsigned long long c = j < V ? (unsigned long long)counts[j] : 0ull;
     const int ngt = __popcll(__ballot(j < V && c > T)), neq = __popcll(__ballot(j < V && c == T));
     if (lane == 0) {
         s_gt[w] = ngt;
@@ -222,25 +234,26 @@ __global__ void __launch_bounds__(kSelectThreads) sel_write_kernel(const long lo
     __shared__ int s_gt[kSelWaves + 1], s_eq[kSelWaves + 1];
     __shared__ int s_red[2 * kSelWaves];
     __shared__ unsigned hs[2 * kBytes * kDigits];
-    stage_tables(b, hs);
-    unsigned long long T;
-    int r;
-    sel_threshold(hs, V, k, T, r);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    // ids above / at the threshold in the workgroups before this one
+    // requested before the walk: this thread's count, and the ids above / at the threshold in the workgroups
+    // before this one
+    const int j = blockIdx.x * kSelectThreads + tid;
+    const unsigned long long c = j < V ? (unsigned long long)counts[j] : 0ull;
     int gb = 0, eb = 0;
     for (int x = tid; x < (int)blockIdx.x; x += kSelectThreads) {
         gb += (int)b.tab[2 * x];
         eb += (int)b.tab[2 * x + 1];
     }
+    stage_tables(b, hs);
+    unsigned long long T;
+    int r;
+    sel_threshold(hs, V, k, T, r);
     gb = wave_sum_i32(gb);
     eb = wave_sum_i32(eb);
     if (lane == 0) {
         s_red[w] = gb;
         s_red[kSelWaves + w] = eb;
     }
-    const int j = blockIdx.x * kSelectThreads + tid;
-    const unsigned long long c = j < V ? (unsigned long long)counts[j] : 0ull;
     const bool gt = j < V && c > T, eq = j < V && c == T;
     const unsigned long long bg = __ballot(gt), be = __ballot(eq);
     if (lane == 0) {
