@@ -1172,7 +1172,8 @@ def test_build_sixteen_heads_in_one_batch_llama_vocabulary():
                                           (3000, 200, 12, 4, 9, "bf16"), (32768, 4096, 64, 8, 8, "bf16"),
                                           (5000, 3072, 8, 8, 8, "bf16"), (32768, 2048, 1, 1, 1, "bf16"),
                                           (4200, 1024, 16, 8, 100, "bf16"), (4200, 1024, 64, 8, 512, "bf16"),
-                                          (4200, 1024, 65, 8, 8, "bf16"), (16384, 2048, 5, 11, 55, "bf16")])
+                                          (4200, 1024, 65, 8, 8, "bf16"), (16384, 2048, 5, 11, 55, "bf16"),
+                                          (65536, 3072, 8, 8, 8, "bf16"), (3000, 200, 7, 9, 20, "bf16")])
 def test_draft_tree_level_equals_step_then_expand(k, d, n, m, K, dt):
     # fused behind the step where one kernel sees all rows' results (the last workgroup of the step's merge
     # kernel, for up to 512 candidates), step + expansion kernel otherwise: same results either way, and both equal to the oracle's step followed by the oracle's
