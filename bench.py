@@ -19,7 +19,9 @@ the device: the other workloads' draft steps ("other_configs": 1B chain and its
 full-vocabulary control, task head, 3B full-vocabulary control, 8B tree, stress),
 1000 consecutive tree steps as one span with their ids checked against the
 oracle on sampled steps ("tree_run"), the k x n x m sweep of the 3B shape
-("sweep") and the paper's own trimmed sizes ("paper_k").  --quick skips those.
+("sweep"), the paper's own trimmed sizes ("paper_k") and the stress workload's
+calibration ("stress_calibration": 10^8 ids counted, the d = 8192 head selected
+and gathered).  --quick skips those.
 
 Prints ONE JSON line on stdout.  Everything else goes to stderr.
 """
@@ -494,6 +496,50 @@ def main():
             paper_k += time_shapes(3072, kk, [(1, 1), (8, 8)], 91, names=["3B-shaped head"] * 2)
             paper_k += time_shapes(4096, kk, [(32, 8), (64, 8)], 92, names=["8B-shaped head, tree"] * 2)
 
+    # ------------------------------------------------------------------ the stress configuration's calibration
+    # 10^8 ids, Zipf(1.05), counted; the head of d = 8192 selected and gathered (its draft step is the "stress" row
+    # of other_configs).  The full head is drawn on the device: the gather is a copy, whatever the values.
+    stress_cal = None
+    if not args.quick and not args.no_calibration:
+        n8 = 100_000_000
+        t0 = time.time()
+        ids8 = torch.from_numpy(synth.zipf_ids(n8, V, 1.05, 505, True)).to(dev)
+        log(f"stress calibration ids ready in {time.time() - t0:.1f}s")
+        counts8 = torch.zeros(V, dtype=torch.int64, device=dev)
+        ws_c8 = torch.empty(vt.load_library().vt_count_tokens_ws_bytes(V, n8), dtype=torch.uint8, device=dev)
+        vt.count_tokens(ids8, V, counts=counts8, ws=ws_c8)
+        once8 = counts8.clone()
+        ok8 = int(once8.sum().item()) == n8
+        wake(lambda _: vt.count_tokens(ids8, V, counts=counts8, ws=ws_c8))
+        us_c8 = time_region(lambda _: vt.count_tokens(ids8, V, counts=counts8, ws=ws_c8), 20)
+        counts8.copy_(once8)
+        del ids8, ws_c8
+        d8, k8 = 8192, 32768
+        W8 = torch.empty((V, d8), dtype=torch.bfloat16, device=dev)
+        for lo in range(0, V, 16384):        # drawn in slices: the fp32 draws of the whole head would take 4 GB more
+            W8[lo:lo + 16384] = (torch.randn((min(16384, V - lo), d8), device=dev) * 0.02).to(torch.bfloat16)
+        ws_b8 = torch.empty(vt.load_library().vt_build_trimmed_head_ws_bytes(V, d8, k8), dtype=torch.uint8, device=dev)
+        map8 = torch.empty(k8, dtype=torch.int32, device=dev)
+        Wt8 = torch.empty((k8, d8), dtype=torch.bfloat16, device=dev)
+        for _ in range(2):
+            vt.build_trimmed_head(counts8, W8, k8, ws=ws_b8, out_map=map8, out_W=Wt8)
+        us_s8 = time_region(lambda _: vt.build_trimmed_head(counts8, None, k8, ws=ws_b8, out_map=map8), 20)
+        us_b8 = time_region(lambda _: vt.build_trimmed_head(counts8, W8, k8, ws=ws_b8, out_map=map8, out_W=Wt8), 10)
+        rows8 = torch.randint(0, k8, (64,), device=dev)
+        ok8 = ok8 and bool(torch.equal(Wt8[rows8], W8[map8[rows8].long()]))
+        gb8 = 2 * k8 * d8 * 2
+        stress_cal = {
+            "count_ids": n8, "zipf_s": 1.05, "count_us": round(us_c8, 2),
+            "count_gids_per_s": round(n8 / us_c8 / 1e3, 1), "count_id_stream_gbps": round(n8 * 4 / us_c8 / 1e3, 1),
+            "count_frac_of_hbm_peak": round(n8 * 4 / us_c8 / 1e3 / HBM_PEAK_GBPS, 4),
+            "d": d8, "k": k8, "select_us": round(us_s8, 2), "build_us": round(us_b8, 2),
+            "gather_us": round(us_b8 - us_s8, 2), "gather_gbps": round(gb8 / (us_b8 - us_s8) / 1e3, 1),
+            "gather_frac_of_hbm_peak": round(gb8 / (us_b8 - us_s8) / 1e3 / HBM_PEAK_GBPS, 4),
+            "counts_sum_and_sampled_rows_ok": ok8,
+        }
+        log("stress calibration:", stress_cal)
+        del W8, Wt8, counts8
+
     # ------------------------------------------------------------------ CPU baseline (the oracle, untuned)
     cpu = None
     if not args.no_cpu_baseline:
@@ -563,6 +609,7 @@ def main():
         "hip_graph_us_per_step": graph_us,
         "full_vocab_control": full,
         "tree_selection": tree_sel,
+        "stress_calibration": stress_cal,
         "multi_head_step": multi,
     }
     if tree is not None:
