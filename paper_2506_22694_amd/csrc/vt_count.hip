@@ -16,6 +16,7 @@
 #include "vt_build.h"
 #include "vt_device.h"
 #include "vt_launch.h"
+#include <type_traits>
 
 namespace vt {
 
@@ -53,8 +54,9 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
     const long long nvec = (n_ids - head) / IPV;
     const long long v0 = nvec * chunk / nchunks, v1 = nvec * (chunk + 1) / nchunks;
     unsigned invalid = 0;
+    // One id.  (The scalar head and tail of the stream.)
     auto tally = [&](long long t) {
-        if (t < 0 || t >= (long long)V) {
+        if ((unsigned long long)t >= (unsigned long long)V) {
             invalid += 1u;
         } else {
             const unsigned b = (unsigned)((int)t - lo);
@@ -69,17 +71,62 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
             }
         }
     };
-    const u32x4 *vp = reinterpret_cast<const u32x4 *>(static_cast<const char *>(ids_v) + (size_t)head * IDB);
-    auto tally_vec = [&](const u32x4 q) {
-        if constexpr (IDS64) {
-            tally((long long)(((unsigned long long)q.y << 32) | q.x));
-            tally((long long)(((unsigned long long)q.w << 32) | q.z));
-        } else {
-            tally((long long)(int)q.x);
-            tally((long long)(int)q.y);
-            tally((long long)(int)q.z);
-            tally((long long)(int)q.w);
+    // The ids of NV 16-byte vectors: all their LDS atomics are issued before the first result is looked at -- a
+    // wave that waited for every atomic's return before the next id spent most of its time in that wait -- and the
+    // rare increment that sets bit 15 is handled behind one test for the whole batch.
+    constexpr int IPV0 = IDS64 ? 2 : 4;
+    auto tally_ids = [&](auto ncount, const long long *t) {
+        constexpr int N = decltype(ncount)::value;
+        unsigned b[N], sh[N], old[N];
+        bool in[N];
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            invalid += (unsigned long long)t[q] >= (unsigned long long)V ? 1u : 0u;
+            b[q] = (unsigned)((int)t[q] - lo);
+            in[q] = (unsigned long long)t[q] < (unsigned long long)V && b[q] < (unsigned)nb;
+            sh[q] = (b[q] & 1u) << 4;
+            old[q] = 0u;
         }
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            if (in[q]) old[q] = atomicAdd(&words[b[q] >> 1], 1u << sh[q]);
+        }
+        bool spill = false;
+#pragma unroll
+        for (int q = 0; q < N; ++q) spill |= in[q] && ((old[q] >> sh[q]) & 0xFFFFu) == 0x7FFFu;
+        if (spill) {
+#pragma unroll
+            for (int q = 0; q < N; ++q) {
+                if (in[q] && ((old[q] >> sh[q]) & 0xFFFFu) == 0x7FFFu) {
+                    // this increment set bit 15: 32768 occurrences move from the bin to the result counter
+                    atomicSub(&words[b[q] >> 1], 0x8000u << sh[q]);
+                    atomicAdd(&counts[t[q]], 32768ull);
+                }
+            }
+        }
+    };
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(static_cast<const char *>(ids_v) + (size_t)head * IDB);
+    auto unpack = [&](const u32x4 q, long long *t) {
+        if constexpr (IDS64) {
+            t[0] = (long long)(((unsigned long long)q.y << 32) | q.x);
+            t[1] = (long long)(((unsigned long long)q.w << 32) | q.z);
+        } else {
+            t[0] = (long long)(int)q.x;
+            t[1] = (long long)(int)q.y;
+            t[2] = (long long)(int)q.z;
+            t[3] = (long long)(int)q.w;
+        }
+    };
+    auto tally_vec = [&](const u32x4 q) {
+        long long t[IPV0];
+        unpack(q, t);
+        tally_ids(std::integral_constant<int, IPV0>{}, t);
+    };
+    auto tally_vec2 = [&](const u32x4 q0, const u32x4 q1) {
+        long long t[2 * IPV0];
+        unpack(q0, t);
+        unpack(q1, t + IPV0);
+        tally_ids(std::integral_constant<int, 2 * IPV0>{}, t);
     };
     // kHistUnroll vectors per thread are requested before the first is counted: one 16-byte load per
     // thread in flight (16 KiB per CU) is far below what the memory latency needs.  Plain (cached) loads:
@@ -91,8 +138,9 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
         u32x4 q[kHistUnroll];
 #pragma unroll
         for (int u = 0; u < kHistUnroll; ++u) q[u] = vp[v + (long long)u * kHistThreads];
+        static_assert(kHistUnroll % 2 == 0, "vectors are counted in pairs");
 #pragma unroll
-        for (int u = 0; u < kHistUnroll; ++u) tally_vec(q[u]);
+        for (int u = 0; u < kHistUnroll; u += 2) tally_vec2(q[u], q[u + 1]);
     }
     for (; v < v1; v += kHistThreads) tally_vec(vp[v]);
     if (chunk == 0 && (int)threadIdx.x < head) {   // scalar head
