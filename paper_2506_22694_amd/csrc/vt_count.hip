@@ -77,29 +77,51 @@ __global__ void __launch_bounds__(kHistThreads) hist_partial_kernel(const void *
     constexpr int IPV0 = IDS64 ? 2 : 4;
     auto tally_ids = [&](auto ncount, const long long *t) {
         constexpr int N = decltype(ncount)::value;
-        unsigned b[N], sh[N], old[N];
+        // ids outside [0, V): rare, so one test for the batch (the largest id as an unsigned number) and the count
+        // behind it; only the workgroups of range 0 report them
+        if (range == 0) {
+            bool some;
+            if constexpr (IDS64) {
+                unsigned long long mx = (unsigned long long)t[0];
+#pragma unroll
+                for (int q = 1; q < N; ++q) mx = (unsigned long long)t[q] > mx ? (unsigned long long)t[q] : mx;
+                some = mx >= (unsigned long long)V;
+            } else {
+                unsigned mx = (unsigned)(int)t[0];       // a negative id is a large unsigned number
+#pragma unroll
+                for (int q = 1; q < N; ++q) mx = (unsigned)(int)t[q] > mx ? (unsigned)(int)t[q] : mx;
+                some = mx >= (unsigned)V;
+            }
+            if (some) {
+#pragma unroll
+                for (int q = 0; q < N; ++q) invalid += (unsigned long long)t[q] >= (unsigned long long)V ? 1u : 0u;
+            }
+        }
+        unsigned b[N], inc[N], old[N];
         bool in[N];
 #pragma unroll
         for (int q = 0; q < N; ++q) {
-            invalid += (unsigned long long)t[q] >= (unsigned long long)V ? 1u : 0u;
+            // bin inside this range; an id outside [lo, lo + nb) -- a negative one too, V < 2^31 -- wraps far past nb
+            // (a 64-bit id is first checked as a whole: its low half alone could land anywhere)
             b[q] = (unsigned)((int)t[q] - lo);
-            in[q] = (unsigned long long)t[q] < (unsigned long long)V && b[q] < (unsigned)nb;
-            sh[q] = (b[q] & 1u) << 4;
+            in[q] = b[q] < (unsigned)nb && (!IDS64 || (unsigned long long)t[q] < (unsigned long long)V);
+            inc[q] = 1u + (b[q] & 1u) * 0xFFFFu;        // 1 for the low half of the word, 0x10000 for the high one
             old[q] = 0u;
         }
 #pragma unroll
         for (int q = 0; q < N; ++q) {
-            if (in[q]) old[q] = atomicAdd(&words[b[q] >> 1], 1u << sh[q]);
+            if (in[q]) old[q] = atomicAdd(&words[b[q] >> 1], inc[q]);
         }
+        // the increment that found 0x7FFF in its bin set bit 15
         bool spill = false;
 #pragma unroll
-        for (int q = 0; q < N; ++q) spill |= in[q] && ((old[q] >> sh[q]) & 0xFFFFu) == 0x7FFFu;
+        for (int q = 0; q < N; ++q) spill |= in[q] && (old[q] & (inc[q] * 0x7FFFu)) == inc[q] * 0x7FFFu;
         if (spill) {
 #pragma unroll
             for (int q = 0; q < N; ++q) {
-                if (in[q] && ((old[q] >> sh[q]) & 0xFFFFu) == 0x7FFFu) {
-                    // this increment set bit 15: 32768 occurrences move from the bin to the result counter
-                    atomicSub(&words[b[q] >> 1], 0x8000u << sh[q]);
+                if (in[q] && (old[q] & (inc[q] * 0x7FFFu)) == inc[q] * 0x7FFFu) {
+                    // 32768 occurrences move from the bin to the result counter
+                    atomicSub(&words[b[q] >> 1], inc[q] * 0x8000u);
                     atomicAdd(&counts[t[q]], 32768ull);
                 }
             }
