@@ -91,6 +91,7 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
     __shared__ unsigned long long red64[kRowWaves];
     __shared__ unsigned tmax[2 * kRowWaves];
     __shared__ unsigned long long cand[kRowMaxCand];
+    __shared__ int candj[kRowMaxCand];
     __shared__ unsigned s_ncand;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int i = blockIdx.x;
@@ -162,14 +163,23 @@ __global__ void __launch_bounds__(kRowThreads) row_select_kernel(const float *__
         for (int u = 0; u < kRowVals; ++u) {
             const int j = stretch_index<VEC>(base, u, tid);
             if (j < k && v[u] >= Tf) {
+                // logit and position now, the target id later: a load from the map here would put a trip to
+                // memory behind every candidate a wave finds, one after the other
                 const unsigned slot = atomicAdd(&s_ncand, 1u);
-                if (slot < (unsigned)kRowMaxCand) cand[slot] = make_key(v[u], map[j]);
+                if (slot < (unsigned)kRowMaxCand) {
+                    cand[slot] = (unsigned long long)__float_as_uint(v[u]);
+                    candj[slot] = j;
+                }
             }
         }
     }
     __syncthreads();
     const int ncand = (int)s_ncand;
     if (ncand <= kRowMaxCand) {
+        // the candidates' target ids, all requested at once
+        for (int c = tid; c < ncand; c += kRowThreads)
+            cand[c] = make_key(__uint_as_float((unsigned)cand[c]), map[candj[c]]);
+        __syncthreads();
         // rank by counting: keys are distinct (distinct target ids)
         for (int c = tid; c < ncand; c += kRowThreads) {
             const unsigned long long key = cand[c];
