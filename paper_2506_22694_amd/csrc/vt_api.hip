@@ -321,7 +321,12 @@ StepPlan plan_step_impl(int n, int k, int d, int m, int dtype, bool force_gemv, 
         // The per-tile candidate lists cost n * L selection rounds per tile and grow to megabytes; beyond a point
         // (measured: 12 or more tokens per row, or n * L from about 1280; always when the lists no longer fit the
         // merge's LDS staging) the kernel stores its logits instead and a workgroup per hidden row finishes the step.
-        p.row_select = p.L > vt::kRowSelectMinL || n * p.L >= vt::kRowSelectMinWork || fc < 1;
+        // With more than 8 hidden rows the tile epilogue selects by threshold only up to 8 tokens per row (four rows per
+        // wave, 16 candidate slots each) and takes L rounds beyond: there the per-row tail wins from 9 tokens on
+        // (measured, k = 32768, d = 4096: n = 64, m = 9: 58.4 against 60.1 us, m = 11: 58.5 / 61.8; n = 32, m = 10:
+        // 53.8 / 55.1).
+        const int max_list = n > vt::kGemvMaxN ? vt::kRowSelectMinLManyRows : vt::kRowSelectMinL;
+        p.row_select = p.L > max_list || n * p.L >= vt::kRowSelectMinWork || fc < 1;
         // one hidden row per workgroup: n <= 256 rows spread over as many CUs, and a merging wave has its
         // SIMD to itself (the selection rounds are bound by instruction issue)
         p.fin_conc = 1;

@@ -65,7 +65,8 @@ struct StepArgs {
 
 // ---- matrix-core path (n > 8) ----
 constexpr int kMfmaTileRows = 128;     // rows of W_trim per workgroup (16 per wave)
-constexpr int kRowSelectMinL = 11;      // matrix-core path: with more tokens per row than this, or
+constexpr int kRowSelectMinL = 11;      // matrix-core path: with more tokens per row than this (8 with more than 8 hidden rows), or
+constexpr int kRowSelectMinLManyRows = 8;
 // small-n path: the same switch when L > 12 - n / 2 (measured crossovers: L = 8 at n = 8, 10 at n = 4, 11-12 at n = 1)
 constexpr int kGemvRowSelectBase = 12;
 constexpr int kRowSelectMinWork = 1280; // with n * min(m, 128) from this value on, the kernel stores its logits and a

@@ -408,7 +408,7 @@ __device__ __forceinline__ unsigned wave_min_of_group_max_u32(unsigned v, int gs
     return gsteps > 5 ? (r[0] > r[1] ? r[0] : r[1]) : (r[0] < r[1] ? r[0] : r[1]);
 }
 
-constexpr int kDirectKeysPerLane = 32;      // 2048 keys stay in registers
+constexpr int kDirectKeysPerLane = 48;      // up to 3072 keys stay in registers (256 lists of 12)
 constexpr int kDirectMaxCand = 128;
 
 // 16 bytes per lane with the coherence of acquire_u64 (agent scope: not served from this XCD's L2).
@@ -422,9 +422,16 @@ __device__ __forceinline__ void wait_loads16(u32x4 (&r)[16]) {
                    "+v"(r[8]), "+v"(r[9]), "+v"(r[10]), "+v"(r[11]), "+v"(r[12]), "+v"(r[13]), "+v"(r[14]),
                    "+v"(r[15]));
 }
+__device__ __forceinline__ void wait_loads24(u32x4 (&r)[24]) {
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]),
+                   "+v"(r[8]), "+v"(r[9]), "+v"(r[10]), "+v"(r[11]), "+v"(r[12]), "+v"(r[13]), "+v"(r[14]),
+                   "+v"(r[15]), "+v"(r[16]), "+v"(r[17]), "+v"(r[18]), "+v"(r[19]), "+v"(r[20]), "+v"(r[21]),
+                   "+v"(r[22]), "+v"(r[23]));
+}
 
 // All `total` <= 64 U published keys of a hidden row (any order) are held in registers, U per lane
-// (U = 32: read as 16 pairs, `total` even and src 16-byte aligned; U = 4: one key per load).
+// (U = 32 or 48: read as U / 2 pairs, `total` even and src 16-byte aligned; U = 4: one key per load).
 // With G = the power of two >= m, the lanes form G groups; every group's best logit is a different
 // key, so at least G >= m keys reach T = the smallest of the group maxima, and the m best keys are
 // among the keys whose logit reaches T (a few dozen).  Those are compacted into LDS and ranked by
@@ -437,23 +444,24 @@ __device__ __forceinline__ bool finalize_row_direct(const unsigned long long *__
                                                     LseFn &&lse_fn, float &lse_out, unsigned long long *stage,
                                                     int *__restrict__ out_ids_row, float *__restrict__ out_logp_row,
                                                     int lane) {
-    static_assert(U == 32 || U == 4, "unsupported register budget");
+    static_assert(U == 48 || U == 32 || U == 4, "unsupported register budget");
     unsigned long long kreg[U];
-    if constexpr (U == 32) {
-        u32x4 r[16];
+    if constexpr (U >= 32) {
+        u32x4 r[U / 2];
         const int npairs = total >> 1;
         // Straight-line code from the first request to the wait: the compiler does not know that these
         // registers are still in flight, and a branch in between (say, around the requests past the end)
         // makes it copy them at the join -- before their values have arrived.  Requests past the end
         // re-read the last pair instead.
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
+        for (int u = 0; u < U / 2; ++u) {
             const int e = u * kWave + lane;
             acquire_load16(r[u], src + 2 * (FULL ? e : min(e, npairs - 1)));
         }
-        wait_loads16(r);
+        if constexpr (U == 32) wait_loads16(r);
+        else wait_loads24(r);
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
+        for (int u = 0; u < U / 2; ++u) {
             const bool valid = FULL || u * kWave + lane < npairs;
             kreg[2 * u] = valid ? (((unsigned long long)r[u][1] << 32) | r[u][0]) : kNoKey;
             kreg[2 * u + 1] = valid ? (((unsigned long long)r[u][3] << 32) | r[u][2]) : kNoKey;
@@ -556,6 +564,8 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
         bool done;
         if (total_keys == 32 * kWave)
             done = finalize_row_direct<32, true>(pkeys_row, total_keys, m, lse_fn, lse, stage, out_ids_row, out_logp_row, lane);
+        else if (total_keys > 32 * kWave)
+            done = finalize_row_direct<48, false>(pkeys_row, total_keys, m, lse_fn, lse, stage, out_ids_row, out_logp_row, lane);
         else if (total_keys > 4 * kWave)
             done = finalize_row_direct<32, false>(pkeys_row, total_keys, m, lse_fn, lse, stage, out_ids_row, out_logp_row, lane);
         else
