@@ -430,6 +430,14 @@ __device__ __forceinline__ void wait_loads24(u32x4 (&r)[24]) {
                    "+v"(r[22]), "+v"(r[23]));
 }
 
+// The first active lane's value in every lane.  The row's log-sum-exp goes through this before it is subtracted
+// from the logits: the lanes of a wave-wide float sum were found to differ in the last bits (the same terms in
+// another association), and tokens with bit-identical logits must get bit-identical log-probs whichever lane
+// writes them.
+__device__ __forceinline__ float lane_uniform(float x) {
+    return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(x)));
+}
+
 // All `total` <= 64 U published keys of a hidden row (any order) are held in registers, U per lane
 // (U = 32 or 48: read as U / 2 pairs, `total` even and src 16-byte aligned; U = 4: one key per load).
 // With G = the power of two >= m, the lanes form G groups; every group's best logit is a different
@@ -559,7 +567,7 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
                 }
             }
             const float M = wave_max(lm);
-            return M + __logf(wave_sum(ls * __expf(lm - M)));
+            return lane_uniform(M + __logf(wave_sum(ls * __expf(lm - M))));
         };
         bool done;
         if (total_keys == 32 * kWave)
@@ -595,7 +603,7 @@ __device__ __forceinline__ void finalize_row(const unsigned long long *__restric
             }
         }
         const float M = wave_max(lm);
-        lse = M + __logf(wave_sum(ls * __expf(lm - M)));
+        lse = lane_uniform(M + __logf(wave_sum(ls * __expf(lm - M))));
     }
 
     unsigned res_ord = 0u;

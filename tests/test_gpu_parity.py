@@ -339,6 +339,16 @@ def test_step_paper_trimmed_sizes_full_size(k, n, d, m):
     _paper_size_case(k, n, d, m)
 
 
+# nine to twelve tokens per row: up to 256 lists of 12 keys are merged from registers like 256 lists of 8 (another
+# instance of the merge, with lanes past the end); from 9 tokens on, more than 8 hidden rows take the per-row tail.
+# Exact ties planted across tiles as above (seven copies of the best row: all of the first eight ranks tie).
+@pytest.mark.parametrize("k,n,d,m", [(32768, 8, 3072, 9), (32768, 8, 3072, 12), (32768, 1, 2048, 10),
+                                     (65536, 1, 3072, 12), (65536, 2, 3072, 11), (32975, 8, 3072, 10),
+                                     (32768, 12, 3072, 10), (32768, 64, 4096, 9), (8192, 8, 3072, 10)])
+def test_step_nine_to_twelve_tokens_per_row(k, n, d, m):
+    _paper_size_case(k, n, d, m)
+
+
 # few hidden rows on heads of 20 .. 28 thousand rows: tiles of six and seven waves
 @pytest.mark.parametrize("k,n,d,m", [(22786, 2, 3072, 8), (22786, 4, 3072, 8), (24576, 1, 2048, 1), (26000, 1, 3072, 1),
                                      (28672, 1, 3072, 8), (20481, 3, 3072, 4)])
