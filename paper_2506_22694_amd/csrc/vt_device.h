@@ -39,7 +39,10 @@ constexpr unsigned long long kNoKey = 0ull;
 // ---- wave-wide all-reductions on DPP / permlane swaps (no LDS traffic) ----
 // Four DPP steps reduce within a row of 16 lanes; permlane16_swap and
 // permlane32_swap (gfx950) then combine the four rows.  Every lane receives the
-// result and the combination order is fixed, so float sums are reproducible.
+// result and the combination order is fixed, so float sums are reproducible from run to run.
+// (Lane to lane a float sum may differ in the last bits when the summand is a product: the compiler
+// may contract it with the first step into a fused multiply-add.  Where all lanes must use the same
+// value, take one lane's.)
 template <int CTRL>
 __device__ __forceinline__ unsigned dpp_mov(unsigned v) {
     return __builtin_amdgcn_update_dpp(0u, v, CTRL, 0xF, 0xF, false);

@@ -431,9 +431,10 @@ __device__ __forceinline__ void wait_loads24(u32x4 (&r)[24]) {
 }
 
 // The first active lane's value in every lane.  The row's log-sum-exp goes through this before it is subtracted
-// from the logits: the lanes of a wave-wide float sum were found to differ in the last bits (the same terms in
-// another association), and tokens with bit-identical logits must get bit-identical log-probs whichever lane
-// writes them.
+// from the logits: the lanes' copies of a wave-wide float sum can differ in the last bits (the summand is a product,
+// and the compiler contracts it with the first exchange step into a fused multiply-add -- a lane's own product
+// unrounded, its partner's rounded), and tokens with bit-identical logits must get bit-identical log-probs
+// whichever lane writes them.
 __device__ __forceinline__ float lane_uniform(float x) {
     return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(x)));
 }
