@@ -53,6 +53,27 @@ __device__ __forceinline__ unsigned long long wave_select_top(unsigned (&ord)[Q]
 
 __device__ __forceinline__ unsigned wave_min_of_group_max_u32(unsigned v, int gsteps);
 
+// The largest value P << 16 such that at least `kth` lanes hold v >= P << 16 (0 if fewer than kth lanes hold anything
+// but 0): the upper half of the kth largest v, selected one bit at a time.  All 64 lanes take part.
+__device__ __forceinline__ unsigned wave_kth_largest_prefix16(unsigned v, int kth) {
+    unsigned T = 0u;
+    unsigned long long alive = ~0ull;
+    int need = kth;
+#pragma unroll
+    for (int b = 31; b >= 16; --b) {
+        const unsigned long long ones = __ballot((v >> b) & 1u) & alive;
+        const int c = __popcll(ones);
+        if (c >= need) {
+            alive = ones;
+            T |= 1u << b;
+        } else {
+            need -= c;
+            alive &= ~ones;
+        }
+    }
+    return T;
+}
+
 // ------------------------------------------------------------------ top-L of a wave's candidates, by threshold
 // Two candidates per lane (ord = 0: none).  With G = the power of two >= L the lanes form G groups; every
 // group's best logit is a different candidate, so at least L candidates reach T = the smallest group maximum
@@ -63,9 +84,14 @@ __device__ __forceinline__ void wave_publish_top_by_threshold(const unsigned (&o
                                                               unsigned long long *cand,
                                                               unsigned long long *__restrict__ pkeys_slot, int lane) {
     const unsigned top = ord[0] > ord[1] ? ord[0] : ord[1];
-    int gsteps = 6;
-    while ((kWave >> gsteps) < L) --gsteps;
-    unsigned T = wave_min_of_group_max_u32(top, gsteps);
+    unsigned T;
+    if (L <= 8) {
+        int gsteps = 6;
+        while ((kWave >> gsteps) < L) --gsteps;
+        T = wave_min_of_group_max_u32(top, gsteps);
+    } else {
+        T = wave_kth_largest_prefix16(top, L);      // (16 or more groups would pass several times L candidates)
+    }
     T = T == 0u ? 1u : T;               // a group without candidates: every real candidate passes
     const bool c0 = ord[0] >= T, c1 = ord[1] >= T;
     const unsigned long long m0 = __ballot(c0), m1 = __ballot(c1);
@@ -115,9 +141,14 @@ __device__ __forceinline__ bool wave_publish_top_by_threshold_q(const unsigned (
     unsigned top = ord[0];
 #pragma unroll
     for (int q = 1; q < Q; ++q) top = ord[q] > top ? ord[q] : top;
-    int gsteps = 6;
-    while ((kWave >> gsteps) < L) --gsteps;
-    unsigned T = wave_min_of_group_max_u32(top, gsteps);
+    unsigned T;
+    if (L <= 8) {
+        int gsteps = 6;
+        while ((kWave >> gsteps) < L) --gsteps;
+        T = wave_min_of_group_max_u32(top, gsteps);
+    } else {
+        T = wave_kth_largest_prefix16(top, L);
+    }
     T = T == 0u ? 1u : T;
     int ncand = 0;
 #pragma unroll
@@ -491,9 +522,17 @@ __device__ __forceinline__ bool finalize_row_direct(const unsigned long long *__
         const unsigned o = (unsigned)(kreg[u] >> 32);
         top = o > top ? o : top;
     }
-    int gsteps = 6;                     // G = 64 >> gsteps groups, G >= m
-    while ((kWave >> gsteps) < m) --gsteps;
-    unsigned T = wave_min_of_group_max_u32(top, gsteps);
+    unsigned T;
+    if (m <= 8) {
+        int gsteps = 6;                 // G = 64 >> gsteps groups, G >= m
+        while ((kWave >> gsteps) < m) --gsteps;
+        T = wave_min_of_group_max_u32(top, gsteps);
+    } else {
+        // 9 or more tokens: the power of two above m would make 16 or more groups and several times m candidates.
+        // Instead T = the upper 16 bits of the m-th largest of the lanes' best logits, found bit by bit with ballots
+        // (at least m lanes, hence m keys, reach it; if fewer than m lanes hold a key at all, T comes out as 0).
+        T = wave_kth_largest_prefix16(top, m);
+    }
     T = T == 0u ? 1u : T;               // an empty group: every real key is a candidate (real keys have a non-zero high word)
     int ncand = 0;
 #pragma unroll
