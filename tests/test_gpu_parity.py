@@ -349,6 +349,26 @@ def test_step_nine_to_twelve_tokens_per_row(k, n, d, m):
     _paper_size_case(k, n, d, m)
 
 
+# The m log-probs a step returns and the full log-softmax it can return beside them come from the same logits and
+# the same log-sum-exp: each returned (id, log-prob) must be, bit for bit, the entry of out_logp_full at that id's
+# position -- on every kernel pairing (small-n kernel, matrix cores with lists, with the per-row tail, many rows).
+@pytest.mark.parametrize("k,n,d,m,dt", [(32768, 8, 3072, 8, "bf16"), (65536, 2, 3072, 8, "bf16"), (32768, 1, 2048, 1, "bf16"),
+                                        (32975, 8, 3072, 10, "bf16"), (8192, 8, 3072, 16, "bf16"),
+                                        (32768, 64, 4096, 8, "bf16"), (32768, 40, 4096, 12, "bf16"),
+                                        (16384, 100, 2048, 8, "bf16"), (4096, 4, 256, 4, "f32"), (5000, 3, 200, 7, "bf16")])
+def test_step_returned_logprobs_are_entries_of_the_full_logsoftmax(k, n, d, m, dt):
+    W, map_ = synth.trimmed_head_direct(k, d, seed=3 * k + n, dtype=dt)
+    h = synth.hidden_rows(n, d, seed=3 * k + n + 1, dtype=dt)
+    oi, ol, lse, full = run_step(h, W, map_, m, return_lse=True, return_full=True)
+    pos = {int(t): j for j, t in enumerate(map_)}
+    ids, lp, f = oi.cpu().numpy(), ol.cpu().numpy().view(np.uint32), full.cpu().numpy().view(np.uint32)
+    for i in range(n):
+        cols = [pos[int(t)] for t in ids[i]]
+        assert np.array_equal(lp[i], f[i, cols]), (i, lp[i], f[i, cols])
+    ref = oracle.draft_head_step(h, W, map_, m)
+    assert check_step(oi, ol, ref, map_, m, lse) <= 2
+
+
 # few hidden rows on heads of 20 .. 28 thousand rows: tiles of six and seven waves
 @pytest.mark.parametrize("k,n,d,m", [(22786, 2, 3072, 8), (22786, 4, 3072, 8), (24576, 1, 2048, 1), (26000, 1, 3072, 1),
                                      (28672, 1, 3072, 8), (20481, 3, 3072, 4)])
